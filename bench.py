@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused Sinkhorn hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+One "step" is one pass of the whole hot path over the workload, inputs already resident
+in HBM: fs_row_norms of both clouds, fs_solve (all stages and iterations), fs_marginal_err,
+fs_apply_plan (V = y), fs_apply_plan_T (U) and the gradient assembly 2(diag(a) x - P y).
+The default workload is the large low-dimension annealed problem (n = m = 262144, d = 3,
+eps 1.0 -> 0.01 over 20 stages x 10 iterations).  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = fp32 vector-ALU issue slots per second.
+# (The published 157.3 TFLOP/s fp32 vector peak is this number x 2 flop (FMA) x 2 (packed
+# fp32, which this GPU pool requires to be switched off).)
+VALU_LANE_SLOTS_PER_S = 256 * 4 * 16 * 2.4e9
+PEAKS = {"bf16": 2.5e15, "f64": 78.6e12}
+
+
+def algorithmic_slots_per_pair(d: int, exp_cost: float = 4.0) -> float:
+    """Issue slots the method itself needs per (i, j) pair on the vector ALU: d FMAs for the
+    score, one subtraction of the running max, one exp2 (a transcendental occupies the ALU
+    for `exp_cost` full-rate slots: quarter rate), one accumulation of the sum."""
+    return d + 1 + exp_cost + 1
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="lowdim_anneal")
+    ap.add_argument("--n", type=int, default=None, help="override n = m (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path is single-GPU; "
+              "see DESIGN.md for how it would shard). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2602_03067_amd import binding, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    w = workloads.make(args.workload, n=args.n, m=args.n)
+    ctx = binding.Context(0)
+    prob = binding.problem_from_workload(w)
+    V = prob.y.float() if w.V is None else torch.from_numpy(w.V).to("cuda:0")
+    if w.U is not None:
+        U = torch.from_numpy(w.U).to("cuda:0")
+    else:
+        U = torch.from_numpy(np.random.Generator(np.random.PCG64(w.seed + 7)).standard_normal(
+            (w.n, min(w.d, 64))).astype(np.float32)).to("cuda:0")
+    can_apply = w.compute == "fp32"
+    f = torch.zeros(w.n, device="cuda:0")
+    g = torch.zeros(w.m, device="cuda:0")
+    xf = prob.x.float()
+    a_col = prob.a.unsqueeze(1)
+
+    def step():
+        f.zero_()
+        g.zero_()
+        ctx.fs_row_norms(prob.x)
+        ctx.fs_row_norms(prob.y)
+        ctx.fs_solve(prob, w.eps_start, w.eps_end, w.n_stages, w.iters, f, g)
+        er, ec = ctx.fs_marginal_err(prob, w.eps_end, f, g)
+        grad = None
+        if can_apply:
+            PY = ctx.fs_apply_plan(prob, w.eps_end, f, g, V)
+            ctx.fs_apply_plan_T(prob, w.eps_end, f, g, U)
+            if V.shape[1] == w.d:
+                grad = 2.0 * (a_col * xf - PY)     # Cor. 4 (elementwise assembly)
+        return er, ec, grad
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.fs_profile_enable(True)
+    ctx.fs_profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        er, ec, _ = step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    avg_ms, launches, pairs = ctx.fs_profile_read()
+    ctx.fs_profile_enable(False)
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    iters = w.total_iters
+    value = iters * args.steps / elapsed
+
+    # ---- roofline of the dominant kernel (the streaming LSE pass) -------------------------
+    if w.compute == "bf16_mfma":
+        flops = 2.0 * w.d * pairs
+        roof = {"bound": "mfma", "achieved": flops / (avg_ms * 1e-3) / 1e12, "peak": PEAKS["bf16"] / 1e12,
+                "unit": "TFLOP/s"}
+        dtype = "bf16"
+    elif w.d > 16:
+        flops = 2.0 * w.d * pairs
+        roof = {"bound": "mfma", "achieved": flops / (avg_ms * 1e-3) / 1e12, "peak": PEAKS["f64"] / 1e12,
+                "unit": "TFLOP/s"}
+        dtype = "f64"
+    else:
+        slots = algorithmic_slots_per_pair(w.d) * pairs
+        roof = {"bound": "alu", "achieved": slots / (avg_ms * 1e-3) / 1e12,
+                "peak": VALU_LANE_SLOTS_PER_S / 1e12, "unit": "Tlane-op/s"}
+        dtype = "f32"
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = "streaming LSE half-step"
+    roof["avg_launch_ms"] = avg_ms
+    roof["launches"] = launches
+    roof["pairs_per_launch"] = pairs
+
+    out = {
+        "metric": "Sinkhorn iterations/sec (fused f+g)", "value": value, "unit": "iterations/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "n": w.n, "m": w.m, "d": w.d, "eps_start": w.eps_start,
+                   "eps_end": w.eps_end, "stages": w.n_stages, "iters_per_stage": w.iters,
+                   "step": "row_norms + solve + marginal_err + apply_plan + apply_plan_T + grad"},
+        "marginal_err": {"row": er, "col": ec},
+        "roofline": roof,
+    }
+
+    # ---- the float64 oracle on the host cores, on a bounded sample -------------------------
+    if not args.no_cpu_baseline:
+        import oracle
+        R = max(1, min(w.n, w.m, int(2.0e9 / max(w.n, w.m) / max(1.0, w.d / 8.0))))
+        rows = np.arange(R)
+        gz = np.zeros(w.m)
+        fz = np.zeros(w.n)
+        eps = float(np.float32(w.eps_end))
+        t1 = time.perf_counter()
+        oracle.update_f(w.x, w.y, w.b, eps, gz, rows=rows)
+        tf = time.perf_counter() - t1
+        t1 = time.perf_counter()
+        oracle.update_g(w.x, w.y, w.a, eps, fz, cols=rows)
+        tg = time.perf_counter() - t1
+        it_time = tf * (w.n / R) + tg * (w.m / R)
+        out["cpu_baseline"] = {
+            "value": 1.0 / it_time, "unit": "iterations/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": "one f half-step and one g half-step restricted to %d rows against all "
+                      "columns (%.1f s), extrapolated linearly in rows to a full iteration" % (R, tf + tg),
+        }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

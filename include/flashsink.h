@@ -1,0 +1,178 @@
+/*
+ * flashsink.h -- C ABI of libflashsink: fused log-domain Sinkhorn for entropic
+ * optimal transport with squared-Euclidean cost on AMD MI355X (gfx950).
+ *
+ * Problem (paper Section 2.1): source points x in R^{n x d} with weights a,
+ * target points y in R^{m x d} with weights b, cost C_ij = |x_i - y_j|^2,
+ * regularisation eps > 0, dual potentials f in R^n, g in R^m.  Every half-step
+ * is evaluated as a streaming row-wise LogSumExp of biased dot-product scores
+ * (Prop. 1); no n x m matrix is ever stored.
+ *
+ * Conventions common to all entry points
+ *  - Every pointer inside fs_problem and every pointer argument is a DEVICE
+ *    pointer owned by the caller, unless the argument is marked "host".
+ *    Inputs are never written.  Outputs must not alias inputs.
+ *  - x, y are row-major with leading dimensions ldx, ldy (in elements, >= d).
+ *  - Potentials that cross this interface are the UNSHIFTED f, g of Eq. 2-3, in
+ *    float.  The shift by the squared norms (Prop. 1) is internal.
+ *  - a == NULL / b == NULL means uniform weights 1/n, 1/m.  Weights must be
+ *    positive; a zero weight removes its point from every sum (log 0 = -inf).
+ *  - All work is enqueued on the stream given to fs_create; calls return
+ *    without synchronising, except fs_marginal_err (it returns host scalars)
+ *    and calls that have to grow the context's workspace (they synchronise the
+ *    stream once, before the old workspace is released).
+ *  - Errors are reported by status code only; nothing throws or aborts.
+ *    Argument validation happens on the host before any launch.  The message
+ *    of the last failure on a context is available from fs_last_error.
+ *  - A context is not thread-safe; use one per thread/stream.
+ *  - The library allocates device memory only for the context's workspace
+ *    (derived copies of x and y, squared norms, bias vectors, partial
+ *    reductions); it is grown on demand and released by fs_destroy.
+ */
+#ifndef FLASHSINK_H
+#define FLASHSINK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fs_ctx fs_ctx;
+
+typedef enum {
+    FS_OK = 0,
+    FS_ERR_INVALID_ARG = 1, /* null pointer, aliasing, bad enum value                  */
+    FS_ERR_BAD_SHAPE = 2,   /* n, m, d, p <= 0, ld < d, sizes beyond the supported max */
+    FS_ERR_BAD_EPS = 3,     /* eps <= 0 or not finite, n_stages < 1, iters < 0         */
+    FS_ERR_BAD_WEIGHTS = 4, /* reserved for explicit weight validation                 */
+    FS_ERR_UNSUPPORTED = 5, /* dtype/compute combination not available                 */
+    FS_ERR_ALLOC = 6,       /* device allocation failed                                */
+    FS_ERR_DEVICE = 7       /* a HIP call failed (message in fs_last_error)            */
+} fs_status;
+
+/* storage type of x and y */
+typedef enum { FS_F32 = 0, FS_BF16 = 1 } fs_dtype;
+
+/*
+ * Arithmetic of the score tile 2<x_i, y_j>:
+ *  FS_COMPUTE_FP32       d <= 16: fp32 vector ALU on coordinates centred at the common
+ *                        mean (the cost is translation invariant); d > 16: the
+ *                        contraction runs on the fp64 matrix cores, because at
+ *                        |score| ~ 1e3 fp32 products cannot hold 1e-4 absolute.
+ *                        Potentials agree with a float64 reference to 1e-4*eps.
+ *  FS_COMPUTE_BF16_MFMA  x, y rounded to bfloat16 (RNE), products on the bf16 matrix
+ *                        cores with fp32 accumulation; norms are taken from the
+ *                        rounded points.  Needs d >= 16.  Agreement 2e-2*eps.
+ */
+typedef enum { FS_COMPUTE_FP32 = 0, FS_COMPUTE_BF16_MFMA = 1 } fs_compute;
+
+typedef struct {
+    const void *x;      /* n x d, row-major, dtype below                 */
+    const void *y;      /* m x d                                         */
+    int32_t dtype;      /* fs_dtype                                      */
+    int32_t compute;    /* fs_compute                                    */
+    int64_t n, m, d;    /* n, m <= 2^24 points, d <= 8192                */
+    int64_t ldx, ldy;   /* leading dimensions in elements (>= d)         */
+    const float *a;     /* n weights or NULL (uniform)                   */
+    const float *b;     /* m weights or NULL (uniform)                   */
+} fs_problem;
+
+/*
+ * Create a context bound to HIP device `device` and to `hip_stream` (a hipStream_t
+ * passed as void*, NULL = the default stream).  Fails with FS_ERR_DEVICE if the
+ * device cannot be used.  The context owns its workspace only.
+ * device == -1 creates a host-only context: every entry point still validates its
+ * arguments and reports argument errors, and otherwise returns FS_ERR_DEVICE without
+ * touching a GPU (used to test the interface on machines without one).
+ */
+fs_status fs_create(fs_ctx **ctx, int device, void *hip_stream);
+
+/* Synchronises the stream, frees the workspace and the context.  NULL is allowed. */
+fs_status fs_destroy(fs_ctx *ctx);
+
+const char *fs_status_str(fs_status s);
+const char *fs_last_error(const fs_ctx *ctx); /* "" if none; valid until the next call */
+
+/* Library build info: "flashsink <version> gfx950". */
+const char *fs_version(void);
+
+/*
+ * Squared row norms alpha_i = |pts_i|^2 (Prop. 1, definition of alpha and beta).
+ * pts: rows x d (ld elements per row) of `dtype`; out: rows floats.  Accumulated in
+ * float64 and rounded once.
+ */
+fs_status fs_row_norms(fs_ctx *ctx, const void *pts, int32_t dtype, int64_t rows, int64_t d,
+                       int64_t ld, float *out);
+
+/*
+ * One half-step, Eq. 2 evaluated in the form of Prop. 1 / Alg. 1:
+ *   f_i = alpha_i - eps * LSE_j[(2<x_i,y_j> - beta_j + g_j)/eps + log b_j].
+ * g: m floats in; f_out: n floats out.
+ */
+fs_status fs_update_f(fs_ctx *ctx, const fs_problem *prob, float eps, const float *g,
+                      float *f_out);
+
+/*
+ * The other half-step, Eq. 3 in the form of Prop. 1 / Alg. 3:
+ *   g_j = beta_j - eps * LSE_i[(2<y_j,x_i> - alpha_i + f_i)/eps + log a_i].
+ */
+fs_status fs_update_g(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f,
+                      float *g_out);
+
+/*
+ * Alternating Sinkhorn with a fixed iteration count (App. B, Gauss-Seidel form):
+ * n_stages * iters_per_stage iterations, each "f from g, then g from the new f".
+ * Stage s uses eps_s = eps_start * (eps_end/eps_start)^(s/(n_stages-1)), evaluated
+ * in double and rounded to float, endpoints exact; n_stages == 1 uses eps_end.
+ * f (n floats) and g (m floats) are read as the starting potentials (f is never
+ * read by the first half-step, g is) and overwritten with the result.  Between
+ * half-steps the potentials are kept in float64 inside the workspace; they are
+ * rounded to float once, at the end.
+ */
+fs_status fs_solve(fs_ctx *ctx, const fs_problem *prob, float eps_start, float eps_end,
+                   int32_t n_stages, int32_t iters_per_stage, float *f, float *g);
+
+/*
+ * L1 violation of the marginals of the plan induced by (f, g) (Prop. 3):
+ *   r_i = a_i exp((f_i - f_i^+)/eps),  c_j = b_j exp((g_j - g_j^+)/eps),
+ *   *err_row_l1 = sum_i |r_i - a_i|,   *err_col_l1 = sum_j |c_j - b_j|,
+ * where f^+, g^+ are one half-step from (f, g).  The two results are HOST floats;
+ * either pointer may be NULL to skip that side.  Synchronises the stream.
+ */
+fs_status fs_marginal_err(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f,
+                          const float *g, float *err_row_l1 /* host */,
+                          float *err_col_l1 /* host */);
+
+/*
+ * out = P V with P_ij = a_i b_j exp((f_i + g_j - C_ij)/eps) for ANY potentials
+ * (Prop. 3, Alg. 2): one streaming pass, P never stored.
+ * V: m x p (ldv), out: n x p (ldo), r_out: NULL or n floats receiving P 1_m.
+ * The gradient of Cor. 4 is 2*(diag(a) x - P y) (or with r_out in place of a, App. G).
+ */
+fs_status fs_apply_plan(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f,
+                        const float *g, const float *V, int64_t p, int64_t ldv, float *out,
+                        int64_t ldo, float *r_out);
+
+/*
+ * out = P^T U (Alg. 4).  U: n x p (ldu), out: m x p (ldo), c_out: NULL or m floats
+ * receiving P^T 1_n.
+ */
+fs_status fs_apply_plan_T(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f,
+                          const float *g, const float *U, int64_t p, int64_t ldu, float *out,
+                          int64_t ldo, float *c_out);
+
+/*
+ * Timing hook for benchmarks: average duration in milliseconds of the streaming
+ * LSE kernel launches (the dominant kernel) recorded with HIP events on the
+ * context's stream since the last call of this function, and their count.
+ * Recording is off until fs_profile_enable(ctx, 1).  Synchronises the stream.
+ */
+fs_status fs_profile_enable(fs_ctx *ctx, int32_t on);
+fs_status fs_profile_read(fs_ctx *ctx, double *avg_ms /* host */, int64_t *launches /* host */,
+                          double *pairs_per_launch /* host */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASHSINK_H */

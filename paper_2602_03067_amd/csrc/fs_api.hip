@@ -1,0 +1,502 @@
+// C ABI of libflashsink: argument validation, workspace management and the
+// orchestration of the streaming passes.  All arithmetic of the method runs in
+// the kernels of fs_prep.hip / fs_lowd.hip / fs_f64.hip / fs_bf16.hip.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+
+#include <new>
+
+#include "fs_internal.h"
+
+namespace fs {
+
+fs_status fail(Ctx *c, fs_status s, const char *fmt, ...)
+{
+    if (c) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        c->err = buf;
+    }
+    return s;
+}
+
+void prof_begin(Ctx *c, double pairs)
+{
+    if (!c->prof_on) return;
+    if (c->ev_used + 2 > c->ev_pool.size()) {
+        for (int k = 0; k < 2; ++k) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return;
+            c->ev_pool.push_back(e);
+        }
+    }
+    (void)hipEventRecord(c->ev_pool[c->ev_used], c->stream);
+    c->prof_pairs += pairs;
+}
+
+void prof_end(Ctx *c)
+{
+    if (!c->prof_on || c->ev_used + 2 > c->ev_pool.size()) return;
+    (void)hipEventRecord(c->ev_pool[c->ev_used + 1], c->stream);
+    c->ev_used += 2;
+}
+
+namespace {
+
+Path choose_path(const fs_problem *p)
+{
+    if (p->compute == FS_COMPUTE_BF16_MFMA) return Path::BF16;
+    return p->d <= kLowdMaxD ? Path::LowD : Path::F64;
+}
+
+fs_status validate_problem(Ctx *c, const fs_problem *p)
+{
+    if (!c) return FS_ERR_INVALID_ARG;
+    c->err.clear();
+    if (!p) return fail(c, FS_ERR_INVALID_ARG, "problem is NULL");
+    if (!p->x || !p->y) return fail(c, FS_ERR_INVALID_ARG, "x or y is NULL");
+    if (p->dtype != FS_F32 && p->dtype != FS_BF16)
+        return fail(c, FS_ERR_INVALID_ARG, "unknown dtype %d", (int)p->dtype);
+    if (p->compute != FS_COMPUTE_FP32 && p->compute != FS_COMPUTE_BF16_MFMA)
+        return fail(c, FS_ERR_INVALID_ARG, "unknown compute mode %d", (int)p->compute);
+    if (p->n <= 0 || p->m <= 0 || p->d <= 0)
+        return fail(c, FS_ERR_BAD_SHAPE, "n, m, d must be positive (got %lld, %lld, %lld)",
+                    (long long)p->n, (long long)p->m, (long long)p->d);
+    if (p->n > (int64_t(1) << 24) || p->m > (int64_t(1) << 24) || p->d > 8192)
+        return fail(c, FS_ERR_BAD_SHAPE, "n, m <= 2^24 and d <= 8192 are supported");
+    if (p->ldx < p->d || p->ldy < p->d)
+        return fail(c, FS_ERR_BAD_SHAPE, "leading dimension smaller than d");
+    if (p->compute == FS_COMPUTE_BF16_MFMA && p->d < 16)
+        return fail(c, FS_ERR_UNSUPPORTED,
+                    "bf16 matrix-core mode needs d >= 16 (d = %lld is not a dense contraction)",
+                    (long long)p->d);
+    return FS_OK;
+}
+
+fs_status validate_eps(Ctx *c, float eps)
+{
+    if (!(eps > 0.0f) || !isfinite(eps)) return fail(c, FS_ERR_BAD_EPS, "eps must be positive and finite");
+    return FS_OK;
+}
+
+bool overlap(const void *p, size_t pb, const void *q, size_t qb)
+{
+    if (!p || !q) return false;
+    const char *a = (const char *)p, *b = (const char *)q;
+    return a < b + qb && b < a + pb;
+}
+
+size_t pts_bytes(const fs_problem *p, bool is_x)
+{
+    size_t es = p->dtype == FS_BF16 ? 2 : 4;
+    int64_t rows = is_x ? p->n : p->m;
+    int64_t ld = is_x ? p->ldx : p->ldy;
+    return (size_t)((rows - 1) * ld + p->d) * es;
+}
+
+// An output may not overlap x, y, a, b.
+fs_status check_out(Ctx *c, const fs_problem *p, const void *out, size_t bytes, const char *name)
+{
+    if (!out) return fail(c, FS_ERR_INVALID_ARG, "%s is NULL", name);
+    if (overlap(out, bytes, p->x, pts_bytes(p, true)) || overlap(out, bytes, p->y, pts_bytes(p, false)) ||
+        overlap(out, bytes, p->a, (size_t)p->n * 4) || overlap(out, bytes, p->b, (size_t)p->m * 4))
+        return fail(c, FS_ERR_INVALID_ARG, "%s overlaps an input of the problem", name);
+    return FS_OK;
+}
+
+double stage_eps(double e0, double e1, int stages, int s)
+{
+    if (stages <= 1 || s >= stages - 1) return (double)(float)e1;
+    if (s <= 0) return (double)(float)e0;
+    return (double)(float)(e0 * pow(e1 / e0, (double)s / (double)(stages - 1)));
+}
+
+int max_splits_for(const Ctx *c, Path path, int64_t n_res, int64_t n_str)
+{
+    (void)c;
+    (void)path;
+    (void)n_res;
+    (void)n_str;
+    return kMaxSplits;
+}
+
+// Lay the prepared problem out in the workspace; returns bytes needed.  With base == nullptr
+// only the size is computed.
+size_t layout(const Ctx *c, const fs_problem *p, Prepared *P, char *base, size_t extra)
+{
+    Arena A;
+    P->path = choose_path(p);
+    P->d = p->d;
+    auto side = [&](Side &S, int64_t cnt, const float *w) {
+        S.cnt = cnt;
+        S.w = w;
+        S.log_uniform = -log((double)cnt);
+        S.cnt_pad = round_up(cnt, 1024);
+        size_t o;
+        switch (P->path) {
+        case Path::LowD:
+            P->dp = (int)round_up(p->d + 1, 4);
+            o = A.take((size_t)S.cnt_pad * P->dp * 4);
+            S.packed = base ? (float *)(base + o) : nullptr;
+            break;
+        case Path::F64:
+            P->kp = (int)round_up(p->d, 4);
+            o = A.take((size_t)S.cnt_pad * P->kp * 8);
+            S.pts_d = base ? (double *)(base + o) : nullptr;
+            o = A.take((size_t)S.cnt_pad * 8);
+            S.bias_d = base ? (double *)(base + o) : nullptr;
+            break;
+        case Path::BF16:
+            P->kp = (int)round_up(p->d, 32);
+            o = A.take((size_t)S.cnt_pad * P->kp * 2);
+            S.pts_b = base ? (uint16_t *)(base + o) : nullptr;
+            o = A.take((size_t)S.cnt_pad * 4);
+            S.bias_f = base ? (float *)(base + o) : nullptr;
+            break;
+        }
+        o = A.take((size_t)S.cnt_pad * 8);
+        S.norm = base ? (double *)(base + o) : nullptr;
+        o = A.take((size_t)S.cnt_pad * 8);
+        S.pot = base ? (double *)(base + o) : nullptr;
+    };
+    side(P->X, p->n, p->a);
+    side(P->Y, p->m, p->b);
+    int64_t big = P->X.cnt_pad > P->Y.cnt_pad ? P->X.cnt_pad : P->Y.cnt_pad;
+    int ms = max_splits_for(c, P->path, p->n, p->m);
+    P->partial_bytes = (size_t)ms * big * 16;
+    size_t o = A.take(P->partial_bytes);
+    P->partial = base ? (void *)(base + o) : nullptr;
+    o = A.take((size_t)ceil_div(big, 256) * 8);
+    P->dev_part = base ? (double *)(base + o) : nullptr;
+    o = A.take(8 * 8);
+    P->scalars = base ? (double *)(base + o) : nullptr;
+    o = A.take((size_t)(256 + 1) * 16 * 8);
+    P->mean = base ? (double *)(base + o) : nullptr;
+    o = A.take(extra);
+    (void)o;
+    return A.off;
+}
+
+fs_status ensure_ws(Ctx *c, size_t need)
+{
+    if (need <= c->ws_bytes) return FS_OK;
+    FS_HIP(c, hipStreamSynchronize(c->stream));
+    if (c->ws) {
+        FS_HIP(c, hipFree(c->ws));
+        c->ws = nullptr;
+        c->ws_bytes = 0;
+    }
+    void *pnew = nullptr;
+    hipError_t e = hipMalloc(&pnew, need);
+    if (e != hipSuccess)
+        return fail(c, FS_ERR_ALLOC, "workspace of %zu bytes: %s", need, hipGetErrorString(e));
+    c->ws = (char *)pnew;
+    c->ws_bytes = need;
+    return FS_OK;
+}
+
+// Validate, size the workspace, lay the problem out and run the prologue kernels.
+// `extra` bytes are reserved after the prepared problem; *extra_ptr receives their address.
+fs_status prepare(Ctx *c, const fs_problem *p, Prepared *P, size_t extra, char **extra_ptr)
+{
+    if (c->device < 0) return fail(c, FS_ERR_DEVICE, "host-only context: arguments are valid, nothing was launched");
+    FS_HIP(c, hipSetDevice(c->device));
+    size_t need = layout(c, p, P, nullptr, extra);
+    fs_status st = ensure_ws(c, need);
+    if (st != FS_OK) return st;
+    layout(c, p, P, c->ws, extra);
+    if (extra_ptr) *extra_ptr = c->ws + (need - ((extra + 255) & ~size_t(255)));
+    return launch_prepare(c, p, P);
+}
+
+fs_status run_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits)
+{
+    switch (P->path) {
+    case Path::LowD: return lowd_lse(c, P, res, str, eps, splits);
+    case Path::F64: return f64_lse(c, P, res, str, eps, splits);
+    case Path::BF16: return bf16_lse(c, P, res, str, eps, splits);
+    }
+    return FS_ERR_UNSUPPORTED;
+}
+
+fs_status apply_common(Ctx *c, const fs_problem *prob, float eps, const float *f, const float *g,
+                       const float *V, int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass,
+                       bool transposed)
+{
+    fs_status st = validate_problem(c, prob);
+    if (st != FS_OK) return st;
+    if ((st = validate_eps(c, eps)) != FS_OK) return st;
+    if (!f || !g || !V) return fail(c, FS_ERR_INVALID_ARG, "f, g or the matrix to apply is NULL");
+    if (p <= 0 || p > 4096 || ldv < p || ldo < p) return fail(c, FS_ERR_BAD_SHAPE, "need 0 < p <= 4096, ld >= p");
+    int64_t out_rows = transposed ? prob->m : prob->n;
+    int64_t in_rows = transposed ? prob->n : prob->m;
+    if ((st = check_out(c, prob, out, (size_t)((out_rows - 1) * ldo + p) * 4, "out")) != FS_OK) return st;
+    if (mass && (st = check_out(c, prob, mass, (size_t)out_rows * 4, "mass output")) != FS_OK) return st;
+    if (overlap(out, (size_t)((out_rows - 1) * ldo + p) * 4, V, (size_t)((in_rows - 1) * ldv + p) * 4) ||
+        overlap(out, (size_t)((out_rows - 1) * ldo + p) * 4, f, (size_t)prob->n * 4) ||
+        overlap(out, (size_t)((out_rows - 1) * ldo + p) * 4, g, (size_t)prob->m * 4))
+        return fail(c, FS_ERR_INVALID_ARG, "out overlaps an input");
+    Prepared P;
+    int64_t n_res = transposed ? prob->m : prob->n;
+    int64_t n_str = transposed ? prob->n : prob->m;
+    size_t extra = 0;
+    switch (choose_path(prob)) {
+    case Path::LowD: extra = lowd_apply_ws(c, n_res, n_str, p); break;
+    case Path::F64: extra = f64_apply_ws(c, n_res, n_str, prob->d, p); break;
+    case Path::BF16:
+        return fail(c, FS_ERR_UNSUPPORTED, "plan application is not available in bf16 mode; use FS_COMPUTE_FP32");
+    }
+    if ((st = prepare(c, prob, &P, extra, &P.extra)) != FS_OK) return st;
+    P.extra_bytes = extra;
+    if ((st = launch_bias_from_user(c, &P, &P.X, f, eps)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps)) != FS_OK) return st;
+    Side *res = transposed ? &P.Y : &P.X;
+    Side *str = transposed ? &P.X : &P.Y;
+    switch (P.path) {
+    case Path::LowD: return lowd_apply(c, &P, res, str, eps, V, p, ldv, out, ldo, mass);
+    case Path::F64: return f64_apply(c, &P, res, str, eps, V, p, ldv, out, ldo, mass);
+    case Path::BF16: break;
+    }
+    return FS_ERR_UNSUPPORTED;
+}
+
+}  // namespace
+}  // namespace fs
+
+using namespace fs;
+
+extern "C" {
+
+const char *fs_version(void) { return "flashsink 0.1 gfx950"; }
+
+const char *fs_status_str(fs_status s)
+{
+    switch (s) {
+    case FS_OK: return "ok";
+    case FS_ERR_INVALID_ARG: return "invalid argument";
+    case FS_ERR_BAD_SHAPE: return "bad shape";
+    case FS_ERR_BAD_EPS: return "bad eps or iteration count";
+    case FS_ERR_BAD_WEIGHTS: return "bad weights";
+    case FS_ERR_UNSUPPORTED: return "unsupported";
+    case FS_ERR_ALLOC: return "device allocation failed";
+    case FS_ERR_DEVICE: return "device error";
+    }
+    return "unknown status";
+}
+
+const char *fs_last_error(const fs_ctx *ctx)
+{
+    return ctx ? reinterpret_cast<const Ctx *>(ctx)->err.c_str() : "";
+}
+
+fs_status fs_create(fs_ctx **ctx, int device, void *hip_stream)
+{
+    if (!ctx) return FS_ERR_INVALID_ARG;
+    *ctx = nullptr;
+    if (device == -1) {   // host-only context: argument validation works, nothing can be launched
+        Ctx *h = new (std::nothrow) Ctx;
+        if (!h) return FS_ERR_ALLOC;
+        h->device = -1;
+        *ctx = reinterpret_cast<fs_ctx *>(h);
+        return FS_OK;
+    }
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return FS_ERR_DEVICE;
+    if (hipSetDevice(device) != hipSuccess) return FS_ERR_DEVICE;
+    Ctx *c = new (std::nothrow) Ctx;
+    if (!c) return FS_ERR_ALLOC;
+    c->device = device;
+    c->stream = (hipStream_t)hip_stream;
+    int cu = 0;
+    if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cu > 0)
+        c->num_cu = cu;
+    *ctx = reinterpret_cast<fs_ctx *>(c);
+    return FS_OK;
+}
+
+fs_status fs_destroy(fs_ctx *ctx)
+{
+    if (!ctx) return FS_OK;
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    if (c->device >= 0) {
+        (void)hipSetDevice(c->device);
+        (void)hipStreamSynchronize(c->stream);
+        for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+        if (c->ws) (void)hipFree(c->ws);
+    }
+    delete c;
+    return FS_OK;
+}
+
+fs_status fs_row_norms(fs_ctx *ctx, const void *pts, int32_t dtype, int64_t rows, int64_t d, int64_t ld,
+                       float *out)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    if (!c) return FS_ERR_INVALID_ARG;
+    c->err.clear();
+    if (!pts || !out) return fail(c, FS_ERR_INVALID_ARG, "pts or out is NULL");
+    if (dtype != FS_F32 && dtype != FS_BF16) return fail(c, FS_ERR_INVALID_ARG, "unknown dtype");
+    if (rows <= 0 || d <= 0 || ld < d) return fail(c, FS_ERR_BAD_SHAPE, "rows, d must be positive and ld >= d");
+    size_t es = dtype == FS_BF16 ? 2 : 4;
+    if (overlap(out, (size_t)rows * 4, pts, (size_t)((rows - 1) * ld + d) * es))
+        return fail(c, FS_ERR_INVALID_ARG, "out overlaps pts");
+    if (c->device < 0) return fail(c, FS_ERR_DEVICE, "host-only context: arguments are valid, nothing was launched");
+    FS_HIP(c, hipSetDevice(c->device));
+    return launch_row_norms(c, pts, dtype, rows, d, ld, out);
+}
+
+fs_status fs_update_f(fs_ctx *ctx, const fs_problem *prob, float eps, const float *g, float *f_out)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    fs_status st = validate_problem(c, prob);
+    if (st != FS_OK) return st;
+    if ((st = validate_eps(c, eps)) != FS_OK) return st;
+    if (!g) return fail(c, FS_ERR_INVALID_ARG, "g is NULL");
+    if ((st = check_out(c, prob, f_out, (size_t)prob->n * 4, "f_out")) != FS_OK) return st;
+    if (overlap(f_out, (size_t)prob->n * 4, g, (size_t)prob->m * 4))
+        return fail(c, FS_ERR_INVALID_ARG, "f_out overlaps g");
+    Prepared P;
+    if ((st = prepare(c, prob, &P, 0, nullptr)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps)) != FS_OK) return st;
+    int splits = 1;
+    if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits)) != FS_OK) return st;
+    return launch_finalize(c, &P, &P.X, splits, eps, 0.0, f_out, nullptr);
+}
+
+fs_status fs_update_g(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, float *g_out)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    fs_status st = validate_problem(c, prob);
+    if (st != FS_OK) return st;
+    if ((st = validate_eps(c, eps)) != FS_OK) return st;
+    if (!f) return fail(c, FS_ERR_INVALID_ARG, "f is NULL");
+    if ((st = check_out(c, prob, g_out, (size_t)prob->m * 4, "g_out")) != FS_OK) return st;
+    if (overlap(g_out, (size_t)prob->m * 4, f, (size_t)prob->n * 4))
+        return fail(c, FS_ERR_INVALID_ARG, "g_out overlaps f");
+    Prepared P;
+    if ((st = prepare(c, prob, &P, 0, nullptr)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.X, f, eps)) != FS_OK) return st;
+    int splits = 1;
+    if ((st = run_lse(c, &P, &P.Y, &P.X, eps, &splits)) != FS_OK) return st;
+    return launch_finalize(c, &P, &P.Y, splits, eps, 0.0, g_out, nullptr);
+}
+
+fs_status fs_solve(fs_ctx *ctx, const fs_problem *prob, float eps_start, float eps_end, int32_t n_stages,
+                   int32_t iters_per_stage, float *f, float *g)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    fs_status st = validate_problem(c, prob);
+    if (st != FS_OK) return st;
+    if ((st = validate_eps(c, eps_end)) != FS_OK) return st;
+    if (n_stages < 1 || iters_per_stage < 0)
+        return fail(c, FS_ERR_BAD_EPS, "need n_stages >= 1 and iters_per_stage >= 0");
+    if (n_stages > 1 && (st = validate_eps(c, eps_start)) != FS_OK) return st;
+    if ((st = check_out(c, prob, f, (size_t)prob->n * 4, "f")) != FS_OK) return st;
+    if ((st = check_out(c, prob, g, (size_t)prob->m * 4, "g")) != FS_OK) return st;
+    if (overlap(f, (size_t)prob->n * 4, g, (size_t)prob->m * 4))
+        return fail(c, FS_ERR_INVALID_ARG, "f overlaps g");
+    if (iters_per_stage == 0) return c->device < 0 ? fail(c, FS_ERR_DEVICE, "host-only context") : FS_OK;
+
+    Prepared P;
+    if ((st = prepare(c, prob, &P, 0, nullptr)) != FS_OK) return st;
+    double eps0 = stage_eps(eps_start, eps_end, n_stages, 0);
+    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps0)) != FS_OK) return st;
+    for (int s = 0; s < n_stages; ++s) {
+        double eps = stage_eps(eps_start, eps_end, n_stages, s);
+        for (int t = 0; t < iters_per_stage; ++t) {
+            bool last = (s == n_stages - 1) && (t == iters_per_stage - 1);
+            double eps_next = eps;
+            if (t == iters_per_stage - 1 && !last) eps_next = stage_eps(eps_start, eps_end, n_stages, s + 1);
+            int splits = 1;
+            // Alg. 1: f from g
+            if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits)) != FS_OK) return st;
+            if ((st = launch_finalize(c, &P, &P.X, splits, eps, eps, last ? f : nullptr, nullptr)) != FS_OK)
+                return st;
+            // Alg. 3: g from the new f
+            if ((st = run_lse(c, &P, &P.Y, &P.X, eps, &splits)) != FS_OK) return st;
+            if ((st = launch_finalize(c, &P, &P.Y, splits, eps, last ? 0.0 : eps_next, last ? g : nullptr,
+                                      nullptr)) != FS_OK)
+                return st;
+        }
+    }
+    return FS_OK;
+}
+
+fs_status fs_marginal_err(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, const float *g,
+                          float *err_row_l1, float *err_col_l1)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    fs_status st = validate_problem(c, prob);
+    if (st != FS_OK) return st;
+    if ((st = validate_eps(c, eps)) != FS_OK) return st;
+    if (!f || !g) return fail(c, FS_ERR_INVALID_ARG, "f or g is NULL");
+    Prepared P;
+    if ((st = prepare(c, prob, &P, 0, nullptr)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.X, f, eps)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps)) != FS_OK) return st;
+    if ((st = launch_fill_f64(c, P.scalars, 0.0, 8)) != FS_OK) return st;
+    int splits = 1;
+    if (err_row_l1) {
+        if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits)) != FS_OK) return st;
+        if ((st = launch_finalize(c, &P, &P.X, splits, eps, 0.0, nullptr, P.scalars + 0)) != FS_OK) return st;
+    }
+    if (err_col_l1) {
+        if ((st = run_lse(c, &P, &P.Y, &P.X, eps, &splits)) != FS_OK) return st;
+        if ((st = launch_finalize(c, &P, &P.Y, splits, eps, 0.0, nullptr, P.scalars + 1)) != FS_OK) return st;
+    }
+    double host[2] = {0.0, 0.0};
+    FS_HIP(c, hipMemcpyAsync(host, P.scalars, sizeof host, hipMemcpyDeviceToHost, c->stream));
+    FS_HIP(c, hipStreamSynchronize(c->stream));
+    if (err_row_l1) *err_row_l1 = (float)host[0];
+    if (err_col_l1) *err_col_l1 = (float)host[1];
+    return FS_OK;
+}
+
+fs_status fs_apply_plan(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, const float *g,
+                        const float *V, int64_t p, int64_t ldv, float *out, int64_t ldo, float *r_out)
+{
+    return apply_common(reinterpret_cast<Ctx *>(ctx), prob, eps, f, g, V, p, ldv, out, ldo, r_out, false);
+}
+
+fs_status fs_apply_plan_T(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, const float *g,
+                          const float *U, int64_t p, int64_t ldu, float *out, int64_t ldo, float *c_out)
+{
+    return apply_common(reinterpret_cast<Ctx *>(ctx), prob, eps, f, g, U, p, ldu, out, ldo, c_out, true);
+}
+
+fs_status fs_profile_enable(fs_ctx *ctx, int32_t on)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    if (!c) return FS_ERR_INVALID_ARG;
+    c->prof_on = on != 0;
+    return FS_OK;
+}
+
+fs_status fs_profile_read(fs_ctx *ctx, double *avg_ms, int64_t *launches, double *pairs_per_launch)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    if (!c) return FS_ERR_INVALID_ARG;
+    if (c->device < 0) return fail(c, FS_ERR_DEVICE, "host-only context");
+    FS_HIP(c, hipStreamSynchronize(c->stream));
+    double total = 0.0;
+    int64_t cnt = 0;
+    for (size_t k = 0; k + 1 < c->ev_used; k += 2) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, c->ev_pool[k], c->ev_pool[k + 1]) == hipSuccess) {
+            total += ms;
+            ++cnt;
+        }
+    }
+    if (avg_ms) *avg_ms = cnt ? total / (double)cnt : 0.0;
+    if (launches) *launches = cnt;
+    if (pairs_per_launch) *pairs_per_launch = cnt ? c->prof_pairs / (double)cnt : 0.0;
+    c->ev_used = 0;
+    c->prof_pairs = 0.0;
+    return FS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,149 @@
+// Internal declarations shared by the translation units of libflashsink.
+// Nothing here is part of the C ABI (see include/flashsink.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "flashsink.h"
+
+namespace fs {
+
+// ---------------------------------------------------------------------------------------
+// constants
+// ---------------------------------------------------------------------------------------
+constexpr double kLog2e = 1.4426950408889634074;   // log2(e)
+constexpr double kLn2 = 0.69314718055994530942;    // ln(2)
+constexpr float kNegInit = -3.0e38f;               // finite "-inf" seed of the running max
+constexpr int kLowdMaxD = 16;                      // d <= 16: fp32 vector-ALU path
+constexpr int kMaxSplits = 64;                     // max column splits of one streaming pass
+
+enum class Path { LowD, F64, BF16 };
+
+// ---------------------------------------------------------------------------------------
+// context
+// ---------------------------------------------------------------------------------------
+struct Ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    int num_cu = 256;
+    // grow-only device workspace
+    char *ws = nullptr;
+    size_t ws_bytes = 0;
+    std::string err;
+    // profiling of the streaming LSE launches
+    bool prof_on = false;
+    std::vector<hipEvent_t> ev_pool;   // pairs (start, stop)
+    size_t ev_used = 0;
+    double prof_pairs = 0.0;           // pair evaluations summed over recorded launches
+};
+
+fs_status fail(Ctx *c, fs_status s, const char *fmt, ...);
+
+#define FS_HIP(ctx, expr)                                                                     \
+    do {                                                                                      \
+        hipError_t e__ = (expr);                                                              \
+        if (e__ != hipSuccess)                                                                \
+            return fs::fail((ctx), FS_ERR_DEVICE, "%s failed: %s", #expr, hipGetErrorString(e__)); \
+    } while (0)
+
+// Linear sub-allocator over the workspace (256-byte aligned pieces).
+struct Arena {
+    size_t off = 0;
+    size_t take(size_t bytes)
+    {
+        size_t o = off;
+        off += (bytes + 255) & ~size_t(255);
+        return o;
+    }
+};
+
+inline int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
+inline int64_t ceil_div(int64_t v, int64_t q) { return (v + q - 1) / q; }
+
+// ---------------------------------------------------------------------------------------
+// One side (x or y) of a prepared problem: the derived copy the kernels read, its squared
+// norms, the shifted potential and the bias it contributes when it is the streamed side.
+// ---------------------------------------------------------------------------------------
+struct Side {
+    int64_t cnt = 0;       // real points
+    int64_t cnt_pad = 0;   // rows of the derived copy (padding rows: zero coordinates, bias -inf)
+    const float *w = nullptr;   // weights (device) or nullptr = uniform
+    double log_uniform = 0.0;   // log(1/cnt)
+    // LowD: packed float [cnt_pad][dp], dp = round_up(d+1, 4); slot d holds the bias
+    float *packed = nullptr;
+    // F64: double [cnt_pad][kp], kp = round_up(d, 4), bias in bias_d[cnt_pad]
+    double *pts_d = nullptr;
+    double *bias_d = nullptr;
+    // BF16: uint16 [cnt_pad][kp], kp = round_up(d, 32), bias in bias_f[cnt_pad]
+    uint16_t *pts_b = nullptr;
+    float *bias_f = nullptr;
+    double *norm = nullptr;   // [cnt] squared norms of the derived points
+    double *pot = nullptr;    // [cnt] shifted potential (f - alpha or g - beta), float64
+};
+
+struct Prepared {
+    Path path = Path::LowD;
+    int64_t d = 0;
+    int dp = 0;   // LowD: floats per packed point
+    int kp = 0;   // F64 / BF16: padded contraction length
+    Side X, Y;
+    // partial reductions of a streaming pass: [splits][max(n,m)_pad] records
+    void *partial = nullptr;
+    size_t partial_bytes = 0;
+    double *dev_part = nullptr;  // [ceil(max(n,m)/256)] per-block sums of the marginal deviation
+    double *scalars = nullptr;   // [8] device doubles (marginal errors, centring sums...)
+    double *mean = nullptr;      // [kLowdMaxD] common mean (LowD)
+    char *extra = nullptr;       // entry-point specific scratch (plan application partials)
+    size_t extra_bytes = 0;
+};
+
+// ---------------------------------------------------------------------------------------
+// kernel launchers (implemented in the path-specific translation units)
+// ---------------------------------------------------------------------------------------
+
+// Launch-shape decision of one streaming pass.
+struct PassShape {
+    int rows_per_block = 0;
+    int row_blocks = 0;
+    int splits = 1;
+    int64_t cols_per_split = 0;   // multiple of the column tile
+};
+
+// fs_prep.hip
+fs_status launch_prepare(Ctx *c, const fs_problem *p, Prepared *P);
+fs_status launch_bias_from_user(Ctx *c, const Prepared *P, Side *side, const float *pot_user,
+                                double eps);
+fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, int splits, double eps_cur,
+                          double eps_next_bias, float *user_out, double *abs_dev_sum);
+fs_status launch_row_norms(Ctx *c, const void *pts, int dtype, int64_t rows, int64_t d, int64_t ld,
+                           float *out);
+fs_status launch_fill_f64(Ctx *c, double *dst, double v, int64_t cnt);
+
+// fs_lowd.hip
+PassShape lowd_shape(const Ctx *c, int64_t n_res, int64_t n_str);
+fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,
+                   int *splits_out);
+size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t p);
+fs_status lowd_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,
+                     const float *V, int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out);
+
+// fs_f64.hip
+fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,
+                  int *splits_out);
+size_t f64_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t d, int64_t p);
+fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,
+                    const float *V, int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out);
+
+// fs_bf16.hip
+fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,
+                   int *splits_out);
+
+// profiling helpers (fs_api.hip)
+void prof_begin(Ctx *c, double pairs);
+void prof_end(Ctx *c);
+
+}  // namespace fs

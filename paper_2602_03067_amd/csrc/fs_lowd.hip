@@ -1,0 +1,352 @@
+// Low-dimension (d <= 16) streaming passes on the fp32 vector ALU.
+//
+// With three coordinates there is no dense contraction to give to the matrix
+// cores: a score costs d FMAs and the pass is bound by the exp2 rate.  Mapping:
+// every lane owns R resident rows (their pre-scaled coordinates and the running
+// (max, sum) live in registers, so the row reduction never crosses lanes); the
+// streamed points are staged in LDS in tiles of 256, packed as
+// (coord_0..coord_{d-1}, bias) so that one broadcast ds_read_b128 serves all 64
+// lanes of a wave and all R rows of a lane.
+//
+// Scores are in base 2:  s_ij = (2 log2e / eps) <x_i, y_j> + bias_j  (Alg. 1, line "score tile
+// + bias", times log2 e), so exp and log are single v_exp_f32 / v_log_f32 instructions.
+// The online LSE of Alg. 1 is applied per register chunk of T columns.
+#include "fs_internal.h"
+
+namespace fs {
+namespace {
+
+constexpr int kBlock = 256;   // threads per workgroup
+constexpr int kTJ = 256;      // streamed points per LDS tile
+constexpr int kT = 8;         // columns per register chunk
+
+__device__ inline float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
+
+template <int D, int R>
+__global__ __launch_bounds__(kBlock) void k_lse_lowd(const float *__restrict__ res, const float *__restrict__ str,
+                                                     float cscale, int tiles_per_split, int n_tiles,
+                                                     double2 *__restrict__ partial, int64_t partial_stride)
+{
+    constexpr int DP = (D + 1 + 3) / 4 * 4;
+    constexpr int Q = DP / 4;               // float4 per packed point
+    __shared__ float4 tile[2][kTJ * Q];
+
+    const int tid = threadIdx.x;
+    const int64_t row0 = (int64_t)blockIdx.x * (kBlock * R);
+
+    float xs[R][D];
+    float mrun[R], srun[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const float *px = res + (row0 + r * kBlock + tid) * DP;
+#pragma unroll
+        for (int k = 0; k < D; ++k) xs[r][k] = px[k] * cscale;
+        mrun[r] = kNegInit;
+        srun[r] = 0.0f;
+    }
+
+    const int t_begin = blockIdx.y * tiles_per_split;
+    const int t_end = min(n_tiles, t_begin + tiles_per_split);
+    const float4 *gsrc = reinterpret_cast<const float4 *>(str);
+
+    float4 pre[Q];
+    if (t_begin < t_end) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q) pre[q] = gsrc[(int64_t)t_begin * (kTJ * Q) + q * kBlock + tid];
+#pragma unroll
+        for (int q = 0; q < Q; ++q) tile[0][q * kBlock + tid] = pre[q];
+    }
+    __syncthreads();
+
+    int buf = 0;
+    for (int t = t_begin; t < t_end; ++t) {
+        const bool more = (t + 1 < t_end);
+        if (more) {
+#pragma unroll
+            for (int q = 0; q < Q; ++q) pre[q] = gsrc[(int64_t)(t + 1) * (kTJ * Q) + q * kBlock + tid];
+        }
+        const float4 *tl = tile[buf];
+#pragma unroll 2
+        for (int j = 0; j < kTJ; j += kT) {
+            float sc[R][kT];
+#pragma unroll
+            for (int c = 0; c < kT; ++c) {
+                float yv[DP];
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    float4 v = tl[(j + c) * Q + q];
+                    yv[4 * q + 0] = v.x;
+                    yv[4 * q + 1] = v.y;
+                    yv[4 * q + 2] = v.z;
+                    yv[4 * q + 3] = v.w;
+                }
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    float acc = yv[D];   // bias
+#pragma unroll
+                    for (int k = 0; k < D; ++k) acc = fmaf(xs[r][k], yv[k], acc);
+                    sc[r][c] = acc;
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                float mnew = mrun[r];
+#pragma unroll
+                for (int c = 0; c < kT; c += 2) mnew = fmaxf(mnew, fmaxf(sc[r][c], sc[r][c + 1]));
+                float acc = srun[r] * fast_exp2(mrun[r] - mnew);
+#pragma unroll
+                for (int c = 0; c < kT; ++c) acc += fast_exp2(sc[r][c] - mnew);
+                srun[r] = acc;
+                mrun[r] = mnew;
+            }
+        }
+        if (more) {
+#pragma unroll
+            for (int q = 0; q < Q; ++q) tile[buf ^ 1][q * kBlock + tid] = pre[q];
+        }
+        __syncthreads();
+        buf ^= 1;
+    }
+
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int64_t row = row0 + r * kBlock + tid;
+        partial[(int64_t)blockIdx.y * partial_stride + row] = make_double2((double)mrun[r], (double)srun[r]);
+    }
+}
+
+// ---- plan application (Alg. 2 / Alg. 4): the same pass with a value accumulator ----------
+// Every lane owns ONE resident row and PC columns of the output; the streamed tile carries
+// the PC values of each streamed point next to its coordinates.
+template <int D, int PC>
+__global__ __launch_bounds__(kBlock) void k_apply_lowd(const float *__restrict__ res, const float *__restrict__ str,
+                                                       const float *__restrict__ V, int64_t ldv, int p0, int p,
+                                                       int64_t n_str, float cscale, int tiles_per_split, int n_tiles,
+                                                       double2 *__restrict__ partial, int64_t partial_stride,
+                                                       float *__restrict__ opart, int64_t opart_stride)
+{
+    constexpr int DP = (D + 1 + 3) / 4 * 4;
+    constexpr int Q = DP / 4;
+    __shared__ float4 tile[kTJ * Q];
+    __shared__ float vt[kTJ][PC];
+
+    const int tid = threadIdx.x;
+    const int64_t row = (int64_t)blockIdx.x * kBlock + tid;
+
+    float xs[D];
+    {
+        const float *px = res + row * DP;
+#pragma unroll
+        for (int k = 0; k < D; ++k) xs[k] = px[k] * cscale;
+    }
+    float mrun = kNegInit, srun = 0.0f;
+    float O[PC];
+#pragma unroll
+    for (int c = 0; c < PC; ++c) O[c] = 0.0f;
+
+    const int t_begin = blockIdx.y * tiles_per_split;
+    const int t_end = min(n_tiles, t_begin + tiles_per_split);
+    const float4 *gsrc = reinterpret_cast<const float4 *>(str);
+
+    for (int t = t_begin; t < t_end; ++t) {
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < Q; ++q) tile[q * kBlock + tid] = gsrc[(int64_t)t * (kTJ * Q) + q * kBlock + tid];
+        {
+            int64_t j = (int64_t)t * kTJ + tid;
+#pragma unroll
+            for (int c = 0; c < PC; ++c) vt[tid][c] = (j < n_str && p0 + c < p) ? V[j * ldv + p0 + c] : 0.0f;
+        }
+        __syncthreads();
+        for (int j = 0; j < kTJ; j += kT) {
+            float sc[kT];
+#pragma unroll
+            for (int c = 0; c < kT; ++c) {
+                float yv[DP];
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    float4 v = tile[(j + c) * Q + q];
+                    yv[4 * q + 0] = v.x;
+                    yv[4 * q + 1] = v.y;
+                    yv[4 * q + 2] = v.z;
+                    yv[4 * q + 3] = v.w;
+                }
+                float acc = yv[D];
+#pragma unroll
+                for (int k = 0; k < D; ++k) acc = fmaf(xs[k], yv[k], acc);
+                sc[c] = acc;
+            }
+            float mnew = mrun;
+#pragma unroll
+            for (int c = 0; c < kT; ++c) mnew = fmaxf(mnew, sc[c]);
+            float scale = fast_exp2(mrun - mnew);
+            srun *= scale;
+#pragma unroll
+            for (int c = 0; c < PC; ++c) O[c] *= scale;
+#pragma unroll
+            for (int c = 0; c < kT; ++c) {
+                float e = fast_exp2(sc[c] - mnew);
+                srun += e;
+#pragma unroll
+                for (int q = 0; q < PC; ++q) O[q] = fmaf(e, vt[j + c][q], O[q]);
+            }
+            mrun = mnew;
+        }
+    }
+    partial[(int64_t)blockIdx.y * partial_stride + row] = make_double2((double)mrun, (double)srun);
+#pragma unroll
+    for (int c = 0; c < PC; ++c) opart[((int64_t)blockIdx.y * opart_stride + row) * PC + c] = O[c];
+}
+
+// merge the splits of an application pass and apply the epilogue of Alg. 2:
+//   out_i = w_i * exp(pot_i/eps + LSEmax) * O_i   with everything in base 2;  mass_i = same with s.
+__global__ void k_apply_finalize(const double2 *partial, int64_t stride, const float *opart, int64_t opart_stride,
+                                 int PC, int splits, int64_t cnt, double inv_eps, const float *w, double log_uniform,
+                                 const double *pot, int p0, int p, float *out, int64_t ldo, float *mass_out)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= cnt) return;
+    double M = -INFINITY;
+    for (int k = 0; k < splits; ++k) {
+        double mk = partial[(int64_t)k * stride + i].x;
+        M = mk > M ? mk : M;
+    }
+    double lw = w ? log((double)w[i]) : log_uniform;
+    // row factor  a_i * exp(fhat_i/eps + m_i): add the exponents BEFORE exponentiating
+    double fac = exp2((pot[i] * inv_eps + lw) * kLog2e + M);
+    double S = 0.0;
+    for (int c = 0; c < PC; ++c) {
+        if (p0 + c >= p) break;
+        double acc = 0.0;
+        for (int k = 0; k < splits; ++k) {
+            double2 ms = partial[(int64_t)k * stride + i];
+            acc += exp2(ms.x - M) * (double)opart[((int64_t)k * opart_stride + i) * PC + c];
+        }
+        out[i * ldo + p0 + c] = (float)(fac * acc);
+    }
+    if (mass_out && p0 == 0) {
+        for (int k = 0; k < splits; ++k) {
+            double2 ms = partial[(int64_t)k * stride + i];
+            S += exp2(ms.x - M) * ms.y;
+        }
+        mass_out[i] = (float)(fac * S);
+    }
+}
+
+constexpr int kApplyPC = 4;   // output columns per application pass
+
+template <int D>
+void launch_lse_d(int R, dim3 grid, hipStream_t st, const float *res, const float *str, float cscale, int tps,
+                  int n_tiles, double2 *partial, int64_t stride)
+{
+    switch (R) {
+    case 4: hipLaunchKernelGGL((k_lse_lowd<D, 4>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride); break;
+    case 2: hipLaunchKernelGGL((k_lse_lowd<D, 2>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride); break;
+    default: hipLaunchKernelGGL((k_lse_lowd<D, 1>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride); break;
+    }
+}
+
+#define FS_LOWD_DISPATCH(D_, CALL)                                                                       \
+    switch (D_) {                                                                                        \
+    case 1: { constexpr int DD = 1; CALL; } break;   case 2: { constexpr int DD = 2; CALL; } break;     \
+    case 3: { constexpr int DD = 3; CALL; } break;   case 4: { constexpr int DD = 4; CALL; } break;     \
+    case 5: { constexpr int DD = 5; CALL; } break;   case 6: { constexpr int DD = 6; CALL; } break;     \
+    case 7: { constexpr int DD = 7; CALL; } break;   case 8: { constexpr int DD = 8; CALL; } break;     \
+    case 9: { constexpr int DD = 9; CALL; } break;   case 10: { constexpr int DD = 10; CALL; } break;   \
+    case 11: { constexpr int DD = 11; CALL; } break; case 12: { constexpr int DD = 12; CALL; } break;   \
+    case 13: { constexpr int DD = 13; CALL; } break; case 14: { constexpr int DD = 14; CALL; } break;   \
+    case 15: { constexpr int DD = 15; CALL; } break; default: { constexpr int DD = 16; CALL; } break;   \
+    }
+
+}  // namespace
+
+PassShape lowd_shape(const Ctx *c, int64_t n_res, int64_t n_str)
+{
+    PassShape s;
+    int R = n_res >= 131072 ? 4 : (n_res >= 16384 ? 2 : 1);
+    s.rows_per_block = kBlock * R;
+    s.row_blocks = (int)ceil_div(n_res, s.rows_per_block);
+    int n_tiles = (int)ceil_div(n_str, kTJ);
+    int target = 4 * c->num_cu;
+    int splits = (int)ceil_div(target, s.row_blocks);
+    if (splits > n_tiles) splits = n_tiles;
+    if (splits > kMaxSplits) splits = kMaxSplits;
+    if (splits < 1) splits = 1;
+    int tps = (int)ceil_div(n_tiles, splits);
+    s.splits = (int)ceil_div(n_tiles, tps);
+    s.cols_per_split = (int64_t)tps * kTJ;
+    return s;
+}
+
+fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out)
+{
+    PassShape s = lowd_shape(c, res->cnt, str->cnt);
+    const int R = s.rows_per_block / kBlock;
+    const int n_tiles = (int)ceil_div(str->cnt, kTJ);
+    const int tps = (int)(s.cols_per_split / kTJ);
+    // host-side shape checks: every access of the kernel stays inside the padded copies
+    if ((int64_t)s.row_blocks * s.rows_per_block > res->cnt_pad || (int64_t)n_tiles * kTJ > str->cnt_pad ||
+        (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes)
+        return fail(c, FS_ERR_DEVICE, "internal: low-d launch shape exceeds the padded buffers");
+    const float cscale = (float)(2.0 * kLog2e / eps);
+    dim3 grid((unsigned)s.row_blocks, (unsigned)s.splits);
+    prof_begin(c, (double)res->cnt * (double)str->cnt);
+    FS_LOWD_DISPATCH((int)P->d, launch_lse_d<DD>(R, grid, c->stream, res->packed, str->packed, cscale, tps, n_tiles,
+                                                 (double2 *)P->partial, res->cnt_pad));
+    prof_end(c);
+    FS_HIP(c, hipGetLastError());
+    *splits_out = s.splits;
+    return FS_OK;
+}
+
+static PassShape apply_shape(const Ctx *c, int64_t n_res, int64_t n_str)
+{
+    PassShape s;
+    s.rows_per_block = kBlock;
+    s.row_blocks = (int)ceil_div(n_res, kBlock);
+    int n_tiles = (int)ceil_div(n_str, kTJ);
+    int target = 4 * c->num_cu;
+    int splits = (int)ceil_div(target, s.row_blocks);
+    if (splits > n_tiles) splits = n_tiles;
+    if (splits > kMaxSplits) splits = kMaxSplits;
+    if (splits < 1) splits = 1;
+    int tps = (int)ceil_div(n_tiles, splits);
+    s.splits = (int)ceil_div(n_tiles, tps);
+    s.cols_per_split = (int64_t)tps * kTJ;
+    return s;
+}
+
+size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t p)
+{
+    (void)p;
+    PassShape s = apply_shape(c, n_res, n_str);
+    return (size_t)s.splits * (size_t)round_up(n_res, 1024) * kApplyPC * 4;
+}
+
+fs_status lowd_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, const float *V,
+                     int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out)
+{
+    PassShape s = apply_shape(c, res->cnt, str->cnt);
+    const int n_tiles = (int)ceil_div(str->cnt, kTJ);
+    const int tps = (int)(s.cols_per_split / kTJ);
+    if ((int64_t)s.row_blocks * kBlock > res->cnt_pad || (int64_t)n_tiles * kTJ > str->cnt_pad ||
+        (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes ||
+        (size_t)s.splits * res->cnt_pad * kApplyPC * 4 > P->extra_bytes)
+        return fail(c, FS_ERR_DEVICE, "internal: low-d apply launch shape exceeds the padded buffers");
+    const float cscale = (float)(2.0 * kLog2e / eps);
+    dim3 grid((unsigned)s.row_blocks, (unsigned)s.splits);
+    float *opart = (float *)P->extra;
+    for (int p0 = 0; p0 < p; p0 += kApplyPC) {
+        FS_LOWD_DISPATCH((int)P->d,
+                         hipLaunchKernelGGL((k_apply_lowd<DD, kApplyPC>), grid, dim3(kBlock), 0, c->stream, res->packed,
+                                            str->packed, V, ldv, p0, (int)p, str->cnt, cscale, tps, n_tiles,
+                                            (double2 *)P->partial, res->cnt_pad, opart, res->cnt_pad));
+        hipLaunchKernelGGL(k_apply_finalize, dim3((unsigned)ceil_div(res->cnt, 256)), dim3(256), 0, c->stream,
+                           (const double2 *)P->partial, res->cnt_pad, opart, res->cnt_pad, kApplyPC, s.splits, res->cnt,
+                           1.0 / eps, res->w, res->log_uniform, res->pot, p0, (int)p, out, ldo, mass_out);
+    }
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
+}  // namespace fs

@@ -1,0 +1,317 @@
+// O(n d) kernels around the streaming passes: derived copies of the point
+// clouds and their squared norms (Prop. 1: alpha, beta), the per-point bias
+// (Alg. 1, "precompute bias"), and the merge of the per-split LSE statistics into
+// the new shifted potential.
+#include "fs_internal.h"
+
+namespace fs {
+namespace {
+
+__device__ inline float bf16_to_float(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// round-to-nearest-even float -> bfloat16 bits (NaN kept quiet)
+__device__ inline uint16_t float_to_bf16(float v)
+{
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ inline float load_pt(const void *pts, int dtype, int64_t idx)
+{
+    return dtype == FS_BF16 ? bf16_to_float(((const uint16_t *)pts)[idx]) : ((const float *)pts)[idx];
+}
+
+// block-wide sum of one double per thread (blockDim.x == 256); result valid in thread 0
+__device__ inline double block_sum_256(double v, double *sh)
+{
+    sh[threadIdx.x] = v;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) sh[threadIdx.x] += sh[threadIdx.x + s];
+        __syncthreads();
+    }
+    return sh[0];
+}
+
+__global__ void k_fill_f64(double *dst, double v, int64_t cnt)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < cnt) dst[i] = v;
+}
+
+// ---- squared row norms, float64 accumulation --------------------------------------------
+__global__ void k_row_norms(const void *pts, int dtype, int64_t rows, int64_t d, int64_t ld, float *out)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows) return;
+    double s = 0.0;
+    for (int64_t k = 0; k < d; ++k) {
+        double v = (double)load_pt(pts, dtype, i * ld + k);
+        s += v * v;
+    }
+    out[i] = (float)s;
+}
+
+// ---- common mean of both clouds (low-d path), deterministic two-stage reduction ---------
+// stage 1: block b writes the coordinate sums of its slice to part[b][0..15]
+__global__ __launch_bounds__(256) void k_coord_sums(const void *pts, int dtype, int64_t rows, int d, int64_t ld,
+                                                    double *part)
+{
+    __shared__ double sh[256];
+    double acc[kLowdMaxD];
+    for (int k = 0; k < kLowdMaxD; ++k) acc[k] = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < rows; i += (int64_t)gridDim.x * 256)
+        for (int k = 0; k < d; ++k) acc[k] += (double)load_pt(pts, dtype, i * ld + k);
+    for (int k = 0; k < kLowdMaxD; ++k) {
+        double t = block_sum_256(acc[k], sh);
+        if (threadIdx.x == 0) part[(int64_t)blockIdx.x * kLowdMaxD + k] = t;
+        __syncthreads();
+    }
+}
+
+// stage 2: mean[k] = (sum of partX[.][k] + sum of partY[.][k]) / (n + m), one thread per coordinate
+__global__ void k_mean_final(const double *partX, const double *partY, int blocks, double inv_cnt, double *mean)
+{
+    int k = threadIdx.x;
+    if (k >= kLowdMaxD) return;
+    double s = 0.0;
+    for (int b = 0; b < blocks; ++b) s += partX[(int64_t)b * kLowdMaxD + k];
+    for (int b = 0; b < blocks; ++b) s += partY[(int64_t)b * kLowdMaxD + k];
+    mean[k] = s * inv_cnt;
+}
+
+// ---- low-d derived copy: centred float coordinates, packed with a bias slot -------------
+__global__ void k_prep_lowd(const void *pts, int dtype, int64_t cnt, int64_t cnt_pad, int d, int64_t ld, int dp,
+                            const double *mean, float *packed, double *norm)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= cnt_pad) return;
+    float *o = packed + i * dp;
+    double nrm = 0.0;
+    for (int k = 0; k < dp; ++k) {
+        float v = 0.0f;
+        if (i < cnt && k < d) {
+            v = (float)((double)load_pt(pts, dtype, i * ld + k) - mean[k]);
+            nrm += (double)v * (double)v;
+        }
+        o[k] = v;
+    }
+    o[d] = -INFINITY;   // bias slot: padding rows never contribute; real rows are set per half-step
+    norm[i] = nrm;
+}
+
+// ---- float64 derived copy (fp64 matrix-core path) ----------------------------------------
+__global__ void k_prep_f64(const void *pts, int dtype, int64_t cnt, int64_t cnt_pad, int64_t d, int64_t ld, int kp,
+                           double *out, double *bias, double *norm)
+{
+    // one wave-sized group of 64 threads per row, strided over the coordinates
+    int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    int lane = threadIdx.x & 63;
+    if (row >= cnt_pad) return;
+    double nrm = 0.0;
+    for (int k = lane; k < kp; k += 64) {
+        double v = 0.0;
+        if (row < cnt && k < d) v = (double)load_pt(pts, dtype, row * ld + k);
+        out[row * kp + k] = v;
+        nrm += v * v;
+    }
+    for (int off = 32; off > 0; off >>= 1) nrm += __shfl_xor(nrm, off, 64);
+    if (lane == 0) {
+        norm[row] = nrm;
+        bias[row] = -INFINITY;
+    }
+}
+
+// ---- bfloat16 derived copy (bf16 matrix-core path); norms of the ROUNDED points ----------
+__global__ void k_prep_bf16(const void *pts, int dtype, int64_t cnt, int64_t cnt_pad, int64_t d, int64_t ld, int kp,
+                            uint16_t *out, float *bias, double *norm)
+{
+    int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    int lane = threadIdx.x & 63;
+    if (row >= cnt_pad) return;
+    double nrm = 0.0;
+    for (int k = lane; k < kp; k += 64) {
+        uint16_t h = 0;
+        if (row < cnt && k < d) {
+            h = dtype == FS_BF16 ? ((const uint16_t *)pts)[row * ld + k]
+                                 : float_to_bf16(((const float *)pts)[row * ld + k]);
+            double v = (double)bf16_to_float(h);
+            nrm += v * v;
+        }
+        out[row * kp + k] = h;
+    }
+    for (int off = 32; off > 0; off >>= 1) nrm += __shfl_xor(nrm, off, 64);
+    if (lane == 0) {
+        norm[row] = nrm;
+        bias[row] = -INFINITY;
+    }
+}
+
+// Where the bias of point i of a side lives, by path.
+struct BiasSink {
+    float *packed;   // LowD: packed[i*dp + d]
+    int dp, d;
+    float *bias_f;   // BF16
+    double *bias_d;  // F64
+};
+
+__device__ inline void store_bias(const BiasSink &s, int64_t i, double bias2)
+{
+    if (s.packed) s.packed[i * s.dp + s.d] = (float)bias2;
+    if (s.bias_f) s.bias_f[i] = (float)bias2;
+    if (s.bias_d) s.bias_d[i] = bias2;
+}
+
+// bias in base-2 units of a streamed point:  ((pot_shifted)/eps + log w) * log2(e)
+// (Alg. 1: (ghat_j + delta_j)/eps with delta = eps*log b)
+__device__ inline double bias2_of(double pot_shifted, double inv_eps, const float *w, double log_uniform, int64_t i)
+{
+    double lw = w ? log((double)w[i]) : log_uniform;
+    return (pot_shifted * inv_eps + lw) * kLog2e;
+}
+
+// ---- shifted potential + bias from a user potential (unshifted, float) -------------------
+__global__ void k_bias_from_user(const float *pot_user, const double *norm, int64_t cnt, double inv_eps,
+                                 const float *w, double log_uniform, double *pot, BiasSink sink)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= cnt) return;
+    double ps = (double)pot_user[i] - norm[i];   // fhat = f - alpha, ghat = g - beta (Prop. 1)
+    pot[i] = ps;
+    store_bias(sink, i, bias2_of(ps, inv_eps, w, log_uniform, i));
+}
+
+// ---- merge the per-split (max, sum) statistics of a streaming pass -----------------------
+//   LSE_2 = M + log2(sum_k s_k 2^(m_k - M)),  pot_new = -eps * ln2 * LSE_2      (Alg. 1, last lines)
+// and, as asked: store pot_new, the bias for the pass that streams this side next, the
+// unshifted potential for the caller, or the marginal deviation |w e^((pot_old-pot_new)/eps) - w|.
+__global__ __launch_bounds__(256) void k_finalize(const double2 *partial, int64_t stride, int splits, int64_t cnt,
+                                                  double eps, double inv_eps_next, const float *w,
+                                                  double log_uniform, const double *norm, double *pot,
+                                                  BiasSink sink, float *user_out, double *dev_part)
+{
+    __shared__ double sh[256];
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    double dev = 0.0;
+    if (i < cnt) {
+        double M = -INFINITY;
+        for (int k = 0; k < splits; ++k) {
+            double mk = partial[(int64_t)k * stride + i].x;
+            M = mk > M ? mk : M;
+        }
+        double S = 0.0;
+        for (int k = 0; k < splits; ++k) {
+            double2 ms = partial[(int64_t)k * stride + i];
+            S += ms.y * exp2(ms.x - M);
+        }
+        double pot_new = -eps * kLn2 * (M + log2(S));
+        if (dev_part) {
+            double wi = w ? (double)w[i] : exp(log_uniform);
+            dev = fabs(wi * exp((pot[i] - pot_new) / eps) - wi);   // Prop. 3: r = a exp((fhat - fhat+)/eps)
+        } else {
+            pot[i] = pot_new;
+            if (inv_eps_next > 0.0) store_bias(sink, i, bias2_of(pot_new, inv_eps_next, w, log_uniform, i));
+            if (user_out) user_out[i] = (float)(pot_new + norm[i]);
+        }
+    }
+    if (dev_part) {
+        double t = block_sum_256(dev, sh);
+        if (threadIdx.x == 0) dev_part[blockIdx.x] = t;
+    }
+}
+
+// sum of `cnt` doubles by one block, fixed order
+__global__ __launch_bounds__(256) void k_sum_to(const double *part, int64_t cnt, double *dst)
+{
+    __shared__ double sh[256];
+    double acc = 0.0;
+    for (int64_t i = threadIdx.x; i < cnt; i += 256) acc += part[i];
+    double t = block_sum_256(acc, sh);
+    if (threadIdx.x == 0) *dst = t;
+}
+
+BiasSink sink_of(const Prepared *P, const Side *s)
+{
+    BiasSink k{};
+    k.packed = s->packed;
+    k.dp = P->dp;
+    k.d = (int)P->d;
+    k.bias_f = s->bias_f;
+    k.bias_d = s->bias_d;
+    return k;
+}
+
+}  // namespace
+
+fs_status launch_fill_f64(Ctx *c, double *dst, double v, int64_t cnt)
+{
+    hipLaunchKernelGGL(k_fill_f64, dim3((unsigned)ceil_div(cnt, 256)), dim3(256), 0, c->stream, dst, v, cnt);
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
+fs_status launch_row_norms(Ctx *c, const void *pts, int dtype, int64_t rows, int64_t d, int64_t ld, float *out)
+{
+    hipLaunchKernelGGL(k_row_norms, dim3((unsigned)ceil_div(rows, 256)), dim3(256), 0, c->stream, pts, dtype, rows, d,
+                       ld, out);
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
+fs_status launch_prepare(Ctx *c, const fs_problem *p, Prepared *P)
+{
+    const int dtype = p->dtype;
+    struct In { const void *pts; int64_t ld; Side *S; };
+    In in[2] = {{p->x, p->ldx, &P->X}, {p->y, p->ldy, &P->Y}};
+    if (P->path == Path::LowD) {
+        // the reserved area holds 16 doubles (mean) + 2 x 128 x 16 doubles (per-block sums of x, of y)
+        const int half = 128;
+        double *partX = P->mean + kLowdMaxD;
+        double *partY = partX + (size_t)half * kLowdMaxD;
+        hipLaunchKernelGGL(k_coord_sums, dim3(half), dim3(256), 0, c->stream, p->x, dtype, p->n, (int)p->d, p->ldx,
+                           partX);
+        hipLaunchKernelGGL(k_coord_sums, dim3(half), dim3(256), 0, c->stream, p->y, dtype, p->m, (int)p->d, p->ldy,
+                           partY);
+        hipLaunchKernelGGL(k_mean_final, dim3(1), dim3(64), 0, c->stream, partX, partY, half,
+                           1.0 / (double)(p->n + p->m), P->mean);
+        for (auto &s : in)
+            hipLaunchKernelGGL(k_prep_lowd, dim3((unsigned)ceil_div(s.S->cnt_pad, 256)), dim3(256), 0, c->stream, s.pts,
+                               dtype, s.S->cnt, s.S->cnt_pad, (int)p->d, s.ld, P->dp, P->mean, s.S->packed, s.S->norm);
+    } else if (P->path == Path::F64) {
+        for (auto &s : in)
+            hipLaunchKernelGGL(k_prep_f64, dim3((unsigned)ceil_div(s.S->cnt_pad, 4)), dim3(256), 0, c->stream, s.pts,
+                               dtype, s.S->cnt, s.S->cnt_pad, p->d, s.ld, P->kp, s.S->pts_d, s.S->bias_d, s.S->norm);
+    } else {
+        for (auto &s : in)
+            hipLaunchKernelGGL(k_prep_bf16, dim3((unsigned)ceil_div(s.S->cnt_pad, 4)), dim3(256), 0, c->stream, s.pts,
+                               dtype, s.S->cnt, s.S->cnt_pad, p->d, s.ld, P->kp, s.S->pts_b, s.S->bias_f, s.S->norm);
+    }
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
+fs_status launch_bias_from_user(Ctx *c, const Prepared *P, Side *side, const float *pot_user, double eps)
+{
+    hipLaunchKernelGGL(k_bias_from_user, dim3((unsigned)ceil_div(side->cnt, 256)), dim3(256), 0, c->stream, pot_user,
+                       side->norm, side->cnt, 1.0 / eps, side->w, side->log_uniform, side->pot, sink_of(P, side));
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
+fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, int splits, double eps_cur, double eps_next_bias,
+                          float *user_out, double *abs_dev_sum)
+{
+    const unsigned blocks = (unsigned)ceil_div(res->cnt, 256);
+    double *dev_part = abs_dev_sum ? P->dev_part : nullptr;   // per-block sums of the marginal deviation
+    hipLaunchKernelGGL(k_finalize, dim3(blocks), dim3(256), 0, c->stream, (const double2 *)P->partial, res->cnt_pad,
+                       splits, res->cnt, eps_cur, eps_next_bias > 0.0 ? 1.0 / eps_next_bias : 0.0, res->w,
+                       res->log_uniform, res->norm, res->pot, sink_of(P, res), user_out, dev_part);
+    if (abs_dev_sum)
+        hipLaunchKernelGGL(k_sum_to, dim3(1), dim3(256), 0, c->stream, dev_part, (int64_t)blocks, abs_dev_sum);
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
+}  // namespace fs

@@ -1,0 +1,135 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header
+declares, and validates arguments on the host (through a host-only context)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2602_03067_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return binding.load_library()
+
+
+@pytest.fixture()
+def hctx(lib):
+    h = ctypes.c_void_p()
+    assert lib.fs_create(ctypes.byref(h), -1, None) == 0
+    yield h
+    lib.fs_destroy(h)
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "flashsink.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fs_[a-z_A-Z0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    for required in ("fs_row_norms", "fs_update_f", "fs_update_g", "fs_solve", "fs_marginal_err",
+                     "fs_apply_plan", "fs_apply_plan_T"):
+        assert required in names
+    for name in names:
+        assert hasattr(lib, name), name
+    assert set(names) == set(binding.EXPORTS)
+    assert lib.fs_version().decode().startswith("flashsink")
+
+
+def _prob(**kw):
+    base = dict(x=4096, y=8192, dtype=0, compute=0, n=10, m=12, d=3, ldx=3, ldy=3, a=None, b=None)
+    base.update(kw)
+    return binding.FsProblem(base["x"], base["y"], base["dtype"], base["compute"], base["n"],
+                             base["m"], base["d"], base["ldx"], base["ldy"], base["a"], base["b"])
+
+
+F = ctypes.c_float
+P = ctypes.c_void_p
+
+
+def test_status_strings(lib):
+    seen = {lib.fs_status_str(s).decode() for s in range(8)}
+    assert len(seen) == 8 and "ok" in seen
+
+
+def test_valid_arguments_reach_the_device_stage(lib, hctx):
+    p = _prob()
+    st = lib.fs_update_f(hctx, ctypes.byref(p), F(0.1), P(1 << 20), P(1 << 21))
+    assert st == 7 and b"host-only" in lib.fs_last_error(hctx)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(x=None), 1), (dict(y=None), 1), (dict(dtype=5), 1), (dict(compute=9), 1),
+    (dict(n=0), 2), (dict(m=-3), 2), (dict(d=0), 2), (dict(ldx=2), 2), (dict(ldy=1), 2),
+    (dict(n=(1 << 24) + 1), 2), (dict(d=9000, ldx=9000, ldy=9000), 2),
+    (dict(compute=1, d=8, ldx=8, ldy=8), 5),
+])
+def test_problem_validation(lib, hctx, kw, status):
+    p = _prob(**kw)
+    assert lib.fs_update_f(hctx, ctypes.byref(p), F(0.1), P(1 << 20), P(1 << 21)) == status
+    assert lib.fs_last_error(hctx) != b""
+    assert lib.fs_solve(hctx, ctypes.byref(p), F(0.1), F(0.1), 1, 1, P(1 << 21), P(1 << 20)) == status
+
+
+@pytest.mark.parametrize("eps", [0.0, -1.0, float("nan"), float("inf")])
+def test_eps_validation(lib, hctx, eps):
+    p = _prob()
+    assert lib.fs_update_f(hctx, ctypes.byref(p), F(eps), P(1 << 20), P(1 << 21)) == 3
+    assert lib.fs_update_g(hctx, ctypes.byref(p), F(eps), P(1 << 20), P(1 << 21)) == 3
+    assert lib.fs_solve(hctx, ctypes.byref(p), F(1.0), F(eps), 1, 1, P(1 << 21), P(1 << 20)) == 3
+    assert lib.fs_solve(hctx, ctypes.byref(p), F(eps), F(0.1), 3, 1, P(1 << 21), P(1 << 20)) == 3
+    e = F()
+    assert lib.fs_marginal_err(hctx, ctypes.byref(p), F(eps), P(1 << 21), P(1 << 20),
+                               ctypes.byref(e), ctypes.byref(e)) == 3
+
+
+def test_solve_count_validation(lib, hctx):
+    p = _prob()
+    assert lib.fs_solve(hctx, ctypes.byref(p), F(1.0), F(0.1), 0, 1, P(1 << 21), P(1 << 20)) == 3
+    assert lib.fs_solve(hctx, ctypes.byref(p), F(1.0), F(0.1), 1, -1, P(1 << 21), P(1 << 20)) == 3
+
+
+def test_null_and_aliasing(lib, hctx):
+    p = _prob()
+    assert lib.fs_update_f(hctx, ctypes.byref(p), F(0.1), None, P(1 << 21)) == 1
+    assert lib.fs_update_f(hctx, ctypes.byref(p), F(0.1), P(1 << 20), None) == 1
+    assert lib.fs_update_f(hctx, None, F(0.1), P(1 << 20), P(1 << 21)) == 1
+    # output on top of x, and on top of the input potential
+    assert lib.fs_update_f(hctx, ctypes.byref(p), F(0.1), P(1 << 20), P(4096 + 8)) == 1
+    assert lib.fs_update_f(hctx, ctypes.byref(p), F(0.1), P(1 << 20), P((1 << 20) + 4)) == 1
+    assert lib.fs_solve(hctx, ctypes.byref(p), F(0.1), F(0.1), 1, 1, P(1 << 21), P((1 << 21) + 8)) == 1
+    assert lib.fs_update_f(None, ctypes.byref(p), F(0.1), P(1 << 20), P(1 << 21)) == 1
+
+
+def test_apply_validation(lib, hctx):
+    p = _prob()
+    args = lambda pp, ldv, ldo, out=1 << 22: (hctx, ctypes.byref(p), F(0.1), P(1 << 21), P(1 << 20),
+                                              P(1 << 23), pp, ldv, P(out), ldo, None)
+    assert lib.fs_apply_plan(*args(0, 4, 4)) == 2
+    assert lib.fs_apply_plan(*args(4, 3, 4)) == 2
+    assert lib.fs_apply_plan_T(*args(4, 4, 2)) == 2
+    assert lib.fs_apply_plan(*args(4, 4, 4, out=1 << 23)) == 1     # out aliases V
+    assert lib.fs_apply_plan(*args(4, 4, 4)) == 7                  # valid: reaches device stage
+
+
+def test_row_norms_validation(lib, hctx):
+    assert lib.fs_row_norms(hctx, None, 0, 4, 3, 3, P(1 << 20)) == 1
+    assert lib.fs_row_norms(hctx, P(4096), 0, 0, 3, 3, P(1 << 20)) == 2
+    assert lib.fs_row_norms(hctx, P(4096), 0, 4, 3, 2, P(1 << 20)) == 2
+    assert lib.fs_row_norms(hctx, P(4096), 0, 4, 3, 3, P(4100)) == 1
+    assert lib.fs_row_norms(hctx, P(4096), 0, 4, 3, 3, P(1 << 20)) == 7
+
+
+def test_no_gpu_means_loud_failure(lib):
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    h = ctypes.c_void_p()
+    assert lib.fs_create(ctypes.byref(h), 0, None) == 7
+    with pytest.raises(RuntimeError):
+        binding.Context(0)
