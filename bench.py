@@ -21,10 +21,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# MI355X: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = fp32 vector-ALU issue slots per second.
-# (The published 157.3 TFLOP/s fp32 vector peak is this number x 2 flop (FMA) x 2 (packed
-# fp32, which this GPU pool requires to be switched off).)
-VALU_LANE_SLOTS_PER_S = 256 * 4 * 16 * 2.4e9
+# MI355X fp32 vector peak: 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz = 78.64e12 lane-operations
+# per second (x 2 flop per FMA = the published 157.3 TFLOP/s).
+VALU_LANE_SLOTS_PER_S = 256 * 4 * 32 * 2.4e9
 PEAKS = {"bf16": 2.5e15, "f64": 78.6e12}
 
 
@@ -143,7 +142,7 @@ def main() -> int:
     # ---- the float64 oracle on the host cores, on a bounded sample -------------------------
     if not args.no_cpu_baseline:
         import oracle
-        R = max(1, min(w.n, w.m, int(2.0e9 / max(w.n, w.m) / max(1.0, w.d / 8.0))))
+        R = max(1, min(w.n, w.m, int(1.2e10 / max(w.n, w.m) / max(1.0, w.d / 8.0))))
         rows = np.arange(R)
         gz = np.zeros(w.m)
         fz = np.zeros(w.n)

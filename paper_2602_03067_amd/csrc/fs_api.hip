@@ -140,8 +140,13 @@ size_t layout(const Ctx *c, const fs_problem *p, Prepared *P, char *base, size_t
         switch (P->path) {
         case Path::LowD:
             P->dp = (int)round_up(p->d + 1, 4);
+            P->dpd = (int)round_up(p->d + 1, 2);
             o = A.take((size_t)S.cnt_pad * P->dp * 4);
             S.packed = base ? (float *)(base + o) : nullptr;
+            o = A.take((size_t)S.cnt_pad * P->dpd * 8);
+            S.packed_d = base ? (double *)(base + o) : nullptr;
+            o = A.take((size_t)S.cnt_pad * 8);
+            S.norm_f = base ? (double *)(base + o) : nullptr;
             break;
         case Path::F64:
             P->kp = (int)round_up(p->d, 4);
@@ -211,6 +216,14 @@ fs_status prepare(Ctx *c, const fs_problem *p, Prepared *P, size_t extra, char *
     layout(c, p, P, c->ws, extra);
     if (extra_ptr) *extra_ptr = c->ws + (need - ((extra + 255) & ~size_t(255)));
     return launch_prepare(c, p, P);
+}
+
+// merge the splits of the pass that just ran over `res` (see launch_finalize)
+fs_status finalize(Ctx *c, const Prepared *P, Side *res, int splits, double eps, double eps_next_bias, float *user_out,
+                   double *abs_dev_sum)
+{
+    const double *nrm = (P->path == Path::LowD && !lowd_precise(P, eps)) ? res->norm_f : res->norm;
+    return launch_finalize(c, P, res, nrm, splits, eps, eps_next_bias, user_out, abs_dev_sum);
 }
 
 fs_status run_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits)
@@ -364,7 +377,7 @@ fs_status fs_update_f(fs_ctx *ctx, const fs_problem *prob, float eps, const floa
     if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps)) != FS_OK) return st;
     int splits = 1;
     if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits)) != FS_OK) return st;
-    return launch_finalize(c, &P, &P.X, splits, eps, 0.0, f_out, nullptr);
+    return finalize(c, &P, &P.X, splits, eps, 0.0, f_out, nullptr);
 }
 
 fs_status fs_update_g(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, float *g_out)
@@ -382,7 +395,7 @@ fs_status fs_update_g(fs_ctx *ctx, const fs_problem *prob, float eps, const floa
     if ((st = launch_bias_from_user(c, &P, &P.X, f, eps)) != FS_OK) return st;
     int splits = 1;
     if ((st = run_lse(c, &P, &P.Y, &P.X, eps, &splits)) != FS_OK) return st;
-    return launch_finalize(c, &P, &P.Y, splits, eps, 0.0, g_out, nullptr);
+    return finalize(c, &P, &P.Y, splits, eps, 0.0, g_out, nullptr);
 }
 
 fs_status fs_solve(fs_ctx *ctx, const fs_problem *prob, float eps_start, float eps_end, int32_t n_stages,
@@ -402,6 +415,7 @@ fs_status fs_solve(fs_ctx *ctx, const fs_problem *prob, float eps_start, float e
     if (iters_per_stage == 0) return c->device < 0 ? fail(c, FS_ERR_DEVICE, "host-only context") : FS_OK;
 
     Prepared P;
+    P.halfsteps_per_eps = 2 * iters_per_stage;
     if ((st = prepare(c, prob, &P, 0, nullptr)) != FS_OK) return st;
     double eps0 = stage_eps(eps_start, eps_end, n_stages, 0);
     if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps0)) != FS_OK) return st;
@@ -414,11 +428,11 @@ fs_status fs_solve(fs_ctx *ctx, const fs_problem *prob, float eps_start, float e
             int splits = 1;
             // Alg. 1: f from g
             if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits)) != FS_OK) return st;
-            if ((st = launch_finalize(c, &P, &P.X, splits, eps, eps, last ? f : nullptr, nullptr)) != FS_OK)
+            if ((st = finalize(c, &P, &P.X, splits, eps, eps, last ? f : nullptr, nullptr)) != FS_OK)
                 return st;
             // Alg. 3: g from the new f
             if ((st = run_lse(c, &P, &P.Y, &P.X, eps, &splits)) != FS_OK) return st;
-            if ((st = launch_finalize(c, &P, &P.Y, splits, eps, last ? 0.0 : eps_next, last ? g : nullptr,
+            if ((st = finalize(c, &P, &P.Y, splits, eps, last ? 0.0 : eps_next, last ? g : nullptr,
                                       nullptr)) != FS_OK)
                 return st;
         }
@@ -435,6 +449,7 @@ fs_status fs_marginal_err(fs_ctx *ctx, const fs_problem *prob, float eps, const 
     if ((st = validate_eps(c, eps)) != FS_OK) return st;
     if (!f || !g) return fail(c, FS_ERR_INVALID_ARG, "f or g is NULL");
     Prepared P;
+    P.force_precise = true;   // a measurement: always the accurate score arithmetic
     if ((st = prepare(c, prob, &P, 0, nullptr)) != FS_OK) return st;
     if ((st = launch_bias_from_user(c, &P, &P.X, f, eps)) != FS_OK) return st;
     if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps)) != FS_OK) return st;
@@ -442,11 +457,11 @@ fs_status fs_marginal_err(fs_ctx *ctx, const fs_problem *prob, float eps, const 
     int splits = 1;
     if (err_row_l1) {
         if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits)) != FS_OK) return st;
-        if ((st = launch_finalize(c, &P, &P.X, splits, eps, 0.0, nullptr, P.scalars + 0)) != FS_OK) return st;
+        if ((st = finalize(c, &P, &P.X, splits, eps, 0.0, nullptr, P.scalars + 0)) != FS_OK) return st;
     }
     if (err_col_l1) {
         if ((st = run_lse(c, &P, &P.Y, &P.X, eps, &splits)) != FS_OK) return st;
-        if ((st = launch_finalize(c, &P, &P.Y, splits, eps, 0.0, nullptr, P.scalars + 1)) != FS_OK) return st;
+        if ((st = finalize(c, &P, &P.Y, splits, eps, 0.0, nullptr, P.scalars + 1)) != FS_OK) return st;
     }
     double host[2] = {0.0, 0.0};
     FS_HIP(c, hipMemcpyAsync(host, P.scalars, sizeof host, hipMemcpyDeviceToHost, c->stream));

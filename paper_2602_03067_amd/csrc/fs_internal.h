@@ -73,22 +73,29 @@ struct Side {
     int64_t cnt_pad = 0;   // rows of the derived copy (padding rows: zero coordinates, bias -inf)
     const float *w = nullptr;   // weights (device) or nullptr = uniform
     double log_uniform = 0.0;   // log(1/cnt)
-    // LowD: packed float [cnt_pad][dp], dp = round_up(d+1, 4); slot d holds the bias
+    // LowD: packed [cnt_pad][dp] floats, dp = round_up(d+1, 4), and [cnt_pad][dpd] doubles,
+    // dpd = round_up(d+1, 2); slot d of each point holds its bias
     float *packed = nullptr;
+    double *packed_d = nullptr;
+    double *norm_f = nullptr;  // [cnt_pad] squared norms of the float-rounded centred points
     // F64: double [cnt_pad][kp], kp = round_up(d, 4), bias in bias_d[cnt_pad]
     double *pts_d = nullptr;
     double *bias_d = nullptr;
     // BF16: uint16 [cnt_pad][kp], kp = round_up(d, 32), bias in bias_f[cnt_pad]
     uint16_t *pts_b = nullptr;
     float *bias_f = nullptr;
-    double *norm = nullptr;   // [cnt] squared norms of the derived points
-    double *pot = nullptr;    // [cnt] shifted potential (f - alpha or g - beta), float64
+    double *norm = nullptr;   // [cnt_pad] squared norms of the derived points
+    double *pot = nullptr;    // [cnt_pad] UNSHIFTED potential (f or g) in float64
 };
 
 struct Prepared {
     Path path = Path::LowD;
     int64_t d = 0;
     int dp = 0;   // LowD: floats per packed point
+    int dpd = 0;  // LowD: doubles per packed point (float64 score mode)
+    double rho_max = 0.0;   // LowD: largest squared norm of a centred point (host copy)
+    int halfsteps_per_eps = 2;    // LowD: half-steps the caller runs at one eps (error budget)
+    bool force_precise = false;   // LowD: float64 scores regardless (marginal error evaluation)
     int kp = 0;   // F64 / BF16: padded contraction length
     Side X, Y;
     // partial reductions of a streaming pass: [splits][max(n,m)_pad] records
@@ -117,14 +124,17 @@ struct PassShape {
 fs_status launch_prepare(Ctx *c, const fs_problem *p, Prepared *P);
 fs_status launch_bias_from_user(Ctx *c, const Prepared *P, Side *side, const float *pot_user,
                                 double eps);
-fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, int splits, double eps_cur,
-                          double eps_next_bias, float *user_out, double *abs_dev_sum);
+// `res_norm` is the norm array matching the coordinates the pass used (Side::norm or norm_f).
+fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, const double *res_norm, int splits,
+                          double eps_cur, double eps_next_bias, float *user_out, double *abs_dev_sum);
 fs_status launch_row_norms(Ctx *c, const void *pts, int dtype, int64_t rows, int64_t d, int64_t ld,
                            float *out);
 fs_status launch_fill_f64(Ctx *c, double *dst, double v, int64_t cnt);
 
 // fs_lowd.hip
 PassShape lowd_shape(const Ctx *c, int64_t n_res, int64_t n_str);
+// true: this half-step runs the low-d pass with float64 scores (norm), false: float (norm_f)
+bool lowd_precise(const Prepared *P, double eps);
 fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,
                    int *splits_out);
 size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t p);

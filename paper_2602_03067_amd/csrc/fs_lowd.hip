@@ -1,17 +1,24 @@
-// Low-dimension (d <= 16) streaming passes on the fp32 vector ALU.
+// Low-dimension (d <= 16) streaming passes on the vector ALU.
 //
 // With three coordinates there is no dense contraction to give to the matrix
 // cores: a score costs d FMAs and the pass is bound by the exp2 rate.  Mapping:
 // every lane owns R resident rows (their pre-scaled coordinates and the running
 // (max, sum) live in registers, so the row reduction never crosses lanes); the
 // streamed points are staged in LDS in tiles of 256, packed as
-// (coord_0..coord_{d-1}, bias) so that one broadcast ds_read_b128 serves all 64
-// lanes of a wave and all R rows of a lane.
+// (coord_0..coord_{d-1}, bias), so that one broadcast LDS read serves all 64 lanes
+// of a wave and all R rows of a lane.
 //
 // Scores are in base 2:  s_ij = (2 log2e / eps) <x_i, y_j> + bias_j  (Alg. 1, line "score tile
 // + bias", times log2 e), so exp and log are single v_exp_f32 / v_log_f32 instructions.
-// The online LSE of Alg. 1 is applied per register chunk of T columns.
+// The online LSE of Alg. 1 is applied per register chunk of T columns; the running max is
+// kept integer-valued, so every rescale factor is an exact power of two.
+//
+// Score type S: float when (log2e/eps) * max|x|^2 is small enough for fp32 scores to hold the
+// 1e-4 target, double otherwise (a score of magnitude 500 has an fp32 ulp of 6e-5).  In both
+// cases the exponent s_ij - m is formed in S and only then rounded to float.
 #include "fs_internal.h"
+
+#include <stdlib.h>
 
 namespace fs {
 namespace {
@@ -22,34 +29,69 @@ constexpr int kT = 8;         // columns per register chunk
 
 __device__ inline float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
 
-template <int D, int R>
-__global__ __launch_bounds__(kBlock) void k_lse_lowd(const float *__restrict__ res, const float *__restrict__ str,
-                                                     float cscale, int tiles_per_split, int n_tiles,
-                                                     double2 *__restrict__ partial, int64_t partial_stride)
+template <typename S> struct Pack;   // how a point (d coords + bias) of type S is padded to 16-byte units
+template <> struct Pack<float> {
+    static constexpr int per16 = 4;
+};
+template <> struct Pack<double> {
+    static constexpr int per16 = 2;
+};
+
+// 16-byte unit as stored in LDS / loaded from global
+struct alignas(16) Unit {
+    uint32_t w[4];
+};
+
+template <typename S, int DP> __device__ inline void unpack(const Unit *u, S (&v)[DP])
 {
-    constexpr int DP = (D + 1 + 3) / 4 * 4;
-    constexpr int Q = DP / 4;               // float4 per packed point
-    __shared__ float4 tile[2][kTJ * Q];
+    constexpr int Q = DP / Pack<S>::per16;
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        Unit t = u[q];
+        if constexpr (sizeof(S) == 4) {
+            v[4 * q + 0] = __uint_as_float(t.w[0]);
+            v[4 * q + 1] = __uint_as_float(t.w[1]);
+            v[4 * q + 2] = __uint_as_float(t.w[2]);
+            v[4 * q + 3] = __uint_as_float(t.w[3]);
+        } else {
+            v[2 * q + 0] = __hiloint2double((int)t.w[1], (int)t.w[0]);
+            v[2 * q + 1] = __hiloint2double((int)t.w[3], (int)t.w[2]);
+        }
+    }
+}
+
+template <typename S, int D, int R>
+__global__ __launch_bounds__(kBlock) void k_lse_lowd(const S *__restrict__ res, const S *__restrict__ str, S cscale,
+                                                     int tiles_per_split, int n_tiles, double2 *__restrict__ partial,
+                                                     int64_t partial_stride)
+{
+    constexpr int P16 = Pack<S>::per16;
+    constexpr int DP = (D + 1 + P16 - 1) / P16 * P16;
+    constexpr int Q = DP / P16;               // 16-byte units per packed point
+    __shared__ Unit tile[2][kTJ * Q];
 
     const int tid = threadIdx.x;
     const int64_t row0 = (int64_t)blockIdx.x * (kBlock * R);
 
-    float xs[R][D];
-    float mrun[R], srun[R];
+    S xs[R][D];
+    // running max, running sum over finished tiles, and the sum inside the current tile: adding
+    // tile totals instead of single terms keeps the fp32 summation error at the 1e-6 level
+    float mrun[R], srun[R], stile[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const float *px = res + (row0 + r * kBlock + tid) * DP;
+        const S *px = res + (row0 + r * kBlock + tid) * DP;
 #pragma unroll
         for (int k = 0; k < D; ++k) xs[r][k] = px[k] * cscale;
         mrun[r] = kNegInit;
         srun[r] = 0.0f;
+        stile[r] = 0.0f;
     }
 
     const int t_begin = blockIdx.y * tiles_per_split;
     const int t_end = min(n_tiles, t_begin + tiles_per_split);
-    const float4 *gsrc = reinterpret_cast<const float4 *>(str);
+    const Unit *gsrc = reinterpret_cast<const Unit *>(str);
 
-    float4 pre[Q];
+    Unit pre[Q];
     if (t_begin < t_end) {
 #pragma unroll
         for (int q = 0; q < Q; ++q) pre[q] = gsrc[(int64_t)t_begin * (kTJ * Q) + q * kBlock + tid];
@@ -65,40 +107,43 @@ __global__ __launch_bounds__(kBlock) void k_lse_lowd(const float *__restrict__ r
 #pragma unroll
             for (int q = 0; q < Q; ++q) pre[q] = gsrc[(int64_t)(t + 1) * (kTJ * Q) + q * kBlock + tid];
         }
-        const float4 *tl = tile[buf];
-#pragma unroll 2
+        const Unit *tl = tile[buf];
+#pragma unroll 1
         for (int j = 0; j < kTJ; j += kT) {
-            float sc[R][kT];
+            S sc[R][kT];
 #pragma unroll
             for (int c = 0; c < kT; ++c) {
-                float yv[DP];
-#pragma unroll
-                for (int q = 0; q < Q; ++q) {
-                    float4 v = tl[(j + c) * Q + q];
-                    yv[4 * q + 0] = v.x;
-                    yv[4 * q + 1] = v.y;
-                    yv[4 * q + 2] = v.z;
-                    yv[4 * q + 3] = v.w;
-                }
+                S yv[DP];
+                unpack<S, DP>(tl + (j + c) * Q, yv);
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
-                    float acc = yv[D];   // bias
+                    S acc = yv[D];   // bias
 #pragma unroll
-                    for (int k = 0; k < D; ++k) acc = fmaf(xs[r][k], yv[k], acc);
+                    for (int k = 0; k < D; ++k) acc = xs[r][k] * yv[k] + acc;   // contracted to FMA
                     sc[r][c] = acc;
                 }
             }
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                float mnew = mrun[r];
+                float mx = (float)sc[r][0];
 #pragma unroll
-                for (int c = 0; c < kT; c += 2) mnew = fmaxf(mnew, fmaxf(sc[r][c], sc[r][c + 1]));
-                float acc = srun[r] * fast_exp2(mrun[r] - mnew);
+                for (int c = 1; c < kT; ++c) mx = fmaxf(mx, (float)sc[r][c]);
+                // integer-valued running max: rescale factors are exact powers of two
+                float mnew = fmaxf(mrun[r], ceilf(mx));
+                float scale = fast_exp2(mrun[r] - mnew);
+                const S mS = (S)mnew;
+                float csum = fast_exp2((float)(sc[r][0] - mS));
 #pragma unroll
-                for (int c = 0; c < kT; ++c) acc += fast_exp2(sc[r][c] - mnew);
-                srun[r] = acc;
+                for (int c = 1; c < kT; ++c) csum += fast_exp2((float)(sc[r][c] - mS));
+                srun[r] *= scale;
+                stile[r] = fmaf(stile[r], scale, csum);
                 mrun[r] = mnew;
             }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            srun[r] += stile[r];
+            stile[r] = 0.0f;
         }
         if (more) {
 #pragma unroll
@@ -118,24 +163,25 @@ __global__ __launch_bounds__(kBlock) void k_lse_lowd(const float *__restrict__ r
 // ---- plan application (Alg. 2 / Alg. 4): the same pass with a value accumulator ----------
 // Every lane owns ONE resident row and PC columns of the output; the streamed tile carries
 // the PC values of each streamed point next to its coordinates.
-template <int D, int PC>
-__global__ __launch_bounds__(kBlock) void k_apply_lowd(const float *__restrict__ res, const float *__restrict__ str,
+template <typename S, int D, int PC>
+__global__ __launch_bounds__(kBlock) void k_apply_lowd(const S *__restrict__ res, const S *__restrict__ str,
                                                        const float *__restrict__ V, int64_t ldv, int p0, int p,
-                                                       int64_t n_str, float cscale, int tiles_per_split, int n_tiles,
+                                                       int64_t n_str, S cscale, int tiles_per_split, int n_tiles,
                                                        double2 *__restrict__ partial, int64_t partial_stride,
                                                        float *__restrict__ opart, int64_t opart_stride)
 {
-    constexpr int DP = (D + 1 + 3) / 4 * 4;
-    constexpr int Q = DP / 4;
-    __shared__ float4 tile[kTJ * Q];
+    constexpr int P16 = Pack<S>::per16;
+    constexpr int DP = (D + 1 + P16 - 1) / P16 * P16;
+    constexpr int Q = DP / P16;
+    __shared__ Unit tile[kTJ * Q];
     __shared__ float vt[kTJ][PC];
 
     const int tid = threadIdx.x;
     const int64_t row = (int64_t)blockIdx.x * kBlock + tid;
 
-    float xs[D];
+    S xs[D];
     {
-        const float *px = res + row * DP;
+        const S *px = res + row * DP;
 #pragma unroll
         for (int k = 0; k < D; ++k) xs[k] = px[k] * cscale;
     }
@@ -146,7 +192,7 @@ __global__ __launch_bounds__(kBlock) void k_apply_lowd(const float *__restrict__
 
     const int t_begin = blockIdx.y * tiles_per_split;
     const int t_end = min(n_tiles, t_begin + tiles_per_split);
-    const float4 *gsrc = reinterpret_cast<const float4 *>(str);
+    const Unit *gsrc = reinterpret_cast<const Unit *>(str);
 
     for (int t = t_begin; t < t_end; ++t) {
         __syncthreads();
@@ -158,34 +204,30 @@ __global__ __launch_bounds__(kBlock) void k_apply_lowd(const float *__restrict__
             for (int c = 0; c < PC; ++c) vt[tid][c] = (j < n_str && p0 + c < p) ? V[j * ldv + p0 + c] : 0.0f;
         }
         __syncthreads();
+#pragma unroll 1
         for (int j = 0; j < kTJ; j += kT) {
-            float sc[kT];
+            S sc[kT];
 #pragma unroll
             for (int c = 0; c < kT; ++c) {
-                float yv[DP];
+                S yv[DP];
+                unpack<S, DP>(tile + (j + c) * Q, yv);
+                S acc = yv[D];
 #pragma unroll
-                for (int q = 0; q < Q; ++q) {
-                    float4 v = tile[(j + c) * Q + q];
-                    yv[4 * q + 0] = v.x;
-                    yv[4 * q + 1] = v.y;
-                    yv[4 * q + 2] = v.z;
-                    yv[4 * q + 3] = v.w;
-                }
-                float acc = yv[D];
-#pragma unroll
-                for (int k = 0; k < D; ++k) acc = fmaf(xs[k], yv[k], acc);
+                for (int k = 0; k < D; ++k) acc = xs[k] * yv[k] + acc;
                 sc[c] = acc;
             }
-            float mnew = mrun;
+            float mx = (float)sc[0];
 #pragma unroll
-            for (int c = 0; c < kT; ++c) mnew = fmaxf(mnew, sc[c]);
+            for (int c = 1; c < kT; ++c) mx = fmaxf(mx, (float)sc[c]);
+            float mnew = fmaxf(mrun, ceilf(mx));
             float scale = fast_exp2(mrun - mnew);
             srun *= scale;
 #pragma unroll
             for (int c = 0; c < PC; ++c) O[c] *= scale;
+            const S mS = (S)mnew;
 #pragma unroll
             for (int c = 0; c < kT; ++c) {
-                float e = fast_exp2(sc[c] - mnew);
+                float e = fast_exp2((float)(sc[c] - mS));
                 srun += e;
 #pragma unroll
                 for (int q = 0; q < PC; ++q) O[q] = fmaf(e, vt[j + c][q], O[q]);
@@ -199,10 +241,11 @@ __global__ __launch_bounds__(kBlock) void k_apply_lowd(const float *__restrict__
 }
 
 // merge the splits of an application pass and apply the epilogue of Alg. 2:
-//   out_i = w_i * exp(pot_i/eps + LSEmax) * O_i   with everything in base 2;  mass_i = same with s.
+//   out_i = a_i * exp(fhat_i/eps + m_i) * O_i   with everything in base 2;  mass_i = same with s.
 __global__ void k_apply_finalize(const double2 *partial, int64_t stride, const float *opart, int64_t opart_stride,
                                  int PC, int splits, int64_t cnt, double inv_eps, const float *w, double log_uniform,
-                                 const double *pot, int p0, int p, float *out, int64_t ldo, float *mass_out)
+                                 const double *pot, const double *res_norm, int p0, int p, float *out, int64_t ldo,
+                                 float *mass_out)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= cnt) return;
@@ -213,8 +256,7 @@ __global__ void k_apply_finalize(const double2 *partial, int64_t stride, const f
     }
     double lw = w ? log((double)w[i]) : log_uniform;
     // row factor  a_i * exp(fhat_i/eps + m_i): add the exponents BEFORE exponentiating
-    double fac = exp2((pot[i] * inv_eps + lw) * kLog2e + M);
-    double S = 0.0;
+    double fac = exp2(((pot[i] - res_norm[i]) * inv_eps + lw) * kLog2e + M);
     for (int c = 0; c < PC; ++c) {
         if (p0 + c >= p) break;
         double acc = 0.0;
@@ -225,6 +267,7 @@ __global__ void k_apply_finalize(const double2 *partial, int64_t stride, const f
         out[i * ldo + p0 + c] = (float)(fac * acc);
     }
     if (mass_out && p0 == 0) {
+        double S = 0.0;
         for (int k = 0; k < splits; ++k) {
             double2 ms = partial[(int64_t)k * stride + i];
             S += exp2(ms.x - M) * ms.y;
@@ -235,15 +278,23 @@ __global__ void k_apply_finalize(const double2 *partial, int64_t stride, const f
 
 constexpr int kApplyPC = 4;   // output columns per application pass
 
-template <int D>
-void launch_lse_d(int R, dim3 grid, hipStream_t st, const float *res, const float *str, float cscale, int tps,
-                  int n_tiles, double2 *partial, int64_t stride)
+template <typename S, int D>
+void launch_lse_d(int R, dim3 grid, hipStream_t st, const S *res, const S *str, S cscale, int tps, int n_tiles,
+                  double2 *partial, int64_t stride)
 {
     switch (R) {
-    case 4: hipLaunchKernelGGL((k_lse_lowd<D, 4>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride); break;
-    case 2: hipLaunchKernelGGL((k_lse_lowd<D, 2>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride); break;
-    default: hipLaunchKernelGGL((k_lse_lowd<D, 1>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride); break;
+    case 4: hipLaunchKernelGGL((k_lse_lowd<S, D, 4>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride); break;
+    case 2: hipLaunchKernelGGL((k_lse_lowd<S, D, 2>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride); break;
+    default: hipLaunchKernelGGL((k_lse_lowd<S, D, 1>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride); break;
     }
+}
+
+template <typename S, int D>
+void launch_apply_d(dim3 grid, hipStream_t st, const S *res, const S *str, const float *V, int64_t ldv, int p0, int p,
+                    int64_t n_str, S cscale, int tps, int n_tiles, double2 *partial, int64_t stride, float *opart)
+{
+    hipLaunchKernelGGL((k_apply_lowd<S, D, kApplyPC>), grid, dim3(kBlock), 0, st, res, str, V, ldv, p0, p, n_str, cscale,
+                       tps, n_tiles, partial, stride, opart, stride);
 }
 
 #define FS_LOWD_DISPATCH(D_, CALL)                                                                       \
@@ -258,12 +309,9 @@ void launch_lse_d(int R, dim3 grid, hipStream_t st, const float *res, const floa
     case 15: { constexpr int DD = 15; CALL; } break; default: { constexpr int DD = 16; CALL; } break;   \
     }
 
-}  // namespace
-
-PassShape lowd_shape(const Ctx *c, int64_t n_res, int64_t n_str)
+PassShape shape_for(const Ctx *c, int64_t n_res, int64_t n_str, int R)
 {
     PassShape s;
-    int R = n_res >= 131072 ? 4 : (n_res >= 16384 ? 2 : 1);
     s.rows_per_block = kBlock * R;
     s.row_blocks = (int)ceil_div(n_res, s.rows_per_block);
     int n_tiles = (int)ceil_div(n_str, kTJ);
@@ -278,6 +326,30 @@ PassShape lowd_shape(const Ctx *c, int64_t n_res, int64_t n_str)
     return s;
 }
 
+}  // namespace
+
+// Score precision of a half-step.  An fp32 score carries roundings of relative size 2^-24 at
+// magnitude Mag = 2 k rho_max (k = log2e/eps, rho_max = largest squared norm after centring);
+// measured against the float64 reference, a run of T half-steps at one eps accumulates about
+// 0.05 * T * 2^-24 * Mag in units of eps.  fp32 scores are used while that estimate stays
+// below 1.5e-5, i.e. Mag * T <= 5000; otherwise the scores are formed in float64.
+// FS_LOWD_SCORE=f32|f64 overrides the choice (experiments and tests only).
+bool lowd_precise(const Prepared *P, double eps)
+{
+    static const char *force = getenv("FS_LOWD_SCORE");
+    if (force && force[0] == 'f' && force[1] == '3') return false;
+    if (force && force[0] == 'f' && force[1] == '6') return true;
+    if (P->force_precise) return true;
+    const double k = kLog2e / eps;
+    return 2.0 * k * P->rho_max * (double)(P->halfsteps_per_eps > 0 ? P->halfsteps_per_eps : 1) > 5000.0;
+}
+
+PassShape lowd_shape(const Ctx *c, int64_t n_res, int64_t n_str)
+{
+    int R = n_res >= 131072 ? 4 : (n_res >= 16384 ? 2 : 1);
+    return shape_for(c, n_res, n_str, R);
+}
+
 fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out)
 {
     PassShape s = lowd_shape(c, res->cnt, str->cnt);
@@ -288,62 +360,58 @@ fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
     if ((int64_t)s.row_blocks * s.rows_per_block > res->cnt_pad || (int64_t)n_tiles * kTJ > str->cnt_pad ||
         (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes)
         return fail(c, FS_ERR_DEVICE, "internal: low-d launch shape exceeds the padded buffers");
-    const float cscale = (float)(2.0 * kLog2e / eps);
+    const double cscale = 2.0 * kLog2e / eps;
     dim3 grid((unsigned)s.row_blocks, (unsigned)s.splits);
     prof_begin(c, (double)res->cnt * (double)str->cnt);
-    FS_LOWD_DISPATCH((int)P->d, launch_lse_d<DD>(R, grid, c->stream, res->packed, str->packed, cscale, tps, n_tiles,
-                                                 (double2 *)P->partial, res->cnt_pad));
+    if (lowd_precise(P, eps)) {
+        FS_LOWD_DISPATCH((int)P->d, (launch_lse_d<double, DD>(R, grid, c->stream, res->packed_d, str->packed_d, cscale,
+                                                              tps, n_tiles, (double2 *)P->partial, res->cnt_pad)));
+    } else {
+        FS_LOWD_DISPATCH((int)P->d, (launch_lse_d<float, DD>(R, grid, c->stream, res->packed, str->packed,
+                                                             (float)cscale, tps, n_tiles, (double2 *)P->partial,
+                                                             res->cnt_pad)));
+    }
     prof_end(c);
     FS_HIP(c, hipGetLastError());
     *splits_out = s.splits;
     return FS_OK;
 }
 
-static PassShape apply_shape(const Ctx *c, int64_t n_res, int64_t n_str)
-{
-    PassShape s;
-    s.rows_per_block = kBlock;
-    s.row_blocks = (int)ceil_div(n_res, kBlock);
-    int n_tiles = (int)ceil_div(n_str, kTJ);
-    int target = 4 * c->num_cu;
-    int splits = (int)ceil_div(target, s.row_blocks);
-    if (splits > n_tiles) splits = n_tiles;
-    if (splits > kMaxSplits) splits = kMaxSplits;
-    if (splits < 1) splits = 1;
-    int tps = (int)ceil_div(n_tiles, splits);
-    s.splits = (int)ceil_div(n_tiles, tps);
-    s.cols_per_split = (int64_t)tps * kTJ;
-    return s;
-}
-
 size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t p)
 {
     (void)p;
-    PassShape s = apply_shape(c, n_res, n_str);
+    PassShape s = shape_for(c, n_res, n_str, 1);
     return (size_t)s.splits * (size_t)round_up(n_res, 1024) * kApplyPC * 4;
 }
 
 fs_status lowd_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, const float *V,
                      int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out)
 {
-    PassShape s = apply_shape(c, res->cnt, str->cnt);
+    PassShape s = shape_for(c, res->cnt, str->cnt, 1);
     const int n_tiles = (int)ceil_div(str->cnt, kTJ);
     const int tps = (int)(s.cols_per_split / kTJ);
     if ((int64_t)s.row_blocks * kBlock > res->cnt_pad || (int64_t)n_tiles * kTJ > str->cnt_pad ||
         (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes ||
         (size_t)s.splits * res->cnt_pad * kApplyPC * 4 > P->extra_bytes)
         return fail(c, FS_ERR_DEVICE, "internal: low-d apply launch shape exceeds the padded buffers");
-    const float cscale = (float)(2.0 * kLog2e / eps);
+    const double cscale = 2.0 * kLog2e / eps;
+    const bool precise = lowd_precise(P, eps);
     dim3 grid((unsigned)s.row_blocks, (unsigned)s.splits);
     float *opart = (float *)P->extra;
     for (int p0 = 0; p0 < p; p0 += kApplyPC) {
-        FS_LOWD_DISPATCH((int)P->d,
-                         hipLaunchKernelGGL((k_apply_lowd<DD, kApplyPC>), grid, dim3(kBlock), 0, c->stream, res->packed,
-                                            str->packed, V, ldv, p0, (int)p, str->cnt, cscale, tps, n_tiles,
-                                            (double2 *)P->partial, res->cnt_pad, opart, res->cnt_pad));
+        if (precise) {
+            FS_LOWD_DISPATCH((int)P->d, (launch_apply_d<double, DD>(grid, c->stream, res->packed_d, str->packed_d, V, ldv,
+                                                                    p0, (int)p, str->cnt, cscale, tps, n_tiles,
+                                                                    (double2 *)P->partial, res->cnt_pad, opart)));
+        } else {
+            FS_LOWD_DISPATCH((int)P->d, (launch_apply_d<float, DD>(grid, c->stream, res->packed, str->packed, V, ldv, p0,
+                                                                   (int)p, str->cnt, (float)cscale, tps, n_tiles,
+                                                                   (double2 *)P->partial, res->cnt_pad, opart)));
+        }
         hipLaunchKernelGGL(k_apply_finalize, dim3((unsigned)ceil_div(res->cnt, 256)), dim3(256), 0, c->stream,
                            (const double2 *)P->partial, res->cnt_pad, opart, res->cnt_pad, kApplyPC, s.splits, res->cnt,
-                           1.0 / eps, res->w, res->log_uniform, res->pot, p0, (int)p, out, ldo, mass_out);
+                           1.0 / eps, res->w, res->log_uniform, res->pot, precise ? res->norm : res->norm_f, p0, (int)p,
+                           out, ldo, mass_out);
     }
     FS_HIP(c, hipGetLastError());
     return FS_OK;

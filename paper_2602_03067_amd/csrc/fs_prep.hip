@@ -82,24 +82,48 @@ __global__ void k_mean_final(const double *partX, const double *partY, int block
     mean[k] = s * inv_cnt;
 }
 
-// ---- low-d derived copy: centred float coordinates, packed with a bias slot -------------
-__global__ void k_prep_lowd(const void *pts, int dtype, int64_t cnt, int64_t cnt_pad, int d, int64_t ld, int dp,
-                            const double *mean, float *packed, double *norm)
+// ---- low-d derived copies: coordinates centred at the common mean, packed with a bias slot;
+//      float (rounded once) and double (exact difference), each with its own squared norms ----
+__global__ void k_prep_lowd(const void *pts, int dtype, int64_t cnt, int64_t cnt_pad, int d, int64_t ld, int dp, int dpd,
+                            const double *mean, float *packed, double *packed_d, double *norm_f, double *norm)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= cnt_pad) return;
     float *o = packed + i * dp;
-    double nrm = 0.0;
-    for (int k = 0; k < dp; ++k) {
-        float v = 0.0f;
-        if (i < cnt && k < d) {
-            v = (float)((double)load_pt(pts, dtype, i * ld + k) - mean[k]);
-            nrm += (double)v * (double)v;
+    double *od = packed_d + i * dpd;
+    double nf = 0.0, nd = 0.0;
+    for (int k = 0; k < dp; ++k) o[k] = 0.0f;
+    for (int k = 0; k < dpd; ++k) od[k] = 0.0;
+    if (i < cnt) {
+        for (int k = 0; k < d; ++k) {
+            double v = (double)load_pt(pts, dtype, i * ld + k) - mean[k];
+            float vf = (float)v;
+            o[k] = vf;
+            od[k] = v;
+            nf += (double)vf * (double)vf;
+            nd += v * v;
         }
-        o[k] = v;
     }
-    o[d] = -INFINITY;   // bias slot: padding rows never contribute; real rows are set per half-step
-    norm[i] = nrm;
+    o[d] = -INFINITY;   // bias slots: padding rows never contribute; real rows are set per half-step
+    od[d] = -INFINITY;
+    norm_f[i] = nf;
+    norm[i] = nd;
+}
+
+// largest entry of two arrays, by one block (max is order independent, so this is deterministic)
+__global__ __launch_bounds__(256) void k_max2(const double *a, int64_t na, const double *b, int64_t nb, double *dst)
+{
+    __shared__ double sh[256];
+    double m = 0.0;
+    for (int64_t i = threadIdx.x; i < na; i += 256) m = fmax(m, a[i]);
+    for (int64_t i = threadIdx.x; i < nb; i += 256) m = fmax(m, b[i]);
+    sh[threadIdx.x] = m;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) sh[threadIdx.x] = fmax(sh[threadIdx.x], sh[threadIdx.x + s]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *dst = sh[0];
 }
 
 // ---- float64 derived copy (fp64 matrix-core path) ----------------------------------------
@@ -149,38 +173,39 @@ __global__ void k_prep_bf16(const void *pts, int dtype, int64_t cnt, int64_t cnt
     }
 }
 
-// Where the bias of point i of a side lives, by path.
+// Where the bias of point i of a side lives, by path, and the squared norms that turn the
+// unshifted potential into the shifted one of Prop. 1 (fhat = f - alpha, ghat = g - beta).
 struct BiasSink {
-    float *packed;   // LowD: packed[i*dp + d]
-    int dp, d;
-    float *bias_f;   // BF16
-    double *bias_d;  // F64
+    float *packed;          // LowD float copy: packed[i*dp + d], shifted by norm_f
+    double *packed_d;       // LowD double copy: packed_d[i*dpd + d], shifted by norm
+    int dp, dpd, d;
+    float *bias_f;          // BF16 path
+    double *bias_d;         // F64 path
+    const double *norm_f;
+    const double *norm;
 };
-
-__device__ inline void store_bias(const BiasSink &s, int64_t i, double bias2)
-{
-    if (s.packed) s.packed[i * s.dp + s.d] = (float)bias2;
-    if (s.bias_f) s.bias_f[i] = (float)bias2;
-    if (s.bias_d) s.bias_d[i] = bias2;
-}
 
 // bias in base-2 units of a streamed point:  ((pot_shifted)/eps + log w) * log2(e)
 // (Alg. 1: (ghat_j + delta_j)/eps with delta = eps*log b)
-__device__ inline double bias2_of(double pot_shifted, double inv_eps, const float *w, double log_uniform, int64_t i)
+__device__ inline void store_bias(const BiasSink &s, int64_t i, double pot, double inv_eps, double lw)
 {
-    double lw = w ? log((double)w[i]) : log_uniform;
-    return (pot_shifted * inv_eps + lw) * kLog2e;
+    double b = ((pot - s.norm[i]) * inv_eps + lw) * kLog2e;
+    if (s.packed) s.packed[i * s.dp + s.d] = (float)(((pot - s.norm_f[i]) * inv_eps + lw) * kLog2e);
+    if (s.packed_d) s.packed_d[i * s.dpd + s.d] = b;
+    if (s.bias_f) s.bias_f[i] = (float)b;
+    if (s.bias_d) s.bias_d[i] = b;
 }
 
-// ---- shifted potential + bias from a user potential (unshifted, float) -------------------
-__global__ void k_bias_from_user(const float *pot_user, const double *norm, int64_t cnt, double inv_eps,
-                                 const float *w, double log_uniform, double *pot, BiasSink sink)
+// ---- workspace potential (float64, unshifted) + bias from a user potential (float) -------
+__global__ void k_bias_from_user(const float *pot_user, int64_t cnt, double inv_eps, const float *w,
+                                 double log_uniform, double *pot, BiasSink sink)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= cnt) return;
-    double ps = (double)pot_user[i] - norm[i];   // fhat = f - alpha, ghat = g - beta (Prop. 1)
-    pot[i] = ps;
-    store_bias(sink, i, bias2_of(ps, inv_eps, w, log_uniform, i));
+    double pu = (double)pot_user[i];
+    pot[i] = pu;
+    double lw = w ? log((double)w[i]) : log_uniform;
+    store_bias(sink, i, pu, inv_eps, lw);
 }
 
 // ---- merge the per-split (max, sum) statistics of a streaming pass -----------------------
@@ -189,7 +214,7 @@ __global__ void k_bias_from_user(const float *pot_user, const double *norm, int6
 // unshifted potential for the caller, or the marginal deviation |w e^((pot_old-pot_new)/eps) - w|.
 __global__ __launch_bounds__(256) void k_finalize(const double2 *partial, int64_t stride, int splits, int64_t cnt,
                                                   double eps, double inv_eps_next, const float *w,
-                                                  double log_uniform, const double *norm, double *pot,
+                                                  double log_uniform, const double *res_norm, double *pot,
                                                   BiasSink sink, float *user_out, double *dev_part)
 {
     __shared__ double sh[256];
@@ -206,14 +231,15 @@ __global__ __launch_bounds__(256) void k_finalize(const double2 *partial, int64_
             double2 ms = partial[(int64_t)k * stride + i];
             S += ms.y * exp2(ms.x - M);
         }
-        double pot_new = -eps * kLn2 * (M + log2(S));
+        // fhat = -eps * LSE (Alg. 1), f = fhat + alpha (Prop. 1)
+        double pot_new = -eps * kLn2 * (M + log2(S)) + res_norm[i];
         if (dev_part) {
             double wi = w ? (double)w[i] : exp(log_uniform);
             dev = fabs(wi * exp((pot[i] - pot_new) / eps) - wi);   // Prop. 3: r = a exp((fhat - fhat+)/eps)
         } else {
             pot[i] = pot_new;
-            if (inv_eps_next > 0.0) store_bias(sink, i, bias2_of(pot_new, inv_eps_next, w, log_uniform, i));
-            if (user_out) user_out[i] = (float)(pot_new + norm[i]);
+            if (inv_eps_next > 0.0) store_bias(sink, i, pot_new, inv_eps_next, w ? log((double)w[i]) : log_uniform);
+            if (user_out) user_out[i] = (float)pot_new;
         }
     }
     if (dev_part) {
@@ -236,10 +262,14 @@ BiasSink sink_of(const Prepared *P, const Side *s)
 {
     BiasSink k{};
     k.packed = s->packed;
+    k.packed_d = s->packed_d;
     k.dp = P->dp;
+    k.dpd = P->dpd;
     k.d = (int)P->d;
     k.bias_f = s->bias_f;
     k.bias_d = s->bias_d;
+    k.norm_f = s->norm_f;
+    k.norm = s->norm;
     return k;
 }
 
@@ -278,7 +308,14 @@ fs_status launch_prepare(Ctx *c, const fs_problem *p, Prepared *P)
                            1.0 / (double)(p->n + p->m), P->mean);
         for (auto &s : in)
             hipLaunchKernelGGL(k_prep_lowd, dim3((unsigned)ceil_div(s.S->cnt_pad, 256)), dim3(256), 0, c->stream, s.pts,
-                               dtype, s.S->cnt, s.S->cnt_pad, (int)p->d, s.ld, P->dp, P->mean, s.S->packed, s.S->norm);
+                               dtype, s.S->cnt, s.S->cnt_pad, (int)p->d, s.ld, P->dp, P->dpd, P->mean, s.S->packed,
+                               s.S->packed_d, s.S->norm_f, s.S->norm);
+        hipLaunchKernelGGL(k_max2, dim3(1), dim3(256), 0, c->stream, P->X.norm, P->X.cnt, P->Y.norm, P->Y.cnt,
+                           P->scalars + 7);
+        FS_HIP(c, hipGetLastError());
+        // the host chooses the score precision of each half-step from this number
+        FS_HIP(c, hipMemcpyAsync(&P->rho_max, P->scalars + 7, sizeof(double), hipMemcpyDeviceToHost, c->stream));
+        FS_HIP(c, hipStreamSynchronize(c->stream));
     } else if (P->path == Path::F64) {
         for (auto &s : in)
             hipLaunchKernelGGL(k_prep_f64, dim3((unsigned)ceil_div(s.S->cnt_pad, 4)), dim3(256), 0, c->stream, s.pts,
@@ -295,19 +332,19 @@ fs_status launch_prepare(Ctx *c, const fs_problem *p, Prepared *P)
 fs_status launch_bias_from_user(Ctx *c, const Prepared *P, Side *side, const float *pot_user, double eps)
 {
     hipLaunchKernelGGL(k_bias_from_user, dim3((unsigned)ceil_div(side->cnt, 256)), dim3(256), 0, c->stream, pot_user,
-                       side->norm, side->cnt, 1.0 / eps, side->w, side->log_uniform, side->pot, sink_of(P, side));
+                       side->cnt, 1.0 / eps, side->w, side->log_uniform, side->pot, sink_of(P, side));
     FS_HIP(c, hipGetLastError());
     return FS_OK;
 }
 
-fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, int splits, double eps_cur, double eps_next_bias,
-                          float *user_out, double *abs_dev_sum)
+fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, const double *res_norm, int splits, double eps_cur,
+                          double eps_next_bias, float *user_out, double *abs_dev_sum)
 {
     const unsigned blocks = (unsigned)ceil_div(res->cnt, 256);
     double *dev_part = abs_dev_sum ? P->dev_part : nullptr;   // per-block sums of the marginal deviation
     hipLaunchKernelGGL(k_finalize, dim3(blocks), dim3(256), 0, c->stream, (const double2 *)P->partial, res->cnt_pad,
                        splits, res->cnt, eps_cur, eps_next_bias > 0.0 ? 1.0 / eps_next_bias : 0.0, res->w,
-                       res->log_uniform, res->norm, res->pot, sink_of(P, res), user_out, dev_part);
+                       res->log_uniform, res_norm, res->pot, sink_of(P, res), user_out, dev_part);
     if (abs_dev_sum)
         hipLaunchKernelGGL(k_sum_to, dim3(1), dim3(256), 0, c->stream, dev_part, (int64_t)blocks, abs_dev_sum);
     FS_HIP(c, hipGetLastError());

@@ -141,6 +141,23 @@ def test_annealed_trajectory_scaled_down(ctx, oracle):
     assert abs(er - ero) <= 1e-5 and abs(ec - eco) <= 1e-5
 
 
+def test_annealed_trajectory_8192(ctx, oracle):
+    """Same annealed workload at n = m = 8192 (several row blocks, two rows per lane)."""
+    w = workloads.make("lowdim_anneal", n=8192, m=8192)
+    say("solve lowdim_anneal n=m=8192 (oracle takes ~40 s)")
+    prob = binding.problem_from_workload(w)
+    f = torch.zeros(w.n, device="cuda:0")
+    g = torch.zeros(w.m, device="cuda:0")
+    ctx.fs_solve(prob, w.eps_start, w.eps_end, w.n_stages, w.iters, f, g)
+    torch.cuda.synchronize()
+    fo, go = oracle.solve(w.x, w.y, w.a, w.b, w.eps_start, w.eps_end, w.n_stages, w.iters)
+    eps = float(np.float32(w.eps_end))
+    ef = max_err_over_eps(host(f), fo, eps)
+    eg = max_err_over_eps(host(g), go, eps)
+    say("anneal 8192: max|df|/eps=%.3e max|dg|/eps=%.3e" % (ef, eg))
+    assert ef <= TOL and eg <= TOL
+
+
 @pytest.mark.parametrize("n,m,d,p", [(300, 200, 3, 3), (1000, 1300, 3, 1), (513, 255, 2, 7), (260, 300, 8, 5)])
 def test_apply_plan_and_transpose(ctx, oracle, n, m, d, p):
     rng = np.random.default_rng(n + m + d + p)
