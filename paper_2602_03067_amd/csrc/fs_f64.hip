@@ -1,14 +1,384 @@
-// fp64 matrix-core path (placeholder until the kernels land).
+// fp32-accuracy path for d > 16: the score contraction <x_i, y_j> runs on the fp64 matrix
+// cores (v_mfma_f64_16x16x4_f64).
+//
+// Why fp64: with d = 64 and eps = 0.1 a score (2<x,y> - |y|^2 + g)/eps reaches ~2e3, where an
+// fp32 ulp is 1.2e-4 -- the whole error budget of 1e-4.  MI355X has 78.6 TFLOP/s of fp64 MFMA,
+// so the exact route costs 2x the fp32-MFMA time instead of the accuracy.
+//
+// Mapping of one 16x16x4 MFMA (a wrong assumption here fails every parity test of this path):
+//   A operand: lane l supplies A[i = l%16][k = l/16]        -> i = STREAMED point
+//   B operand: lane l supplies B[k = l/16][j = l%16]        -> j = RESIDENT row
+//   D result : lane l, register r holds D[i = 4r + l/16][j = l%16]
+// so the four accumulator registers of a lane are four streamed points of ONE resident row:
+// the online LSE of Alg. 1 runs inside the lane, and lanes are merged only once, at the end.
+// For plan application (Alg. 2/4) the exponentiated tile is, register by register, already
+// in A-operand layout for the second contraction  O[j][c] += sum_i E[i][j] V[i][c]  (k = l/16
+// <-> i = 4r + k), so P never leaves the registers.
+//
+// Workgroup: 256 threads = 4 waves; 64 resident rows (4 column blocks j of 16) x tiles of 64
+// streamed points (16 per wave).  The resident block lives in LDS for the whole pass when
+// d <= 64; streamed points go through LDS in contraction chunks of 32.
 #include "fs_internal.h"
+
 namespace fs {
-fs_status f64_lse(Ctx *c, const Prepared *, const Side *, const Side *, double, int *)
+namespace {
+
+typedef double d4 __attribute__((ext_vector_type(4)));
+
+constexpr int BR = 64;     // resident rows per workgroup
+constexpr int BC = 64;     // streamed points per tile
+constexpr int KC = 32;     // contraction chunk staged for the streamed points
+constexpr int KRES = 64;   // resident coordinates kept in LDS across the pass
+constexpr int LDR = KRES + 1;   // odd leading dimensions: conflict-free 8-byte column reads
+constexpr int LDS_ = KC + 1;
+constexpr int PCH = 64;    // value columns per application pass
+
+__device__ inline float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
+
+struct PassArgs {
+    const double *res;       // [res_pad][kp]
+    const double *str;       // [str_pad][kp]
+    const double *bias;      // [str_pad], base-2 bias of the streamed points (-inf on padding)
+    int kp;
+    double cscale;           // 2 log2(e) / eps
+    int tiles_per_split, n_tiles;
+    double2 *partial;        // [splits][partial_stride] (max, sum)
+    int64_t partial_stride;
+    // application only
+    const float *V;          // [n_str][ldv]
+    int64_t ldv, n_str;
+    int p0, p;
+    float *opart;            // [splits][partial_stride][PCH]
+};
+
+template <bool APPLY> __global__ __launch_bounds__(256) void k_pass_f64(PassArgs a)
 {
-    return fail(c, FS_ERR_UNSUPPORTED, "d > 16 in fp32 mode is not built yet");
+    __shared__ double res_lds[BR * LDR];          // 33,280 B; reused for the final merge
+    __shared__ double str_lds[BC * LDS_];         // 16,896 B
+    __shared__ double bias_lds[BC];
+    __shared__ float vt[APPLY ? BC * PCH : 1];    // 16,384 B (application)
+    __shared__ float mw[4][BR];                   // per-wave running max (final merge)
+    __shared__ float sred[BR][17];                // per-(wave, lane group) sums (final merge)
+
+    const int tid = threadIdx.x;
+    const int w = tid >> 6, l = tid & 63, lg = l >> 4, lj = l & 15;
+    const int kp = a.kp;
+    const int64_t row0 = (int64_t)blockIdx.x * BR;
+    const bool res_cached = kp <= KRES;
+    const int n_chunks = (kp + KC - 1) / KC;
+
+    if (res_cached) {
+        const int per_row = kp >> 1;   // double2 per row
+        for (int e = tid; e < BR * per_row; e += 256) {
+            int r = e / per_row, kk = (e - r * per_row) * 2;
+            double2 v = *reinterpret_cast<const double2 *>(a.res + (row0 + r) * kp + kk);
+            res_lds[r * LDR + kk] = v.x;
+            res_lds[r * LDR + kk + 1] = v.y;
+        }
+    }
+
+    float mrun[4], srun[4];
+    d4 O[APPLY ? 4 : 1][APPLY ? 4 : 1];
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt) {
+        mrun[jt] = kNegInit;
+        srun[jt] = 0.0f;
+    }
+    if constexpr (APPLY) {
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct) O[jt][ct] = d4{0.0, 0.0, 0.0, 0.0};
+    }
+
+    const int t_begin = blockIdx.y * a.tiles_per_split;
+    const int t_end = min(a.n_tiles, t_begin + a.tiles_per_split);
+
+    for (int t = t_begin; t < t_end; ++t) {
+        const int64_t col0 = (int64_t)t * BC;
+        d4 acc[4];
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) acc[jt] = d4{0.0, 0.0, 0.0, 0.0};
+
+        for (int ch = 0; ch < n_chunks; ++ch) {
+            const int kc0 = ch * KC;
+            const int kw = min(KC, kp - kc0);
+            __syncthreads();   // previous chunk (and the previous tile's epilogue) is done with LDS
+            // streamed chunk: 64 points x KC doubles, zero beyond kp
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                int e = tid + 256 * q;
+                int cidx = e >> 4, kk = (e & 15) * 2;
+                double2 v = make_double2(0.0, 0.0);
+                if (kk < kw) v = *reinterpret_cast<const double2 *>(a.str + (col0 + cidx) * kp + kc0 + kk);
+                str_lds[cidx * LDS_ + kk] = v.x;
+                str_lds[cidx * LDS_ + kk + 1] = v.y;
+            }
+            if (!res_cached) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    int e = tid + 256 * q;
+                    int r = e >> 4, kk = (e & 15) * 2;
+                    double2 v = make_double2(0.0, 0.0);
+                    if (kk < kw) v = *reinterpret_cast<const double2 *>(a.res + (row0 + r) * kp + kc0 + kk);
+                    res_lds[r * LDR + kk] = v.x;
+                    res_lds[r * LDR + kk + 1] = v.y;
+                }
+            }
+            if (ch == 0) {
+                if (tid < BC) bias_lds[tid] = a.bias[col0 + tid];
+                if constexpr (APPLY) {
+                    for (int e = tid; e < BC * PCH; e += 256) {
+                        int cidx = e >> 6, cc = e & 63;
+                        int64_t j = col0 + cidx;
+                        vt[e] = (j < a.n_str && a.p0 + cc < a.p) ? a.V[j * a.ldv + a.p0 + cc] : 0.0f;
+                    }
+                }
+            }
+            __syncthreads();
+            const int kbase = res_cached ? kc0 : 0;
+            const double *sa = str_lds + (16 * w + lj) * LDS_ + lg;
+            const double *sb = res_lds + lj * LDR + kbase + lg;
+            for (int kk = 0; kk < kw; kk += 4) {
+                double av = sa[kk];
+#pragma unroll
+                for (int jt = 0; jt < 4; ++jt) {
+                    double bv = sb[jt * 16 * LDR + kk];
+                    acc[jt] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[jt], 0, 0, 0);
+                }
+            }
+        }
+
+        // ---- tile epilogue: scores of this lane = cscale * acc + bias of its streamed points
+        double bias[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bias[r] = bias_lds[16 * w + 4 * r + lg];
+
+        if constexpr (!APPLY) {
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) {
+                double s[4];
+                float mx = kNegInit;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    s[r] = fma(acc[jt][r], a.cscale, bias[r]);
+                    mx = fmaxf(mx, (float)s[r]);
+                }
+                float mnew = fmaxf(mrun[jt], ceilf(mx));
+                float scale = fast_exp2(mrun[jt] - mnew);
+                double md = (double)mnew;
+                float csum = 0.0f;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) csum += fast_exp2((float)(s[r] - md));
+                srun[jt] = fmaf(srun[jt], scale, csum);
+                mrun[jt] = mnew;
+            }
+        } else {
+            double s[4][4];
+            float mx[4];
+            bool raise = false;
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) {
+                float m = kNegInit;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    s[jt][r] = fma(acc[jt][r], a.cscale, bias[r]);
+                    m = fmaxf(m, (float)s[jt][r]);
+                }
+                // the stabiliser of a resident row must be common to the four lane groups,
+                // because the second MFMA sums over them
+                m = fmaxf(m, __shfl_xor(m, 16, 64));
+                m = fmaxf(m, __shfl_xor(m, 32, 64));
+                mx[jt] = m;
+                raise = raise || (m > mrun[jt] + 40.0f);
+            }
+            if (__any(raise)) {
+                // rare: lift the (integer) stabilisers and rescale sums and accumulators exactly
+#pragma unroll
+                for (int jt = 0; jt < 4; ++jt) {
+                    float mnew = fmaxf(mrun[jt], ceilf(mx[jt]));
+                    float scale = fast_exp2(mrun[jt] - mnew);
+                    srun[jt] *= scale;
+                    mrun[jt] = mnew;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        // accumulator register r holds resident row 4r + lg of this column block
+                        double sc = (double)__shfl(scale, 4 * r + lg, 64);
+#pragma unroll
+                        for (int ct = 0; ct < 4; ++ct) O[jt][ct][r] *= sc;
+                    }
+                }
+            }
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) {
+                double md = (double)mrun[jt];
+                double E[4];
+                float csum = 0.0f;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float e = fast_exp2((float)(s[jt][r] - md));
+                    csum += e;
+                    E[r] = (double)e;
+                }
+                srun[jt] += csum;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+#pragma unroll
+                    for (int ct = 0; ct < 4; ++ct) {
+                        double vv = (double)vt[(16 * w + 4 * r + lg) * PCH + 16 * ct + lj];
+                        O[jt][ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(E[r], vv, O[jt][ct], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- merge the 4 waves x 4 lane groups of every resident row ---------------------------
+    __syncthreads();
+    if constexpr (APPLY) {
+        if (lg == 0) {
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) mw[w][16 * jt + lj] = mrun[jt];
+        }
+    } else {
+        // per-lane maxima differ: reduce them over the lane groups first
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) {
+            float m = mrun[jt];
+            m = fmaxf(m, __shfl_xor(m, 16, 64));
+            m = fmaxf(m, __shfl_xor(m, 32, 64));
+            srun[jt] *= fast_exp2(mrun[jt] - m);
+            mrun[jt] = m;
+            if (lg == 0) mw[w][16 * jt + lj] = m;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt) {
+        int r = 16 * jt + lj;
+        float M = fmaxf(fmaxf(mw[0][r], mw[1][r]), fmaxf(mw[2][r], mw[3][r]));
+        sred[r][4 * w + lg] = srun[jt] * fast_exp2(mrun[jt] - M);
+    }
+    if constexpr (APPLY) {
+        double *obuf = res_lds;   // [BR][PCH] doubles = 32 KB <= sizeof(res_lds)
+        for (int ww = 0; ww < 4; ++ww) {
+            if (w == ww) {
+#pragma unroll
+                for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        int row = 16 * jt + 4 * r + lg;
+                        float M = fmaxf(fmaxf(mw[0][row], mw[1][row]), fmaxf(mw[2][row], mw[3][row]));
+                        double sc = (double)fast_exp2(mw[w][row] - M);
+#pragma unroll
+                        for (int ct = 0; ct < 4; ++ct) {
+                            int idx = row * PCH + 16 * ct + lj;
+                            double v = O[jt][ct][r] * sc;
+                            obuf[idx] = (ww == 0) ? v : obuf[idx] + v;
+                        }
+                    }
+            }
+            __syncthreads();
+        }
+        for (int e = tid; e < BR * PCH; e += 256) {
+            int r = e >> 6, cc = e & 63;
+            a.opart[((int64_t)blockIdx.y * a.partial_stride + row0 + r) * PCH + cc] = (float)obuf[e];
+        }
+    }
+    __syncthreads();
+    if (tid < BR) {
+        float M = fmaxf(fmaxf(mw[0][tid], mw[1][tid]), fmaxf(mw[2][tid], mw[3][tid]));
+        double S = 0.0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) S += (double)sred[tid][k];
+        a.partial[(int64_t)blockIdx.y * a.partial_stride + row0 + tid] = make_double2((double)M, S);
+    }
 }
-size_t f64_apply_ws(const Ctx *, int64_t, int64_t, int64_t, int64_t) { return 0; }
-fs_status f64_apply(Ctx *c, const Prepared *, const Side *, const Side *, double, const float *, int64_t, int64_t,
-                    float *, int64_t, float *)
+
+PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str)
 {
-    return fail(c, FS_ERR_UNSUPPORTED, "d > 16 in fp32 mode is not built yet");
+    PassShape s;
+    s.rows_per_block = BR;
+    s.row_blocks = (int)ceil_div(n_res, BR);
+    int n_tiles = (int)ceil_div(n_str, BC);
+    int target = 2 * c->num_cu;
+    int splits = (int)ceil_div(target, s.row_blocks);
+    if (splits > n_tiles) splits = n_tiles;
+    if (splits > kMaxSplits) splits = kMaxSplits;
+    if (splits < 1) splits = 1;
+    int tps = (int)ceil_div(n_tiles, splits);
+    s.splits = (int)ceil_div(n_tiles, tps);
+    s.cols_per_split = (int64_t)tps * BC;
+    return s;
 }
+
+}  // namespace
+
+fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out)
+{
+    PassShape s = shape_f64(c, res->cnt, str->cnt);
+    PassArgs a{};
+    a.res = res->pts_d;
+    a.str = str->pts_d;
+    a.bias = str->bias_d;
+    a.kp = P->kp;
+    a.cscale = 2.0 * kLog2e / eps;
+    a.n_tiles = (int)ceil_div(str->cnt, BC);
+    a.tiles_per_split = (int)(s.cols_per_split / BC);
+    a.partial = (double2 *)P->partial;
+    a.partial_stride = res->cnt_pad;
+    if ((int64_t)s.row_blocks * BR > res->cnt_pad || (int64_t)a.n_tiles * BC > str->cnt_pad ||
+        (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp & 3) != 0)
+        return fail(c, FS_ERR_DEVICE, "internal: fp64 launch shape exceeds the padded buffers");
+    prof_begin(c, (double)res->cnt * (double)str->cnt);
+    hipLaunchKernelGGL(k_pass_f64<false>, dim3((unsigned)s.row_blocks, (unsigned)s.splits), dim3(256), 0, c->stream, a);
+    prof_end(c);
+    FS_HIP(c, hipGetLastError());
+    *splits_out = s.splits;
+    return FS_OK;
+}
+
+size_t f64_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t d, int64_t p)
+{
+    (void)d;
+    (void)p;
+    PassShape s = shape_f64(c, n_res, n_str);
+    return (size_t)s.splits * (size_t)round_up(n_res, 1024) * PCH * 4;
+}
+
+fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, const float *V,
+                    int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out)
+{
+    PassShape s = shape_f64(c, res->cnt, str->cnt);
+    PassArgs a{};
+    a.res = res->pts_d;
+    a.str = str->pts_d;
+    a.bias = str->bias_d;
+    a.kp = P->kp;
+    a.cscale = 2.0 * kLog2e / eps;
+    a.n_tiles = (int)ceil_div(str->cnt, BC);
+    a.tiles_per_split = (int)(s.cols_per_split / BC);
+    a.partial = (double2 *)P->partial;
+    a.partial_stride = res->cnt_pad;
+    a.V = V;
+    a.ldv = ldv;
+    a.n_str = str->cnt;
+    a.p = (int)p;
+    a.opart = (float *)P->extra;
+    if ((int64_t)s.row_blocks * BR > res->cnt_pad || (int64_t)a.n_tiles * BC > str->cnt_pad ||
+        (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp & 3) != 0 ||
+        (size_t)s.splits * res->cnt_pad * PCH * 4 > P->extra_bytes)
+        return fail(c, FS_ERR_DEVICE, "internal: fp64 apply launch shape exceeds the padded buffers");
+    for (int p0 = 0; p0 < p; p0 += PCH) {
+        a.p0 = p0;
+        hipLaunchKernelGGL(k_pass_f64<true>, dim3((unsigned)s.row_blocks, (unsigned)s.splits), dim3(256), 0, c->stream,
+                           a);
+        fs_status st = launch_apply_finalize(c, P, res, res->norm, s.splits, eps, a.opart, PCH, p0, (int)p, out, ldo,
+                                             mass_out);
+        if (st != FS_OK) return st;
+    }
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
 }  // namespace fs

@@ -130,6 +130,11 @@ fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, const double *re
 fs_status launch_row_norms(Ctx *c, const void *pts, int dtype, int64_t rows, int64_t d, int64_t ld,
                            float *out);
 fs_status launch_fill_f64(Ctx *c, double *dst, double v, int64_t cnt);
+// merge the splits of an application pass (partial (max,sum) + opart[split][row][PC]) and apply
+// the epilogue  out_i = w_i exp(pot_shifted_i/eps + m_i) O_i  for columns p0 .. p0+PC-1
+fs_status launch_apply_finalize(Ctx *c, const Prepared *P, const Side *res, const double *res_norm, int splits,
+                                double eps, const float *opart, int PC, int p0, int p, float *out, int64_t ldo,
+                                float *mass_out);
 
 // fs_lowd.hip
 PassShape lowd_shape(const Ctx *c, int64_t n_res, int64_t n_str);

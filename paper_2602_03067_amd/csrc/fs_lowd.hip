@@ -240,42 +240,6 @@ __global__ __launch_bounds__(kBlock) void k_apply_lowd(const S *__restrict__ res
     for (int c = 0; c < PC; ++c) opart[((int64_t)blockIdx.y * opart_stride + row) * PC + c] = O[c];
 }
 
-// merge the splits of an application pass and apply the epilogue of Alg. 2:
-//   out_i = a_i * exp(fhat_i/eps + m_i) * O_i   with everything in base 2;  mass_i = same with s.
-__global__ void k_apply_finalize(const double2 *partial, int64_t stride, const float *opart, int64_t opart_stride,
-                                 int PC, int splits, int64_t cnt, double inv_eps, const float *w, double log_uniform,
-                                 const double *pot, const double *res_norm, int p0, int p, float *out, int64_t ldo,
-                                 float *mass_out)
-{
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= cnt) return;
-    double M = -INFINITY;
-    for (int k = 0; k < splits; ++k) {
-        double mk = partial[(int64_t)k * stride + i].x;
-        M = mk > M ? mk : M;
-    }
-    double lw = w ? log((double)w[i]) : log_uniform;
-    // row factor  a_i * exp(fhat_i/eps + m_i): add the exponents BEFORE exponentiating
-    double fac = exp2(((pot[i] - res_norm[i]) * inv_eps + lw) * kLog2e + M);
-    for (int c = 0; c < PC; ++c) {
-        if (p0 + c >= p) break;
-        double acc = 0.0;
-        for (int k = 0; k < splits; ++k) {
-            double2 ms = partial[(int64_t)k * stride + i];
-            acc += exp2(ms.x - M) * (double)opart[((int64_t)k * opart_stride + i) * PC + c];
-        }
-        out[i * ldo + p0 + c] = (float)(fac * acc);
-    }
-    if (mass_out && p0 == 0) {
-        double S = 0.0;
-        for (int k = 0; k < splits; ++k) {
-            double2 ms = partial[(int64_t)k * stride + i];
-            S += exp2(ms.x - M) * ms.y;
-        }
-        mass_out[i] = (float)(fac * S);
-    }
-}
-
 constexpr int kApplyPC = 4;   // output columns per application pass
 
 template <typename S, int D>
@@ -408,10 +372,9 @@ fs_status lowd_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str
                                                                    (int)p, str->cnt, (float)cscale, tps, n_tiles,
                                                                    (double2 *)P->partial, res->cnt_pad, opart)));
         }
-        hipLaunchKernelGGL(k_apply_finalize, dim3((unsigned)ceil_div(res->cnt, 256)), dim3(256), 0, c->stream,
-                           (const double2 *)P->partial, res->cnt_pad, opart, res->cnt_pad, kApplyPC, s.splits, res->cnt,
-                           1.0 / eps, res->w, res->log_uniform, res->pot, precise ? res->norm : res->norm_f, p0, (int)p,
-                           out, ldo, mass_out);
+        fs_status st = launch_apply_finalize(c, P, res, precise ? res->norm : res->norm_f, s.splits, eps, opart,
+                                             kApplyPC, p0, (int)p, out, ldo, mass_out);
+        if (st != FS_OK) return st;
     }
     FS_HIP(c, hipGetLastError());
     return FS_OK;

@@ -258,6 +258,42 @@ __global__ __launch_bounds__(256) void k_sum_to(const double *part, int64_t cnt,
     if (threadIdx.x == 0) *dst = t;
 }
 
+// merge the splits of an application pass and apply the epilogue of Alg. 2:
+//   out_i = a_i * exp(fhat_i/eps + m_i) * O_i   with everything in base 2;  mass_i = same with s.
+__global__ void k_apply_finalize(const double2 *partial, int64_t stride, const float *opart, int64_t opart_stride,
+                                 int PC, int splits, int64_t cnt, double inv_eps, const float *w, double log_uniform,
+                                 const double *pot, const double *res_norm, int p0, int p, float *out, int64_t ldo,
+                                 float *mass_out)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= cnt) return;
+    double M = -INFINITY;
+    for (int k = 0; k < splits; ++k) {
+        double mk = partial[(int64_t)k * stride + i].x;
+        M = mk > M ? mk : M;
+    }
+    double lw = w ? log((double)w[i]) : log_uniform;
+    // row factor  a_i * exp(fhat_i/eps + m_i): add the exponents BEFORE exponentiating
+    double fac = exp2(((pot[i] - res_norm[i]) * inv_eps + lw) * kLog2e + M);
+    for (int c = 0; c < PC; ++c) {
+        if (p0 + c >= p) break;
+        double acc = 0.0;
+        for (int k = 0; k < splits; ++k) {
+            double2 ms = partial[(int64_t)k * stride + i];
+            acc += exp2(ms.x - M) * (double)opart[((int64_t)k * opart_stride + i) * PC + c];
+        }
+        out[i * ldo + p0 + c] = (float)(fac * acc);
+    }
+    if (mass_out && p0 == 0) {
+        double S = 0.0;
+        for (int k = 0; k < splits; ++k) {
+            double2 ms = partial[(int64_t)k * stride + i];
+            S += exp2(ms.x - M) * ms.y;
+        }
+        mass_out[i] = (float)(fac * S);
+    }
+}
+
 BiasSink sink_of(const Prepared *P, const Side *s)
 {
     BiasSink k{};
@@ -274,6 +310,17 @@ BiasSink sink_of(const Prepared *P, const Side *s)
 }
 
 }  // namespace
+
+fs_status launch_apply_finalize(Ctx *c, const Prepared *P, const Side *res, const double *res_norm, int splits,
+                                double eps, const float *opart, int PC, int p0, int p, float *out, int64_t ldo,
+                                float *mass_out)
+{
+    hipLaunchKernelGGL(k_apply_finalize, dim3((unsigned)ceil_div(res->cnt, 256)), dim3(256), 0, c->stream,
+                       (const double2 *)P->partial, res->cnt_pad, opart, res->cnt_pad, PC, splits, res->cnt, 1.0 / eps,
+                       res->w, res->log_uniform, res->pot, res_norm, p0, p, out, ldo, mass_out);
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
 
 fs_status launch_fill_f64(Ctx *c, double *dst, double v, int64_t cnt)
 {
