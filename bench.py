@@ -42,6 +42,9 @@ def main() -> int:
     ap.add_argument("--workload", default="lowdim_anneal")
     ap.add_argument("--n", type=int, default=None, help="override n = m (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (outside the timed region), so that a "
+                         "rocprofv3 --pmc run has a kernel of known traffic to scale its counters by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path is single-GPU; "
@@ -90,6 +93,12 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")   # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     ctx.fs_profile_enable(True)
     ctx.fs_profile_read()
     t0 = time.perf_counter()
