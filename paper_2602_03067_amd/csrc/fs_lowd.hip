@@ -26,6 +26,7 @@ namespace {
 constexpr int kBlock = 256;   // threads per workgroup
 constexpr int kTJ = 256;      // streamed points per LDS tile
 constexpr int kT = 8;         // columns per register chunk
+constexpr float kLazyMax = 1.152921504606846976e18f;   // 2^60: largest chunk sum taken without rescaling
 
 __device__ inline float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
 
@@ -123,22 +124,41 @@ __global__ __launch_bounds__(kBlock) void k_lse_lowd(const S *__restrict__ res, 
                     sc[r][c] = acc;
                 }
             }
+            // Lazy stabiliser: exponents are taken against the CURRENT (integer) running max, which
+            // may be exceeded by up to 2^60 before anything is rescaled.  Only when a chunk sum
+            // leaves that range (or the max is still the initial sentinel) does the wave take the
+            // slow branch: lift the max to ceil(chunk max) and rescale by an exact power of two.
+            float csum[R];
+            bool bad = false;
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                float mx = (float)sc[r][0];
+                const S mS = (S)mrun[r];
+                float acc = fast_exp2((float)(sc[r][0] - mS));
 #pragma unroll
-                for (int c = 1; c < kT; ++c) mx = fmaxf(mx, (float)sc[r][c]);
-                // integer-valued running max: rescale factors are exact powers of two
-                float mnew = fmaxf(mrun[r], ceilf(mx));
-                float scale = fast_exp2(mrun[r] - mnew);
-                const S mS = (S)mnew;
-                float csum = fast_exp2((float)(sc[r][0] - mS));
-#pragma unroll
-                for (int c = 1; c < kT; ++c) csum += fast_exp2((float)(sc[r][c] - mS));
-                srun[r] *= scale;
-                stile[r] = fmaf(stile[r], scale, csum);
-                mrun[r] = mnew;
+                for (int c = 1; c < kT; ++c) acc += fast_exp2((float)(sc[r][c] - mS));
+                csum[r] = acc;
+                bad = bad || !(acc < kLazyMax);
             }
+            if (__any(bad)) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    float mx = (float)sc[r][0];
+#pragma unroll
+                    for (int c = 1; c < kT; ++c) mx = fmaxf(mx, (float)sc[r][c]);
+                    float mnew = fmaxf(mrun[r], ceilf(mx));
+                    float scale = fast_exp2(mrun[r] - mnew);
+                    const S mS = (S)mnew;
+                    float acc = fast_exp2((float)(sc[r][0] - mS));
+#pragma unroll
+                    for (int c = 1; c < kT; ++c) acc += fast_exp2((float)(sc[r][c] - mS));
+                    csum[r] = acc;
+                    srun[r] *= scale;
+                    stile[r] *= scale;
+                    mrun[r] = mnew;
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r) stile[r] += csum[r];
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
