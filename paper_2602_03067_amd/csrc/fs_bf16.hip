@@ -5,8 +5,9 @@
 // Shape of the work.  A resident row block at d = 784..1024 does not fit on chip (256 rows x
 // 800 x 2 B = 400 KB), so unlike Alg. 1 the pass is organised as a GEMM with an LSE epilogue:
 // a workgroup owns 256 resident rows (j) and a group of streamed tiles (i); for every streamed
-// tile of 128 points it runs the full contraction over d in chunks of 64 through LDS, then folds
-// the 128 x 256 scores into the per-row running (max, sum).  Groups of streamed tiles ("splits")
+// tile of 256 points it runs the full contraction over d in chunks of 32 through a four-stage
+// LDS ring filled by direct global->LDS loads (three stages in flight), then folds
+// the 256 x 256 scores into the per-row running (max, sum).  Groups of streamed tiles ("splits")
 // are merged afterwards.  Concurrent workgroups of one XCD form 8 x 8 super-tiles, so each panel
 // chunk fetched into that XCD's L2 is shared by eight workgroups.
 //
@@ -17,54 +18,138 @@
 // the row-wise LSE runs inside the lane; lanes/waves are merged once per workgroup.
 #include "fs_internal.h"
 
+
 namespace fs {
 namespace {
 
 typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 
-constexpr int BI = 128;          // streamed points per tile (2 waves x 64)
+constexpr int BI = 256;          // streamed points per tile (4 waves x 64)
 constexpr int BJ = 256;          // resident rows per workgroup (2 waves x 128)
-constexpr int KC = 64;           // contraction chunk (bf16 elements)
-constexpr int ROWB = KC * 2 + 16;   // LDS bytes per row: 128 data + 16 pad -> conflict-free b128 reads
-constexpr int PIECES = (BI + BJ) * (KC * 2 / 16) / 256;   // 16-byte pieces per thread per chunk = 12
+constexpr int NT = 512;          // threads per workgroup: 8 waves, two per SIMD
+constexpr int KC = 32;           // contraction chunk per pipeline stage (bf16 elements) = 64 B per row
+constexpr int ROWS = BI + BJ;
+constexpr int STAGE_BYTES = ROWS * KC * 2;   // 32,768 B
+constexpr int NSTAGE = 4;        // ring of stages filled by direct global->LDS loads (3 in flight)
+constexpr int NBIAS = 8;         // ring of bias tiles (one per stage, deeper than the data ring)
+constexpr float kLazyMax = 1.152921504606846976e18f;   // 2^60
 
 __device__ inline float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
 
+// Direct global -> LDS loads (no registers in between): lane l's 16 (4) bytes land at
+// lds_off + 16 l (4 l); lds_off must be wave-uniform.  Issued as inline assembly so that the
+// compiler does not serialise them against the LDS reads of OTHER ring slots; completion is
+// tracked by hand with s_waitcnt vmcnt (VMEM operations retire in order).
+__device__ inline void dma16(const void *g, unsigned lds_off)
+{
+    unsigned m = __builtin_amdgcn_readfirstlane(lds_off);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m) : "memory", "m0");
+}
+__device__ inline void dma4(const void *g, unsigned lds_off)
+{
+    unsigned m = __builtin_amdgcn_readfirstlane(lds_off);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(g), "s"(m) : "memory", "m0");
+}
+// all LDS reads of this wave have returned, then the workgroup barrier
+__device__ inline void lds_done_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 struct BfArgs {
-    const uint16_t *res;     // [res_pad][kp] bf16
-    const uint16_t *str;     // [str_pad][kp] bf16
+    const uint16_t *res;     // resident side, tiled bf16 copy (see k_prep_bf16)
+    const uint16_t *str;     // streamed side, tiled bf16 copy
     const float *bias;       // [str_pad] base-2 bias of the streamed points (-inf on padding)
     int kp;                  // multiple of 32
     float cscale;            // 2 log2(e) / eps
     int n_jtiles, n_itiles, splits, tiles_per_split;
-    int work_per_xcd;        // work items assigned to one XCD (contiguous range)
     double2 *partial;
     int64_t partial_stride;
 };
 
-__global__ __launch_bounds__(256, 2) void k_lse_bf16(BfArgs a)
+// LDS layout of a stage: row r (0..255 streamed, 256..511 resident) occupies 64 bytes = four
+// 16-byte pieces; piece p is stored at position p ^ ((r >> 1) & 3), which makes the 8 lanes that
+// the LDS serves per cycle hit 8 different 16-byte bank groups when they read one MFMA fragment.
+// The derived bf16 copies in HBM already have this layout in 1 KB tiles (16 rows x 32 coordinates),
+// so every direct load is a linear 1 KB copy: measured 52 B/clk/CU from L2 against 26 B/clk/CU for
+// 64-byte row segments, and a 256 x 256 tile needs 32 B/clk/CU at full MFMA rate.
+//
+// Schedule of one stage g in every wave (F0/F1 = fragment registers of the two 16-wide k-steps):
+//     read F1(g) | 8 MFMA on F0(g) | 4 MFMA on F1(g) | wait "stage g+1 landed" + barrier |
+//     read F0(g+1) | 4 MFMA on F1(g)
+// with the five direct loads of stage g+3 issued between the MFMA groups.  The loads are throttled
+// by the L1 path (a stage is 32 KB = ~630 cycles at 52 B/clk/CU), so they are issued while MFMAs
+// execute; the barrier and the LDS latency of the next fragments hide behind the last MFMA group.
+__global__ __launch_bounds__(NT, 1) void k_lse_bf16(BfArgs a)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[(BI + BJ) * ROWB];   // 55,296 B
-    __shared__ float bias_lds[BI];
-    __shared__ float2 red[BJ][4];
+    __shared__ __attribute__((aligned(1024))) unsigned char ring[NSTAGE * STAGE_BYTES];   // 131,072 B
+    __shared__ __attribute__((aligned(256))) float bias_ring[NBIAS][BI];                 // 8,192 B
 
-    // ---- which (resident tile, split) this workgroup owns: XCD-contiguous, 8 x 8 super-tiles
+    // ---- which (resident tile, split) this workgroup owns.  Workgroups go to XCDs round-robin;
+    // each XCD gets a contiguous, equally long run of the work list, which is ordered in patches of
+    // 8 resident tiles x 8 splits (clipped at the edges), so that the ~32 workgroups running on an
+    // XCD at any time share their panels through that XCD's L2.
     const int b = blockIdx.x;
-    const int wk = (b & 7) * a.work_per_xcd + (b >> 3);
-    const int sj = (a.n_jtiles + 7) >> 3;
-    const int sup = wk >> 6, within = wk & 63;
-    const int jtile = (sup % sj) * 8 + (within & 7);
-    const int split = (sup / sj) * 8 + (within >> 3);
-    if ((b >> 3) >= a.work_per_xcd || jtile >= a.n_jtiles || split >= a.splits) return;
+    const int total = a.n_jtiles * a.splits;
+    const int per = (total + 7) >> 3;
+    const int lb = b >> 3;
+    const int idx = (b & 7) * per + lb;
+    if (lb >= per || idx >= total) return;
+    int jtile, split;
+    {
+        const int NJ = a.n_jtiles, full = a.splits >> 3, gsz = NJ * 8;
+        int gs, rem, h;
+        if (idx < full * gsz) {
+            gs = idx / gsz;
+            rem = idx - gs * gsz;
+            h = 8;
+        } else {
+            gs = full;
+            rem = idx - full * gsz;
+            h = a.splits - 8 * full;
+        }
+        const int pj = rem / (8 * h);
+        const int r = rem - pj * 8 * h;
+        const int wp = min(8, NJ - 8 * pj);
+        jtile = 8 * pj + r % wp;
+        split = 8 * gs + r / wp;
+    }
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, l = tid & 63;
-    const int wi = w & 1, wj = w >> 1;
+    const int wi = w & 3, wj = w >> 2;
     const int lh = l >> 5, lr = l & 31;
-    const int kp = a.kp;
-    const int n_chunks = (kp + KC - 1) / KC;
+    const int n_chunks = a.kp / KC;
     const int64_t row0 = (int64_t)jtile * BJ;
+    const int t_begin = split * a.tiles_per_split;
+    const int t_end = min(a.n_itiles, t_begin + a.tiles_per_split);
+    const int G = (t_end - t_begin) * n_chunks;   // pipeline stages of this workgroup
+
+    const unsigned ring_off = (unsigned)(size_t)ring;
+    const unsigned bias_off = (unsigned)(size_t)&bias_ring[0][0];
+
+    // The bf16 copies are stored as 1 KB tiles (16 rows x 32 coordinates, already swizzled), tile
+    // (row block rb, chunk ch) at byte ((rb * n_chunks + ch) << 10): a stage is 32 linear 1 KB
+    // copies, four per wave (segments 8q + w; 0..15 streamed rows, 16..31 resident rows).
+    const unsigned char *res_tiles =
+        reinterpret_cast<const unsigned char *>(a.res) + (((int64_t)jtile * 16 * n_chunks) << 10) + l * 16;
+    const unsigned char *str_tiles = reinterpret_cast<const unsigned char *>(a.str) + l * 16;
+
+    int pt = t_begin, pch = 0, pg = 0;   // next stage to issue: tile, chunk, stage number
+    auto issue_piece = [&](int q) {      // q = 0..3: 1 KB of points, q = 4: bias, then advance
+        if (q < 4) {
+            const int sidx = 8 * q + w;
+            const unsigned char *src = q < 2 ? str_tiles + ((((int64_t)pt * 16 + sidx) * n_chunks + pch) << 10)
+                                             : res_tiles + ((((int64_t)(sidx - 16)) * n_chunks + pch) << 10);
+            dma16(src, ring_off + (pg & (NSTAGE - 1)) * STAGE_BYTES + sidx * 1024);
+        } else {
+            // both resident-side halves (wj) load the same 256 bytes: every wave issues five loads
+            dma4(a.bias + (int64_t)pt * BI + wi * 64 + l, bias_off + (pg & (NBIAS - 1)) * (BI * 4) + wi * 256);
+            ++pg;
+            if (++pch == n_chunks) {
+                pch = 0;
+                ++pt;
+            }
+        }
+    };
 
     float mrun[4], srun[4];
 #pragma unroll
@@ -73,12 +158,34 @@ __global__ __launch_bounds__(256, 2) void k_lse_bf16(BfArgs a)
         srun[jt] = 0.0f;
     }
 
-    // per-thread pieces of a chunk: piece e = tid + 256 q covers row e/8, bytes (e%8)*16..+15
-    const int t_begin = split * a.tiles_per_split;
-    const int t_end = min(a.n_itiles, t_begin + a.tiles_per_split);
+    // fragment addressing inside a stage
+    const int sw = (lr >> 1) & 3;
+    const int offA = (64 * wi + lr) * 64, offB = (BI + 128 * wj + lr) * 64;
+    const int pk0 = ((0 + lh) ^ sw) * 16, pk1 = ((2 + lh) ^ sw) * 16;
+    bf8 a0[2], b0[4], a1[2], b1[4];
+    auto read_frags = [&](bf8(&af)[2], bf8(&bf)[4], int stage, int pk) {
+        const unsigned char *sb = ring + (stage & (NSTAGE - 1)) * STAGE_BYTES + pk;
+#pragma unroll
+        for (int it = 0; it < 2; ++it) af[it] = *reinterpret_cast<const bf8 *>(sb + offA + it * 32 * 64);
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) bf[jt] = *reinterpret_cast<const bf8 *>(sb + offB + jt * 32 * 64);
+    };
 
+    // ---- prologue: three stages in flight, stage 0 landed, its first fragments on the way ----
+    for (int k = 0; k < 3 && k < G; ++k)
+#pragma unroll
+        for (int q = 0; q < 5; ++q) issue_piece(q);
+    if (G > 2)
+        asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+    else if (G > 1)
+        asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_done_barrier();
+    read_frags(a0, b0, 0, pk0);
+
+    int g = 0;
     for (int t = t_begin; t < t_end; ++t) {
-        const int64_t col0 = (int64_t)t * BI;
         f16v acc[2][4];
 #pragma unroll
         for (int it = 0; it < 2; ++it)
@@ -87,97 +194,118 @@ __global__ __launch_bounds__(256, 2) void k_lse_bf16(BfArgs a)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[it][jt][r] = 0.0f;
 
-        uint4 pre[PIECES];
-        auto load_chunk = [&](int ch) {
-            const int kc0 = ch * KC;
-            const int kw16 = min(KC, kp - kc0) >> 3;   // valid 16-byte pieces per row (4 or 8)
+        for (int ch = 0; ch < n_chunks; ++ch, ++g) {
+            const bool more3 = g + 3 < G;   // stage g+3 exists: its loads are issued during this stage
+            read_frags(a1, b1, g, pk1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int q = 0; q < PIECES; ++q) {
-                int e = tid + 256 * q;
-                int row = e >> 3, part = e & 7;
-                const uint16_t *src = row < BI ? a.str + (col0 + row) * kp : a.res + (row0 + row - BI) * kp;
-                uint4 v = make_uint4(0u, 0u, 0u, 0u);
-                if (part < kw16) v = *reinterpret_cast<const uint4 *>(src + kc0 + part * 8);
-                pre[q] = v;
+            for (int jt = 0; jt < 4; ++jt) acc[0][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[0], b0[jt], acc[0][jt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more3) issue_piece(0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) acc[1][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[1], b0[jt], acc[1][jt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more3) issue_piece(1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) acc[0][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[0], b1[jt], acc[0][jt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more3) issue_piece(2);
+            if (g + 1 < G) {
+                // stage g+1 has landed for this wave: newer loads still in flight are stage g+2
+                // (5) and the 3 pieces of stage g+3 issued above
+                if (more3)
+                    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                else if (g + 2 < G)
+                    asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+                else
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                // ... and for all waves; everyone has also finished reading stage g-1 (whose ring
+                // slot the loads of stage g+3 go to) and, after this barrier, F0 may be refilled
+                lds_done_barrier();
+                read_frags(a0, b0, g + 1, pk0);
             }
-        };
-        load_chunk(0);
-
-        for (int ch = 0; ch < n_chunks; ++ch) {
-            __syncthreads();   // everyone is done reading the previous chunk
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int q = 0; q < PIECES; ++q) {
-                int e = tid + 256 * q;
-                *reinterpret_cast<uint4 *>(lds + (e >> 3) * ROWB + (e & 7) * 16) = pre[q];
-            }
-            if (ch == 0 && tid < BI) bias_lds[tid] = a.bias[col0 + tid];
-            __syncthreads();
-            if (ch + 1 < n_chunks) load_chunk(ch + 1);
-
-            const int ksteps = min(KC, kp - ch * KC) >> 4;   // 2 or 4
-            const unsigned char *pa = lds + (64 * wi + lr) * ROWB + lh * 16;
-            const unsigned char *pb = lds + (BI + 128 * wj + lr) * ROWB + lh * 16;
-            for (int ks = 0; ks < ksteps; ++ks) {
-                bf8 af[2], bfr[4];
-#pragma unroll
-                for (int it = 0; it < 2; ++it)
-                    af[it] = *reinterpret_cast<const bf8 *>(pa + it * 32 * ROWB + ks * 32);
-#pragma unroll
-                for (int jt = 0; jt < 4; ++jt)
-                    bfr[jt] = *reinterpret_cast<const bf8 *>(pb + jt * 32 * ROWB + ks * 32);
-#pragma unroll
-                for (int it = 0; it < 2; ++it)
-#pragma unroll
-                    for (int jt = 0; jt < 4; ++jt)
-                        acc[it][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[it], bfr[jt], acc[it][jt], 0, 0, 0);
+            for (int jt = 0; jt < 4; ++jt) acc[1][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[1], b1[jt], acc[1][jt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more3) {
+                issue_piece(3);
+                issue_piece(4);
             }
         }
 
         // ---- epilogue: fold 2 x 16 streamed points per resident row into (max, sum) ----------
+        // lazy stabiliser: exponents against the current integer running max; the slow branch
+        // (lift the max, rescale by an exact power of two) runs only when a sum leaves [0, 2^60)
+        const int bslot = (g - 1) & (NBIAS - 1);   // the last stage of this tile carried its bias
         float bias[2][16];
 #pragma unroll
         for (int it = 0; it < 2; ++it)
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
-                float4 bv = *reinterpret_cast<const float4 *>(&bias_lds[64 * wi + 32 * it + 8 * g4 + 4 * lh]);
+                float4 bv = *reinterpret_cast<const float4 *>(&bias_ring[bslot][64 * wi + 32 * it + 8 * g4 + 4 * lh]);
                 bias[it][4 * g4 + 0] = bv.x;
                 bias[it][4 * g4 + 1] = bv.y;
                 bias[it][4 * g4 + 2] = bv.z;
                 bias[it][4 * g4 + 3] = bv.w;
             }
+        float csum[4];
+        bool bad = false;
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt) {
-            float sc[2][16];
-            float mx = kNegInit;
+            const float m = mrun[jt];
+            float s0 = 0.0f, s1 = 0.0f;
 #pragma unroll
-            for (int it = 0; it < 2; ++it)
-#pragma unroll
-                for (int r = 0; r < 16; r += 2) {
-                    sc[it][r] = fmaf(acc[it][jt][r], a.cscale, bias[it][r]);
-                    sc[it][r + 1] = fmaf(acc[it][jt][r + 1], a.cscale, bias[it][r + 1]);
-                    mx = fmaxf(mx, fmaxf(sc[it][r], sc[it][r + 1]));
-                }
-            float mnew = fmaxf(mrun[jt], ceilf(mx));
-            float scale = fast_exp2(mrun[jt] - mnew);
-            float csum = 0.0f;
-#pragma unroll
-            for (int it = 0; it < 2; ++it)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) csum += fast_exp2(sc[it][r] - mnew);
-            srun[jt] = fmaf(srun[jt], scale, csum);
-            mrun[jt] = mnew;
+            for (int r = 0; r < 16; ++r) {
+                s0 += fast_exp2(fmaf(acc[0][jt][r], a.cscale, bias[0][r]) - m);
+                s1 += fast_exp2(fmaf(acc[1][jt][r], a.cscale, bias[1][r]) - m);
+            }
+            csum[jt] = s0 + s1;
+            bad = bad || !(csum[jt] < kLazyMax);
         }
+        if (__any(bad)) {
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) {
+                float mx = kNegInit;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    mx = fmaxf(mx, fmaf(acc[0][jt][r], a.cscale, bias[0][r]));
+                    mx = fmaxf(mx, fmaf(acc[1][jt][r], a.cscale, bias[1][r]));
+                }
+                float mnew = fmaxf(mrun[jt], ceilf(mx));
+                float s0 = 0.0f, s1 = 0.0f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    s0 += fast_exp2(fmaf(acc[0][jt][r], a.cscale, bias[0][r]) - mnew);
+                    s1 += fast_exp2(fmaf(acc[1][jt][r], a.cscale, bias[1][r]) - mnew);
+                }
+                csum[jt] = s0 + s1;
+                srun[jt] *= fast_exp2(mrun[jt] - mnew);
+                mrun[jt] = mnew;
+            }
+        }
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) srun[jt] += csum[jt];
     }
 
-    // ---- merge the 2 lane halves x 2 streamed-side waves of every resident row -------------
+    // ---- merge the 2 lane halves x 4 streamed-side waves of every resident row -------------
+    lds_done_barrier();   // the ring is free: reuse it for the merge
+    float2 *red = reinterpret_cast<float2 *>(ring);   // [BJ][8]
 #pragma unroll
-    for (int jt = 0; jt < 4; ++jt) red[128 * wj + 32 * jt + lr][2 * wi + lh] = make_float2(mrun[jt], srun[jt]);
+    for (int jt = 0; jt < 4; ++jt) red[(128 * wj + 32 * jt + lr) * 8 + 2 * wi + lh] = make_float2(mrun[jt], srun[jt]);
     __syncthreads();
-    {
-        float2 p0 = red[tid][0], p1 = red[tid][1], p2 = red[tid][2], p3 = red[tid][3];
-        float M = fmaxf(fmaxf(p0.x, p1.x), fmaxf(p2.x, p3.x));
-        double S = (double)(p0.y * fast_exp2(p0.x - M)) + (double)(p1.y * fast_exp2(p1.x - M)) +
-                   (double)(p2.y * fast_exp2(p2.x - M)) + (double)(p3.y * fast_exp2(p3.x - M));
+    if (tid < BJ) {
+        float M = kNegInit;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) M = fmaxf(M, red[tid * 8 + k].x);
+        double S = 0.0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            float2 q = red[tid * 8 + k];
+            S += (double)(q.y * fast_exp2(q.x - M));
+        }
         a.partial[(int64_t)split * a.partial_stride + row0 + tid] = make_double2((double)M, S);
     }
 }
@@ -194,24 +322,36 @@ fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
     a.cscale = (float)(2.0 * kLog2e / eps);
     a.n_jtiles = (int)ceil_div(res->cnt, BJ);
     a.n_itiles = (int)ceil_div(str->cnt, BI);
-    // enough (resident tile, split) work items for ~8 rounds over 2 workgroups per CU
-    int target = 16 * c->num_cu;
-    int splits = (int)ceil_div(target, a.n_jtiles);
-    if (splits > a.n_itiles) splits = a.n_itiles;
-    if (splits > kMaxSplits) splits = kMaxSplits;
-    if (splits < 1) splits = 1;
-    a.tiles_per_split = (int)ceil_div(a.n_itiles, splits);
-    a.splits = (int)ceil_div(a.n_itiles, a.tiles_per_split);
-    const int sj = (a.n_jtiles + 7) / 8, sg = (a.splits + 7) / 8;
-    const int work = sj * sg * 64;                 // super-tile grid, including idle corners
-    a.work_per_xcd = (work + 7) / 8;
+    // One workgroup per CU at a time.  Pick the number of splits of the streamed side that
+    // minimises  rounds x tiles-per-workgroup  (rounds = ceil(workgroups / CUs)), i.e. the time
+    // including the idle tail of the last round; prefer fewer, longer workgroups on near-ties.
+    {
+        int best_s = 1;
+        double best_cost = 1e300;
+        const int smax = a.n_itiles < kMaxSplits ? a.n_itiles : kMaxSplits;
+        for (int sp = 1; sp <= smax; ++sp) {
+            int tps = (int)ceil_div(a.n_itiles, sp);
+            int seff = (int)ceil_div(a.n_itiles, tps);
+            if (seff != sp) continue;
+            double rounds = (double)ceil_div((int64_t)a.n_jtiles * seff, c->num_cu);
+            double cost = rounds * (tps + 0.25);   // 0.25: pipeline fill and merge of a workgroup
+            if (cost < best_cost * 0.99) {
+                best_cost = cost;
+                best_s = sp;
+            }
+        }
+        a.splits = best_s;
+        a.tiles_per_split = (int)ceil_div(a.n_itiles, best_s);
+    }
+    const int total = a.n_jtiles * a.splits;
+    const int per = (total + 7) / 8;
     a.partial = (double2 *)P->partial;
     a.partial_stride = res->cnt_pad;
     if ((int64_t)a.n_jtiles * BJ > res->cnt_pad || (int64_t)a.n_itiles * BI > str->cnt_pad ||
         (size_t)a.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp & 31) != 0 || a.kp < 32)
         return fail(c, FS_ERR_DEVICE, "internal: bf16 launch shape exceeds the padded buffers");
     prof_begin(c, (double)res->cnt * (double)str->cnt);
-    hipLaunchKernelGGL(k_lse_bf16, dim3((unsigned)(a.work_per_xcd * 8)), dim3(256), 0, c->stream, a);
+    hipLaunchKernelGGL(k_lse_bf16, dim3((unsigned)(per * 8)), dim3(NT), 0, c->stream, a);
     prof_end(c);
     FS_HIP(c, hipGetLastError());
     *splits_out = a.splits;

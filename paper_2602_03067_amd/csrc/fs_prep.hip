@@ -149,22 +149,43 @@ __global__ void k_prep_f64(const void *pts, int dtype, int64_t cnt, int64_t cnt_
 }
 
 // ---- bfloat16 derived copy (bf16 matrix-core path); norms of the ROUNDED points ----------
+// Layout: the copy is stored in 1 KB tiles of 16 rows x 32 coordinates, tile (rb, ch) at
+// ((rb * n_chunks + ch) * 1024) bytes; inside a tile row r occupies 64 bytes and its 16-byte
+// piece p (coordinates 8p..8p+7 of the chunk) sits at position p ^ ((r >> 1) & 3).  This is
+// exactly the image a pipeline stage needs in LDS, so the streaming kernel fills LDS with
+// linear 1 KB direct loads and reads MFMA fragments without bank conflicts.
 __global__ void k_prep_bf16(const void *pts, int dtype, int64_t cnt, int64_t cnt_pad, int64_t d, int64_t ld, int kp,
                             uint16_t *out, float *bias, double *norm)
 {
     int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     int lane = threadIdx.x & 63;
     if (row >= cnt_pad) return;
+    const int n_chunks = kp >> 5;
+    const int64_t rb = row >> 4;
+    const int rl = (int)(row & 15);
     double nrm = 0.0;
-    for (int k = lane; k < kp; k += 64) {
-        uint16_t h = 0;
-        if (row < cnt && k < d) {
-            h = dtype == FS_BF16 ? ((const uint16_t *)pts)[row * ld + k]
-                                 : float_to_bf16(((const float *)pts)[row * ld + k]);
-            double v = (double)bf16_to_float(h);
-            nrm += v * v;
+    for (int pi = lane; pi < (kp >> 3); pi += 64) {   // one 16-byte piece = 8 coordinates
+        uint16_t h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            int k = pi * 8 + e;
+            h[e] = 0;
+            if (row < cnt && k < d) {
+                h[e] = dtype == FS_BF16 ? ((const uint16_t *)pts)[row * ld + k]
+                                        : float_to_bf16(((const float *)pts)[row * ld + k]);
+                double v = (double)bf16_to_float(h[e]);
+                nrm += v * v;
+            }
         }
-        out[row * kp + k] = h;
+        const int ch = pi >> 2, piece = pi & 3;
+        const int pos = piece ^ ((rl >> 1) & 3);
+        uint4 v;
+        v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+        v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+        v.z = (uint32_t)h[4] | ((uint32_t)h[5] << 16);
+        v.w = (uint32_t)h[6] | ((uint32_t)h[7] << 16);
+        *reinterpret_cast<uint4 *>(reinterpret_cast<unsigned char *>(out) + ((rb * n_chunks + ch) << 10) + rl * 64 +
+                                   pos * 16) = v;
     }
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_xor(nrm, off, 64);
     if (lane == 0) {
