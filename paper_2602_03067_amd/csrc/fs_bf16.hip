@@ -73,11 +73,15 @@ struct BfArgs {
 // 64-byte row segments, and a 256 x 256 tile needs 32 B/clk/CU at full MFMA rate.
 //
 // Schedule of one stage g in every wave (F0/F1 = fragment registers of the two 16-wide k-steps):
-//     read F1(g) | 8 MFMA on F0(g) | 4 MFMA on F1(g) | wait "stage g+1 landed" + barrier |
-//     read F0(g+1) | 4 MFMA on F1(g)
-// with the five direct loads of stage g+3 issued between the MFMA groups.  The loads are throttled
-// by the L1 path (a stage is 32 KB = ~630 cycles at 52 B/clk/CU), so they are issued while MFMAs
-// execute; the barrier and the LDS latency of the next fragments hide behind the last MFMA group.
+//     4 MFMA on F0(g) | read F1(g) | 4 MFMA on F0(g) | 4 MFMA on F1(g) |
+//     wait "stage g+1 landed" + barrier | read F0(g+1) | 4 MFMA on F1(g)
+// with the direct loads of stage g+3 issued between the first MFMAs by ONE of the two waves of
+// every SIMD (alternating per stage): VMEM issue blocks the wave when the L1 path is busy (a stage
+// is 32 KB = ~630 cycles at 52 B/clk/CU), and the sibling wave keeps the MFMA pipe busy meanwhile.
+// The barrier and the LDS latency of the next fragments hide behind the last MFMAs.
+// Ceiling: with random operands the matrix cores sustain ~1.83 PFLOP/s here (a loop of nothing but
+// this MFMA: 2.42 PFLOP/s on constant operands, 1.83 on uniform random ones), i.e. the chip is
+// power-limited well below the 2.5 PFLOP/s peak that the roofline fraction is quoted against.
 __global__ __launch_bounds__(NT, 1) void k_lse_bf16(BfArgs a)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char ring[NSTAGE * STAGE_BYTES];   // 131,072 B
@@ -133,19 +137,27 @@ __global__ __launch_bounds__(NT, 1) void k_lse_bf16(BfArgs a)
         reinterpret_cast<const unsigned char *>(a.res) + (((int64_t)jtile * 16 * n_chunks) << 10) + l * 16;
     const unsigned char *str_tiles = reinterpret_cast<const unsigned char *>(a.str) + l * 16;
 
-    int pt = t_begin, pch = 0, pg = 0;   // next stage to issue: tile, chunk, stage number
-    auto issue_piece = [&](int q) {      // q = 0..3: 1 KB of points, q = 4: bias, then advance
-        if (q < 4) {
-            const int sidx = 8 * q + w;
-            const unsigned char *src = q < 2 ? str_tiles + ((((int64_t)pt * 16 + sidx) * n_chunks + pch) << 10)
+    // Loads of a stage are issued by the four waves whose resident-side index wj equals the stage
+    // parity (one wave per SIMD), nine pieces each: eight 1 KB tiles (segments 4q + wi) and 256 B
+    // of bias.  A wave that stalls on the L1 path while issuing leaves the MFMA pipe of its SIMD to
+    // its sibling wave, which issues nothing during that stage.
+    int pg = wj, pch = wj, pt = t_begin;   // next stage this wave issues: number, chunk, tile
+    while (pch >= n_chunks) {
+        pch -= n_chunks;
+        ++pt;
+    }
+    auto issue_piece = [&](int q) {      // q = 0..7: 1 KB of points, q = 8: bias, then advance by two stages
+        if (q < 8) {
+            const int sidx = 4 * q + wi;
+            const unsigned char *src = q < 4 ? str_tiles + ((((int64_t)pt * 16 + sidx) * n_chunks + pch) << 10)
                                              : res_tiles + ((((int64_t)(sidx - 16)) * n_chunks + pch) << 10);
             dma16(src, ring_off + (pg & (NSTAGE - 1)) * STAGE_BYTES + sidx * 1024);
         } else {
-            // both resident-side halves (wj) load the same 256 bytes: every wave issues five loads
             dma4(a.bias + (int64_t)pt * BI + wi * 64 + l, bias_off + (pg & (NBIAS - 1)) * (BI * 4) + wi * 256);
-            ++pg;
-            if (++pch == n_chunks) {
-                pch = 0;
+            pg += 2;
+            pch += 2;
+            while (pch >= n_chunks) {
+                pch -= n_chunks;
                 ++pt;
             }
         }
@@ -172,15 +184,16 @@ __global__ __launch_bounds__(NT, 1) void k_lse_bf16(BfArgs a)
     };
 
     // ---- prologue: three stages in flight, stage 0 landed, its first fragments on the way ----
-    for (int k = 0; k < 3 && k < G; ++k)
+    // (even waves issue stages 0 and 2, odd waves stage 1)
+    while (pg < 3 && pg < G)
 #pragma unroll
-        for (int q = 0; q < 5; ++q) issue_piece(q);
-    if (G > 2)
-        asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
-    else if (G > 1)
-        asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-    else
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        for (int q = 0; q < 9; ++q) issue_piece(q);
+    if (wj == 0) {
+        if (G > 2)
+            asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     lds_done_barrier();
     read_frags(a0, b0, 0, pk0);
 
@@ -195,45 +208,62 @@ __global__ __launch_bounds__(NT, 1) void k_lse_bf16(BfArgs a)
                 for (int r = 0; r < 16; ++r) acc[it][jt][r] = 0.0f;
 
         for (int ch = 0; ch < n_chunks; ++ch, ++g) {
-            const bool more3 = g + 3 < G;   // stage g+3 exists: its loads are issued during this stage
+            // this wave issues stage g+3 now iff the parities match; it is then also the one that
+            // issued stage g+1 and has to see it landed before the barrier below
+            const bool mine = ((g + 1) & 1) == wj;
+            const bool issue = mine && g + 3 < G;
+#define FS_MFMA(IT, JT, AF, BF) acc[IT][JT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(AF[IT], BF[JT], acc[IT][JT], 0, 0, 0)
+#define FS_PIECE(Q)                          \
+    __builtin_amdgcn_sched_barrier(0);       \
+    if (issue) issue_piece(Q);               \
+    __builtin_amdgcn_sched_barrier(0)
+            // (only F0(g) is pending here, so the wait the compiler puts before the first MFMA is
+            // exactly "F0 has arrived"; F1 is requested behind the first MFMA group)
+            FS_MFMA(0, 0, a0, b0);
+            FS_PIECE(0);
+            FS_MFMA(0, 1, a0, b0);
+            FS_PIECE(1);
+            FS_MFMA(0, 2, a0, b0);
+            FS_PIECE(2);
+            FS_MFMA(0, 3, a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
             read_frags(a1, b1, g, pk1);
+            FS_PIECE(3);
+            FS_MFMA(1, 0, a0, b0);
+            FS_PIECE(4);
+            FS_MFMA(1, 1, a0, b0);
+            FS_PIECE(5);
+            FS_MFMA(1, 2, a0, b0);
+            FS_PIECE(6);
+            FS_MFMA(1, 3, a0, b0);
+            FS_PIECE(7);
+            FS_MFMA(0, 0, a1, b1);
+            FS_PIECE(8);
+            FS_MFMA(0, 1, a1, b1);
+            FS_MFMA(0, 2, a1, b1);
+            FS_MFMA(0, 3, a1, b1);
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int jt = 0; jt < 4; ++jt) acc[0][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[0], b0[jt], acc[0][jt], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (more3) issue_piece(0);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int jt = 0; jt < 4; ++jt) acc[1][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[1], b0[jt], acc[1][jt], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (more3) issue_piece(1);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int jt = 0; jt < 4; ++jt) acc[0][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[0], b1[jt], acc[0][jt], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (more3) issue_piece(2);
             if (g + 1 < G) {
-                // stage g+1 has landed for this wave: newer loads still in flight are stage g+2
-                // (5) and the 3 pieces of stage g+3 issued above
-                if (more3)
-                    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-                else if (g + 2 < G)
-                    asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-                else
-                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                // ... and for all waves; everyone has also finished reading stage g-1 (whose ring
-                // slot the loads of stage g+3 go to) and, after this barrier, F0 may be refilled
+                if (mine) {
+                    // stage g+1 (issued by this wave) has landed: the only newer loads of this wave
+                    // are the nine pieces of stage g+3 issued above
+                    if (issue)
+                        asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+                    else
+                        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                }
+                // ... and after the barrier for all waves; everyone has also finished reading stage
+                // g-1 (whose ring slot the loads of stage g+3 go to), and F0 may be refilled
                 lds_done_barrier();
                 read_frags(a0, b0, g + 1, pk0);
             }
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int jt = 0; jt < 4; ++jt) acc[1][jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[1], b1[jt], acc[1][jt], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (more3) {
-                issue_piece(3);
-                issue_piece(4);
-            }
+            FS_MFMA(1, 0, a1, b1);
+            FS_MFMA(1, 1, a1, b1);
+            FS_MFMA(1, 2, a1, b1);
+            FS_MFMA(1, 3, a1, b1);
+#undef FS_MFMA
+#undef FS_PIECE
         }
 
         // ---- epilogue: fold 2 x 16 streamed points per resident row into (max, sum) ----------
