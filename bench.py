@@ -25,6 +25,11 @@ if ROOT not in sys.path:
 # per second (x 2 flop per FMA = the published 157.3 TFLOP/s).
 VALU_LANE_SLOTS_PER_S = 256 * 4 * 32 * 2.4e9
 PEAKS = {"bf16": 2.5e15, "f64": 78.6e12}
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this script on the default size of each workload, scaled by what the same counters read for a
+# 1 GiB device copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); the summaries are under profiles/.
+MEASURED_TRAFFIC = {"lowdim_anneal": 141.98e6, "mnist_shape": 16173.99e6, "embedding": 4383.64e6,
+                    "transport_grad": 77.65e6}
 
 
 def algorithmic_slots_per_pair(d: int, exp_cost: float = 4.0) -> float:
@@ -130,7 +135,7 @@ def main() -> int:
                 "peak": VALU_LANE_SLOTS_PER_S / 1e12, "unit": "Tlane-op/s"}
         dtype = "f32"
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = MEASURED_TRAFFIC.get(w.name) if args.n is None else None
     roof["kernel"] = "streaming LSE half-step"
     roof["avg_launch_ms"] = avg_ms
     roof["launches"] = launches
