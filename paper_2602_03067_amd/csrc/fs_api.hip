@@ -147,6 +147,9 @@ size_t layout(const Ctx *c, const fs_problem *p, Prepared *P, char *base, size_t
             S.packed_d = base ? (double *)(base + o) : nullptr;
             o = A.take((size_t)S.cnt_pad * 8);
             S.norm_f = base ? (double *)(base + o) : nullptr;
+            P->ks = split_ksteps(p->d);
+            o = A.take((size_t)S.cnt_pad * P->ks * 32);
+            S.split = (base && P->ks) ? (uint16_t *)(base + o) : nullptr;
             break;
         case Path::F64:
             P->kp = (int)round_up(p->d, 4);

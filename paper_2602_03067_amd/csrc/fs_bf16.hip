@@ -37,20 +37,6 @@ constexpr float kLazyMax = 1.152921504606846976e18f;   // 2^60
 
 __device__ inline float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
 
-// Direct global -> LDS loads (no registers in between): lane l's 16 (4) bytes land at
-// lds_off + 16 l (4 l); lds_off must be wave-uniform.  Issued as inline assembly so that the
-// compiler does not serialise them against the LDS reads of OTHER ring slots; completion is
-// tracked by hand with s_waitcnt vmcnt (VMEM operations retire in order).
-__device__ inline void dma16(const void *g, unsigned lds_off)
-{
-    unsigned m = __builtin_amdgcn_readfirstlane(lds_off);
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m) : "memory", "m0");
-}
-__device__ inline void dma4(const void *g, unsigned lds_off)
-{
-    unsigned m = __builtin_amdgcn_readfirstlane(lds_off);
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(g), "s"(m) : "memory", "m0");
-}
 // all LDS reads of this wave have returned, then the workgroup barrier
 __device__ inline void lds_done_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 

@@ -21,6 +21,54 @@ constexpr float kNegInit = -3.0e38f;               // finite "-inf" seed of the 
 constexpr int kLowdMaxD = 16;                      // d <= 16: fp32 vector-ALU path
 constexpr int kMaxSplits = 64;                     // max column splits of one streaming pass
 
+// fp32-accurate scores on the bf16 matrix cores (low-d path).  A float v is the sum of three bf16
+// pieces v1 + v2 + v3 (each the bf16 rounding of what the previous ones leave).  A product c x_k y_k
+// is then the sum of the eight piece products of relative size >= 2^-24,
+//     x1 y1, x1 y2, x2 y1, x1 y3, x2 y2, x3 y1, x2 y3, x3 y2,
+// so a point is stored as one 16-byte "piece" of eight bf16 per coordinate:
+//     streamed role, coordinate k:  y1 y2 y1 y3 y2 y1 y3 y2      resident role:  x1 x1 x2 x1 x2 x3 x2 x3
+//     piece d (streamed):           b1 b2 b3  1  1  1  0  0      (resident):      1  1  1 m1 m2 m3  0  0
+// with b = the point's bias and m = minus the resident row's running max (an integer, exact in
+// three pieces).  One row of MFMA 32x32x16 steps over 16 ks = 8 (d + 1) padded slots then yields
+// score - max directly, with fp32 accumulation; measured error equals that of an fp32 FMA chain.
+// Direct global -> LDS loads (no registers in between): lane l's 16 (4) bytes land at
+// lds_off + 16 l (4 l); lds_off must be wave-uniform.  Issued as inline assembly so that the
+// compiler does not serialise them against the LDS reads of OTHER ring slots; completion is
+// tracked by hand with s_waitcnt vmcnt (VMEM operations retire in order).
+__device__ inline void dma16(const void *g, unsigned lds_off)
+{
+    unsigned m = __builtin_amdgcn_readfirstlane(lds_off);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m) : "memory", "m0");
+}
+__device__ inline void dma4(const void *g, unsigned lds_off)
+{
+    unsigned m = __builtin_amdgcn_readfirstlane(lds_off);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(g), "s"(m) : "memory", "m0");
+}
+
+inline int split_ksteps(int64_t d) { return (int)(8 * d + 6 + 15) / 16; }   // 1..9 for d = 1..16
+// Position (in 16-byte units) of piece `piece` inside the record of point `point`: 64-byte records
+// (ks = 2) are rotated so that the eight lanes the LDS serves per cycle read eight different bank
+// groups when 32 consecutive records are read at one piece; HBM holds the records already rotated,
+// so tiles are copied to LDS linearly.
+__host__ __device__ inline int split_piece_pos(int ks, int64_t point, int piece)
+{
+    return ks == 2 ? (piece ^ (int)((point >> 1) & 3)) : piece;
+}
+__device__ inline void split3(float v, __bf16 (&p)[3])
+{
+    p[0] = (__bf16)v;
+    const bool fin = fabsf(v) < INFINITY;   // an infinite bias (padding) stays in the first piece
+    float r = fin ? v - (float)p[0] : 0.0f;
+    p[1] = (__bf16)r;
+    r -= (float)p[1];
+    p[2] = (__bf16)r;
+}
+__device__ inline uint32_t bf16_pair(__bf16 lo, __bf16 hi)
+{
+    return (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+}
+
 enum class Path { LowD, F64, BF16 };
 
 // ---------------------------------------------------------------------------------------
@@ -78,6 +126,9 @@ struct Side {
     float *packed = nullptr;
     double *packed_d = nullptr;
     double *norm_f = nullptr;  // [cnt_pad] squared norms of the float-rounded centred points
+    // LowD: the packed floats again as [cnt_pad][16 ks] bf16 "split" records for the
+    // matrix cores (layout: see split_ksteps)
+    uint16_t *split = nullptr;
     // F64: double [cnt_pad][kp], kp = round_up(d, 4), bias in bias_d[cnt_pad]
     double *pts_d = nullptr;
     double *bias_d = nullptr;
@@ -93,6 +144,7 @@ struct Prepared {
     int64_t d = 0;
     int dp = 0;   // LowD: floats per packed point
     int dpd = 0;  // LowD: doubles per packed point (float64 score mode)
+    int ks = 0;   // LowD: 16-wide contraction steps of a split record
     double rho_max = 0.0;   // LowD: largest squared norm of a centred point (host copy)
     int halfsteps_per_eps = 2;    // LowD: half-steps the caller runs at one eps (error budget)
     bool force_precise = false;   // LowD: float64 scores regardless (marginal error evaluation)

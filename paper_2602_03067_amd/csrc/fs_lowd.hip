@@ -1,21 +1,22 @@
-// Low-dimension (d <= 16) streaming passes on the vector ALU.
+// Low-dimension (d <= 16) streaming passes.
 //
-// With three coordinates there is no dense contraction to give to the matrix
-// cores: a score costs d FMAs and the pass is bound by the exp2 rate.  Mapping:
-// every lane owns R resident rows (their pre-scaled coordinates and the running
-// (max, sum) live in registers, so the row reduction never crosses lanes); the
-// streamed points are staged in LDS in tiles of 256, packed as
-// (coord_0..coord_{d-1}, bias), so that one broadcast LDS read serves all 64 lanes
-// of a wave and all R rows of a lane.
+// The pass is bound by the exp2 rate of the vector ALU (one quarter-rate v_exp_f32 per pair), so
+// everything else is kept off that ALU as far as possible:
+//  * fp32-accuracy half-steps (k_lse_lowd_split) form the scores on the bf16 matrix cores from
+//    operands split into three bf16 pieces; the vector ALU does one exp2 and one add per pair;
+//  * float64-score half-steps and the plan application (k_lse_lowd<double>, k_apply_lowd) run on
+//    the vector ALU: every lane owns R resident rows (pre-scaled coordinates and the running
+//    (max, sum) in registers, so the row reduction never crosses lanes); the streamed points are
+//    staged in LDS in tiles of 256, packed as (coord_0..coord_{d-1}, bias), so that one broadcast
+//    LDS read serves all 64 lanes of a wave and all R rows of a lane.
 //
 // Scores are in base 2:  s_ij = (2 log2e / eps) <x_i, y_j> + bias_j  (Alg. 1, line "score tile
 // + bias", times log2 e), so exp and log are single v_exp_f32 / v_log_f32 instructions.
-// The online LSE of Alg. 1 is applied per register chunk of T columns; the running max is
-// kept integer-valued, so every rescale factor is an exact power of two.
+// The online LSE of Alg. 1 is applied per chunk of streamed points; the running max is kept
+// integer-valued, so every rescale factor is an exact power of two.
 //
-// Score type S: float when (log2e/eps) * max|x|^2 is small enough for fp32 scores to hold the
-// 1e-4 target, double otherwise (a score of magnitude 500 has an fp32 ulp of 6e-5).  In both
-// cases the exponent s_ij - m is formed in S and only then rounded to float.
+// Score precision: fp32 when (log2e/eps) * max|x|^2 is small enough for fp32 scores to hold the
+// 1e-4 target, float64 otherwise (a score of magnitude 500 has an fp32 ulp of 6e-5).
 #include "fs_internal.h"
 
 #include <stdlib.h>
@@ -180,6 +181,213 @@ __global__ __launch_bounds__(kBlock) void k_lse_lowd(const S *__restrict__ res, 
     }
 }
 
+// ---- fp32-accurate scores on the bf16 matrix cores ("split" records) -------------------------
+// On the vector ALU the d FMAs of a score cost as much as its exp2.  The fp32 matrix instructions
+// do not help: measured, their time adds to the vector ALU's (a K = 4 fp32 MFMA variant of this
+// pass gained 10 %).  The bf16 ones are 16 times faster and take only ~13 cycles of vector issue
+// each.  With the operands split into three bf16 pieces (see split_ksteps), KS = (8 d + 6)/16
+// rounded up MFMA 32x32x16 per 32 x 32 pairs (two for d = 3) deliver score - max at fp32 accuracy,
+// and the vector ALU is left with one exp2 and one add per pair.
+// A = 32 streamed points (lane l: point l%32, slots 8(l/32)..+7 of the K-step), B = 32 resident
+// rows, so a lane's 16 result registers are 16 streamed points of ONE resident row (l%32); the two
+// lane halves of a row are merged once at the end.  The running max sits in the operand B itself
+// (three slots against ones in A), so the lazy stabiliser costs nothing in the common path: when a
+// chunk sum leaves [0, 2^60), the wave zeroes those slots, recomputes the chunk's raw scores,
+// lifts the integer max, writes it back into B and takes the chunk's sums again.
+typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+template <int KS, int R, int TJ, int CH>
+__global__ __launch_bounds__(kBlock, 2) void k_lse_lowd_split(const float *__restrict__ res, const uint16_t *__restrict__ str,
+                                                             float cscale, int d, int dp, int tiles_per_split,
+                                                             int n_tiles, double2 *__restrict__ partial,
+                                                             int64_t partial_stride)
+{
+    constexpr int NP = 2 * KS;               // 16-byte pieces per record
+    constexpr int UPT = TJ * NP / kBlock;    // pieces each thread moves per tile
+    constexpr int NG = TJ / 32;              // groups of 32 streamed points per tile
+    static_assert(TJ * NP % kBlock == 0 && NG % CH == 0, "tile shape");
+    __shared__ Unit tile[2][TJ * NP];
+
+    const int tid = threadIdx.x;
+    const int w = tid >> 6, l = tid & 63;
+    const int lj = l & 31, lh = l >> 5;
+    const int64_t row0 = (int64_t)blockIdx.x * (128 * R) + w * (32 * R);
+    const bool holds_max = (lh == (d & 1));   // piece d = 2 (KS-1) + (d & 1) lives in K-step KS-1 of these lanes
+    auto lds_pos = [](int point, int piece) { return point * NP + split_piece_pos(KS, point, piece); };
+
+    bf8 b[R][KS];
+    float mrun[R], srun[R], stile[R];
+    auto set_max = [&](int r, float neg_m) {   // slots 3..5 of piece d <- pieces of -max
+        __bf16 q[3];
+        split3(neg_m, q);
+        if (holds_max) {
+            b[r][KS - 1][3] = q[0];
+            b[r][KS - 1][4] = q[1];
+            b[r][KS - 1][5] = q[2];
+        }
+    };
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const float *px = res + (row0 + 32 * r + lj) * dp;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int c = 2 * ks + lh;
+            __bf16 x[3];
+            split3(c < d ? px[c] * cscale : 0.0f, x);
+            bf8 v = {x[0], x[0], x[1], x[0], x[1], x[2], x[1], x[2]};
+            if (c == d) {
+                const __bf16 one = (__bf16)1.0f, zero = (__bf16)0.0f;
+                v = bf8{one, one, one, zero, zero, zero, zero, zero};
+            }
+            b[r][ks] = v;
+        }
+        mrun[r] = kNegInit;
+        srun[r] = 0.0f;
+        stile[r] = 0.0f;
+        set_max(r, -kNegInit);
+    }
+
+    const int t_begin = blockIdx.y * tiles_per_split;
+    const int t_end = min(n_tiles, t_begin + tiles_per_split);
+    const Unit *gsrc = reinterpret_cast<const Unit *>(str);
+
+    // a tile is a linear 16 KS TJ / 8 byte copy, moved by direct global -> LDS loads (no registers)
+    const unsigned tile_off = (unsigned)(size_t)&tile[0][0];
+    auto fetch = [&](int t, int bufi) {
+#pragma unroll
+        for (int q = 0; q < UPT; ++q)
+            dma16(gsrc + (int64_t)t * (TJ * NP) + q * kBlock + tid, tile_off + (bufi * (TJ * NP) + q * kBlock + w * 64) * 16);
+    };
+    if (t_begin < t_end) fetch(t_begin, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    auto load_a = [&](const Unit *tl, int grp, bf8(&av)[KS]) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) av[ks] = *reinterpret_cast<const bf8 *>(tl + lds_pos(grp * 32 + lj, 2 * ks + lh));
+    };
+    auto scores = [&](const bf8(&av)[KS], f16v(&dd)[R]) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            f16v z;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) z[e] = 0.0f;
+            dd[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[0], b[r][0], z, 0, 0, 0);
+#pragma unroll
+            for (int ks = 1; ks < KS; ++ks) dd[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[ks], b[r][ks], dd[r], 0, 0, 0);
+        }
+    };
+    // Sums of exp2(score - max) over one chunk of CH x 32 streamed points.  The chunk is a pipeline
+    // of CH x R steps (32 streamed points x 32 resident rows each): while the vector ALU takes the
+    // exponentials of step s, the matrix pipe computes step s + 1, its KS instructions spread evenly
+    // between them.  (Instructions of one wave overlap across the two pipes only if they alternate
+    // at this grain; a wave that issues its MFMAs back to back stalls the vector ALU.)
+    auto chunk_sums = [&](const Unit *tl, int c0, float(&csum)[R]) {
+        constexpr int NS = CH * R;
+        bf8 av[2][KS];
+        f16v dd[2];
+        f16v z;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) z[e] = 0.0f;
+        load_a(tl, c0, av[0]);
+        if (CH > 1 && R == 1) load_a(tl, c0 + 1, av[1]);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            dd[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[0][ks], b[0][ks], ks == 0 ? z : dd[0], 0, 0, 0);
+#pragma unroll
+        for (int st = 0; st < NS; ++st) {
+            const int g = st / R, r = st % R;
+            const int sn = st + 1, gn = sn / R, rn = sn % R;
+            // request the A operands of a later group into the buffer whose group is fully produced
+            if (R == 1) {
+                if (g + 2 < CH) load_a(tl, c0 + g + 2, av[g & 1]);
+            } else if (r == 0 && g + 1 < CH) {
+                load_a(tl, c0 + g + 1, av[(g + 1) & 1]);
+            }
+            float acc = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (sn < NS)
+                    dd[sn & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[gn & 1][ks], b[rn][ks], ks == 0 ? z : dd[sn & 1], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                const int e0 = 16 * ks / KS, e1 = 16 * (ks + 1) / KS;
+                float part = fast_exp2(dd[st & 1][e0]);
+#pragma unroll
+                for (int e = e0 + 1; e < e1; ++e) part += fast_exp2(dd[st & 1][e]);
+                acc = ks == 0 ? part : acc + part;
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            csum[r] = g == 0 ? acc : csum[r] + acc;
+        }
+    };
+
+    int buf = 0;
+    for (int t = t_begin; t < t_end; ++t) {
+        if (t + 1 < t_end) fetch(t + 1, buf ^ 1);   // that buffer was last read before the previous barrier
+        const Unit *tl = tile[buf];
+#pragma unroll 1
+        for (int c0 = 0; c0 < NG; c0 += CH) {
+            float csum[R];
+            chunk_sums(tl, c0, csum);
+            bool bad = false;
+#pragma unroll
+            for (int r = 0; r < R; ++r) bad = bad || !(csum[r] < kLazyMax);
+            if (__any(bad)) {
+                float mx[R];
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    mx[r] = kNegInit;
+                    set_max(r, 0.0f);
+                }
+#pragma unroll
+                for (int g = 0; g < CH; ++g) {
+                    bf8 av[KS];
+                    f16v dd[R];
+                    load_a(tl, c0 + g, av);
+                    scores(av, dd);
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) mx[r] = fmaxf(mx[r], dd[r][e]);
+                }
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    // the max of a row sits once in B and serves both lane halves: lift it for both
+                    const float mrow = fmaxf(mx[r], __shfl_xor(mx[r], 32));
+                    const float mnew = fmaxf(mrun[r], ceilf(mrow));
+                    const float scale = fast_exp2(mrun[r] - mnew);
+                    srun[r] *= scale;
+                    stile[r] *= scale;
+                    mrun[r] = mnew;
+                    set_max(r, -mnew);
+                }
+                chunk_sums(tl, c0, csum);   // all exponents are <= 0 now: no second check
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r) stile[r] += csum[r];
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            srun[r] += stile[r];
+            stile[r] = 0.0f;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of the next tile has landed
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    // merge the two lane halves (streamed points 8q+4h .. of every 32) of each resident row
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const float m = mrun[r], sv = srun[r];
+        const float mo = __shfl_xor(m, 32), so = __shfl_xor(sv, 32);
+        const float M = fmaxf(m, mo);
+        const float S = sv * fast_exp2(m - M) + so * fast_exp2(mo - M);
+        if (lh == 0) partial[(int64_t)blockIdx.y * partial_stride + row0 + 32 * r + lj] = make_double2((double)M, (double)S);
+    }
+}
+
 // ---- plan application (Alg. 2 / Alg. 4): the same pass with a value accumulator ----------
 // Every lane owns ONE resident row and PC columns of the output; the streamed tile carries
 // the PC values of each streamed point next to its coordinates.
@@ -262,14 +470,14 @@ __global__ __launch_bounds__(kBlock) void k_apply_lowd(const S *__restrict__ res
 
 constexpr int kApplyPC = 4;   // output columns per application pass
 
-template <typename S, int D>
-void launch_lse_d(int R, dim3 grid, hipStream_t st, const S *res, const S *str, S cscale, int tps, int n_tiles,
-                  double2 *partial, int64_t stride)
+template <int D>
+void launch_lse_d(int R, dim3 grid, hipStream_t st, const double *res, const double *str, double cscale, int tps,
+                  int n_tiles, double2 *partial, int64_t stride)
 {
     if (R == 2)
-        hipLaunchKernelGGL((k_lse_lowd<S, D, 2>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride);
+        hipLaunchKernelGGL((k_lse_lowd<double, D, 2>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride);
     else
-        hipLaunchKernelGGL((k_lse_lowd<S, D, 1>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride);
+        hipLaunchKernelGGL((k_lse_lowd<double, D, 1>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride);
 }
 
 template <typename S, int D>
@@ -292,12 +500,12 @@ void launch_apply_d(dim3 grid, hipStream_t st, const S *res, const S *str, const
     case 15: { constexpr int DD = 15; CALL; } break; default: { constexpr int DD = 16; CALL; } break;   \
     }
 
-PassShape shape_for(const Ctx *c, int64_t n_res, int64_t n_str, int R)
+PassShape shape_for(const Ctx *c, int64_t n_res, int64_t n_str, int rows_per_block, int tj = kTJ)
 {
     PassShape s;
-    s.rows_per_block = kBlock * R;
+    s.rows_per_block = rows_per_block;
     s.row_blocks = (int)ceil_div(n_res, s.rows_per_block);
-    int n_tiles = (int)ceil_div(n_str, kTJ);
+    int n_tiles = (int)ceil_div(n_str, tj);
     // measured at n = m = 262144: the pass time falls from 12.2 ms at 4 workgroups per CU to a
     // plateau of ~10.6 ms at 24..64 (more waves to hide LDS latency, finer load balance)
     int target = 32 * c->num_cu;
@@ -307,7 +515,7 @@ PassShape shape_for(const Ctx *c, int64_t n_res, int64_t n_str, int R)
     if (splits < 1) splits = 1;
     int tps = (int)ceil_div(n_tiles, splits);
     s.splits = (int)ceil_div(n_tiles, tps);
-    s.cols_per_split = (int64_t)tps * kTJ;
+    s.cols_per_split = (int64_t)tps * tj;
     return s;
 }
 
@@ -333,29 +541,56 @@ PassShape lowd_shape(const Ctx *c, int64_t n_res, int64_t n_str)
 {
     // two rows per lane halve the LDS reads per pair; four cost occupancy and were slower
     int R = n_res >= 32768 ? 2 : 1;
-    return shape_for(c, n_res, n_str, R);
+    return shape_for(c, n_res, n_str, kBlock * R);
+}
+
+// split-record pass: a wave owns kSplitR groups of 32 resident rows, a workgroup 128 kSplitR rows;
+// streamed tiles of kSplitTJ points (two LDS buffers of 32 KS kSplitTJ bytes), chunks of kSplitCH x 32
+// streamed points between two checks of the lazy stabiliser.  Measured at n = m = 262144, d = 3:
+// (R, TJ, CH) = (2,128,4) 6.62 ms, (2,256,4) 6.69, (4,256,2) 6.68, (2,256,8) 6.71, (1,128,4) 7.03.
+constexpr int kSplitR = 2, kSplitTJ = 128, kSplitCH = 4;
+
+template <int KS>
+void launch_lse_split(dim3 grid, hipStream_t st, const float *res, const uint16_t *str, float cscale, int d, int dp,
+                      int tps, int n_tiles, double2 *partial, int64_t stride)
+{
+    hipLaunchKernelGGL((k_lse_lowd_split<KS, kSplitR, kSplitTJ, kSplitCH>), grid, dim3(kBlock), 0, st, res, str, cscale, d,
+                       dp, tps, n_tiles, partial, stride);
 }
 
 fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out)
 {
-    PassShape s = lowd_shape(c, res->cnt, str->cnt);
-    const int R = s.rows_per_block / kBlock;
-    const int n_tiles = (int)ceil_div(str->cnt, kTJ);
-    const int tps = (int)(s.cols_per_split / kTJ);
+    // fp32-accuracy half-steps run on the bf16 matrix cores from the split records, float64 ones
+    // on the vector ALU
+    const bool precise = lowd_precise(P, eps);
+    const int tj = precise ? kTJ : kSplitTJ;
+    PassShape s = precise ? lowd_shape(c, res->cnt, str->cnt) : shape_for(c, res->cnt, str->cnt, 128 * kSplitR, tj);
+    const int n_tiles = (int)ceil_div(str->cnt, tj);
+    const int tps = (int)(s.cols_per_split / tj);
     // host-side shape checks: every access of the kernel stays inside the padded copies
-    if ((int64_t)s.row_blocks * s.rows_per_block > res->cnt_pad || (int64_t)n_tiles * kTJ > str->cnt_pad ||
-        (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes)
+    if ((int64_t)s.row_blocks * s.rows_per_block > res->cnt_pad || (int64_t)n_tiles * tj > str->cnt_pad ||
+        (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (!precise && P->ks != split_ksteps(P->d)))
         return fail(c, FS_ERR_DEVICE, "internal: low-d launch shape exceeds the padded buffers");
     const double cscale = 2.0 * kLog2e / eps;
     dim3 grid((unsigned)s.row_blocks, (unsigned)s.splits);
+    double2 *part = (double2 *)P->partial;
     prof_begin(c, (double)res->cnt * (double)str->cnt);
-    if (lowd_precise(P, eps)) {
-        FS_LOWD_DISPATCH((int)P->d, (launch_lse_d<double, DD>(R, grid, c->stream, res->packed_d, str->packed_d, cscale,
-                                                              tps, n_tiles, (double2 *)P->partial, res->cnt_pad)));
+    if (precise) {
+        const int R = s.rows_per_block / kBlock;
+        FS_LOWD_DISPATCH((int)P->d, (launch_lse_d<DD>(R, grid, c->stream, res->packed_d, str->packed_d, cscale, tps, n_tiles,
+                                                      part, res->cnt_pad)));
     } else {
-        FS_LOWD_DISPATCH((int)P->d, (launch_lse_d<float, DD>(R, grid, c->stream, res->packed, str->packed,
-                                                             (float)cscale, tps, n_tiles, (double2 *)P->partial,
-                                                             res->cnt_pad)));
+#define FS_SPLIT_CASE(K)                                                                                             \
+    case K:                                                                                                          \
+        launch_lse_split<K>(grid, c->stream, res->packed, str->split, (float)cscale, (int)P->d, P->dp, tps, n_tiles, part, \
+                            res->cnt_pad);                                                                           \
+        break;
+        switch (P->ks) {
+            FS_SPLIT_CASE(1) FS_SPLIT_CASE(2) FS_SPLIT_CASE(3) FS_SPLIT_CASE(4) FS_SPLIT_CASE(5)
+            FS_SPLIT_CASE(6) FS_SPLIT_CASE(7) FS_SPLIT_CASE(8) FS_SPLIT_CASE(9)
+        default: prof_end(c); return fail(c, FS_ERR_DEVICE, "internal: split record length");
+        }
+#undef FS_SPLIT_CASE
     }
     prof_end(c);
     FS_HIP(c, hipGetLastError());
@@ -366,14 +601,14 @@ fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
 size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t p)
 {
     (void)p;
-    PassShape s = shape_for(c, n_res, n_str, 1);
+    PassShape s = shape_for(c, n_res, n_str, kBlock);
     return (size_t)s.splits * (size_t)round_up(n_res, 1024) * kApplyPC * 4;
 }
 
 fs_status lowd_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, const float *V,
                      int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out)
 {
-    PassShape s = shape_for(c, res->cnt, str->cnt, 1);
+    PassShape s = shape_for(c, res->cnt, str->cnt, kBlock);
     const int n_tiles = (int)ceil_div(str->cnt, kTJ);
     const int tps = (int)(s.cols_per_split / kTJ);
     if ((int64_t)s.row_blocks * kBlock > res->cnt_pad || (int64_t)n_tiles * kTJ > str->cnt_pad ||

@@ -82,10 +82,21 @@ __global__ void k_mean_final(const double *partX, const double *partY, int block
     mean[k] = s * inv_cnt;
 }
 
+// piece d of a streamed-role split record: the bias in three bf16 pieces, then the three ones
+// that pick up the resident row's (negated) running max
+__device__ inline uint4 split_bias_piece(float bias)
+{
+    __bf16 b[3];
+    split3(bias, b);
+    const __bf16 one = (__bf16)1.0f;
+    return make_uint4(bf16_pair(b[0], b[1]), bf16_pair(b[2], one), bf16_pair(one, one), 0u);
+}
+
 // ---- low-d derived copies: coordinates centred at the common mean, packed with a bias slot;
 //      float (rounded once) and double (exact difference), each with its own squared norms ----
 __global__ void k_prep_lowd(const void *pts, int dtype, int64_t cnt, int64_t cnt_pad, int d, int64_t ld, int dp, int dpd,
-                            const double *mean, float *packed, double *packed_d, double *norm_f, double *norm)
+                            const double *mean, float *packed, double *packed_d, double *norm_f, double *norm,
+                            uint16_t *split, int ks)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= cnt_pad) return;
@@ -108,6 +119,20 @@ __global__ void k_prep_lowd(const void *pts, int dtype, int64_t cnt, int64_t cnt
     od[d] = -INFINITY;
     norm_f[i] = nf;
     norm[i] = nd;
+    if (split) {   // streamed-role split record of the float copy
+        uint4 *rec = reinterpret_cast<uint4 *>(split) + i * (2 * ks);
+        for (int k = 0; k < 2 * ks; ++k) {
+            uint4 u = make_uint4(0, 0, 0, 0);
+            if (k < d) {
+                __bf16 y[3];
+                split3(o[k], y);
+                u = make_uint4(bf16_pair(y[0], y[1]), bf16_pair(y[0], y[2]), bf16_pair(y[1], y[0]), bf16_pair(y[2], y[1]));
+            } else if (k == d) {
+                u = split_bias_piece(-INFINITY);
+            }
+            rec[split_piece_pos(ks, i, k)] = u;
+        }
+    }
 }
 
 // largest entry of two arrays, by one block (max is order independent, so this is deterministic)
@@ -198,6 +223,8 @@ __global__ void k_prep_bf16(const void *pts, int dtype, int64_t cnt, int64_t cnt
 // unshifted potential into the shifted one of Prop. 1 (fhat = f - alpha, ghat = g - beta).
 struct BiasSink {
     float *packed;          // LowD float copy: packed[i*dp + d], shifted by norm_f
+    uint16_t *split;        // LowD split records (same value as the float copy), ks > 0
+    int ks;
     double *packed_d;       // LowD double copy: packed_d[i*dpd + d], shifted by norm
     int dp, dpd, d;
     float *bias_f;          // BF16 path
@@ -211,7 +238,11 @@ struct BiasSink {
 __device__ inline void store_bias(const BiasSink &s, int64_t i, double pot, double inv_eps, double lw)
 {
     double b = ((pot - s.norm[i]) * inv_eps + lw) * kLog2e;
-    if (s.packed) s.packed[i * s.dp + s.d] = (float)(((pot - s.norm_f[i]) * inv_eps + lw) * kLog2e);
+    if (s.packed) {
+        const float bf = (float)(((pot - s.norm_f[i]) * inv_eps + lw) * kLog2e);
+        s.packed[i * s.dp + s.d] = bf;
+        if (s.split) reinterpret_cast<uint4 *>(s.split)[i * (2 * s.ks) + split_piece_pos(s.ks, i, s.d)] = split_bias_piece(bf);
+    }
     if (s.packed_d) s.packed_d[i * s.dpd + s.d] = b;
     if (s.bias_f) s.bias_f[i] = (float)b;
     if (s.bias_d) s.bias_d[i] = b;
@@ -320,6 +351,8 @@ BiasSink sink_of(const Prepared *P, const Side *s)
     BiasSink k{};
     k.packed = s->packed;
     k.packed_d = s->packed_d;
+    k.split = s->split;
+    k.ks = P->ks;
     k.dp = P->dp;
     k.dpd = P->dpd;
     k.d = (int)P->d;
@@ -377,7 +410,7 @@ fs_status launch_prepare(Ctx *c, const fs_problem *p, Prepared *P)
         for (auto &s : in)
             hipLaunchKernelGGL(k_prep_lowd, dim3((unsigned)ceil_div(s.S->cnt_pad, 256)), dim3(256), 0, c->stream, s.pts,
                                dtype, s.S->cnt, s.S->cnt_pad, (int)p->d, s.ld, P->dp, P->dpd, P->mean, s.S->packed,
-                               s.S->packed_d, s.S->norm_f, s.S->norm);
+                               s.S->packed_d, s.S->norm_f, s.S->norm, s.S->split, P->ks);
         hipLaunchKernelGGL(k_max2, dim3(1), dim3(256), 0, c->stream, P->X.norm, P->X.cnt, P->Y.norm, P->Y.cnt,
                            P->scalars + 7);
         FS_HIP(c, hipGetLastError());
