@@ -164,8 +164,10 @@ fs_status fs_apply_plan_T(fs_ctx *ctx, const fs_problem *prob, float eps, const 
 
 /*
  * Timing hook for benchmarks: average duration in milliseconds of the streaming
- * LSE kernel launches (the dominant kernel) recorded with HIP events on the
- * context's stream since the last call of this function, and their count.
+ * LSE kernel launches recorded with HIP events on the context's stream since the
+ * last call of this function, and their count.  Where a solve mixes two LSE
+ * kernels (low-d problems: fp32-accuracy and float64-score half-steps), the
+ * figures are those of the kernel with the larger total time (the dominant one).
  * Recording is off until fs_profile_enable(ctx, 1).  Synchronises the stream.
  */
 fs_status fs_profile_enable(fs_ctx *ctx, int32_t on);

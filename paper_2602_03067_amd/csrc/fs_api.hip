@@ -24,7 +24,7 @@ fs_status fail(Ctx *c, fs_status s, const char *fmt, ...)
     return s;
 }
 
-void prof_begin(Ctx *c, double pairs)
+void prof_begin(Ctx *c, double pairs, int kind)
 {
     if (!c->prof_on) return;
     if (c->ev_used + 2 > c->ev_pool.size()) {
@@ -35,7 +35,10 @@ void prof_begin(Ctx *c, double pairs)
         }
     }
     (void)hipEventRecord(c->ev_pool[c->ev_used], c->stream);
-    c->prof_pairs += pairs;
+    c->ev_kind.resize(c->ev_used / 2 + 1);
+    c->ev_pairs.resize(c->ev_used / 2 + 1);
+    c->ev_kind[c->ev_used / 2] = kind;
+    c->ev_pairs[c->ev_used / 2] = pairs;
 }
 
 void prof_end(Ctx *c)
@@ -500,20 +503,23 @@ fs_status fs_profile_read(fs_ctx *ctx, double *avg_ms, int64_t *launches, double
     if (!c) return FS_ERR_INVALID_ARG;
     if (c->device < 0) return fail(c, FS_ERR_DEVICE, "host-only context");
     FS_HIP(c, hipStreamSynchronize(c->stream));
-    double total = 0.0;
-    int64_t cnt = 0;
+    // per kernel kind; the one with the largest total time is the dominant kernel
+    double total[2] = {0.0, 0.0}, pairs[2] = {0.0, 0.0};
+    int64_t cnt[2] = {0, 0};
     for (size_t k = 0; k + 1 < c->ev_used; k += 2) {
         float ms = 0.0f;
         if (hipEventElapsedTime(&ms, c->ev_pool[k], c->ev_pool[k + 1]) == hipSuccess) {
-            total += ms;
-            ++cnt;
+            const int kind = c->ev_kind[k / 2] ? 1 : 0;
+            total[kind] += ms;
+            pairs[kind] += c->ev_pairs[k / 2];
+            ++cnt[kind];
         }
     }
-    if (avg_ms) *avg_ms = cnt ? total / (double)cnt : 0.0;
-    if (launches) *launches = cnt;
-    if (pairs_per_launch) *pairs_per_launch = cnt ? c->prof_pairs / (double)cnt : 0.0;
+    const int dom = total[1] > total[0] ? 1 : 0;
+    if (avg_ms) *avg_ms = cnt[dom] ? total[dom] / (double)cnt[dom] : 0.0;
+    if (launches) *launches = cnt[dom];
+    if (pairs_per_launch) *pairs_per_launch = cnt[dom] ? pairs[dom] / (double)cnt[dom] : 0.0;
     c->ev_used = 0;
-    c->prof_pairs = 0.0;
     return FS_OK;
 }
 

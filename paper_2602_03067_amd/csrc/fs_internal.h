@@ -86,7 +86,9 @@ struct Ctx {
     bool prof_on = false;
     std::vector<hipEvent_t> ev_pool;   // pairs (start, stop)
     size_t ev_used = 0;
-    double prof_pairs = 0.0;           // pair evaluations summed over recorded launches
+    std::vector<int> ev_kind;          // per recorded launch: which kernel it was (0 = the path's main
+                                       // kernel, 1 = the low-d float64-score kernel)
+    std::vector<double> ev_pairs;      // per recorded launch: pair evaluations
 };
 
 fs_status fail(Ctx *c, fs_status s, const char *fmt, ...);
@@ -146,6 +148,9 @@ struct Prepared {
     int dpd = 0;  // LowD: doubles per packed point (float64 score mode)
     int ks = 0;   // LowD: 16-wide contraction steps of a split record
     double rho_max = 0.0;   // LowD: largest squared norm of a centred point (host copy)
+    // LowD: size of the biases that the caller's potentials give, in base-2 units:
+    //   |bias| <= pot_mag_eps / eps + logw_mag   (potential part, scaling like 1/eps, and log-weight part)
+    double pot_mag_eps = 0.0, logw_mag = 0.0;
     int halfsteps_per_eps = 2;    // LowD: half-steps the caller runs at one eps (error budget)
     bool force_precise = false;   // LowD: float64 scores regardless (marginal error evaluation)
     int kp = 0;   // F64 / BF16: padded contraction length
@@ -174,8 +179,7 @@ struct PassShape {
 
 // fs_prep.hip
 fs_status launch_prepare(Ctx *c, const fs_problem *p, Prepared *P);
-fs_status launch_bias_from_user(Ctx *c, const Prepared *P, Side *side, const float *pot_user,
-                                double eps);
+fs_status launch_bias_from_user(Ctx *c, Prepared *P, Side *side, const float *pot_user, double eps);
 // `res_norm` is the norm array matching the coordinates the pass used (Side::norm or norm_f).
 fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, const double *res_norm, int splits,
                           double eps_cur, double eps_next_bias, float *user_out, double *abs_dev_sum);
@@ -210,7 +214,7 @@ fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
                    int *splits_out);
 
 // profiling helpers (fs_api.hip)
-void prof_begin(Ctx *c, double pairs);
+void prof_begin(Ctx *c, double pairs, int kind = 0);
 void prof_end(Ctx *c);
 
 }  // namespace fs

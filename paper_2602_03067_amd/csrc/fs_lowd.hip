@@ -522,19 +522,22 @@ PassShape shape_for(const Ctx *c, int64_t n_res, int64_t n_str, int rows_per_blo
 }  // namespace
 
 // Score precision of a half-step.  An fp32 score carries roundings of relative size 2^-24 at
-// magnitude Mag = 2 k rho_max (k = log2e/eps, rho_max = largest squared norm after centring);
+// magnitude Mag = max(2 k rho_max, largest |bias| the caller's potentials give), k = log2e/eps,
+// rho_max = largest squared norm after centring.  A single half-step can be off by about
+// 1.5 * 2^-24 * Mag * ln2 in units of eps when few terms dominate a row (no averaging), and,
 // measured against the float64 reference, a run of T half-steps at one eps accumulates about
-// 0.05 * T * 2^-24 * Mag in units of eps.  fp32 scores are used while that estimate stays
-// below 1.5e-5, i.e. Mag * T <= 5000; otherwise the scores are formed in float64.
+// 0.05..0.07 * T * 2^-24 * Mag.  fp32 scores are used while both stay below ~3e-5 and 2e-5, i.e.
+// Mag <= 480 and Mag * T <= 5000; otherwise the scores are formed in float64.
 // FS_LOWD_SCORE=f32|f64 overrides the choice (experiments and tests only).
 bool lowd_precise(const Prepared *P, double eps)
 {
-    static const char *force = getenv("FS_LOWD_SCORE");
+    const char *force = getenv("FS_LOWD_SCORE");
     if (force && force[0] == 'f' && force[1] == '3') return false;
     if (force && force[0] == 'f' && force[1] == '6') return true;
     if (P->force_precise) return true;
     const double k = kLog2e / eps;
-    return 2.0 * k * P->rho_max * (double)(P->halfsteps_per_eps > 0 ? P->halfsteps_per_eps : 1) > 5000.0;
+    const double mag = fmax(2.0 * k * P->rho_max, P->pot_mag_eps / eps + P->logw_mag);
+    return mag > 480.0 || mag * (double)(P->halfsteps_per_eps > 0 ? P->halfsteps_per_eps : 1) > 5000.0;
 }
 
 PassShape lowd_shape(const Ctx *c, int64_t n_res, int64_t n_str)
@@ -574,7 +577,7 @@ fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
     const double cscale = 2.0 * kLog2e / eps;
     dim3 grid((unsigned)s.row_blocks, (unsigned)s.splits);
     double2 *part = (double2 *)P->partial;
-    prof_begin(c, (double)res->cnt * (double)str->cnt);
+    prof_begin(c, (double)res->cnt * (double)str->cnt, precise ? 1 : 0);
     if (precise) {
         const int R = s.rows_per_block / kBlock;
         FS_LOWD_DISPATCH((int)P->d, (launch_lse_d<DD>(R, grid, c->stream, res->packed_d, str->packed_d, cscale, tps, n_tiles,

@@ -249,15 +249,33 @@ __device__ inline void store_bias(const BiasSink &s, int64_t i, double pot, doub
 }
 
 // ---- workspace potential (float64, unshifted) + bias from a user potential (float) -------
+// `absmax` (optional) receives the largest finite |(pot - norm)/eps| log2e in absmax[1] and the
+// largest finite |log w| log2e in absmax[0] (the two parts of a bias, which scale differently with
+// eps), as bit patterns of non-negative doubles (for those, the order of the bit patterns is the
+// order of the values)
 __global__ void k_bias_from_user(const float *pot_user, int64_t cnt, double inv_eps, const float *w,
-                                 double log_uniform, double *pot, BiasSink sink)
+                                 double log_uniform, double *pot, BiasSink sink, unsigned long long *absmax)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= cnt) return;
-    double pu = (double)pot_user[i];
-    pot[i] = pu;
-    double lw = w ? log((double)w[i]) : log_uniform;
-    store_bias(sink, i, pu, inv_eps, lw);
+    double mag_pot = 0.0, mag_w = 0.0;
+    if (i < cnt) {
+        double pu = (double)pot_user[i];
+        pot[i] = pu;
+        double lw = w ? log((double)w[i]) : log_uniform;
+        store_bias(sink, i, pu, inv_eps, lw);
+        mag_pot = fabs((pu - sink.norm[i]) * inv_eps) * kLog2e;
+        mag_w = fabs(lw) < INFINITY ? fabs(lw) * kLog2e : 0.0;   // zero-weight points never contribute
+    }
+    if (absmax) {
+        for (int off = 32; off > 0; off >>= 1) {
+            mag_pot = fmax(mag_pot, __shfl_xor(mag_pot, off));
+            mag_w = fmax(mag_w, __shfl_xor(mag_w, off));
+        }
+        if ((threadIdx.x & 63) == 0) {
+            if (mag_w > 0.0) atomicMax(absmax + 0, (unsigned long long)__double_as_longlong(mag_w));
+            if (mag_pot > 0.0) atomicMax(absmax + 1, (unsigned long long)__double_as_longlong(mag_pot));
+        }
+    }
 }
 
 // ---- merge the per-split (max, sum) statistics of a streaming pass -----------------------
@@ -430,11 +448,26 @@ fs_status launch_prepare(Ctx *c, const fs_problem *p, Prepared *P)
     return FS_OK;
 }
 
-fs_status launch_bias_from_user(Ctx *c, const Prepared *P, Side *side, const float *pot_user, double eps)
+fs_status launch_bias_from_user(Ctx *c, Prepared *P, Side *side, const float *pot_user, double eps)
 {
+    // low-d problems: the size of the bias enters the choice of the score precision (lowd_precise),
+    // so it is measured where a caller's potential comes in (one 8-byte read-back per entry call)
+    unsigned long long *absmax = nullptr;
+    if (P->path == Path::LowD) {
+        absmax = reinterpret_cast<unsigned long long *>(P->scalars + 5);   // scalars[5], [6]
+        fs_status st = launch_fill_f64(c, P->scalars + 5, 0.0, 2);
+        if (st != FS_OK) return st;
+    }
     hipLaunchKernelGGL(k_bias_from_user, dim3((unsigned)ceil_div(side->cnt, 256)), dim3(256), 0, c->stream, pot_user,
-                       side->cnt, 1.0 / eps, side->w, side->log_uniform, side->pot, sink_of(P, side));
+                       side->cnt, 1.0 / eps, side->w, side->log_uniform, side->pot, sink_of(P, side), absmax);
     FS_HIP(c, hipGetLastError());
+    if (absmax) {
+        double mag[2] = {0.0, 0.0};
+        FS_HIP(c, hipMemcpyAsync(mag, P->scalars + 5, 2 * sizeof(double), hipMemcpyDeviceToHost, c->stream));
+        FS_HIP(c, hipStreamSynchronize(c->stream));
+        if (mag[0] > P->logw_mag) P->logw_mag = mag[0];
+        if (mag[1] * eps > P->pot_mag_eps) P->pot_mag_eps = mag[1] * eps;
+    }
     return FS_OK;
 }
 

@@ -1,8 +1,10 @@
-"""GPU parity of the low-dimension (fp32 vector-ALU) path against the float64 oracle.
+"""GPU parity of the low-dimension (d <= 16) path against the float64 oracle.
 
 Tolerances: |f_gpu - f_oracle| / eps <= 1e-4 and marginal errors equal to 1e-5 (the
 fp32-path bar); plan applications 2e-4 relative (Frobenius) and 1e-3 of the largest entry.
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -51,8 +53,12 @@ def test_row_norms(ctx, oracle):
     np.testing.assert_allclose(got, oracle.row_norms(pts[:, :33]), rtol=1e-6)
 
 
+# d = 1..16 covers every record length of the matrix-core pass (1..9 contraction steps), sizes
+# cover one lane, ragged tails of row blocks and streamed tiles, and several splits
 @pytest.mark.parametrize("n,m,d", [(1, 1, 3), (5, 3, 1), (255, 257, 2), (1000, 777, 3),
-                                   (1024, 1024, 3), (2049, 513, 5), (300, 4100, 8), (700, 900, 16)])
+                                   (1024, 1024, 3), (2049, 513, 5), (300, 4100, 8), (700, 900, 16),
+                                   (129, 385, 4), (640, 130, 6), (333, 2000, 7), (513, 300, 10),
+                                   (260, 1100, 12), (1500, 260, 14)])
 def test_single_half_steps(ctx, oracle, n, m, d):
     rng = np.random.default_rng(n * 7 + m * 3 + d)
     x, y, a, b = _rand_problem(rng, n, m, d)
@@ -65,6 +71,39 @@ def test_single_half_steps(ctx, oracle, n, m, d):
     g_gpu = host(ctx.fs_update_g(prob, eps, dev(f)))
     assert max_err_over_eps(f_gpu, oracle.update_f(x, y, b, eps, g), eps) <= TOL
     assert max_err_over_eps(g_gpu, oracle.update_g(x, y, a, eps, f), eps) <= TOL
+
+
+@pytest.mark.parametrize("direction", [1, -1])
+@pytest.mark.parametrize("score", ["auto", "f32"])
+def test_running_max_is_lifted_many_times(ctx, oracle, direction, score):
+    """Potentials that rise steeply along the streamed index: every chunk of streamed points
+    exceeds the running max by more than 2^60, so the lazy stabiliser has to lift the max and
+    rescale in nearly every chunk (and never, after the first one, when they fall).
+    The biases reach 1900 in base 2: on its own the library takes float64 scores there
+    (tolerance 1e-4); with fp32 scores forced, the matrix-core pass is held to what fp32 can
+    give at that magnitude (ulp 1.2e-4 of the score)."""
+    rng = np.random.default_rng(11)
+    n, m, d = 700, 2300, 3
+    x, y, a, b = _rand_problem(rng, n, m, d)
+    eps = float(np.float32(0.3))
+    ramp = np.linspace(0.0, 400.0, m)[::direction]
+    g = (ramp + rng.standard_normal(m)).astype(np.float32)
+    say("update_f with a potential ramp of 400 (%s), scores %s, n=%d m=%d"
+        % ("rising" if direction > 0 else "falling", score, n, m))
+    prob = make_problem(x, y, a, b)
+    old = os.environ.get("FS_LOWD_SCORE")
+    try:
+        if score != "auto":
+            os.environ["FS_LOWD_SCORE"] = score
+        f_gpu = host(ctx.fs_update_f(prob, eps, dev(g)))
+    finally:
+        if old is None:
+            os.environ.pop("FS_LOWD_SCORE", None)
+        else:
+            os.environ["FS_LOWD_SCORE"] = old
+    err = max_err_over_eps(f_gpu, oracle.update_f(x, y, b, eps, g), eps)
+    say("  max|df|/eps = %.3e" % err)
+    assert err <= (TOL if score == "auto" else 1e-3)
 
 
 def test_uniform_weights_by_null_pointer(ctx, oracle):
