@@ -51,7 +51,10 @@ struct PassArgs {
     float *opart;            // [splits][partial_stride][PCH]
 };
 
-template <bool APPLY> __global__ __launch_bounds__(256) void k_pass_f64(PassArgs a)
+// (two workgroups per CU for the LSE pass: with at most 256 registers per lane the compiler keeps
+// the MFMA accumulators in ordinary VGPRs; with more it parks them in AGPRs and copies all of them
+// in and out around every group of MFMAs)
+template <bool APPLY> __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
 {
     __shared__ double res_lds[BR * LDR];          // 33,280 B; reused for the final merge
     __shared__ double str_lds[BC * LDS_];         // 16,896 B
@@ -94,6 +97,44 @@ template <bool APPLY> __global__ __launch_bounds__(256) void k_pass_f64(PassArgs
     const int t_begin = blockIdx.y * a.tiles_per_split;
     const int t_end = min(a.n_tiles, t_begin + a.tiles_per_split);
 
+    // Staging of one (tile, chunk) stage goes through registers: its global loads are issued
+    // before the MFMAs of the previous stage and stored to LDS after them, so the memory latency
+    // is covered by matrix work.
+    double2 pre_s[4], pre_r[4];
+    double pre_b = 0.0;
+    auto fetch = [&](int t, int ch) {
+        const int64_t col0 = (int64_t)t * BC;
+        const int kc0 = ch * KC;
+        const int kw = min(KC, kp - kc0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int e = tid + 256 * q;
+            const int cidx = e >> 4, kk = (e & 15) * 2;
+            pre_s[q] = make_double2(0.0, 0.0);   // zero beyond kp
+            if (kk < kw) pre_s[q] = *reinterpret_cast<const double2 *>(a.str + (col0 + cidx) * kp + kc0 + kk);
+            if (!res_cached) {
+                pre_r[q] = make_double2(0.0, 0.0);
+                if (kk < kw) pre_r[q] = *reinterpret_cast<const double2 *>(a.res + (row0 + cidx) * kp + kc0 + kk);
+            }
+        }
+        if (ch == 0 && tid < BC) pre_b = a.bias[col0 + tid];
+    };
+    auto stash = [&](int ch) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int e = tid + 256 * q;
+            const int cidx = e >> 4, kk = (e & 15) * 2;
+            str_lds[cidx * LDS_ + kk] = pre_s[q].x;
+            str_lds[cidx * LDS_ + kk + 1] = pre_s[q].y;
+            if (!res_cached) {
+                res_lds[cidx * LDR + kk] = pre_r[q].x;
+                res_lds[cidx * LDR + kk + 1] = pre_r[q].y;
+            }
+        }
+        if (ch == 0 && tid < BC) bias_lds[tid] = pre_b;
+    };
+    if (t_begin < t_end) fetch(t_begin, 0);
+
     for (int t = t_begin; t < t_end; ++t) {
         const int64_t col0 = (int64_t)t * BC;
         d4 acc[4];
@@ -104,29 +145,8 @@ template <bool APPLY> __global__ __launch_bounds__(256) void k_pass_f64(PassArgs
             const int kc0 = ch * KC;
             const int kw = min(KC, kp - kc0);
             __syncthreads();   // previous chunk (and the previous tile's epilogue) is done with LDS
-            // streamed chunk: 64 points x KC doubles, zero beyond kp
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                int e = tid + 256 * q;
-                int cidx = e >> 4, kk = (e & 15) * 2;
-                double2 v = make_double2(0.0, 0.0);
-                if (kk < kw) v = *reinterpret_cast<const double2 *>(a.str + (col0 + cidx) * kp + kc0 + kk);
-                str_lds[cidx * LDS_ + kk] = v.x;
-                str_lds[cidx * LDS_ + kk + 1] = v.y;
-            }
-            if (!res_cached) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    int e = tid + 256 * q;
-                    int r = e >> 4, kk = (e & 15) * 2;
-                    double2 v = make_double2(0.0, 0.0);
-                    if (kk < kw) v = *reinterpret_cast<const double2 *>(a.res + (row0 + r) * kp + kc0 + kk);
-                    res_lds[r * LDR + kk] = v.x;
-                    res_lds[r * LDR + kk + 1] = v.y;
-                }
-            }
+            stash(ch);
             if (ch == 0) {
-                if (tid < BC) bias_lds[tid] = a.bias[col0 + tid];
                 if constexpr (APPLY) {
                     for (int e = tid; e < BC * PCH; e += 256) {
                         int cidx = e >> 6, cc = e & 63;
@@ -136,15 +156,34 @@ template <bool APPLY> __global__ __launch_bounds__(256) void k_pass_f64(PassArgs
                 }
             }
             __syncthreads();
+            if (ch + 1 < n_chunks)
+                fetch(t, ch + 1);
+            else if (t + 1 < t_end)
+                fetch(t + 1, 0);
             const int kbase = res_cached ? kc0 : 0;
             const double *sa = str_lds + (16 * w + lj) * LDS_ + lg;
             const double *sb = res_lds + lj * LDR + kbase + lg;
-            for (int kk = 0; kk < kw; kk += 4) {
-                double av = sa[kk];
+            if (kw == KC) {
+                // full chunk: unrolled, so that the accumulators stay where the MFMAs want them
+                // for all eight steps (in the rolled loop below the compiler moves all of them
+                // between AGPRs and VGPRs in every iteration when it has to use AGPRs)
 #pragma unroll
-                for (int jt = 0; jt < 4; ++jt) {
-                    double bv = sb[jt * 16 * LDR + kk];
-                    acc[jt] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[jt], 0, 0, 0);
+                for (int kk = 0; kk < KC; kk += 4) {
+                    double av = sa[kk];
+#pragma unroll
+                    for (int jt = 0; jt < 4; ++jt) {
+                        double bv = sb[jt * 16 * LDR + kk];
+                        acc[jt] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[jt], 0, 0, 0);
+                    }
+                }
+            } else {
+                for (int kk = 0; kk < kw; kk += 4) {
+                    double av = sa[kk];
+#pragma unroll
+                    for (int jt = 0; jt < 4; ++jt) {
+                        double bv = sb[jt * 16 * LDR + kk];
+                        acc[jt] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[jt], 0, 0, 0);
+                    }
                 }
             }
         }
