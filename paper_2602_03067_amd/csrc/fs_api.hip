@@ -153,6 +153,8 @@ size_t layout(const Ctx *c, const fs_problem *p, Prepared *P, char *base, size_t
             P->ks = split_ksteps(p->d);
             o = A.take((size_t)S.cnt_pad * P->ks * 32);
             S.split = (base && P->ks) ? (uint16_t *)(base + o) : nullptr;
+            o = A.take(p->d <= 3 ? (size_t)S.cnt_pad * 96 : 0);
+            S.split_p = (base && p->d <= 3) ? (uint16_t *)(base + o) : nullptr;
             break;
         case Path::F64:
             P->kp = (int)round_up(p->d, 4);

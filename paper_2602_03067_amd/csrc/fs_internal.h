@@ -64,6 +64,24 @@ __device__ inline void split3(float v, __bf16 (&p)[3])
     r -= (float)p[1];
     p[2] = (__bf16)r;
 }
+__device__ inline void split3d(double v, __bf16 (&p)[3])   // three bf16 pieces of a finite double
+{
+    p[0] = (__bf16)(float)v;
+    double r = v - (double)(float)p[0];
+    p[1] = (__bf16)(float)r;
+    r -= (double)(float)p[1];
+    p[2] = (__bf16)(float)r;
+}
+// Grids of the leading digits of the "precise" split records (d <= 3, see k_lse_lowd_split):
+// gy = 2^(Ey-7) with 2^Ey > max |y_k| (from rho_max, the largest squared norm after centring) and
+// gx = 2^(Ex-7) with 2^Ex > (2 log2e/eps) max |x_k|; leading digits are multiples of the grid with
+// at most 8 significant bits.
+inline void split_grids(double rho_max, double eps, double *gx, double *gy)
+{
+    const double r = sqrt(rho_max > 1e-60 ? rho_max : 1e-60);
+    *gy = exp2(floor(log2(r)) + 1.0 - 7.0);
+    *gx = exp2(floor(log2(r * 2.0 * kLog2e / eps)) + 1.0 - 7.0);
+}
 __device__ inline uint32_t bf16_pair(__bf16 lo, __bf16 hi)
 {
     return (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
@@ -131,6 +149,8 @@ struct Side {
     // LowD: the packed floats again as [cnt_pad][16 ks] bf16 "split" records for the
     // matrix cores (layout: see split_ksteps)
     uint16_t *split = nullptr;
+    // LowD, d <= 3: "precise" split records [cnt_pad][48] bf16 built from the float64 copy
+    uint16_t *split_p = nullptr;
     // F64: double [cnt_pad][kp], kp = round_up(d, 4), bias in bias_d[cnt_pad]
     double *pts_d = nullptr;
     double *bias_d = nullptr;

@@ -197,50 +197,100 @@ __global__ __launch_bounds__(kBlock) void k_lse_lowd(const S *__restrict__ res, 
 typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 
-template <int KS, int R, int TJ, int CH>
-__global__ __launch_bounds__(kBlock, 2) void k_lse_lowd_split(const float *__restrict__ res, const uint16_t *__restrict__ str,
-                                                             float cscale, int d, int dp, int tiles_per_split,
-                                                             int n_tiles, double2 *__restrict__ partial,
-                                                             int64_t partial_stride)
+//
+// PRECISE = true is the variant for half-steps that need better than fp32 scores (d <= 3): the
+// operands come from the float64 copies, and the leading part of every term is put on a fixed
+// grid so that the large, mutually cancelling contributions are summed EXACTLY:
+//   c x_k = X1 + rx, X1 a multiple of gx = 2^(Ex-7) (|X1| <= 2^Ex), y_k = Y1 + ry likewise with gy,
+//   bias = (Ba + Bb + Bc) + rb with three 8-bit digits on the grid q = gx gy, max = integer >= q.
+// K-step 0 holds X1 Y1 (three slots), the bias digits against ones and the max pieces against
+// ones: all multiples of q inside a 2^24 q window, so the MFMA's aligned adder loses nothing, and
+// their sum is already within ~2^-6 of the largest term's size of the final score - max.  K-steps 1
+// and 2 add the residual products X1 ry, rx Y1, rx ry (residuals in three bf16 pieces) and rb, whose
+// fp32 accumulation error is relative to that small size.  Measured: error of score - max below
+// 2 ulp of the result for |score| up to 3e4 (an fp32 chain is off by 3.5e-3 there).
+struct SplitArgs {
+    const void *res;        // resident side: packed floats [.][dp] (fp32 variant) or doubles [.][dp] (precise)
+    const uint16_t *str;    // streamed side: split records
+    double cscale;          // 2 log2e / eps
+    double gx;              // precise: grid of the leading digit of c x
+    int d, dp;
+    int tiles_per_split, n_tiles;
+    double2 *partial;
+    int64_t partial_stride;
+};
+
+template <int KS, int R, int TJ, int CH, bool PRECISE>
+__global__ __launch_bounds__(kBlock, 2) void k_lse_lowd_split(SplitArgs a)
 {
     constexpr int NP = 2 * KS;               // 16-byte pieces per record
     constexpr int UPT = TJ * NP / kBlock;    // pieces each thread moves per tile
     constexpr int NG = TJ / 32;              // groups of 32 streamed points per tile
     static_assert(TJ * NP % kBlock == 0 && NG % CH == 0, "tile shape");
+    static_assert(!PRECISE || KS == 3, "the precise record has three K-steps");
     __shared__ Unit tile[2][TJ * NP];
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, l = tid & 63;
     const int lj = l & 31, lh = l >> 5;
+    const int d = a.d;
+    const int tiles_per_split = a.tiles_per_split, n_tiles = a.n_tiles;
+    double2 *__restrict__ partial = a.partial;
+    const int64_t partial_stride = a.partial_stride;
+    const uint16_t *__restrict__ str = a.str;
     const int64_t row0 = (int64_t)blockIdx.x * (128 * R) + w * (32 * R);
-    const bool holds_max = (lh == (d & 1));   // piece d = 2 (KS-1) + (d & 1) lives in K-step KS-1 of these lanes
+    // the piece with the ones and the max slots: piece d = 2 (KS-1) + (d & 1) in the fp32 record,
+    // piece 1 in the precise one
+    constexpr int MK = PRECISE ? 0 : KS - 1;
+    const bool holds_max = PRECISE ? (lh == 1) : (lh == (d & 1));
     auto lds_pos = [](int point, int piece) { return point * NP + split_piece_pos(KS, point, piece); };
 
     bf8 b[R][KS];
     float mrun[R], srun[R], stile[R];
-    auto set_max = [&](int r, float neg_m) {   // slots 3..5 of piece d <- pieces of -max
+    auto set_max = [&](int r, float neg_m) {   // slots 3..5 of that piece <- pieces of -max
         __bf16 q[3];
         split3(neg_m, q);
         if (holds_max) {
-            b[r][KS - 1][3] = q[0];
-            b[r][KS - 1][4] = q[1];
-            b[r][KS - 1][5] = q[2];
+            b[r][MK][3] = q[0];
+            b[r][MK][4] = q[1];
+            b[r][MK][5] = q[2];
         }
     };
+    const __bf16 one = (__bf16)1.0f, zero = (__bf16)0.0f;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const float *px = res + (row0 + 32 * r + lj) * dp;
+        if constexpr (!PRECISE) {
+            const float *px = static_cast<const float *>(a.res) + (row0 + 32 * r + lj) * a.dp;
+            const float cscale = (float)a.cscale;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const int c = 2 * ks + lh;
-            __bf16 x[3];
-            split3(c < d ? px[c] * cscale : 0.0f, x);
-            bf8 v = {x[0], x[0], x[1], x[0], x[1], x[2], x[1], x[2]};
-            if (c == d) {
-                const __bf16 one = (__bf16)1.0f, zero = (__bf16)0.0f;
-                v = bf8{one, one, one, zero, zero, zero, zero, zero};
+            for (int ks = 0; ks < KS; ++ks) {
+                const int c = 2 * ks + lh;
+                __bf16 x[3];
+                split3(c < d ? px[c] * cscale : 0.0f, x);
+                bf8 v = {x[0], x[0], x[1], x[0], x[1], x[2], x[1], x[2]};
+                if (c == d) v = bf8{one, one, one, zero, zero, zero, zero, zero};
+                b[r][ks] = v;
             }
-            b[r][ks] = v;
+        } else {
+            const double *px = static_cast<const double *>(a.res) + (row0 + 32 * r + lj) * a.dp;
+            __bf16 X1[3], rx[3][3];
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+                const double cx = c < d ? px[c] * a.cscale : 0.0;
+                const double x1 = rint(cx / a.gx) * a.gx;
+                X1[c] = (__bf16)(float)x1;
+                split3d(cx - x1, rx[c]);
+            }
+            // pieces 0..5 (piece = 2 ks + lh); see split_precise_record for the streamed counterparts
+            const bf8 p0 = {X1[0], X1[1], X1[2], zero, zero, zero, zero, zero};
+            const bf8 p1 = {one, one, one, zero, zero, zero, zero, zero};
+            const bf8 p5 = {one, one, one, zero, zero, rx[0][1], rx[1][1], rx[2][1]};
+            bf8 pc[3];
+#pragma unroll
+            for (int c = 0; c < 3; ++c) pc[c] = bf8{X1[c], X1[c], X1[c], rx[c][0], rx[c][1], rx[c][2], rx[c][0], rx[c][0]};
+            b[r][0] = lh ? p1 : p0;
+            b[r][1] = lh ? pc[1] : pc[0];
+            b[r][2] = lh ? p5 : pc[2];
         }
         mrun[r] = kNegInit;
         srun[r] = 0.0f;
@@ -554,20 +604,38 @@ PassShape lowd_shape(const Ctx *c, int64_t n_res, int64_t n_str)
 constexpr int kSplitR = 2, kSplitTJ = 128, kSplitCH = 4;
 
 template <int KS>
-void launch_lse_split(dim3 grid, hipStream_t st, const float *res, const uint16_t *str, float cscale, int d, int dp,
-                      int tps, int n_tiles, double2 *partial, int64_t stride)
+void launch_lse_split(dim3 grid, hipStream_t st, const SplitArgs &a)
 {
-    hipLaunchKernelGGL((k_lse_lowd_split<KS, kSplitR, kSplitTJ, kSplitCH>), grid, dim3(kBlock), 0, st, res, str, cscale, d,
-                       dp, tps, n_tiles, partial, stride);
+    hipLaunchKernelGGL((k_lse_lowd_split<KS, kSplitR, kSplitTJ, kSplitCH, false>), grid, dim3(kBlock), 0, st, a);
+}
+
+// Can a float64-score half-step run on the matrix cores from the precise split records?
+// d <= 3; integers (the running max) must be multiples of the grid q = gx gy of the exact part,
+// and the three 8-bit bias digits must cover the largest bias that can come up (the size the
+// caller's potentials give, or four times the cost scale for potentials the iteration produces).
+static bool precise_on_matrix_cores(const Prepared *P, const Side *res, const Side *str, double eps, double *gx_out)
+{
+    const char *force = getenv("FS_LOWD_PRECISE");   // "valu": experiments and tests only
+    if (force && force[0] == 'v') return false;
+    if (P->d > 3 || !str->split_p || !res->packed_d) return false;
+    double gx, gy;
+    split_grids(P->rho_max, eps, &gx, &gy);
+    const double q = gx * gy;
+    const double mag = 2.0 * (kLog2e / eps) * P->rho_max;
+    const double bias_bound = fmax(4.0 * mag, P->pot_mag_eps / eps + P->logw_mag);
+    *gx_out = gx;
+    return q <= 1.0 && bias_bound < 2097152.0 * q;
 }
 
 fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out)
 {
-    // fp32-accuracy half-steps run on the bf16 matrix cores from the split records, float64 ones
-    // on the vector ALU
+    // fp32-accuracy half-steps run on the bf16 matrix cores from the split records; float64-score
+    // ones too when d <= 3 (precise records), else on the vector ALU
     const bool precise = lowd_precise(P, eps);
-    const int tj = precise ? kTJ : kSplitTJ;
-    PassShape s = precise ? lowd_shape(c, res->cnt, str->cnt) : shape_for(c, res->cnt, str->cnt, 128 * kSplitR, tj);
+    double gx = 0.0;
+    const bool valu = precise && !precise_on_matrix_cores(P, res, str, eps, &gx);
+    const int tj = valu ? kTJ : kSplitTJ;
+    PassShape s = valu ? lowd_shape(c, res->cnt, str->cnt) : shape_for(c, res->cnt, str->cnt, 128 * kSplitR, tj);
     const int n_tiles = (int)ceil_div(str->cnt, tj);
     const int tps = (int)(s.cols_per_split / tj);
     // host-side shape checks: every access of the kernel stays inside the padded copies
@@ -578,22 +646,41 @@ fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
     dim3 grid((unsigned)s.row_blocks, (unsigned)s.splits);
     double2 *part = (double2 *)P->partial;
     prof_begin(c, (double)res->cnt * (double)str->cnt, precise ? 1 : 0);
-    if (precise) {
+    if (valu) {
         const int R = s.rows_per_block / kBlock;
         FS_LOWD_DISPATCH((int)P->d, (launch_lse_d<DD>(R, grid, c->stream, res->packed_d, str->packed_d, cscale, tps, n_tiles,
                                                       part, res->cnt_pad)));
     } else {
-#define FS_SPLIT_CASE(K)                                                                                             \
-    case K:                                                                                                          \
-        launch_lse_split<K>(grid, c->stream, res->packed, str->split, (float)cscale, (int)P->d, P->dp, tps, n_tiles, part, \
-                            res->cnt_pad);                                                                           \
-        break;
-        switch (P->ks) {
-            FS_SPLIT_CASE(1) FS_SPLIT_CASE(2) FS_SPLIT_CASE(3) FS_SPLIT_CASE(4) FS_SPLIT_CASE(5)
-            FS_SPLIT_CASE(6) FS_SPLIT_CASE(7) FS_SPLIT_CASE(8) FS_SPLIT_CASE(9)
-        default: prof_end(c); return fail(c, FS_ERR_DEVICE, "internal: split record length");
+        SplitArgs a{};
+        a.cscale = cscale;
+        a.d = (int)P->d;
+        a.tiles_per_split = tps;
+        a.n_tiles = n_tiles;
+        a.partial = part;
+        a.partial_stride = res->cnt_pad;
+        if (precise) {
+            a.res = res->packed_d;
+            a.dp = P->dpd;
+            a.str = str->split_p;
+            a.gx = gx;
+            hipLaunchKernelGGL((k_lse_lowd_split<3, kSplitR, kSplitTJ, kSplitCH, true>), grid, dim3(kBlock), 0, c->stream, a);
+        } else {
+            a.res = res->packed;
+            a.dp = P->dp;
+            a.str = str->split;
+            switch (P->ks) {
+            case 1: launch_lse_split<1>(grid, c->stream, a); break;
+            case 2: launch_lse_split<2>(grid, c->stream, a); break;
+            case 3: launch_lse_split<3>(grid, c->stream, a); break;
+            case 4: launch_lse_split<4>(grid, c->stream, a); break;
+            case 5: launch_lse_split<5>(grid, c->stream, a); break;
+            case 6: launch_lse_split<6>(grid, c->stream, a); break;
+            case 7: launch_lse_split<7>(grid, c->stream, a); break;
+            case 8: launch_lse_split<8>(grid, c->stream, a); break;
+            case 9: launch_lse_split<9>(grid, c->stream, a); break;
+            default: prof_end(c); return fail(c, FS_ERR_DEVICE, "internal: split record length");
+            }
         }
-#undef FS_SPLIT_CASE
     }
     prof_end(c);
     FS_HIP(c, hipGetLastError());

@@ -135,6 +135,55 @@ __global__ void k_prep_lowd(const void *pts, int dtype, int64_t cnt, int64_t cnt
     }
 }
 
+// ---- "precise" split records (d <= 3) from the float64 copy; layout of the six 16-byte pieces
+//      (resident counterparts in k_lse_lowd_split):
+//   0: Y1_0 Y1_1 Y1_2 0 0 0 0 0          leading digits on the grid gy          x  X1_0 X1_1 X1_2
+//   1: Ba Bb Bc 1 1 1 0 0                bias digits on the grid gx gy, ones    x  1 1 1 m1 m2 m3
+//   2+k: ry1 ry2 ry3 Y1 Y1 Y1 ry1 ry2    residual pieces of coordinate k        x  X1 X1 X1 rx1 rx2 rx3 rx1 rx1
+//   5: rb1 rb2 rb3 0 0 ry1_0 ry1_1 ry1_2 bias residual, second-order terms      x  1 1 1 0 0 rx2_0 rx2_1 rx2_2
+__device__ inline uint4 split_precise_bias_digits(double bias, double q)
+{
+    const __bf16 one = (__bf16)1.0f;
+    if (!(fabs(bias) < INFINITY)) {   // padding and zero-weight points: -inf
+        const __bf16 z = (__bf16)0.0f;
+        return make_uint4(bf16_pair((__bf16)(float)bias, z), bf16_pair(z, one), bf16_pair(one, one), 0u);
+    }
+    const double B = rint(bias / q);
+    const double ba = rint(B * (1.0 / 65536.0)) * 65536.0;
+    const double bb = rint((B - ba) * (1.0 / 256.0)) * 256.0;
+    const double bc = B - ba - bb;
+    return make_uint4(bf16_pair((__bf16)(float)(ba * q), (__bf16)(float)(bb * q)),
+                      bf16_pair((__bf16)(float)(bc * q), one), bf16_pair(one, one), 0u);
+}
+__device__ inline uint2 split_precise_bias_residual(double bias, double q)
+{
+    if (!(fabs(bias) < INFINITY)) return make_uint2(0u, 0u);
+    __bf16 rb[3];
+    split3d(bias - rint(bias / q) * q, rb);
+    return make_uint2(bf16_pair(rb[0], rb[1]), bf16_pair(rb[2], (__bf16)0.0f));
+}
+
+__global__ void k_prep_split_precise(const double *packed_d, int64_t cnt_pad, int d, int dpd, double gy, uint16_t *out)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= cnt_pad) return;
+    __bf16 Y1[3], ry[3][3];
+    for (int k = 0; k < 3; ++k) {
+        const double y = k < d ? packed_d[i * dpd + k] : 0.0;
+        const double y1 = rint(y / gy) * gy;
+        Y1[k] = (__bf16)(float)y1;
+        split3d(y - y1, ry[k]);
+    }
+    const __bf16 z = (__bf16)0.0f;
+    uint4 *rec = reinterpret_cast<uint4 *>(out) + i * 6;
+    rec[0] = make_uint4(bf16_pair(Y1[0], Y1[1]), bf16_pair(Y1[2], z), 0u, 0u);
+    rec[1] = split_precise_bias_digits(-INFINITY, 1.0);
+    for (int k = 0; k < 3; ++k)
+        rec[2 + k] = make_uint4(bf16_pair(ry[k][0], ry[k][1]), bf16_pair(ry[k][2], Y1[k]), bf16_pair(Y1[k], Y1[k]),
+                                bf16_pair(ry[k][0], ry[k][1]));
+    rec[5] = make_uint4(0u, 0u, bf16_pair(z, ry[0][0]), bf16_pair(ry[1][0], ry[2][0]));
+}
+
 // largest entry of two arrays, by one block (max is order independent, so this is deterministic)
 __global__ __launch_bounds__(256) void k_max2(const double *a, int64_t na, const double *b, int64_t nb, double *dst)
 {
@@ -225,6 +274,8 @@ struct BiasSink {
     float *packed;          // LowD float copy: packed[i*dp + d], shifted by norm_f
     uint16_t *split;        // LowD split records (same value as the float copy), ks > 0
     int ks;
+    uint16_t *split_p;      // LowD precise split records (d <= 3) and the grid of their bias digits
+    double q;
     double *packed_d;       // LowD double copy: packed_d[i*dpd + d], shifted by norm
     int dp, dpd, d;
     float *bias_f;          // BF16 path
@@ -244,6 +295,11 @@ __device__ inline void store_bias(const BiasSink &s, int64_t i, double pot, doub
         if (s.split) reinterpret_cast<uint4 *>(s.split)[i * (2 * s.ks) + split_piece_pos(s.ks, i, s.d)] = split_bias_piece(bf);
     }
     if (s.packed_d) s.packed_d[i * s.dpd + s.d] = b;
+    if (s.split_p) {
+        uint4 *rec = reinterpret_cast<uint4 *>(s.split_p) + i * 6;
+        rec[1] = split_precise_bias_digits(b, s.q);
+        *reinterpret_cast<uint2 *>(rec + 5) = split_precise_bias_residual(b, s.q);
+    }
     if (s.bias_f) s.bias_f[i] = (float)b;
     if (s.bias_d) s.bias_d[i] = b;
 }
@@ -364,9 +420,18 @@ __global__ void k_apply_finalize(const double2 *partial, int64_t stride, const f
     }
 }
 
-BiasSink sink_of(const Prepared *P, const Side *s)
+// `eps`: the eps of the pass that will stream these biases
+BiasSink sink_of(const Prepared *P, const Side *s, double eps)
 {
     BiasSink k{};
+    k.split_p = s->split_p;
+    if (s->split_p && eps > 0.0) {
+        double gx, gy;
+        split_grids(P->rho_max, eps, &gx, &gy);
+        k.q = gx * gy;
+    } else {
+        k.split_p = nullptr;
+    }
     k.packed = s->packed;
     k.packed_d = s->packed_d;
     k.split = s->split;
@@ -435,6 +500,13 @@ fs_status launch_prepare(Ctx *c, const fs_problem *p, Prepared *P)
         // the host chooses the score precision of each half-step from this number
         FS_HIP(c, hipMemcpyAsync(&P->rho_max, P->scalars + 7, sizeof(double), hipMemcpyDeviceToHost, c->stream));
         FS_HIP(c, hipStreamSynchronize(c->stream));
+        if (p->d <= 3) {   // the grid of the precise records' leading digits depends on rho_max
+            double gx, gy;
+            split_grids(P->rho_max, 1.0, &gx, &gy);
+            for (auto &s : in)
+                hipLaunchKernelGGL(k_prep_split_precise, dim3((unsigned)ceil_div(s.S->cnt_pad, 256)), dim3(256), 0,
+                                   c->stream, s.S->packed_d, s.S->cnt_pad, (int)p->d, P->dpd, gy, s.S->split_p);
+        }
     } else if (P->path == Path::F64) {
         for (auto &s : in)
             hipLaunchKernelGGL(k_prep_f64, dim3((unsigned)ceil_div(s.S->cnt_pad, 4)), dim3(256), 0, c->stream, s.pts,
@@ -459,7 +531,7 @@ fs_status launch_bias_from_user(Ctx *c, Prepared *P, Side *side, const float *po
         if (st != FS_OK) return st;
     }
     hipLaunchKernelGGL(k_bias_from_user, dim3((unsigned)ceil_div(side->cnt, 256)), dim3(256), 0, c->stream, pot_user,
-                       side->cnt, 1.0 / eps, side->w, side->log_uniform, side->pot, sink_of(P, side), absmax);
+                       side->cnt, 1.0 / eps, side->w, side->log_uniform, side->pot, sink_of(P, side, eps), absmax);
     FS_HIP(c, hipGetLastError());
     if (absmax) {
         double mag[2] = {0.0, 0.0};
@@ -478,7 +550,7 @@ fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, const double *re
     double *dev_part = abs_dev_sum ? P->dev_part : nullptr;   // per-block sums of the marginal deviation
     hipLaunchKernelGGL(k_finalize, dim3(blocks), dim3(256), 0, c->stream, (const double2 *)P->partial, res->cnt_pad,
                        splits, res->cnt, eps_cur, eps_next_bias > 0.0 ? 1.0 / eps_next_bias : 0.0, res->w,
-                       res->log_uniform, res_norm, res->pot, sink_of(P, res), user_out, dev_part);
+                       res->log_uniform, res_norm, res->pot, sink_of(P, res, eps_next_bias), user_out, dev_part);
     if (abs_dev_sum)
         hipLaunchKernelGGL(k_sum_to, dim3(1), dim3(256), 0, c->stream, dev_part, (int64_t)blocks, abs_dev_sum);
     FS_HIP(c, hipGetLastError());
