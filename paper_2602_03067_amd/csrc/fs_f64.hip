@@ -26,7 +26,8 @@ namespace {
 typedef double d4 __attribute__((ext_vector_type(4)));
 
 constexpr int BR = 64;     // resident rows per workgroup
-constexpr int BC = 64;     // streamed points per tile
+constexpr int IT = 1;      // 16-point streamed blocks per wave (two were slower: 0.77 vs 0.72 ms at d = 64)
+constexpr int BC = 64 * IT;   // streamed points per tile
 constexpr int KC = 32;     // contraction chunk staged for the streamed points
 constexpr int KRES = 64;   // resident coordinates kept in LDS across the pass
 constexpr int LDR = KRES + 1;   // odd leading dimensions: conflict-free 8-byte column reads
@@ -100,19 +101,19 @@ template <bool APPLY> __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pa
     // Staging of one (tile, chunk) stage goes through registers: its global loads are issued
     // before the MFMAs of the previous stage and stored to LDS after them, so the memory latency
     // is covered by matrix work.
-    double2 pre_s[4], pre_r[4];
+    double2 pre_s[4 * IT], pre_r[4];
     double pre_b = 0.0;
     auto fetch = [&](int t, int ch) {
         const int64_t col0 = (int64_t)t * BC;
         const int kc0 = ch * KC;
         const int kw = min(KC, kp - kc0);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < 4 * IT; ++q) {
             const int e = tid + 256 * q;
             const int cidx = e >> 4, kk = (e & 15) * 2;
             pre_s[q] = make_double2(0.0, 0.0);   // zero beyond kp
             if (kk < kw) pre_s[q] = *reinterpret_cast<const double2 *>(a.str + (col0 + cidx) * kp + kc0 + kk);
-            if (!res_cached) {
+            if (!res_cached && q < 4) {
                 pre_r[q] = make_double2(0.0, 0.0);
                 if (kk < kw) pre_r[q] = *reinterpret_cast<const double2 *>(a.res + (row0 + cidx) * kp + kc0 + kk);
             }
@@ -121,12 +122,12 @@ template <bool APPLY> __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pa
     };
     auto stash = [&](int ch) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < 4 * IT; ++q) {
             const int e = tid + 256 * q;
             const int cidx = e >> 4, kk = (e & 15) * 2;
             str_lds[cidx * LDS_ + kk] = pre_s[q].x;
             str_lds[cidx * LDS_ + kk + 1] = pre_s[q].y;
-            if (!res_cached) {
+            if (!res_cached && q < 4) {
                 res_lds[cidx * LDR + kk] = pre_r[q].x;
                 res_lds[cidx * LDR + kk + 1] = pre_r[q].y;
             }
@@ -137,9 +138,11 @@ template <bool APPLY> __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pa
 
     for (int t = t_begin; t < t_end; ++t) {
         const int64_t col0 = (int64_t)t * BC;
-        d4 acc[4];
+        d4 acc[IT][4];
 #pragma unroll
-        for (int jt = 0; jt < 4; ++jt) acc[jt] = d4{0.0, 0.0, 0.0, 0.0};
+        for (int it = 0; it < IT; ++it)
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) acc[it][jt] = d4{0.0, 0.0, 0.0, 0.0};
 
         for (int ch = 0; ch < n_chunks; ++ch) {
             const int kc0 = ch * KC;
@@ -161,111 +164,114 @@ template <bool APPLY> __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pa
             else if (t + 1 < t_end)
                 fetch(t + 1, 0);
             const int kbase = res_cached ? kc0 : 0;
-            const double *sa = str_lds + (16 * w + lj) * LDS_ + lg;
+            const double *sa = str_lds + (16 * IT * w + lj) * LDS_ + lg;
             const double *sb = res_lds + lj * LDR + kbase + lg;
+            auto kstep = [&](int kk) {
+                double av[IT], bv[4];
+#pragma unroll
+                for (int it = 0; it < IT; ++it) av[it] = sa[it * 16 * LDS_ + kk];
+#pragma unroll
+                for (int jt = 0; jt < 4; ++jt) bv[jt] = sb[jt * 16 * LDR + kk];
+#pragma unroll
+                for (int it = 0; it < IT; ++it)
+#pragma unroll
+                    for (int jt = 0; jt < 4; ++jt)
+                        acc[it][jt] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[it], bv[jt], acc[it][jt], 0, 0, 0);
+            };
             if (kw == KC) {
                 // full chunk: unrolled, so that the accumulators stay where the MFMAs want them
                 // for all eight steps (in the rolled loop below the compiler moves all of them
                 // between AGPRs and VGPRs in every iteration when it has to use AGPRs)
 #pragma unroll
-                for (int kk = 0; kk < KC; kk += 4) {
-                    double av = sa[kk];
-#pragma unroll
-                    for (int jt = 0; jt < 4; ++jt) {
-                        double bv = sb[jt * 16 * LDR + kk];
-                        acc[jt] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[jt], 0, 0, 0);
-                    }
-                }
+                for (int kk = 0; kk < KC; kk += 4) kstep(kk);
             } else {
-                for (int kk = 0; kk < kw; kk += 4) {
-                    double av = sa[kk];
-#pragma unroll
-                    for (int jt = 0; jt < 4; ++jt) {
-                        double bv = sb[jt * 16 * LDR + kk];
-                        acc[jt] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[jt], 0, 0, 0);
-                    }
-                }
+                for (int kk = 0; kk < kw; kk += 4) kstep(kk);
             }
         }
 
-        // ---- tile epilogue: scores of this lane = cscale * acc + bias of its streamed points
-        double bias[4];
+        // ---- tile epilogue, one 16-point streamed block at a time: scores of this lane =
+        //      cscale * acc + bias of its four streamed points
 #pragma unroll
-        for (int r = 0; r < 4; ++r) bias[r] = bias_lds[16 * w + 4 * r + lg];
+        for (int it = 0; it < IT; ++it) {
+            const int sp0 = 16 * IT * w + 16 * it;   // first streamed point of this block within the tile
+            double bias[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) bias[r] = bias_lds[sp0 + 4 * r + lg];
 
-        if constexpr (!APPLY) {
-#pragma unroll
-            for (int jt = 0; jt < 4; ++jt) {
-                double s[4];
-                float mx = kNegInit;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    s[r] = fma(acc[jt][r], a.cscale, bias[r]);
-                    mx = fmaxf(mx, (float)s[r]);
-                }
-                float mnew = fmaxf(mrun[jt], ceilf(mx));
-                float scale = fast_exp2(mrun[jt] - mnew);
-                double md = (double)mnew;
-                float csum = 0.0f;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) csum += fast_exp2((float)(s[r] - md));
-                srun[jt] = fmaf(srun[jt], scale, csum);
-                mrun[jt] = mnew;
-            }
-        } else {
-            double s[4][4];
-            float mx[4];
-            bool raise = false;
-#pragma unroll
-            for (int jt = 0; jt < 4; ++jt) {
-                float m = kNegInit;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    s[jt][r] = fma(acc[jt][r], a.cscale, bias[r]);
-                    m = fmaxf(m, (float)s[jt][r]);
-                }
-                // the stabiliser of a resident row must be common to the four lane groups,
-                // because the second MFMA sums over them
-                m = fmaxf(m, __shfl_xor(m, 16, 64));
-                m = fmaxf(m, __shfl_xor(m, 32, 64));
-                mx[jt] = m;
-                raise = raise || (m > mrun[jt] + 40.0f);
-            }
-            if (__any(raise)) {
-                // rare: lift the (integer) stabilisers and rescale sums and accumulators exactly
+            if constexpr (!APPLY) {
 #pragma unroll
                 for (int jt = 0; jt < 4; ++jt) {
-                    float mnew = fmaxf(mrun[jt], ceilf(mx[jt]));
-                    float scale = fast_exp2(mrun[jt] - mnew);
-                    srun[jt] *= scale;
-                    mrun[jt] = mnew;
+                    double s[4];
+                    float mx = kNegInit;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        // accumulator register r holds resident row 4r + lg of this column block
-                        double sc = (double)__shfl(scale, 4 * r + lg, 64);
+                        s[r] = fma(acc[it][jt][r], a.cscale, bias[r]);
+                        mx = fmaxf(mx, (float)s[r]);
+                    }
+                    float mnew = fmaxf(mrun[jt], ceilf(mx));
+                    float scale = fast_exp2(mrun[jt] - mnew);
+                    double md = (double)mnew;
+                    float csum = 0.0f;
 #pragma unroll
-                        for (int ct = 0; ct < 4; ++ct) O[jt][ct][r] *= sc;
+                    for (int r = 0; r < 4; ++r) csum += fast_exp2((float)(s[r] - md));
+                    srun[jt] = fmaf(srun[jt], scale, csum);
+                    mrun[jt] = mnew;
+                }
+            } else {
+                double s[4][4];
+                float mx[4];
+                bool raise = false;
+#pragma unroll
+                for (int jt = 0; jt < 4; ++jt) {
+                    float m = kNegInit;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        s[jt][r] = fma(acc[it][jt][r], a.cscale, bias[r]);
+                        m = fmaxf(m, (float)s[jt][r]);
+                    }
+                    // the stabiliser of a resident row must be common to the four lane groups,
+                    // because the second MFMA sums over them
+                    m = fmaxf(m, __shfl_xor(m, 16, 64));
+                    m = fmaxf(m, __shfl_xor(m, 32, 64));
+                    mx[jt] = m;
+                    raise = raise || (m > mrun[jt] + 40.0f);
+                }
+                if (__any(raise)) {
+                    // rare: lift the (integer) stabilisers and rescale sums and accumulators exactly
+#pragma unroll
+                    for (int jt = 0; jt < 4; ++jt) {
+                        float mnew = fmaxf(mrun[jt], ceilf(mx[jt]));
+                        float scale = fast_exp2(mrun[jt] - mnew);
+                        srun[jt] *= scale;
+                        mrun[jt] = mnew;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            // accumulator register r holds resident row 4r + lg of this column block
+                            double sc = (double)__shfl(scale, 4 * r + lg, 64);
+#pragma unroll
+                            for (int ct = 0; ct < 4; ++ct) O[jt][ct][r] *= sc;
+                        }
                     }
                 }
-            }
 #pragma unroll
-            for (int jt = 0; jt < 4; ++jt) {
-                double md = (double)mrun[jt];
-                double E[4];
-                float csum = 0.0f;
+                for (int jt = 0; jt < 4; ++jt) {
+                    double md = (double)mrun[jt];
+                    double E[4];
+                    float csum = 0.0f;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float e = fast_exp2((float)(s[jt][r] - md));
-                    csum += e;
-                    E[r] = (double)e;
-                }
-                srun[jt] += csum;
+                    for (int r = 0; r < 4; ++r) {
+                        float e = fast_exp2((float)(s[jt][r] - md));
+                        csum += e;
+                        E[r] = (double)e;
+                    }
+                    srun[jt] += csum;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
+                    for (int r = 0; r < 4; ++r) {
 #pragma unroll
-                    for (int ct = 0; ct < 4; ++ct) {
-                        double vv = (double)vt[(16 * w + 4 * r + lg) * PCH + 16 * ct + lj];
-                        O[jt][ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(E[r], vv, O[jt][ct], 0, 0, 0);
+                        for (int ct = 0; ct < 4; ++ct) {
+                            double vv = (double)vt[(sp0 + 4 * r + lg) * PCH + 16 * ct + lj];
+                            O[jt][ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(E[r], vv, O[jt][ct], 0, 0, 0);
+                        }
                     }
                 }
             }
