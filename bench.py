@@ -47,6 +47,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="lowdim_anneal")
     ap.add_argument("--n", type=int, default=None, help="override n = m (debugging only)")
+    ap.add_argument("--schedule", choices=("alternating", "symmetric"), default="alternating",
+                    help="symmetric: the averaged Jacobi schedule (Eq. 4-5) at eps_end for the same number of "
+                         "iterations (no annealing); the default is the metric's alternating schedule")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (outside the timed region), so that a "
@@ -86,7 +89,10 @@ def main() -> int:
         g.zero_()
         ctx.fs_row_norms(prob.x)
         ctx.fs_row_norms(prob.y)
-        ctx.fs_solve(prob, w.eps_start, w.eps_end, w.n_stages, w.iters, f, g)
+        if args.schedule == "symmetric":
+            ctx.fs_solve_symmetric(prob, w.eps_end, w.total_iters, f, g)
+        else:
+            ctx.fs_solve(prob, w.eps_start, w.eps_end, w.n_stages, w.iters, f, g)
         er, ec = ctx.fs_marginal_err(prob, w.eps_end, f, g)
         grad = None
         if can_apply:
@@ -148,7 +154,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype,
         "data": "synthetic",
         "config": {"workload": w.name, "n": w.n, "m": w.m, "d": w.d, "eps_start": w.eps_start,
-                   "eps_end": w.eps_end, "stages": w.n_stages, "iters_per_stage": w.iters,
+                   "eps_end": w.eps_end, "stages": w.n_stages, "iters_per_stage": w.iters, "schedule": args.schedule,
                    "step": "row_norms + solve + marginal_err + apply_plan + apply_plan_T + grad"},
         "marginal_err": {"row": er, "col": ec},
         "roofline": roof,

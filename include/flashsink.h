@@ -134,6 +134,19 @@ fs_status fs_solve(fs_ctx *ctx, const fs_problem *prob, float eps_start, float e
                    int32_t n_stages, int32_t iters_per_stage, float *f, float *g);
 
 /*
+ * Symmetric (Jacobi, averaged) schedule with a fixed iteration count (Eq. 4-5):
+ * in every iteration both updates read the OLD potentials,
+ *     f <- f/2 + (1/2) (-eps LSE_j[(g_j - C_ij)/eps + log b_j]),
+ *     g <- g/2 + (1/2) (-eps LSE_i[(f_i - C_ij)/eps + log a_i]),
+ * at one eps.  f (n floats) and g (m floats) are both read as the starting
+ * potentials and overwritten with the result; between iterations they are kept
+ * in float64 inside the workspace and rounded to float once, at the end.
+ * Same arguments, validation and error behaviour as fs_solve.
+ */
+fs_status fs_solve_symmetric(fs_ctx *ctx, const fs_problem *prob, float eps, int32_t iters,
+                             float *f /* device, in/out */, float *g /* device, in/out */);
+
+/*
  * L1 violation of the marginals of the plan induced by (f, g) (Prop. 3):
  *   r_i = a_i exp((f_i - f_i^+)/eps),  c_j = b_j exp((g_j - g_j^+)/eps),
  *   *err_row_l1 = sum_i |r_i - a_i|,   *err_col_l1 = sum_j |c_j - b_j|,

@@ -228,10 +228,10 @@ fs_status prepare(Ctx *c, const fs_problem *p, Prepared *P, size_t extra, char *
 
 // merge the splits of the pass that just ran over `res` (see launch_finalize)
 fs_status finalize(Ctx *c, const Prepared *P, Side *res, int splits, double eps, double eps_next_bias, float *user_out,
-                   double *abs_dev_sum)
+                   double *abs_dev_sum, double mix = 1.0)
 {
     const double *nrm = (P->path == Path::LowD && !lowd_precise(P, eps)) ? res->norm_f : res->norm;
-    return launch_finalize(c, P, res, nrm, splits, eps, eps_next_bias, user_out, abs_dev_sum);
+    return launch_finalize(c, P, res, nrm, splits, eps, eps_next_bias, user_out, abs_dev_sum, mix);
 }
 
 fs_status run_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits)
@@ -444,6 +444,50 @@ fs_status fs_solve(fs_ctx *ctx, const fs_problem *prob, float eps_start, float e
                                       nullptr)) != FS_OK)
                 return st;
         }
+    }
+    return FS_OK;
+}
+
+fs_status fs_solve_symmetric(fs_ctx *ctx, const fs_problem *prob, float eps_in, int32_t iters, float *f, float *g)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    fs_status st = validate_problem(c, prob);
+    if (st != FS_OK) return st;
+    if ((st = validate_eps(c, eps_in)) != FS_OK) return st;
+    if (iters < 0) return fail(c, FS_ERR_BAD_EPS, "need iters >= 0");
+    if ((st = check_out(c, prob, f, (size_t)prob->n * 4, "f")) != FS_OK) return st;
+    if ((st = check_out(c, prob, g, (size_t)prob->m * 4, "g")) != FS_OK) return st;
+    if (overlap(f, (size_t)prob->n * 4, g, (size_t)prob->m * 4))
+        return fail(c, FS_ERR_INVALID_ARG, "f overlaps g");
+    if (iters == 0) return c->device < 0 ? fail(c, FS_ERR_DEVICE, "host-only context") : FS_OK;
+
+    const double eps = (double)eps_in;
+    Prepared P;
+    P.halfsteps_per_eps = 2 * iters;
+    // Both passes of an iteration read the old potentials, so the second one must not overwrite
+    // the split partials of the first before they are merged: it gets a partial buffer of its own.
+    Prepared sizing;
+    layout(c, prob, &sizing, nullptr, 0);
+    const size_t second = sizing.partial_bytes;
+    char *second_partial = nullptr;
+    if ((st = prepare(c, prob, &P, second, &second_partial)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.X, f, eps)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps)) != FS_OK) return st;
+    void *const first_partial = P.partial;
+    for (int t = 0; t < iters; ++t) {
+        const bool last = t == iters - 1;
+        int splits_f = 1, splits_g = 1;
+        P.partial = first_partial;
+        if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits_f)) != FS_OK) return st;   // Eq. 4: from the old g
+        P.partial = second_partial;
+        if ((st = run_lse(c, &P, &P.Y, &P.X, eps, &splits_g)) != FS_OK) return st;   // Eq. 5: from the old f
+        // only now are the potentials (and the biases the next iteration streams) replaced
+        P.partial = first_partial;
+        if ((st = finalize(c, &P, &P.X, splits_f, eps, last ? 0.0 : eps, last ? f : nullptr, nullptr, 0.5)) != FS_OK)
+            return st;
+        P.partial = second_partial;
+        if ((st = finalize(c, &P, &P.Y, splits_g, eps, last ? 0.0 : eps, last ? g : nullptr, nullptr, 0.5)) != FS_OK)
+            return st;
     }
     return FS_OK;
 }

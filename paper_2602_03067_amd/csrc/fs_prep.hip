@@ -341,7 +341,7 @@ __global__ void k_bias_from_user(const float *pot_user, int64_t cnt, double inv_
 __global__ __launch_bounds__(256) void k_finalize(const double2 *partial, int64_t stride, int splits, int64_t cnt,
                                                   double eps, double inv_eps_next, const float *w,
                                                   double log_uniform, const double *res_norm, double *pot,
-                                                  BiasSink sink, float *user_out, double *dev_part)
+                                                  BiasSink sink, float *user_out, double *dev_part, double mix)
 {
     __shared__ double sh[256];
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -359,6 +359,7 @@ __global__ __launch_bounds__(256) void k_finalize(const double2 *partial, int64_
         }
         // fhat = -eps * LSE (Alg. 1), f = fhat + alpha (Prop. 1)
         double pot_new = -eps * kLn2 * (M + log2(S)) + res_norm[i];
+        if (mix != 1.0) pot_new = (1.0 - mix) * pot[i] + mix * pot_new;   // averaged schedule (Eq. 4-5)
         if (dev_part) {
             double wi = w ? (double)w[i] : exp(log_uniform);
             dev = fabs(wi * exp((pot[i] - pot_new) / eps) - wi);   // Prop. 3: r = a exp((fhat - fhat+)/eps)
@@ -544,13 +545,13 @@ fs_status launch_bias_from_user(Ctx *c, Prepared *P, Side *side, const float *po
 }
 
 fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, const double *res_norm, int splits, double eps_cur,
-                          double eps_next_bias, float *user_out, double *abs_dev_sum)
+                          double eps_next_bias, float *user_out, double *abs_dev_sum, double mix)
 {
     const unsigned blocks = (unsigned)ceil_div(res->cnt, 256);
     double *dev_part = abs_dev_sum ? P->dev_part : nullptr;   // per-block sums of the marginal deviation
     hipLaunchKernelGGL(k_finalize, dim3(blocks), dim3(256), 0, c->stream, (const double2 *)P->partial, res->cnt_pad,
                        splits, res->cnt, eps_cur, eps_next_bias > 0.0 ? 1.0 / eps_next_bias : 0.0, res->w,
-                       res->log_uniform, res_norm, res->pot, sink_of(P, res, eps_next_bias), user_out, dev_part);
+                       res->log_uniform, res_norm, res->pot, sink_of(P, res, eps_next_bias), user_out, dev_part, mix);
     if (abs_dev_sum)
         hipLaunchKernelGGL(k_sum_to, dim3(1), dim3(256), 0, c->stream, dev_part, (int64_t)blocks, abs_dev_sum);
     FS_HIP(c, hipGetLastError());

@@ -92,6 +92,9 @@ def test_solve_count_validation(lib, hctx):
     p = _prob()
     assert lib.fs_solve(hctx, ctypes.byref(p), F(1.0), F(0.1), 0, 1, P(1 << 21), P(1 << 20)) == 3
     assert lib.fs_solve(hctx, ctypes.byref(p), F(1.0), F(0.1), 1, -1, P(1 << 21), P(1 << 20)) == 3
+    assert lib.fs_solve_symmetric(hctx, ctypes.byref(p), F(0.1), -1, P(1 << 21), P(1 << 20)) == 3
+    assert lib.fs_solve_symmetric(hctx, ctypes.byref(p), F(0.0), 1, P(1 << 21), P(1 << 20)) == 3
+    assert lib.fs_solve_symmetric(hctx, ctypes.byref(p), F(0.1), 1, None, P(1 << 20)) == 1
 
 
 def test_null_and_aliasing(lib, hctx):

@@ -1,0 +1,97 @@
+"""GPU parity of fs_solve_symmetric (Eq. 4-5, the averaged Jacobi schedule) against the float64
+oracle, on the three arithmetic paths.  Tolerances as for fs_solve: |df|/eps <= 1e-4 in fp32-accuracy
+mode, <= 2e-2 in bf16 mode against the oracle on the unrounded inputs (and 2e-4 against the oracle
+on the bf16-rounded inputs, which separates rounding of the data from the kernels' arithmetic)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_03067_amd import binding, workloads
+from tests._gpu_common import dev, host, make_problem, max_err_over_eps, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return binding.Context(0)
+
+
+def _problem(rng, n, m, d, scale):
+    x = (rng.standard_normal((n, d)) * scale).astype(np.float32)
+    y = (rng.standard_normal((m, d)) * scale * 0.8 + 0.2 * scale).astype(np.float32)
+    a = rng.random(n) + 0.1
+    a = (a / a.sum()).astype(np.float32)
+    b = rng.random(m) + 0.1
+    b = (b / b.sum()).astype(np.float32)
+    return x, y, a, b
+
+
+@pytest.mark.parametrize("n,m,d,eps,iters", [(300, 421, 3, 0.25, 25), (1030, 700, 2, 0.05, 12),   # low-d passes
+                                             (260, 300, 8, 0.5, 10),
+                                             (200, 333, 40, 2.0, 15), (130, 257, 64, 1.0, 8)])     # fp64 MFMA pass
+def test_symmetric_fp32_mode(ctx, oracle, n, m, d, eps, iters):
+    rng = np.random.default_rng(1000 * n + m + d)
+    x, y, a, b = _problem(rng, n, m, d, 1.0 if d <= 16 else 0.5)
+    eps = float(np.float32(eps))
+    f0 = (0.1 * rng.standard_normal(n)).astype(np.float32)
+    g0 = (0.1 * rng.standard_normal(m)).astype(np.float32)
+    say("solve_symmetric n=%d m=%d d=%d eps=%g iters=%d (non-zero start)" % (n, m, d, eps, iters))
+    fo, go = oracle.solve_symmetric(x, y, a, b, eps, iters, f0=f0.astype(np.float64), g0=g0.astype(np.float64))
+    prob = make_problem(x, y, a, b)
+    f, g = dev(f0), dev(g0)
+    ctx.fs_solve_symmetric(prob, eps, iters, f, g)
+    ef, eg = max_err_over_eps(host(f), fo, eps), max_err_over_eps(host(g), go, eps)
+    say("  max|df|/eps=%.3e max|dg|/eps=%.3e" % (ef, eg))
+    assert ef <= 1e-4 and eg <= 1e-4
+
+
+def test_symmetric_equal_clouds_keep_f_equal_g(ctx, oracle):
+    """x = y and a = b: under the symmetric schedule f = g at every iteration (the oracle is pinned
+    to this); on the GPU the two passes are the same arithmetic on swapped roles."""
+    rng = np.random.default_rng(5)
+    n, d = 777, 3
+    x, _, a, _ = _problem(rng, n, n, d, 1.0)
+    eps = float(np.float32(0.2))
+    say("solve_symmetric with x = y, a = b: f must equal g, n=%d" % n)
+    prob = make_problem(x, x, a, a)
+    f = torch.zeros(n, device="cuda:0")
+    g = torch.zeros(n, device="cuda:0")
+    ctx.fs_solve_symmetric(prob, eps, 9, f, g)
+    fo, go = oracle.solve_symmetric(x, x, a, a, eps, 9)
+    assert float(np.max(np.abs(host(f) - host(g)))) / eps <= 2e-6
+    assert max_err_over_eps(host(f), fo, eps) <= 1e-4
+
+
+def test_symmetric_bf16_mode(ctx, oracle):
+    rng = np.random.default_rng(77)
+    n, m, d = 300, 520, 96
+    x, y, a, b = _problem(rng, n, m, d, 0.3)
+    eps = float(np.float32(1.5))
+    iters = 10
+    say("solve_symmetric bf16 mode n=%d m=%d d=%d eps=%g iters=%d" % (n, m, d, eps, iters))
+    prob = make_problem(x, y, a, b, compute=binding.FS_COMPUTE_BF16_MFMA)
+    f = torch.zeros(n, device="cuda:0")
+    g = torch.zeros(m, device="cuda:0")
+    ctx.fs_solve_symmetric(prob, eps, iters, f, g)
+    fa, ga = oracle.solve_symmetric(x, y, a, b, eps, iters)
+    xb, yb = workloads.to_bf16_round(x), workloads.to_bf16_round(y)
+    fb, gb = oracle.solve_symmetric(xb, yb, a, b, eps, iters)
+    ea = max(max_err_over_eps(host(f), fa, eps), max_err_over_eps(host(g), ga, eps))
+    eb = max(max_err_over_eps(host(f), fb, eps), max_err_over_eps(host(g), gb, eps))
+    say("  vs oracle on bf16-rounded inputs %.3e, vs oracle on given inputs %.3e" % (eb, ea))
+    assert ea <= 2e-2 and eb <= 2e-4
+
+
+def test_symmetric_zero_iterations_leaves_potentials(ctx):
+    rng = np.random.default_rng(3)
+    x, y, a, b = _problem(rng, 50, 60, 3, 1.0)
+    prob = make_problem(x, y, a, b)
+    f0 = rng.standard_normal(50).astype(np.float32)
+    g0 = rng.standard_normal(60).astype(np.float32)
+    f, g = dev(f0), dev(g0)
+    say("solve_symmetric with iters=0")
+    ctx.fs_solve_symmetric(prob, 0.3, 0, f, g)
+    assert np.array_equal(host(f), f0.astype(np.float64)) and np.array_equal(host(g), g0.astype(np.float64))
