@@ -158,6 +158,17 @@ fs_status fs_marginal_err(fs_ctx *ctx, const fs_problem *prob, float eps, const 
                           float *err_col_l1 /* host */);
 
 /*
+ * Value of the dual objective at the given potentials (App. B, the Lagrangian at its
+ * stationary plan):  <a,f> + <b,g> - eps (sum_ij P_ij - sum_ij a_i b_j)  with P the plan that
+ * (f, g) induce (text after Eq. 3).  At convergence this is the entropic OT value of Eq. 1.
+ * Costs one streaming pass (the total mass of P is the sum of the induced row marginals,
+ * Prop. 3), always with the accurate score arithmetic.  *value is a HOST double; the call
+ * synchronises the stream.
+ */
+fs_status fs_ot_value(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f /* device */,
+                      const float *g /* device */, double *value /* host */);
+
+/*
  * out = P V with P_ij = a_i b_j exp((f_i + g_j - C_ij)/eps) for ANY potentials
  * (Prop. 3, Alg. 2): one streaming pass, P never stored.
  * V: m x p (ldv), out: n x p (ldo), r_out: NULL or n floats receiving P 1_m.

@@ -21,7 +21,7 @@ FS_COMPUTE_FP32, FS_COMPUTE_BF16_MFMA = 0, 1
 
 EXPORTS = (
     "fs_create", "fs_destroy", "fs_status_str", "fs_last_error", "fs_version", "fs_row_norms",
-    "fs_update_f", "fs_update_g", "fs_solve", "fs_solve_symmetric", "fs_marginal_err", "fs_apply_plan",
+    "fs_update_f", "fs_update_g", "fs_solve", "fs_solve_symmetric", "fs_marginal_err", "fs_ot_value", "fs_apply_plan",
     "fs_apply_plan_T", "fs_profile_enable", "fs_profile_read",
 )
 
@@ -72,6 +72,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fs_solve.argtypes = [vp, PP, f32, f32, i32, i32, vp, vp]
     lib.fs_solve_symmetric.argtypes = [vp, PP, f32, i32, vp, vp]
     lib.fs_marginal_err.argtypes = [vp, PP, f32, vp, vp, ctypes.POINTER(f32), ctypes.POINTER(f32)]
+    lib.fs_ot_value.argtypes = [vp, PP, f32, vp, vp, ctypes.POINTER(ctypes.c_double)]
     lib.fs_apply_plan.argtypes = [vp, PP, f32, vp, vp, vp, i64, i64, vp, i64, vp]
     lib.fs_apply_plan_T.argtypes = [vp, PP, f32, vp, vp, vp, i64, i64, vp, i64, vp]
     lib.fs_profile_enable.argtypes = [vp, i32]
@@ -184,6 +185,14 @@ class Context:
         self._check(self.lib.fs_solve(self.h, ctypes.byref(prob.c), eps_start, eps_end,
                                       int(n_stages), int(iters_per_stage), _ptr(f), _ptr(g)),
                     "fs_solve")
+
+    def fs_ot_value(self, prob: Problem, eps: float, f: torch.Tensor, g: torch.Tensor) -> float:
+        _dev_f32(f, "f", (prob.n,))
+        _dev_f32(g, "g", (prob.m,))
+        v = ctypes.c_double()
+        self._check(self.lib.fs_ot_value(self.h, ctypes.byref(prob.c), eps, _ptr(f), _ptr(g), ctypes.byref(v)),
+                    "fs_ot_value")
+        return v.value
 
     def fs_solve_symmetric(self, prob: Problem, eps: float, iters: int, f: torch.Tensor,
                            g: torch.Tensor) -> None:

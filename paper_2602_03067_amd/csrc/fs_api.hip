@@ -523,6 +523,34 @@ fs_status fs_marginal_err(fs_ctx *ctx, const fs_problem *prob, float eps, const 
     return FS_OK;
 }
 
+fs_status fs_ot_value(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, const float *g, double *value)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    fs_status st = validate_problem(c, prob);
+    if (st != FS_OK) return st;
+    if ((st = validate_eps(c, eps)) != FS_OK) return st;
+    if (!f || !g || !value) return fail(c, FS_ERR_INVALID_ARG, "f, g or value is NULL");
+    Prepared P;
+    P.force_precise = true;   // a measurement: always the accurate score arithmetic
+    const size_t scratch_bytes = (3 * (size_t)ceil_div(prob->n, 256) + 2 * (size_t)ceil_div(prob->m, 256)) * 8;
+    char *scratch = nullptr;
+    if ((st = prepare(c, prob, &P, scratch_bytes, &scratch)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.X, f, eps)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps)) != FS_OK) return st;
+    int splits = 1;
+    if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits)) != FS_OK) return st;
+    const double *nrm = (P.path == Path::LowD && !lowd_precise(&P, eps)) ? P.X.norm_f : P.X.norm;
+    if ((st = launch_value_terms(c, &P, &P.X, nrm, &P.Y, splits, eps, reinterpret_cast<double *>(scratch), P.scalars)) !=
+        FS_OK)
+        return st;
+    double h[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    FS_HIP(c, hipMemcpyAsync(h, P.scalars, sizeof h, hipMemcpyDeviceToHost, c->stream));
+    FS_HIP(c, hipStreamSynchronize(c->stream));
+    // App. B: <a,f> + <b,g> - eps (sum_ij P_ij - sum_ij a_i b_j)
+    *value = h[1] + h[3] - (double)eps * (h[0] - h[2] * h[4]);
+    return FS_OK;
+}
+
 fs_status fs_apply_plan(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, const float *g,
                         const float *V, int64_t p, int64_t ldv, float *out, int64_t ldo, float *r_out)
 {

@@ -205,6 +205,8 @@ fs_status launch_bias_from_user(Ctx *c, Prepared *P, Side *side, const float *po
 fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, const double *res_norm, int splits,
                           double eps_cur, double eps_next_bias, float *user_out, double *abs_dev_sum,
                           double mix = 1.0);
+fs_status launch_value_terms(Ctx *c, const Prepared *P, const Side *res, const double *res_norm, const Side *str,
+                             int splits, double eps, double *scratch, double *dst);
 fs_status launch_row_norms(Ctx *c, const void *pts, int dtype, int64_t rows, int64_t d, int64_t ld,
                            float *out);
 fs_status launch_fill_f64(Ctx *c, double *dst, double v, int64_t cnt);

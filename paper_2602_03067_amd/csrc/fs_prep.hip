@@ -385,6 +385,60 @@ __global__ __launch_bounds__(256) void k_sum_to(const double *part, int64_t cnt,
     if (threadIdx.x == 0) *dst = t;
 }
 
+// ---- terms of the dual objective (App. B) -------------------------------------------------
+// After an LSE pass over `res`: mass_i = w_i exp((pot_i - pot_i^+)/eps) is the row sum of the plan
+// that the CURRENT potentials induce (Prop. 3).  Block sums of mass_i, w_i pot_i and w_i go to
+// part[0][.], part[1][.], part[2][.] (part has 3 * gridDim.x doubles).
+__global__ __launch_bounds__(256) void k_value_terms(const double2 *partial, int64_t stride, int splits, int64_t cnt,
+                                                     double eps, const float *w, double log_uniform,
+                                                     const double *res_norm, const double *pot, double *part)
+{
+    __shared__ double sh[256];
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    double t[3] = {0.0, 0.0, 0.0};
+    if (i < cnt) {
+        double M = -INFINITY;
+        for (int k = 0; k < splits; ++k) {
+            double mk = partial[(int64_t)k * stride + i].x;
+            M = mk > M ? mk : M;
+        }
+        double S = 0.0;
+        for (int k = 0; k < splits; ++k) {
+            double2 ms = partial[(int64_t)k * stride + i];
+            S += ms.y * exp2(ms.x - M);
+        }
+        const double pot_new = -eps * kLn2 * (M + log2(S)) + res_norm[i];
+        const double wi = w ? (double)w[i] : exp(log_uniform);
+        t[0] = wi > 0.0 ? wi * exp((pot[i] - pot_new) / eps) : 0.0;
+        t[1] = wi * pot[i];
+        t[2] = wi;
+    }
+    for (int k = 0; k < 3; ++k) {
+        double v = block_sum_256(t[k], sh);
+        if (threadIdx.x == 0) part[(int64_t)k * gridDim.x + blockIdx.x] = v;
+        __syncthreads();
+    }
+}
+
+// block sums of w_i pot_i and w_i: part[0][.], part[1][.]
+__global__ __launch_bounds__(256) void k_weighted_sums(int64_t cnt, const float *w, double log_uniform, const double *pot,
+                                                       double *part)
+{
+    __shared__ double sh[256];
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    double t[2] = {0.0, 0.0};
+    if (i < cnt) {
+        const double wi = w ? (double)w[i] : exp(log_uniform);
+        t[0] = wi * pot[i];
+        t[1] = wi;
+    }
+    for (int k = 0; k < 2; ++k) {
+        double v = block_sum_256(t[k], sh);
+        if (threadIdx.x == 0) part[(int64_t)k * gridDim.x + blockIdx.x] = v;
+        __syncthreads();
+    }
+}
+
 // merge the splits of an application pass and apply the epilogue of Alg. 2:
 //   out_i = a_i * exp(fhat_i/eps + m_i) * O_i   with everything in base 2;  mass_i = same with s.
 __global__ void k_apply_finalize(const double2 *partial, int64_t stride, const float *opart, int64_t opart_stride,
@@ -554,6 +608,24 @@ fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, const double *re
                        res->log_uniform, res_norm, res->pot, sink_of(P, res, eps_next_bias), user_out, dev_part, mix);
     if (abs_dev_sum)
         hipLaunchKernelGGL(k_sum_to, dim3(1), dim3(256), 0, c->stream, dev_part, (int64_t)blocks, abs_dev_sum);
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
+// dst[0..4] <- sum_i mass_i, <w_res, pot_res>, sum w_res, <w_str, pot_str>, sum w_str  (see k_value_terms);
+// `scratch` holds 3 * blocks(res) + 2 * blocks(str) doubles
+fs_status launch_value_terms(Ctx *c, const Prepared *P, const Side *res, const double *res_norm, const Side *str,
+                             int splits, double eps, double *scratch, double *dst)
+{
+    const unsigned br = (unsigned)ceil_div(res->cnt, 256), bs = (unsigned)ceil_div(str->cnt, 256);
+    double *pr = scratch, *ps = scratch + 3 * (size_t)br;
+    hipLaunchKernelGGL(k_value_terms, dim3(br), dim3(256), 0, c->stream, (const double2 *)P->partial, res->cnt_pad, splits,
+                       res->cnt, eps, res->w, res->log_uniform, res_norm, res->pot, pr);
+    hipLaunchKernelGGL(k_weighted_sums, dim3(bs), dim3(256), 0, c->stream, str->cnt, str->w, str->log_uniform, str->pot, ps);
+    for (int k = 0; k < 3; ++k)
+        hipLaunchKernelGGL(k_sum_to, dim3(1), dim3(256), 0, c->stream, pr + (size_t)k * br, (int64_t)br, dst + k);
+    for (int k = 0; k < 2; ++k)
+        hipLaunchKernelGGL(k_sum_to, dim3(1), dim3(256), 0, c->stream, ps + (size_t)k * bs, (int64_t)bs, dst + 3 + k);
     FS_HIP(c, hipGetLastError());
     return FS_OK;
 }

@@ -95,6 +95,9 @@ def test_solve_count_validation(lib, hctx):
     assert lib.fs_solve_symmetric(hctx, ctypes.byref(p), F(0.1), -1, P(1 << 21), P(1 << 20)) == 3
     assert lib.fs_solve_symmetric(hctx, ctypes.byref(p), F(0.0), 1, P(1 << 21), P(1 << 20)) == 3
     assert lib.fs_solve_symmetric(hctx, ctypes.byref(p), F(0.1), 1, None, P(1 << 20)) == 1
+    v = ctypes.c_double()
+    assert lib.fs_ot_value(hctx, ctypes.byref(p), F(0.1), P(1 << 21), P(1 << 20), None) == 1
+    assert lib.fs_ot_value(hctx, ctypes.byref(p), F(-1.0), P(1 << 21), P(1 << 20), ctypes.byref(v)) == 3
 
 
 def test_null_and_aliasing(lib, hctx):
