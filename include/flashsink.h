@@ -147,6 +147,22 @@ fs_status fs_solve_symmetric(fs_ctx *ctx, const fs_problem *prob, float eps, int
                              float *f /* device, in/out */, float *g /* device, in/out */);
 
 /*
+ * Alternating Sinkhorn at one eps with early stopping on the row marginal error
+ * (Prop. 3; after a g-update the column marginal is exact, so the row error is the
+ * whole error).  After every `check_every` iterations, and after `max_iters`, the L1 row
+ * error of the current potentials is measured; the iteration stops when it is <= tol.
+ * The error comes out of the f-update that begins the next iteration, so a check that
+ * does not stop costs no extra pass (it costs one synchronisation).  f is not read on
+ * entry (the first half-step computes it from g).  On return f, g are the potentials
+ * after *iters_done iterations and *err_row_l1 their measured row error; both are HOST
+ * pointers, and the call synchronises the stream.
+ */
+fs_status fs_solve_tol(fs_ctx *ctx, const fs_problem *prob, float eps, int32_t max_iters,
+                       int32_t check_every, float tol, float *f /* device, in/out */,
+                       float *g /* device, in/out */, int32_t *iters_done /* host */,
+                       float *err_row_l1 /* host */);
+
+/*
  * L1 violation of the marginals of the plan induced by (f, g) (Prop. 3):
  *   r_i = a_i exp((f_i - f_i^+)/eps),  c_j = b_j exp((g_j - g_j^+)/eps),
  *   *err_row_l1 = sum_i |r_i - a_i|,   *err_col_l1 = sum_j |c_j - b_j|,

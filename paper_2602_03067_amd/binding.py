@@ -21,7 +21,7 @@ FS_COMPUTE_FP32, FS_COMPUTE_BF16_MFMA = 0, 1
 
 EXPORTS = (
     "fs_create", "fs_destroy", "fs_status_str", "fs_last_error", "fs_version", "fs_row_norms",
-    "fs_update_f", "fs_update_g", "fs_solve", "fs_solve_symmetric", "fs_marginal_err", "fs_ot_value", "fs_apply_plan",
+    "fs_update_f", "fs_update_g", "fs_solve", "fs_solve_symmetric", "fs_solve_tol", "fs_marginal_err", "fs_ot_value", "fs_apply_plan",
     "fs_apply_plan_T", "fs_profile_enable", "fs_profile_read",
 )
 
@@ -71,6 +71,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fs_update_g.argtypes = [vp, PP, f32, vp, vp]
     lib.fs_solve.argtypes = [vp, PP, f32, f32, i32, i32, vp, vp]
     lib.fs_solve_symmetric.argtypes = [vp, PP, f32, i32, vp, vp]
+    lib.fs_solve_tol.argtypes = [vp, PP, f32, i32, i32, f32, vp, vp, ctypes.POINTER(i32), ctypes.POINTER(f32)]
     lib.fs_marginal_err.argtypes = [vp, PP, f32, vp, vp, ctypes.POINTER(f32), ctypes.POINTER(f32)]
     lib.fs_ot_value.argtypes = [vp, PP, f32, vp, vp, ctypes.POINTER(ctypes.c_double)]
     lib.fs_apply_plan.argtypes = [vp, PP, f32, vp, vp, vp, i64, i64, vp, i64, vp]
@@ -185,6 +186,17 @@ class Context:
         self._check(self.lib.fs_solve(self.h, ctypes.byref(prob.c), eps_start, eps_end,
                                       int(n_stages), int(iters_per_stage), _ptr(f), _ptr(g)),
                     "fs_solve")
+
+    def fs_solve_tol(self, prob: Problem, eps: float, max_iters: int, check_every: int, tol: float,
+                     f: torch.Tensor, g: torch.Tensor) -> Tuple[int, float]:
+        """In place like fs_solve; returns (iterations done, measured L1 row marginal error)."""
+        _dev_f32(f, "f", (prob.n,))
+        _dev_f32(g, "g", (prob.m,))
+        done, err = ctypes.c_int32(), ctypes.c_float()
+        self._check(self.lib.fs_solve_tol(self.h, ctypes.byref(prob.c), eps, int(max_iters), int(check_every),
+                                          float(tol), _ptr(f), _ptr(g), ctypes.byref(done), ctypes.byref(err)),
+                    "fs_solve_tol")
+        return done.value, err.value
 
     def fs_ot_value(self, prob: Problem, eps: float, f: torch.Tensor, g: torch.Tensor) -> float:
         _dev_f32(f, "f", (prob.n,))

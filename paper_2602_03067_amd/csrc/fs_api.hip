@@ -228,10 +228,10 @@ fs_status prepare(Ctx *c, const fs_problem *p, Prepared *P, size_t extra, char *
 
 // merge the splits of the pass that just ran over `res` (see launch_finalize)
 fs_status finalize(Ctx *c, const Prepared *P, Side *res, int splits, double eps, double eps_next_bias, float *user_out,
-                   double *abs_dev_sum, double mix = 1.0)
+                   double *abs_dev_sum, double mix = 1.0, double *save_old = nullptr)
 {
     const double *nrm = (P->path == Path::LowD && !lowd_precise(P, eps)) ? res->norm_f : res->norm;
-    return launch_finalize(c, P, res, nrm, splits, eps, eps_next_bias, user_out, abs_dev_sum, mix);
+    return launch_finalize(c, P, res, nrm, splits, eps, eps_next_bias, user_out, abs_dev_sum, mix, save_old);
 }
 
 fs_status run_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits)
@@ -445,6 +445,63 @@ fs_status fs_solve(fs_ctx *ctx, const fs_problem *prob, float eps_start, float e
                 return st;
         }
     }
+    return FS_OK;
+}
+
+fs_status fs_solve_tol(fs_ctx *ctx, const fs_problem *prob, float eps_in, int32_t max_iters, int32_t check_every,
+                       float tol, float *f, float *g, int32_t *iters_done, float *err_row_l1)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    fs_status st = validate_problem(c, prob);
+    if (st != FS_OK) return st;
+    if ((st = validate_eps(c, eps_in)) != FS_OK) return st;
+    if (max_iters < 1 || check_every < 1 || !(tol >= 0.0f))
+        return fail(c, FS_ERR_BAD_EPS, "need max_iters >= 1, check_every >= 1 and tol >= 0");
+    if ((st = check_out(c, prob, f, (size_t)prob->n * 4, "f")) != FS_OK) return st;
+    if ((st = check_out(c, prob, g, (size_t)prob->m * 4, "g")) != FS_OK) return st;
+    if (overlap(f, (size_t)prob->n * 4, g, (size_t)prob->m * 4))
+        return fail(c, FS_ERR_INVALID_ARG, "f overlaps g");
+    if (!iters_done || !err_row_l1) return fail(c, FS_ERR_INVALID_ARG, "iters_done or err_row_l1 is NULL");
+
+    const double eps = (double)eps_in;
+    Prepared P;
+    P.halfsteps_per_eps = 2 * max_iters;
+    char *extra = nullptr;
+    if ((st = prepare(c, prob, &P, (size_t)prob->n * 8, &extra)) != FS_OK) return st;
+    double *f_before = reinterpret_cast<double *>(extra);   // f of the last completed iteration at a check
+    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps)) != FS_OK) return st;
+    if ((st = launch_fill_f64(c, P.scalars, 0.0, 1)) != FS_OK) return st;
+    // The row marginal error of (f_t, g_t) is a by-product of the f-update that starts iteration
+    // t + 1 (Prop. 3: r = a exp((f_t - f_{t+1})/eps)), so a check costs no extra pass unless it stops
+    // the iteration.  `pending`: that f-update has already been done.
+    bool pending = false;
+    int t = 0;
+    double err = -1.0;
+    while (true) {
+        int splits = 1;
+        if (!pending) {   // Alg. 1: f from g
+            if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits)) != FS_OK) return st;
+            if ((st = finalize(c, &P, &P.X, splits, eps, eps, nullptr, nullptr)) != FS_OK) return st;
+        }
+        pending = false;
+        // Alg. 3: g from the new f
+        if ((st = run_lse(c, &P, &P.Y, &P.X, eps, &splits)) != FS_OK) return st;
+        if ((st = finalize(c, &P, &P.Y, splits, eps, eps, nullptr, nullptr)) != FS_OK) return st;
+        ++t;
+        if (t % check_every != 0 && t != max_iters) continue;
+        // the next f-update, measuring the error of (f_t, g_t) on the way
+        if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits)) != FS_OK) return st;
+        if ((st = finalize(c, &P, &P.X, splits, eps, eps, nullptr, P.scalars, 1.0, f_before)) != FS_OK) return st;
+        FS_HIP(c, hipMemcpyAsync(&err, P.scalars, sizeof(double), hipMemcpyDeviceToHost, c->stream));
+        FS_HIP(c, hipStreamSynchronize(c->stream));
+        if (err <= (double)tol || t == max_iters) break;
+        pending = true;
+    }
+    if ((st = launch_export_f32(c, f_before, prob->n, f)) != FS_OK) return st;
+    if ((st = launch_export_f32(c, P.Y.pot, prob->m, g)) != FS_OK) return st;
+    FS_HIP(c, hipStreamSynchronize(c->stream));
+    *iters_done = t;
+    *err_row_l1 = (float)err;
     return FS_OK;
 }
 

@@ -202,9 +202,12 @@ fs_status launch_prepare(Ctx *c, const fs_problem *p, Prepared *P);
 fs_status launch_bias_from_user(Ctx *c, Prepared *P, Side *side, const float *pot_user, double eps);
 // `res_norm` is the norm array matching the coordinates the pass used (Side::norm or norm_f).
 // `mix`: the new potential is (1 - mix) * old + mix * update (1: plain update, 1/2: averaged schedule).
+// `abs_dev_sum` != nullptr measures the marginal deviation instead of storing the update; with
+// `save_old` it does both and leaves the replaced potential in save_old[0..cnt).
 fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, const double *res_norm, int splits,
                           double eps_cur, double eps_next_bias, float *user_out, double *abs_dev_sum,
-                          double mix = 1.0);
+                          double mix = 1.0, double *save_old = nullptr);
+fs_status launch_export_f32(Ctx *c, const double *src, int64_t cnt, float *dst);
 fs_status launch_value_terms(Ctx *c, const Prepared *P, const Side *res, const double *res_norm, const Side *str,
                              int splits, double eps, double *scratch, double *dst);
 fs_status launch_row_norms(Ctx *c, const void *pts, int dtype, int64_t rows, int64_t d, int64_t ld,

@@ -322,12 +322,20 @@ __global__ void k_bias_from_user(const float *pot_user, int64_t cnt, double inv_
         mag_pot = fabs((pu - sink.norm[i]) * inv_eps) * kLog2e;
         mag_w = fabs(lw) < INFINITY ? fabs(lw) * kLog2e : 0.0;   // zero-weight points never contribute
     }
-    if (absmax) {
+    if (absmax) {   // one pair of atomics per workgroup (256 threads)
+        __shared__ double shm[2][4];
         for (int off = 32; off > 0; off >>= 1) {
             mag_pot = fmax(mag_pot, __shfl_xor(mag_pot, off));
             mag_w = fmax(mag_w, __shfl_xor(mag_w, off));
         }
         if ((threadIdx.x & 63) == 0) {
+            shm[0][threadIdx.x >> 6] = mag_w;
+            shm[1][threadIdx.x >> 6] = mag_pot;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            mag_w = fmax(fmax(shm[0][0], shm[0][1]), fmax(shm[0][2], shm[0][3]));
+            mag_pot = fmax(fmax(shm[1][0], shm[1][1]), fmax(shm[1][2], shm[1][3]));
             if (mag_w > 0.0) atomicMax(absmax + 0, (unsigned long long)__double_as_longlong(mag_w));
             if (mag_pot > 0.0) atomicMax(absmax + 1, (unsigned long long)__double_as_longlong(mag_pot));
         }
@@ -341,8 +349,11 @@ __global__ void k_bias_from_user(const float *pot_user, int64_t cnt, double inv_
 __global__ __launch_bounds__(256) void k_finalize(const double2 *partial, int64_t stride, int splits, int64_t cnt,
                                                   double eps, double inv_eps_next, const float *w,
                                                   double log_uniform, const double *res_norm, double *pot,
-                                                  BiasSink sink, float *user_out, double *dev_part, double mix)
+                                                  BiasSink sink, float *user_out, double *dev_part, double mix,
+                                                  double *save_old)
 {
+    // dev_part == nullptr: store the update.  dev_part != nullptr: measure the marginal deviation
+    // only, unless save_old is given: then measure AND store, keeping the old potential in save_old.
     __shared__ double sh[256];
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     double dev = 0.0;
@@ -363,7 +374,9 @@ __global__ __launch_bounds__(256) void k_finalize(const double2 *partial, int64_
         if (dev_part) {
             double wi = w ? (double)w[i] : exp(log_uniform);
             dev = fabs(wi * exp((pot[i] - pot_new) / eps) - wi);   // Prop. 3: r = a exp((fhat - fhat+)/eps)
-        } else {
+        }
+        if (!dev_part || save_old) {
+            if (save_old) save_old[i] = pot[i];
             pot[i] = pot_new;
             if (inv_eps_next > 0.0) store_bias(sink, i, pot_new, inv_eps_next, w ? log((double)w[i]) : log_uniform);
             if (user_out) user_out[i] = (float)pot_new;
@@ -373,6 +386,12 @@ __global__ __launch_bounds__(256) void k_finalize(const double2 *partial, int64_
         double t = block_sum_256(dev, sh);
         if (threadIdx.x == 0) dev_part[blockIdx.x] = t;
     }
+}
+
+__global__ void k_export_f32(const double *src, int64_t cnt, float *dst)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < cnt) dst[i] = (float)src[i];
 }
 
 // sum of `cnt` doubles by one block, fixed order
@@ -514,6 +533,13 @@ fs_status launch_apply_finalize(Ctx *c, const Prepared *P, const Side *res, cons
     return FS_OK;
 }
 
+fs_status launch_export_f32(Ctx *c, const double *src, int64_t cnt, float *dst)
+{
+    hipLaunchKernelGGL(k_export_f32, dim3((unsigned)ceil_div(cnt, 256)), dim3(256), 0, c->stream, src, cnt, dst);
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
 fs_status launch_fill_f64(Ctx *c, double *dst, double v, int64_t cnt)
 {
     hipLaunchKernelGGL(k_fill_f64, dim3((unsigned)ceil_div(cnt, 256)), dim3(256), 0, c->stream, dst, v, cnt);
@@ -599,13 +625,13 @@ fs_status launch_bias_from_user(Ctx *c, Prepared *P, Side *side, const float *po
 }
 
 fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, const double *res_norm, int splits, double eps_cur,
-                          double eps_next_bias, float *user_out, double *abs_dev_sum, double mix)
+                          double eps_next_bias, float *user_out, double *abs_dev_sum, double mix, double *save_old)
 {
     const unsigned blocks = (unsigned)ceil_div(res->cnt, 256);
     double *dev_part = abs_dev_sum ? P->dev_part : nullptr;   // per-block sums of the marginal deviation
     hipLaunchKernelGGL(k_finalize, dim3(blocks), dim3(256), 0, c->stream, (const double2 *)P->partial, res->cnt_pad,
                        splits, res->cnt, eps_cur, eps_next_bias > 0.0 ? 1.0 / eps_next_bias : 0.0, res->w,
-                       res->log_uniform, res_norm, res->pot, sink_of(P, res, eps_next_bias), user_out, dev_part, mix);
+                       res->log_uniform, res_norm, res->pot, sink_of(P, res, eps_next_bias), user_out, dev_part, mix, save_old);
     if (abs_dev_sum)
         hipLaunchKernelGGL(k_sum_to, dim3(1), dim3(256), 0, c->stream, dev_part, (int64_t)blocks, abs_dev_sum);
     FS_HIP(c, hipGetLastError());

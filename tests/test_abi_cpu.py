@@ -95,6 +95,13 @@ def test_solve_count_validation(lib, hctx):
     assert lib.fs_solve_symmetric(hctx, ctypes.byref(p), F(0.1), -1, P(1 << 21), P(1 << 20)) == 3
     assert lib.fs_solve_symmetric(hctx, ctypes.byref(p), F(0.0), 1, P(1 << 21), P(1 << 20)) == 3
     assert lib.fs_solve_symmetric(hctx, ctypes.byref(p), F(0.1), 1, None, P(1 << 20)) == 1
+    it, er = ctypes.c_int32(), F()
+    assert lib.fs_solve_tol(hctx, ctypes.byref(p), F(0.1), 0, 1, F(1e-3), P(1 << 21), P(1 << 20),
+                            ctypes.byref(it), ctypes.byref(er)) == 3
+    assert lib.fs_solve_tol(hctx, ctypes.byref(p), F(0.1), 5, 0, F(1e-3), P(1 << 21), P(1 << 20),
+                            ctypes.byref(it), ctypes.byref(er)) == 3
+    assert lib.fs_solve_tol(hctx, ctypes.byref(p), F(0.1), 5, 1, F(1e-3), P(1 << 21), P(1 << 20), None,
+                            ctypes.byref(er)) == 1
     v = ctypes.c_double()
     assert lib.fs_ot_value(hctx, ctypes.byref(p), F(0.1), P(1 << 21), P(1 << 20), None) == 1
     assert lib.fs_ot_value(hctx, ctypes.byref(p), F(-1.0), P(1 << 21), P(1 << 20), ctypes.byref(v)) == 3

@@ -95,6 +95,13 @@ def test_transport_grad_trajectory_scaled_down(ctx, oracle):
     assert np.linalg.norm(grad_gpu - grad_ref) <= 2e-4 * np.linalg.norm(grad_ref)
     T_gpu = host(PY) / a64                      # barycentric projection (x - T is the other form)
     assert np.linalg.norm(T_gpu - want / a64) <= 2e-4 * np.linalg.norm(want / a64)
+    # the gradient with respect to the other cloud: 2 (diag(b) y - P^T x), by the transposed application
+    PtX = ctx.fs_apply_plan_T(prob, eps, f, g, prob.x)
+    wantX = oracle.apply_plan_T(w.x, w.y, w.a, w.b, eps, fh, gh, w.x)
+    b64 = w.b.astype(np.float64)[:, None]
+    gy_gpu, gy_ref = 2.0 * (b64 * w.y - host(PtX)), 2.0 * (b64 * w.y - wantX)
+    say("grad 2048: gradient wrt y rel=%.3e" % (np.linalg.norm(gy_gpu - gy_ref) / np.linalg.norm(gy_ref)))
+    assert np.linalg.norm(gy_gpu - gy_ref) <= 2e-4 * np.linalg.norm(gy_ref)
 
 
 @pytest.mark.parametrize("n,m,d,p", [(130, 70, 20, 1), (200, 333, 64, 5), (257, 190, 40, 70), (64, 64, 96, 64)])

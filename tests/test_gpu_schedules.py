@@ -1,4 +1,5 @@
-"""GPU parity of fs_solve_symmetric (Eq. 4-5, the averaged Jacobi schedule) against the float64
+"""GPU parity of fs_solve_symmetric (Eq. 4-5, the averaged Jacobi schedule) and of fs_solve_tol (early
+stopping on the row marginal error) against the float64
 oracle, on the three arithmetic paths.  Tolerances as for fs_solve: |df|/eps <= 1e-4 in fp32-accuracy
 mode, <= 2e-2 in bf16 mode against the oracle on the unrounded inputs (and 2e-4 against the oracle
 on the bf16-rounded inputs, which separates rounding of the data from the kernels' arithmetic)."""
@@ -95,3 +96,49 @@ def test_symmetric_zero_iterations_leaves_potentials(ctx):
     say("solve_symmetric with iters=0")
     ctx.fs_solve_symmetric(prob, 0.3, 0, f, g)
     assert np.array_equal(host(f), f0.astype(np.float64)) and np.array_equal(host(g), g0.astype(np.float64))
+
+
+# ---- early stopping on the row marginal error (fs_solve_tol) ---------------------------------
+@pytest.mark.parametrize("n,m,d,eps", [(400, 500, 3, 0.1), (300, 260, 40, 0.15)])
+def test_solve_tol_stops_where_the_oracle_does(ctx, oracle, n, m, d, eps):
+    rng = np.random.default_rng(31 * n + d)
+    x, y, a, b = _problem(rng, n, m, d, 1.0 if d <= 16 else 0.4)
+    eps = float(np.float32(eps))
+    check_every, max_iters = 3, 30
+    # the oracle's trajectory and its row errors at the check points
+    fo, go = np.zeros(n), np.zeros(m)
+    errs = {}
+    for t in range(1, max_iters + 1):
+        fo, go = oracle.solve(x, y, a, b, eps, eps, 1, 1, f0=fo, g0=go)
+        if t % check_every == 0:
+            errs[t] = (oracle.marginal_err(x, y, a, b, eps, fo, go)[0], fo.copy(), go.copy())
+    checks = sorted(errs)
+    # a tolerance well between the errors at the third and fourth check, so that both sides stop at the fourth
+    tol = float(np.sqrt(errs[checks[2]][0] * errs[checks[3]][0]))
+    say("solve_tol n=%d m=%d d=%d eps=%g: oracle errors at checks %s, tol=%.3e"
+        % (n, m, d, eps, ["%.2e" % errs[t][0] for t in checks[:5]], tol))
+    prob = make_problem(x, y, a, b)
+    f = torch.zeros(n, device="cuda:0")
+    g = torch.zeros(m, device="cuda:0")
+    done, err = ctx.fs_solve_tol(prob, eps, max_iters, check_every, tol, f, g)
+    want_err, want_f, want_g = errs[checks[3]]
+    say("  stopped after %d iterations with error %.6e (oracle: %d, %.6e)" % (done, err, checks[3], want_err))
+    assert done == checks[3]
+    assert abs(err - want_err) <= 1e-5
+    assert max_err_over_eps(host(f), want_f, eps) <= 1e-4 and max_err_over_eps(host(g), want_g, eps) <= 1e-4
+
+
+def test_solve_tol_runs_to_max_iters(ctx, oracle):
+    rng = np.random.default_rng(8)
+    n, m, d = 200, 150, 3
+    x, y, a, b = _problem(rng, n, m, d, 1.0)
+    eps = float(np.float32(0.05))
+    say("solve_tol with tol = 0: runs all 7 iterations")
+    prob = make_problem(x, y, a, b)
+    f = torch.zeros(n, device="cuda:0")
+    g = torch.zeros(m, device="cuda:0")
+    done, err = ctx.fs_solve_tol(prob, eps, 7, 5, 0.0, f, g)
+    fo, go = oracle.solve(x, y, a, b, eps, eps, 1, 7)
+    assert done == 7
+    assert abs(err - oracle.marginal_err(x, y, a, b, eps, fo, go)[0]) <= 1e-5
+    assert max_err_over_eps(host(f), fo, eps) <= 1e-4 and max_err_over_eps(host(g), go, eps) <= 1e-4
