@@ -4,7 +4,7 @@ import pytest
 import torch
 
 from paper_2602_03067_amd import binding, workloads
-from tests._gpu_common import dev, make_problem, say
+from tests._gpu_common import dev, host, make_problem, max_err_over_eps, say
 
 pytestmark = pytest.mark.gpu
 
@@ -56,3 +56,39 @@ def test_value_bf16_mode(ctx, oracle):
     got = ctx.fs_ot_value(make_problem(x, y, a, b, compute=binding.FS_COMPUTE_BF16_MFMA), eps, dev(f32), dev(g32))
     say("  dual gpu=%.9f oracle on bf16-rounded inputs=%.9f" % (got, dual_b))
     assert abs(got - dual_b) <= 2e-4 * (abs(dual_b) + eps)
+
+
+def test_debiased_divergence_from_three_solves(ctx, oracle):
+    """S(a, b) = OT(a, b) - OT(a, a)/2 - OT(b, b)/2 with each term the dual value after a fixed
+    number of iterations from zero potentials: three fs_solve + fs_ot_value calls through the ABI,
+    against the same composition of the oracle's functions."""
+    rng = np.random.default_rng(21)
+    n, m, d = 350, 290, 3
+    x, y, a, b = _problem(rng, n, m, d, 1.0)
+    eps = float(np.float32(0.2))
+    iters = 40
+
+    def gpu_value(p, q, wp, wq):
+        prob = make_problem(p, q, wp, wq)
+        f = torch.zeros(len(p), device="cuda:0")
+        g = torch.zeros(len(q), device="cuda:0")
+        ctx.fs_solve(prob, eps, eps, 1, iters, f, g)
+        return ctx.fs_ot_value(prob, eps, f, g), f, g
+
+    def oracle_value(p, q, wp, wq, f32, g32):
+        # the dual value at the SAME float potentials (the solve itself is covered by the solver tests)
+        return oracle.objectives(p, q, wp, wq, eps, f32.astype(np.float64), g32.astype(np.float64))[1]
+
+    say("debiased divergence from three solves, n=%d m=%d" % (n, m))
+    total_gpu, total_ref = 0.0, 0.0
+    for (p, q, wp, wq, coef) in ((x, y, a, b, 1.0), (x, x, a, a, -0.5), (y, y, b, b, -0.5)):
+        v, f, g = gpu_value(p, q, wp, wq)
+        fo, go = oracle.solve(p, q, wp, wq, eps, eps, 1, iters)
+        assert max_err_over_eps(host(f), fo, eps) <= 1e-4 and max_err_over_eps(host(g), go, eps) <= 1e-4
+        ref = oracle_value(p, q, wp, wq, host(f), host(g))
+        assert abs(v - ref) <= 1e-5 * (abs(ref) + eps)
+        total_gpu += coef * v
+        total_ref += coef * oracle.objectives(p, q, wp, wq, eps, fo, go)[1]
+    say("  divergence gpu=%.8f oracle=%.8f" % (total_gpu, total_ref))
+    assert total_gpu > 0.0
+    assert abs(total_gpu - total_ref) <= 2e-5 * (abs(total_ref) + eps)
