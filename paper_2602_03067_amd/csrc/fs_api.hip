@@ -118,15 +118,6 @@ double stage_eps(double e0, double e1, int stages, int s)
     return (double)(float)(e0 * pow(e1 / e0, (double)s / (double)(stages - 1)));
 }
 
-int max_splits_for(const Ctx *c, Path path, int64_t n_res, int64_t n_str)
-{
-    (void)c;
-    (void)path;
-    (void)n_res;
-    (void)n_str;
-    return kMaxSplits;
-}
-
 // Lay the prepared problem out in the workspace; returns bytes needed.  With base == nullptr
 // only the size is computed.
 size_t layout(const Ctx *c, const fs_problem *p, Prepared *P, char *base, size_t extra)
@@ -179,8 +170,9 @@ size_t layout(const Ctx *c, const fs_problem *p, Prepared *P, char *base, size_t
     side(P->X, p->n, p->a);
     side(P->Y, p->m, p->b);
     int64_t big = P->X.cnt_pad > P->Y.cnt_pad ? P->X.cnt_pad : P->Y.cnt_pad;
-    int ms = max_splits_for(c, P->path, p->n, p->m);
-    P->partial_bytes = (size_t)ms * big * 16;
+    // [splits][rows] records of the pass over either side
+    const size_t pbx = (size_t)max_splits(p->n) * P->X.cnt_pad * 16, pby = (size_t)max_splits(p->m) * P->Y.cnt_pad * 16;
+    P->partial_bytes = pbx > pby ? pbx : pby;
     size_t o = A.take(P->partial_bytes);
     P->partial = base ? (void *)(base + o) : nullptr;
     o = A.take((size_t)ceil_div(big, 256) * 8);

@@ -344,7 +344,8 @@ fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
     {
         int best_s = 1;
         double best_cost = 1e300;
-        const int smax = a.n_itiles < kMaxSplits ? a.n_itiles : kMaxSplits;
+        const int cap = max_splits(res->cnt);
+        const int smax = a.n_itiles < cap ? a.n_itiles : cap;
         for (int sp = 1; sp <= smax; ++sp) {
             int tps = (int)ceil_div(a.n_itiles, sp);
             int seff = (int)ceil_div(a.n_itiles, tps);

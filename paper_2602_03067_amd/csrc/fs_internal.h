@@ -19,7 +19,14 @@ constexpr double kLog2e = 1.4426950408889634074;   // log2(e)
 constexpr double kLn2 = 0.69314718055994530942;    // ln(2)
 constexpr float kNegInit = -3.0e38f;               // finite "-inf" seed of the running max
 constexpr int kLowdMaxD = 16;                      // d <= 16: fp32 vector-ALU path
-constexpr int kMaxSplits = 64;                     // max column splits of one streaming pass
+// Most column splits of one streaming pass over `n_res` resident rows: as many as fill the chip
+// even for a handful of rows (n << m), as long as the [splits][rows] partial records stay at 64 MB.
+inline int max_splits(int64_t n_res)
+{
+    const int64_t pad = (n_res + 1023) / 1024 * 1024;
+    const int64_t s = (int64_t(64) << 20) / (pad * 16);
+    return s < 1 ? 1 : (s > 1024 ? 1024 : (int)s);
+}
 
 // fp32-accurate scores on the bf16 matrix cores (low-d path).  A float v is the sum of three bf16
 // pieces v1 + v2 + v3 (each the bf16 rounding of what the previous ones leave).  A product c x_k y_k

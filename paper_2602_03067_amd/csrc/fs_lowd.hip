@@ -561,7 +561,7 @@ PassShape shape_for(const Ctx *c, int64_t n_res, int64_t n_str, int rows_per_blo
     int target = 32 * c->num_cu;
     int splits = (int)ceil_div(target, s.row_blocks);
     if (splits > n_tiles) splits = n_tiles;
-    if (splits > kMaxSplits) splits = kMaxSplits;
+    if (splits > max_splits(n_res)) splits = max_splits(n_res);
     if (splits < 1) splits = 1;
     int tps = (int)ceil_div(n_tiles, splits);
     s.splits = (int)ceil_div(n_tiles, tps);

@@ -142,3 +142,30 @@ def test_solve_tol_runs_to_max_iters(ctx, oracle):
     assert done == 7
     assert abs(err - oracle.marginal_err(x, y, a, b, eps, fo, go)[0]) <= 1e-5
     assert max_err_over_eps(host(f), fo, eps) <= 1e-4 and max_err_over_eps(host(g), go, eps) <= 1e-4
+
+
+# ---- extreme aspect ratio: a few hundred rows against tens of thousands (split reduction) ------
+@pytest.mark.parametrize("d,mode", [(3, "fp32"), (64, "fp32"), (64, "bf16")])
+def test_few_rows_many_columns(ctx, oracle, d, mode):
+    """n = 500, m = 50000: the f-update has two to eight row blocks, so nearly all parallelism comes
+    from splitting the streamed side into hundreds of pieces that are merged afterwards; the
+    g-update is the opposite shape."""
+    rng = np.random.default_rng(500 + d)
+    n, m = 500, 50000
+    x, y, a, b = _problem(rng, n, m, d, 1.0 if d <= 16 else 0.35)
+    eps = float(np.float32(0.3 if d <= 16 else 1.0))
+    g0 = (0.2 * rng.standard_normal(m)).astype(np.float32)
+    f0 = (0.2 * rng.standard_normal(n)).astype(np.float32)
+    say("update_f / update_g n=%d m=%d d=%d %s mode" % (n, m, d, mode))
+    if mode == "bf16":
+        prob = make_problem(x, y, a, b, compute=binding.FS_COMPUTE_BF16_MFMA)
+        xo, yo, tol = workloads.to_bf16_round(x), workloads.to_bf16_round(y), 2e-4
+    else:
+        prob = make_problem(x, y, a, b)
+        xo, yo, tol = x, y, 1e-4
+    f = host(ctx.fs_update_f(prob, eps, dev(g0)))
+    g = host(ctx.fs_update_g(prob, eps, dev(f0)))
+    ef = max_err_over_eps(f, oracle.update_f(xo, yo, b, eps, g0), eps)
+    eg = max_err_over_eps(g, oracle.update_g(xo, yo, a, eps, f0), eps)
+    say("  max|df|/eps=%.3e max|dg|/eps=%.3e" % (ef, eg))
+    assert ef <= tol and eg <= tol
