@@ -494,3 +494,42 @@ def test_sampled_gaussians_near_closed_form(oracle):
     val = float(np.dot(w.a.astype(np.float64), f) + np.dot(w.b.astype(np.float64), g))
     exact = _gaussian_eot(np.zeros(3), np.eye(3), 0.5 * np.ones(3), np.eye(3), 0.1)
     assert abs(val - exact) < 0.5                      # sampling error of 1024 points in 3-d
+
+
+# ---- Hessian-vector product (Thm. 5): the dense oracle against differences of the gradient ----
+def test_hvp_dense_matches_central_differences_of_the_gradient(oracle):
+    """G = d/dh grad_X OT(X + h A) at h = 0, with grad_X OT = 2 (diag(a) X - P* Y) (Cor. 4) taken
+    at CONVERGED potentials of the perturbed clouds: shares no formula with the decomposition."""
+    from oracle import hvp_dense
+    rng = np.random.default_rng(17)
+    n, m, d = 9, 7, 2
+    x = rng.standard_normal((n, d))
+    y = rng.standard_normal((m, d)) * 0.8 + 0.3
+    a = rng.random(n) + 0.5
+    a /= a.sum()
+    b = rng.random(m) + 0.5
+    b /= b.sum()
+    A = rng.standard_normal((n, d))
+    eps = 0.7
+
+    def grad(xx):
+        f, g = oracle.solve(xx, y, a, b, eps, eps, 1, 4000)
+        PY = oracle.apply_plan(xx, y, a, b, eps, f, g, y)
+        return 2.0 * (a[:, None] * xx - PY)
+
+    h = 1e-4
+    G_fd = (grad(x + h * A) - grad(x - h * A)) / (2.0 * h)
+    f, g = oracle.solve(x, y, a, b, eps, eps, 1, 4000)
+    G = hvp_dense.hvp(x, y, a, b, eps, f, g, A)
+    assert np.abs(G - G_fd).max() <= 2e-6 * np.abs(G_fd).max()
+    # a small damping changes little, and the Schur route equals the pseudo-inverse route as tau -> 0
+    G_tau = hvp_dense.hvp(x, y, a, b, eps, f, g, A, tau=1e-9)
+    assert np.abs(G_tau - G).max() <= 1e-5 * np.abs(G).max()
+    # linear in A
+    A2 = rng.standard_normal((n, d))
+    lhs = hvp_dense.hvp(x, y, a, b, eps, f, g, 2.0 * A - 3.0 * A2, tau=1e-6)
+    rhs = 2.0 * hvp_dense.hvp(x, y, a, b, eps, f, g, A, tau=1e-6) - 3.0 * hvp_dense.hvp(x, y, a, b, eps, f, g, A2, tau=1e-6)
+    assert np.abs(lhs - rhs).max() <= 1e-9 * np.abs(rhs).max()
+    # the Hessian is symmetric: <B, T A> = <A, T B>
+    TB = hvp_dense.hvp(x, y, a, b, eps, f, g, A2)
+    assert abs((A2 * G).sum() - (A * TB).sum()) <= 1e-8 * abs((A2 * G).sum())
