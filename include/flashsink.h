@@ -203,6 +203,26 @@ fs_status fs_apply_plan_T(fs_ctx *ctx, const fs_problem *prob, float eps, const 
                           int64_t ldo, float *c_out);
 
 /*
+ * Hessian-vector product G = T A of the entropic OT value with respect to the source
+ * cloud x (Thm. 5): the matrix-free Schur-complement / conjugate-gradient oracle of
+ * App. E, built on streamed applications of the plan that (f, g) induce:
+ * (2 K + 3) transport-vector products, three transport-matrix products and one
+ * Hadamard-weighted transport (Alg. 5), K the number of CG iterations.  The plan's own
+ * marginals are used throughout, so (f, g) need not be converged.
+ *   A   [n x d] device floats, row stride lda: the direction
+ *   tau >= 0    Tikhonov damping of the Schur system (S + tau I); 0 is allowed
+ *   eta, max_cg CG stops at relative residual eta or after max_cg iterations
+ *   out [n x d] device floats, row stride ldo
+ *   cg_iters    HOST int32 (may be NULL): iterations CG took
+ * Available for float32 points, FS_COMPUTE_FP32 and d <= 16 (FS_ERR_UNSUPPORTED
+ * otherwise).  Synchronises the stream (CG's scalars are read by the host).
+ */
+fs_status fs_hvp(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f /* device */,
+                 const float *g /* device */, const float *A /* device */, int64_t lda, float tau,
+                 float eta, int32_t max_cg, float *out /* device */, int64_t ldo,
+                 int32_t *cg_iters /* host, nullable */);
+
+/*
  * Timing hook for benchmarks: average duration in milliseconds of the streaming
  * LSE kernel launches recorded with HIP events on the context's stream since the
  * last call of this function, and their count.  Where a solve mixes two LSE

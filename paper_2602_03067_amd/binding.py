@@ -22,7 +22,7 @@ FS_COMPUTE_FP32, FS_COMPUTE_BF16_MFMA = 0, 1
 EXPORTS = (
     "fs_create", "fs_destroy", "fs_status_str", "fs_last_error", "fs_version", "fs_row_norms",
     "fs_update_f", "fs_update_g", "fs_solve", "fs_solve_symmetric", "fs_solve_tol", "fs_marginal_err", "fs_ot_value", "fs_apply_plan",
-    "fs_apply_plan_T", "fs_profile_enable", "fs_profile_read",
+    "fs_apply_plan_T", "fs_hvp", "fs_profile_enable", "fs_profile_read",
 )
 
 
@@ -76,6 +76,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fs_ot_value.argtypes = [vp, PP, f32, vp, vp, ctypes.POINTER(ctypes.c_double)]
     lib.fs_apply_plan.argtypes = [vp, PP, f32, vp, vp, vp, i64, i64, vp, i64, vp]
     lib.fs_apply_plan_T.argtypes = [vp, PP, f32, vp, vp, vp, i64, i64, vp, i64, vp]
+    lib.fs_hvp.argtypes = [vp, PP, f32, vp, vp, vp, i64, f32, f32, i32, vp, i64, ctypes.POINTER(i32)]
     lib.fs_profile_enable.argtypes = [vp, i32]
     lib.fs_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64),
                                     ctypes.POINTER(ctypes.c_double)]
@@ -242,6 +243,19 @@ class Context:
     def fs_apply_plan_T(self, prob: Problem, eps: float, f, g, U, want_mass: bool = False):
         return self._apply(self.lib.fs_apply_plan_T, "fs_apply_plan_T", prob, eps, f, g, U, prob.m,
                            prob.n, want_mass)
+
+    def fs_hvp(self, prob: Problem, eps: float, f: torch.Tensor, g: torch.Tensor, A: torch.Tensor,
+               tau: float, eta: float, max_cg: int) -> Tuple[torch.Tensor, int]:
+        """Hessian-vector product T A (Thm. 5); returns (G [n x d], CG iterations)."""
+        _dev_f32(f, "f", (prob.n,))
+        _dev_f32(g, "g", (prob.m,))
+        _dev_f32(A, "A", (prob.n, prob.d))
+        out = torch.empty(prob.n, prob.d, dtype=torch.float32, device=f.device)
+        it = ctypes.c_int32()
+        self._check(self.lib.fs_hvp(self.h, ctypes.byref(prob.c), eps, _ptr(f), _ptr(g), _ptr(A), prob.d,
+                                    float(tau), float(eta), int(max_cg), _ptr(out), prob.d, ctypes.byref(it)),
+                    "fs_hvp")
+        return out, it.value
 
     def fs_profile_enable(self, on: bool) -> None:
         self._check(self.lib.fs_profile_enable(self.h, 1 if on else 0), "fs_profile_enable")

@@ -612,6 +612,41 @@ fs_status fs_apply_plan_T(fs_ctx *ctx, const fs_problem *prob, float eps, const 
     return apply_common(reinterpret_cast<Ctx *>(ctx), prob, eps, f, g, U, p, ldu, out, ldo, c_out, true);
 }
 
+fs_status fs_hvp(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, const float *g, const float *A,
+                 int64_t lda, float tau, float eta, int32_t max_cg, float *out, int64_t ldo, int32_t *cg_iters)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    fs_status st = validate_problem(c, prob);
+    if (st != FS_OK) return st;
+    if ((st = validate_eps(c, eps)) != FS_OK) return st;
+    if (!f || !g || !A) return fail(c, FS_ERR_INVALID_ARG, "f, g or A is NULL");
+    if (lda < prob->d || ldo < prob->d) return fail(c, FS_ERR_BAD_SHAPE, "lda and ldo must be at least d");
+    if (!(tau >= 0.0f) || !(eta >= 0.0f) || max_cg < 0)
+        return fail(c, FS_ERR_BAD_EPS, "need tau >= 0, eta >= 0 and max_cg >= 0");
+    if (prob->dtype != FS_F32 || prob->compute != FS_COMPUTE_FP32 || prob->d > kLowdMaxD)
+        return fail(c, FS_ERR_UNSUPPORTED,
+                    "the Hessian-vector product is available for float32 points, FS_COMPUTE_FP32 and d <= 16");
+    const size_t out_bytes = (size_t)((prob->n - 1) * ldo + prob->d) * 4;
+    if ((st = check_out(c, prob, out, out_bytes, "out")) != FS_OK) return st;
+    if (overlap(out, out_bytes, A, (size_t)((prob->n - 1) * lda + prob->d) * 4) ||
+        overlap(out, out_bytes, f, (size_t)prob->n * 4) || overlap(out, out_bytes, g, (size_t)prob->m * 4))
+        return fail(c, FS_ERR_INVALID_ARG, "out overlaps an input");
+    Prepared P;
+    const size_t ws_f = lowd_apply_ws(c, prob->n, prob->m, prob->d), ws_g = lowd_apply_ws(c, prob->m, prob->n, prob->d);
+    const size_t apply_ws = ((ws_f > ws_g ? ws_f : ws_g) + 255) & ~size_t(255);
+    char *extra = nullptr;
+    if ((st = prepare(c, prob, &P, apply_ws + hvp_scratch_bytes(prob->n, prob->m, prob->d), &extra)) != FS_OK) return st;
+    P.extra = extra;
+    P.extra_bytes = apply_ws;
+    if ((st = launch_bias_from_user(c, &P, &P.X, f, eps)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps)) != FS_OK) return st;
+    int iters = 0;
+    st = hvp_run(c, &P, static_cast<const float *>(prob->x), prob->ldx, static_cast<const float *>(prob->y), prob->ldy,
+                 (double)eps, A, lda, (double)tau, (double)eta, max_cg, out, ldo, extra + apply_ws, &iters);
+    if (cg_iters) *cg_iters = iters;
+    return st;
+}
+
 fs_status fs_profile_enable(fs_ctx *ctx, int32_t on)
 {
     Ctx *c = reinterpret_cast<Ctx *>(ctx);

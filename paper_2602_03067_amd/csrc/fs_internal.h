@@ -226,6 +226,12 @@ fs_status launch_apply_finalize(Ctx *c, const Prepared *P, const Side *res, cons
                                 double eps, const float *opart, int PC, int p0, int p, float *out, int64_t ldo,
                                 float *mass_out);
 
+// fs_hvp.hip
+size_t hvp_scratch_bytes(int64_t n, int64_t m, int64_t d);
+fs_status hvp_run(Ctx *c, Prepared *P, const float *x, int64_t ldx, const float *y, int64_t ldy, double eps,
+                  const float *A, int64_t lda, double tau, double eta, int max_cg, float *out, int64_t ldo,
+                  char *scratch, int *cg_iters);
+
 // fs_lowd.hip
 PassShape lowd_shape(const Ctx *c, int64_t n_res, int64_t n_str);
 // true: this half-step runs the low-d pass with float64 scores (norm), false: float (norm_f)
@@ -233,8 +239,11 @@ bool lowd_precise(const Prepared *P, double eps);
 fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,
                    int *splits_out);
 size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t p);
+// had_A != nullptr: Hadamard-weighted transport (Alg. 5), every plan entry times <had_A row i, centred
+// streamed point j>; had_A is [res->cnt][lda] floats.
 fs_status lowd_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,
-                     const float *V, int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out);
+                     const float *V, int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out,
+                     const float *had_A = nullptr, int64_t lda = 0);
 
 // fs_f64.hip
 fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,

@@ -441,12 +441,16 @@ __global__ __launch_bounds__(kBlock, 2) void k_lse_lowd_split(SplitArgs a)
 // ---- plan application (Alg. 2 / Alg. 4): the same pass with a value accumulator ----------
 // Every lane owns ONE resident row and PC columns of the output; the streamed tile carries
 // the PC values of each streamed point next to its coordinates.
-template <typename S, int D, int PC>
+// HAD = true is the Hadamard-weighted transport of Alg. 5, (P o (A Yc^T)) V: every plan entry is
+// multiplied by <A_i, yc_j> with A_i the resident row of a second matrix and yc_j the streamed
+// point as stored (centred at the common mean; the caller adds the mean's share).
+template <typename S, int D, int PC, bool HAD>
 __global__ __launch_bounds__(kBlock) void k_apply_lowd(const S *__restrict__ res, const S *__restrict__ str,
                                                        const float *__restrict__ V, int64_t ldv, int p0, int p,
                                                        int64_t n_str, S cscale, int tiles_per_split, int n_tiles,
                                                        double2 *__restrict__ partial, int64_t partial_stride,
-                                                       float *__restrict__ opart, int64_t opart_stride)
+                                                       float *__restrict__ opart, int64_t opart_stride,
+                                                       const float *__restrict__ had_A, int64_t lda, int64_t n_res)
 {
     constexpr int P16 = Pack<S>::per16;
     constexpr int DP = (D + 1 + P16 - 1) / P16 * P16;
@@ -462,6 +466,11 @@ __global__ __launch_bounds__(kBlock) void k_apply_lowd(const S *__restrict__ res
         const S *px = res + row * DP;
 #pragma unroll
         for (int k = 0; k < D; ++k) xs[k] = px[k] * cscale;
+    }
+    float ar[HAD ? D : 1];
+    if constexpr (HAD) {
+#pragma unroll
+        for (int k = 0; k < D; ++k) ar[k] = row < n_res ? had_A[row * lda + k] : 0.0f;
     }
     float mrun = kNegInit, srun = 0.0f;
     float O[PC];
@@ -485,6 +494,7 @@ __global__ __launch_bounds__(kBlock) void k_apply_lowd(const S *__restrict__ res
 #pragma unroll 1
         for (int j = 0; j < kTJ; j += kT) {
             S sc[kT];
+            float wv[HAD ? kT : 1];
 #pragma unroll
             for (int c = 0; c < kT; ++c) {
                 S yv[DP];
@@ -493,6 +503,12 @@ __global__ __launch_bounds__(kBlock) void k_apply_lowd(const S *__restrict__ res
 #pragma unroll
                 for (int k = 0; k < D; ++k) acc = xs[k] * yv[k] + acc;
                 sc[c] = acc;
+                if constexpr (HAD) {
+                    float wsum = 0.0f;
+#pragma unroll
+                    for (int k = 0; k < D; ++k) wsum = fmaf(ar[k], (float)yv[k], wsum);
+                    wv[c] = wsum;
+                }
             }
             float mx = (float)sc[0];
 #pragma unroll
@@ -507,6 +523,7 @@ __global__ __launch_bounds__(kBlock) void k_apply_lowd(const S *__restrict__ res
             for (int c = 0; c < kT; ++c) {
                 float e = fast_exp2((float)(sc[c] - mS));
                 srun += e;
+                if constexpr (HAD) e *= wv[c];
 #pragma unroll
                 for (int q = 0; q < PC; ++q) O[q] = fmaf(e, vt[j + c][q], O[q]);
             }
@@ -532,10 +549,15 @@ void launch_lse_d(int R, dim3 grid, hipStream_t st, const double *res, const dou
 
 template <typename S, int D>
 void launch_apply_d(dim3 grid, hipStream_t st, const S *res, const S *str, const float *V, int64_t ldv, int p0, int p,
-                    int64_t n_str, S cscale, int tps, int n_tiles, double2 *partial, int64_t stride, float *opart)
+                    int64_t n_str, S cscale, int tps, int n_tiles, double2 *partial, int64_t stride, float *opart,
+                    const float *had_A, int64_t lda, int64_t n_res)
 {
-    hipLaunchKernelGGL((k_apply_lowd<S, D, kApplyPC>), grid, dim3(kBlock), 0, st, res, str, V, ldv, p0, p, n_str, cscale,
-                       tps, n_tiles, partial, stride, opart, stride);
+    if (had_A)
+        hipLaunchKernelGGL((k_apply_lowd<S, D, kApplyPC, true>), grid, dim3(kBlock), 0, st, res, str, V, ldv, p0, p, n_str,
+                           cscale, tps, n_tiles, partial, stride, opart, stride, had_A, lda, n_res);
+    else
+        hipLaunchKernelGGL((k_apply_lowd<S, D, kApplyPC, false>), grid, dim3(kBlock), 0, st, res, str, V, ldv, p0, p, n_str,
+                           cscale, tps, n_tiles, partial, stride, opart, stride, had_A, lda, n_res);
 }
 
 #define FS_LOWD_DISPATCH(D_, CALL)                                                                       \
@@ -696,7 +718,7 @@ size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t p)
 }
 
 fs_status lowd_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, const float *V,
-                     int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out)
+                     int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out, const float *had_A, int64_t lda)
 {
     PassShape s = shape_for(c, res->cnt, str->cnt, kBlock);
     const int n_tiles = (int)ceil_div(str->cnt, kTJ);
@@ -713,11 +735,13 @@ fs_status lowd_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str
         if (precise) {
             FS_LOWD_DISPATCH((int)P->d, (launch_apply_d<double, DD>(grid, c->stream, res->packed_d, str->packed_d, V, ldv,
                                                                     p0, (int)p, str->cnt, cscale, tps, n_tiles,
-                                                                    (double2 *)P->partial, res->cnt_pad, opart)));
+                                                                    (double2 *)P->partial, res->cnt_pad, opart, had_A, lda,
+                                                                    res->cnt)));
         } else {
             FS_LOWD_DISPATCH((int)P->d, (launch_apply_d<float, DD>(grid, c->stream, res->packed, str->packed, V, ldv, p0,
                                                                    (int)p, str->cnt, (float)cscale, tps, n_tiles,
-                                                                   (double2 *)P->partial, res->cnt_pad, opart)));
+                                                                   (double2 *)P->partial, res->cnt_pad, opart, had_A, lda,
+                                                                   res->cnt)));
         }
         fs_status st = launch_apply_finalize(c, P, res, precise ? res->norm : res->norm_f, s.splits, eps, opart,
                                              kApplyPC, p0, (int)p, out, ldo, mass_out);

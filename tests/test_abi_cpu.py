@@ -102,6 +102,13 @@ def test_solve_count_validation(lib, hctx):
                             ctypes.byref(it), ctypes.byref(er)) == 3
     assert lib.fs_solve_tol(hctx, ctypes.byref(p), F(0.1), 5, 1, F(1e-3), P(1 << 21), P(1 << 20), None,
                             ctypes.byref(er)) == 1
+    k = ctypes.c_int32()
+    assert lib.fs_hvp(hctx, ctypes.byref(p), F(0.1), P(1 << 21), P(1 << 20), None, 3, F(1e-5), F(1e-6), 10,
+                      P(1 << 22), 3, ctypes.byref(k)) == 1
+    assert lib.fs_hvp(hctx, ctypes.byref(p), F(0.1), P(1 << 21), P(1 << 20), P(1 << 23), 2, F(1e-5), F(1e-6), 10,
+                      P(1 << 22), 3, ctypes.byref(k)) == 2
+    assert lib.fs_hvp(hctx, ctypes.byref(p), F(0.1), P(1 << 21), P(1 << 20), P(1 << 23), 3, F(-1.0), F(1e-6), 10,
+                      P(1 << 22), 3, ctypes.byref(k)) == 3
     v = ctypes.c_double()
     assert lib.fs_ot_value(hctx, ctypes.byref(p), F(0.1), P(1 << 21), P(1 << 20), None) == 1
     assert lib.fs_ot_value(hctx, ctypes.byref(p), F(-1.0), P(1 << 21), P(1 << 20), ctypes.byref(v)) == 3
