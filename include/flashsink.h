@@ -214,8 +214,8 @@ fs_status fs_apply_plan_T(fs_ctx *ctx, const fs_problem *prob, float eps, const 
  *   eta, max_cg CG stops at relative residual eta or after max_cg iterations
  *   out [n x d] device floats, row stride ldo
  *   cg_iters    HOST int32 (may be NULL): iterations CG took
- * Available for float32 points, FS_COMPUTE_FP32 and d <= 16 (FS_ERR_UNSUPPORTED
- * otherwise).  Synchronises the stream (CG's scalars are read by the host).
+ * Available for float32 points and FS_COMPUTE_FP32 (FS_ERR_UNSUPPORTED otherwise).
+ * Synchronises the stream (CG's scalars are read by the host).
  */
 fs_status fs_hvp(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f /* device */,
                  const float *g /* device */, const float *A /* device */, int64_t lda, float tau,

@@ -623,16 +623,17 @@ fs_status fs_hvp(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f,
     if (lda < prob->d || ldo < prob->d) return fail(c, FS_ERR_BAD_SHAPE, "lda and ldo must be at least d");
     if (!(tau >= 0.0f) || !(eta >= 0.0f) || max_cg < 0)
         return fail(c, FS_ERR_BAD_EPS, "need tau >= 0, eta >= 0 and max_cg >= 0");
-    if (prob->dtype != FS_F32 || prob->compute != FS_COMPUTE_FP32 || prob->d > kLowdMaxD)
-        return fail(c, FS_ERR_UNSUPPORTED,
-                    "the Hessian-vector product is available for float32 points, FS_COMPUTE_FP32 and d <= 16");
+    if (prob->dtype != FS_F32 || prob->compute != FS_COMPUTE_FP32)
+        return fail(c, FS_ERR_UNSUPPORTED, "the Hessian-vector product is available for float32 points and FS_COMPUTE_FP32");
     const size_t out_bytes = (size_t)((prob->n - 1) * ldo + prob->d) * 4;
     if ((st = check_out(c, prob, out, out_bytes, "out")) != FS_OK) return st;
     if (overlap(out, out_bytes, A, (size_t)((prob->n - 1) * lda + prob->d) * 4) ||
         overlap(out, out_bytes, f, (size_t)prob->n * 4) || overlap(out, out_bytes, g, (size_t)prob->m * 4))
         return fail(c, FS_ERR_INVALID_ARG, "out overlaps an input");
     Prepared P;
-    const size_t ws_f = lowd_apply_ws(c, prob->n, prob->m, prob->d), ws_g = lowd_apply_ws(c, prob->m, prob->n, prob->d);
+    const bool lowd = choose_path(prob) == Path::LowD;
+    const size_t ws_f = lowd ? lowd_apply_ws(c, prob->n, prob->m, prob->d) : f64_apply_ws(c, prob->n, prob->m, prob->d, prob->d);
+    const size_t ws_g = lowd ? lowd_apply_ws(c, prob->m, prob->n, prob->d) : f64_apply_ws(c, prob->m, prob->n, prob->d, prob->d);
     const size_t apply_ws = ((ws_f > ws_g ? ws_f : ws_g) + 255) & ~size_t(255);
     char *extra = nullptr;
     if ((st = prepare(c, prob, &P, apply_ws + hvp_scratch_bytes(prob->n, prob->m, prob->d), &extra)) != FS_OK) return st;

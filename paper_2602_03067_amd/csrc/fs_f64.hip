@@ -50,17 +50,24 @@ struct PassArgs {
     int64_t ldv, n_str;
     int p0, p;
     float *opart;            // [splits][partial_stride][PCH]
+    // Hadamard-weighted application only (Alg. 5): every plan entry times <hadA row of the
+    // resident point, streamed point>
+    const float *hadA;       // [n_res][lda]
+    int64_t lda, n_res;
+    int d;                   // real number of coordinates (columns of hadA)
 };
 
 // (two workgroups per CU for the LSE pass: with at most 256 registers per lane the compiler keeps
 // the MFMA accumulators in ordinary VGPRs; with more it parks them in AGPRs and copies all of them
 // in and out around every group of MFMAs)
-template <bool APPLY> __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
+template <bool APPLY, bool HAD = false>
+__global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
 {
     __shared__ double res_lds[BR * LDR];          // 33,280 B; reused for the final merge
     __shared__ double str_lds[BC * LDS_];         // 16,896 B
     __shared__ double bias_lds[BC];
     __shared__ float vt[APPLY ? BC * PCH : 1];    // 16,384 B (application)
+    __shared__ double had_lds[HAD ? BR * LDR : 1];  // 33,280 B: rows of hadA, laid out like res_lds
     __shared__ float mw[4][BR];                   // per-wave running max (final merge)
     __shared__ float sred[BR][17];                // per-(wave, lane group) sums (final merge)
 
@@ -78,6 +85,12 @@ template <bool APPLY> __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pa
             double2 v = *reinterpret_cast<const double2 *>(a.res + (row0 + r) * kp + kk);
             res_lds[r * LDR + kk] = v.x;
             res_lds[r * LDR + kk + 1] = v.y;
+        }
+        if constexpr (HAD) {
+            for (int e = tid; e < BR * kp; e += 256) {
+                int r = e / kp, kk = e - r * kp;
+                had_lds[r * LDR + kk] = (row0 + r < a.n_res && kk < a.d) ? (double)a.hadA[(row0 + r) * a.lda + kk] : 0.0;
+            }
         }
     }
 
@@ -101,7 +114,7 @@ template <bool APPLY> __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pa
     // Staging of one (tile, chunk) stage goes through registers: its global loads are issued
     // before the MFMAs of the previous stage and stored to LDS after them, so the memory latency
     // is covered by matrix work.
-    double2 pre_s[4 * IT], pre_r[4];
+    double2 pre_s[4 * IT], pre_r[4], pre_a[HAD ? 4 : 1];
     double pre_b = 0.0;
     auto fetch = [&](int t, int ch) {
         const int64_t col0 = (int64_t)t * BC;
@@ -116,6 +129,12 @@ template <bool APPLY> __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pa
             if (!res_cached && q < 4) {
                 pre_r[q] = make_double2(0.0, 0.0);
                 if (kk < kw) pre_r[q] = *reinterpret_cast<const double2 *>(a.res + (row0 + cidx) * kp + kc0 + kk);
+                if constexpr (HAD) {
+                    const int64_t rr = row0 + cidx;
+                    const int k0 = kc0 + kk;
+                    pre_a[q].x = (rr < a.n_res && k0 < a.d) ? (double)a.hadA[rr * a.lda + k0] : 0.0;
+                    pre_a[q].y = (rr < a.n_res && k0 + 1 < a.d) ? (double)a.hadA[rr * a.lda + k0 + 1] : 0.0;
+                }
             }
         }
         if (ch == 0 && tid < BC) pre_b = a.bias[col0 + tid];
@@ -130,6 +149,10 @@ template <bool APPLY> __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pa
             if (!res_cached && q < 4) {
                 res_lds[cidx * LDR + kk] = pre_r[q].x;
                 res_lds[cidx * LDR + kk + 1] = pre_r[q].y;
+                if constexpr (HAD) {
+                    had_lds[cidx * LDR + kk] = pre_a[q].x;
+                    had_lds[cidx * LDR + kk + 1] = pre_a[q].y;
+                }
             }
         }
         if (ch == 0 && tid < BC) bias_lds[tid] = pre_b;
@@ -139,10 +162,14 @@ template <bool APPLY> __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pa
     for (int t = t_begin; t < t_end; ++t) {
         const int64_t col0 = (int64_t)t * BC;
         d4 acc[IT][4];
+        d4 accW[HAD ? IT : 1][HAD ? 4 : 1];   // <hadA row, streamed point> (Hadamard weights)
 #pragma unroll
         for (int it = 0; it < IT; ++it)
 #pragma unroll
-            for (int jt = 0; jt < 4; ++jt) acc[it][jt] = d4{0.0, 0.0, 0.0, 0.0};
+            for (int jt = 0; jt < 4; ++jt) {
+                acc[it][jt] = d4{0.0, 0.0, 0.0, 0.0};
+                if constexpr (HAD) accW[it][jt] = d4{0.0, 0.0, 0.0, 0.0};
+            }
 
         for (int ch = 0; ch < n_chunks; ++ch) {
             const int kc0 = ch * KC;
@@ -166,6 +193,7 @@ template <bool APPLY> __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pa
             const int kbase = res_cached ? kc0 : 0;
             const double *sa = str_lds + (16 * IT * w + lj) * LDS_ + lg;
             const double *sb = res_lds + lj * LDR + kbase + lg;
+            const double *sw = had_lds + lj * LDR + kbase + lg;
             auto kstep = [&](int kk) {
                 double av[IT], bv[4];
 #pragma unroll
@@ -177,6 +205,16 @@ template <bool APPLY> __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pa
 #pragma unroll
                     for (int jt = 0; jt < 4; ++jt)
                         acc[it][jt] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[it], bv[jt], acc[it][jt], 0, 0, 0);
+                if constexpr (HAD) {
+                    double wv[4];
+#pragma unroll
+                    for (int jt = 0; jt < 4; ++jt) wv[jt] = sw[jt * 16 * LDR + kk];
+#pragma unroll
+                    for (int it = 0; it < IT; ++it)
+#pragma unroll
+                        for (int jt = 0; jt < 4; ++jt)
+                            accW[it][jt] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[it], wv[jt], accW[it][jt], 0, 0, 0);
+                }
             };
             if (kw == KC) {
                 // full chunk: unrolled, so that the accumulators stay where the MFMAs want them
@@ -263,6 +301,7 @@ template <bool APPLY> __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pa
                         float e = fast_exp2((float)(s[jt][r] - md));
                         csum += e;
                         E[r] = (double)e;
+                        if constexpr (HAD) E[r] *= accW[it][jt][r];
                     }
                     srun[jt] += csum;
 #pragma unroll
@@ -376,7 +415,7 @@ fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, d
         (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp & 3) != 0)
         return fail(c, FS_ERR_DEVICE, "internal: fp64 launch shape exceeds the padded buffers");
     prof_begin(c, (double)res->cnt * (double)str->cnt);
-    hipLaunchKernelGGL(k_pass_f64<false>, dim3((unsigned)s.row_blocks, (unsigned)s.splits), dim3(256), 0, c->stream, a);
+    hipLaunchKernelGGL((k_pass_f64<false, false>), dim3((unsigned)s.row_blocks, (unsigned)s.splits), dim3(256), 0, c->stream, a);
     prof_end(c);
     FS_HIP(c, hipGetLastError());
     *splits_out = s.splits;
@@ -392,7 +431,7 @@ size_t f64_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t d, int64
 }
 
 fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, const float *V,
-                    int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out)
+                    int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out, const float *hadA, int64_t lda)
 {
     PassShape s = shape_f64(c, res->cnt, str->cnt);
     PassArgs a{};
@@ -410,13 +449,21 @@ fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str,
     a.n_str = str->cnt;
     a.p = (int)p;
     a.opart = (float *)P->extra;
+    a.hadA = hadA;
+    a.lda = lda;
+    a.n_res = res->cnt;
+    a.d = (int)P->d;
     if ((int64_t)s.row_blocks * BR > res->cnt_pad || (int64_t)a.n_tiles * BC > str->cnt_pad ||
         (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp & 3) != 0 ||
         (size_t)s.splits * res->cnt_pad * PCH * 4 > P->extra_bytes)
         return fail(c, FS_ERR_DEVICE, "internal: fp64 apply launch shape exceeds the padded buffers");
     for (int p0 = 0; p0 < p; p0 += PCH) {
         a.p0 = p0;
-        hipLaunchKernelGGL(k_pass_f64<true>, dim3((unsigned)s.row_blocks, (unsigned)s.splits), dim3(256), 0, c->stream,
+        if (hadA)
+            hipLaunchKernelGGL((k_pass_f64<true, true>), dim3((unsigned)s.row_blocks, (unsigned)s.splits), dim3(256), 0,
+                               c->stream, a);
+        else
+            hipLaunchKernelGGL((k_pass_f64<true, false>), dim3((unsigned)s.row_blocks, (unsigned)s.splits), dim3(256), 0, c->stream,
                            a);
         fs_status st = launch_apply_finalize(c, P, res, res->norm, s.splits, eps, a.opart, PCH, p0, (int)p, out, ldo,
                                              mass_out);

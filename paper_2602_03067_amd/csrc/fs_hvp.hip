@@ -6,7 +6,7 @@
 // consistent for potentials that are not converged.
 //
 // This file holds the O(n + m) vector kernels and the host loop (conjugate gradients); the
-// O(n m) work is done by the plan-application kernels of the low-d path.
+// O(n m) work is done by the plan-application kernels (low-d or fp64 matrix-core path).
 #include "fs_internal.h"
 
 #include <math.h>
@@ -41,7 +41,8 @@ __global__ void k_rowdot_mean(const float *A, int64_t lda, const double *mean, i
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= rows) return;
     double s = 0.0;
-    for (int k = 0; k < d; ++k) s += (double)A[i * lda + k] * mean[k];
+    if (mean)   // (the fp64 matrix-core path does not centre: no share)
+        for (int k = 0; k < d; ++k) s += (double)A[i * lda + k] * mean[k];
     out[i] = (float)s;
 }
 
@@ -189,6 +190,13 @@ fs_status hvp_run(Ctx *c, Prepared *P, const float *x, int64_t ldx, const float 
 
     Side *X = &P->X, *Y = &P->Y;
     fs_status s;
+    const bool lowd = P->path == Path::LowD;
+    // one streamed application: out = P V (res = X) or P^T V (res = Y); hadA: Hadamard weights (Alg. 5)
+    auto apply = [&](const Side *rs, const Side *ss, const float *V, int64_t p, int64_t ldv, float *o, int64_t ldo_,
+                     float *mass, const float *hadA = nullptr, int64_t lda_ = 0) -> fs_status {
+        return lowd ? lowd_apply(c, P, rs, ss, eps, V, p, ldv, o, ldo_, mass, hadA, lda_)
+                    : f64_apply(c, P, rs, ss, eps, V, p, ldv, o, ldo_, mass, hadA, lda_);
+    };
     auto dot = [&](const float *a, const float *b, int64_t cnt, double *host) -> fs_status {
         hipLaunchKernelGGL(k_dot, g256(cnt), dim3(256), 0, st, a, b, cnt, part);
         hipLaunchKernelGGL(k_sum, dim3(1), dim3(256), 0, st, part, (int64_t)ceil_div(cnt, 256), scal);
@@ -198,16 +206,16 @@ fs_status hvp_run(Ctx *c, Prepared *P, const float *x, int64_t ldx, const float 
     };
 
     // transport-matrix products P Y (with r = P 1) and P^T A (with c = P^T 1); row-wise dots
-    if ((s = lowd_apply(c, P, X, Y, eps, y, d, ldy, PY, d, r)) != FS_OK) return s;
-    if ((s = lowd_apply(c, P, Y, X, eps, A, d, lda, PtA, d, cm)) != FS_OK) return s;
+    if ((s = apply(X, Y, y, d, ldy, PY, d, r)) != FS_OK) return s;
+    if ((s = apply(Y, X, A, d, lda, PtA, d, cm)) != FS_OK) return s;
     hipLaunchKernelGGL(k_rowdot, g256(n), dim3(256), 0, st, x, ldx, A, lda, n, d, u);
     hipLaunchKernelGGL(k_rowdot, g256(n), dim3(256), 0, st, PY, (int64_t)d, A, lda, n, d, uP);
     hipLaunchKernelGGL(k_rowdot, g256(m), dim3(256), 0, st, PtA, (int64_t)d, y, ldy, m, d, rd);
-    hipLaunchKernelGGL(k_rowdot_mean, g256(n), dim3(256), 0, st, A, lda, P->mean, n, d, cA);
+    hipLaunchKernelGGL(k_rowdot_mean, g256(n), dim3(256), 0, st, A, lda, lowd ? P->mean : (const double *)nullptr, n, d, cA);
     // right-hand sides
     hipLaunchKernelGGL(k_rhs_n, g256(n), dim3(256), 0, st, r, u, uP, n, r1, t1);
-    if ((s = lowd_apply(c, P, Y, X, eps, u, 1, 1, Ptu, 1, nullptr)) != FS_OK) return s;
-    if ((s = lowd_apply(c, P, Y, X, eps, t1, 1, 1, Ptt1, 1, nullptr)) != FS_OK) return s;
+    if ((s = apply(Y, X, u, 1, 1, Ptu, 1, nullptr)) != FS_OK) return s;
+    if ((s = apply(Y, X, t1, 1, 1, Ptt1, 1, nullptr)) != FS_OK) return s;
     hipLaunchKernelGGL(k_rhs_m, g256(m), dim3(256), 0, st, Ptu, rd, Ptt1, m, rhs, w2, res, pdir);
     FS_HIP(c, hipGetLastError());
 
@@ -218,9 +226,9 @@ fs_status hvp_run(Ctx *c, Prepared *P, const float *x, int64_t ldx, const float 
     int k = 0;
     for (; k < max_cg; ++k) {
         if (!(rr > 0.0) || sqrt(rr) <= eta * sqrt(rr0)) break;
-        if ((s = lowd_apply(c, P, X, Y, eps, pdir, 1, 1, q1, 1, nullptr)) != FS_OK) return s;
+        if ((s = apply(X, Y, pdir, 1, 1, q1, 1, nullptr)) != FS_OK) return s;
         hipLaunchKernelGGL(k_div, g256(n), dim3(256), 0, st, q1, r, n, q1);
-        if ((s = lowd_apply(c, P, Y, X, eps, q1, 1, 1, Ptq, 1, nullptr)) != FS_OK) return s;
+        if ((s = apply(Y, X, q1, 1, 1, Ptq, 1, nullptr)) != FS_OK) return s;
         hipLaunchKernelGGL(k_schur, g256(m), dim3(256), 0, st, cm, pdir, Ptq, (float)tau, m, Sp);
         double pSp = 0.0;
         if ((s = dot(pdir, Sp, m, &pSp)) != FS_OK) return s;
@@ -235,11 +243,11 @@ fs_status hvp_run(Ctx *c, Prepared *P, const float *x, int64_t ldx, const float 
     if (cg_iters) *cg_iters = k;
 
     // back-substitution, R^T w, Hadamard-weighted transport, assembly
-    if ((s = lowd_apply(c, P, X, Y, eps, w2, 1, 1, Pw2, 1, nullptr)) != FS_OK) return s;
+    if ((s = apply(X, Y, w2, 1, 1, Pw2, 1, nullptr)) != FS_OK) return s;
     hipLaunchKernelGGL(k_w1, g256(n), dim3(256), 0, st, r1, Pw2, r, n, w1);
     hipLaunchKernelGGL(k_scale_rows, g256(m * d), dim3(256), 0, st, w2, y, ldy, m, d, V2);
-    if ((s = lowd_apply(c, P, X, Y, eps, V2, d, d, PV2, d, nullptr)) != FS_OK) return s;
-    if ((s = lowd_apply(c, P, X, Y, eps, y, d, ldy, B5c, d, nullptr, A, lda)) != FS_OK) return s;
+    if ((s = apply(X, Y, V2, d, d, PV2, d, nullptr)) != FS_OK) return s;
+    if ((s = apply(X, Y, y, d, ldy, B5c, d, nullptr, A, lda)) != FS_OK) return s;
     hipLaunchKernelGGL(k_assemble, g256(n * d), dim3(256), 0, st, x, ldx, A, lda, PY, PV2, B5c, r, u, uP, w1, Pw2, cA,
                        1.0 / eps, n, d, out, ldo);
     FS_HIP(c, hipGetLastError());

@@ -250,7 +250,8 @@ fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, d
                   int *splits_out);
 size_t f64_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t d, int64_t p);
 fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,
-                    const float *V, int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out);
+                    const float *V, int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out,
+                    const float *hadA = nullptr, int64_t lda = 0);
 
 // fs_bf16.hip
 fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,

@@ -33,7 +33,8 @@ def _problem(rng, n, m, d):
 
 
 @pytest.mark.parametrize("n,m,d,eps,iters", [(60, 45, 2, 0.5, 200), (300, 260, 3, 0.4, 60), (512, 512, 4, 0.5, 100),
-                                             (130, 700, 8, 1.0, 30)])
+                                             (130, 700, 8, 1.0, 30),
+                                             (200, 170, 20, 2.0, 40), (150, 260, 64, 6.0, 30), (70, 90, 100, 10.0, 20)])
 def test_hvp_matches_dense_oracle(ctx, oracle, n, m, d, eps, iters):
     from oracle import hvp_dense
     rng = np.random.default_rng(7 * n + m + d)
@@ -77,10 +78,10 @@ def test_hvp_is_linear_in_the_direction(ctx, oracle):
 
 def test_hvp_refuses_what_it_does_not_cover(ctx):
     rng = np.random.default_rng(1)
-    x, y, a, b = _problem(rng, 40, 30, 20)
+    x, y, a, b = _problem(rng, 40, 30, 32)
     f = torch.zeros(40, device="cuda:0")
     g = torch.zeros(30, device="cuda:0")
-    A = torch.zeros(40, 20, device="cuda:0")
-    say("hvp with d = 20 is refused")
+    A = torch.zeros(40, 32, device="cuda:0")
+    say("hvp in bf16 mode is refused")
     with pytest.raises(binding.FlashSinkError):
-        ctx.fs_hvp(make_problem(x, y, a, b), 0.5, f, g, A, 1e-5, 1e-6, 10)
+        ctx.fs_hvp(make_problem(x, y, a, b, compute=binding.FS_COMPUTE_BF16_MFMA), 0.5, f, g, A, 1e-5, 1e-6, 10)
