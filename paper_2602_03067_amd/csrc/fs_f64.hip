@@ -60,7 +60,9 @@ struct PassArgs {
 // (two workgroups per CU for the LSE pass: with at most 256 registers per lane the compiler keeps
 // the MFMA accumulators in ordinary VGPRs; with more it parks them in AGPRs and copies all of them
 // in and out around every group of MFMAs)
-template <bool APPLY, bool HAD = false>
+// NCT: 16-column blocks of the value matrix this launch produces (1..4); transport-vector products
+// (one column) then do a quarter of the second contraction
+template <bool APPLY, bool HAD = false, int NCT = 4>
 __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
 {
     __shared__ double res_lds[BR * LDR];          // 33,280 B; reused for the final merge
@@ -95,7 +97,7 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
     }
 
     float mrun[4], srun[4];
-    d4 O[APPLY ? 4 : 1][APPLY ? 4 : 1];
+    d4 O[APPLY ? 4 : 1][APPLY ? NCT : 1];
 #pragma unroll
     for (int jt = 0; jt < 4; ++jt) {
         mrun[jt] = kNegInit;
@@ -105,7 +107,7 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt)
 #pragma unroll
-            for (int ct = 0; ct < 4; ++ct) O[jt][ct] = d4{0.0, 0.0, 0.0, 0.0};
+            for (int ct = 0; ct < NCT; ++ct) O[jt][ct] = d4{0.0, 0.0, 0.0, 0.0};
     }
 
     const int t_begin = blockIdx.y * a.tiles_per_split;
@@ -287,7 +289,7 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
                             // accumulator register r holds resident row 4r + lg of this column block
                             double sc = (double)__shfl(scale, 4 * r + lg, 64);
 #pragma unroll
-                            for (int ct = 0; ct < 4; ++ct) O[jt][ct][r] *= sc;
+                            for (int ct = 0; ct < NCT; ++ct) O[jt][ct][r] *= sc;
                         }
                     }
                 }
@@ -307,7 +309,7 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
 #pragma unroll
-                        for (int ct = 0; ct < 4; ++ct) {
+                        for (int ct = 0; ct < NCT; ++ct) {
                             double vv = (double)vt[(sp0 + 4 * r + lg) * PCH + 16 * ct + lj];
                             O[jt][ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(E[r], vv, O[jt][ct], 0, 0, 0);
                         }
@@ -355,7 +357,7 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
                         float M = fmaxf(fmaxf(mw[0][row], mw[1][row]), fmaxf(mw[2][row], mw[3][row]));
                         double sc = (double)fast_exp2(mw[w][row] - M);
 #pragma unroll
-                        for (int ct = 0; ct < 4; ++ct) {
+                        for (int ct = 0; ct < NCT; ++ct) {
                             int idx = row * PCH + 16 * ct + lj;
                             double v = O[jt][ct][r] * sc;
                             obuf[idx] = (ww == 0) ? v : obuf[idx] + v;
@@ -366,7 +368,7 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
         }
         for (int e = tid; e < BR * PCH; e += 256) {
             int r = e >> 6, cc = e & 63;
-            a.opart[((int64_t)blockIdx.y * a.partial_stride + row0 + r) * PCH + cc] = (float)obuf[e];
+            a.opart[((int64_t)blockIdx.y * a.partial_stride + row0 + r) * PCH + cc] = cc < 16 * NCT ? (float)obuf[e] : 0.0f;
         }
     }
     __syncthreads();
@@ -459,12 +461,25 @@ fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str,
         return fail(c, FS_ERR_DEVICE, "internal: fp64 apply launch shape exceeds the padded buffers");
     for (int p0 = 0; p0 < p; p0 += PCH) {
         a.p0 = p0;
-        if (hadA)
-            hipLaunchKernelGGL((k_pass_f64<true, true>), dim3((unsigned)s.row_blocks, (unsigned)s.splits), dim3(256), 0,
-                               c->stream, a);
-        else
-            hipLaunchKernelGGL((k_pass_f64<true, false>), dim3((unsigned)s.row_blocks, (unsigned)s.splits), dim3(256), 0, c->stream,
-                           a);
+        const dim3 grid((unsigned)s.row_blocks, (unsigned)s.splits);
+        const int nct = (int)ceil_div((p - p0 < PCH ? p - p0 : (int64_t)PCH), 16);
+#define FS_F64_APPLY(H, N) hipLaunchKernelGGL((k_pass_f64<true, H, N>), grid, dim3(256), 0, c->stream, a)
+        if (hadA) {
+            switch (nct) {
+            case 1: FS_F64_APPLY(true, 1); break;
+            case 2: FS_F64_APPLY(true, 2); break;
+            case 3: FS_F64_APPLY(true, 3); break;
+            default: FS_F64_APPLY(true, 4); break;
+            }
+        } else {
+            switch (nct) {
+            case 1: FS_F64_APPLY(false, 1); break;
+            case 2: FS_F64_APPLY(false, 2); break;
+            case 3: FS_F64_APPLY(false, 3); break;
+            default: FS_F64_APPLY(false, 4); break;
+            }
+        }
+#undef FS_F64_APPLY
         fs_status st = launch_apply_finalize(c, P, res, res->norm, s.splits, eps, a.opart, PCH, p0, (int)p, out, ldo,
                                              mass_out);
         if (st != FS_OK) return st;
