@@ -18,6 +18,8 @@
 // the row-wise LSE runs inside the lane; lanes/waves are merged once per workgroup.
 #include "fs_internal.h"
 
+#include <stdlib.h>
+
 
 namespace fs {
 namespace {
@@ -26,12 +28,7 @@ typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 
 constexpr int BI = 256;          // streamed points per tile (4 waves x 64)
-constexpr int BJ = 256;          // resident rows per workgroup (2 waves x 128)
-constexpr int NT = 512;          // threads per workgroup: 8 waves, two per SIMD
 constexpr int KC = 32;           // contraction chunk per pipeline stage (bf16 elements) = 64 B per row
-constexpr int ROWS = BI + BJ;
-constexpr int STAGE_BYTES = ROWS * KC * 2;   // 32,768 B
-constexpr int NSTAGE = 4;        // ring of stages filled by direct global->LDS loads (3 in flight)
 constexpr int NBIAS = 8;         // ring of bias tiles (one per stage, deeper than the data ring)
 constexpr float kLazyMax = 1.152921504606846976e18f;   // 2^60
 
@@ -39,6 +36,7 @@ __device__ inline float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
 
 // all LDS reads of this wave have returned, then the workgroup barrier
 __device__ inline void lds_done_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+template <int N> __device__ inline void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 struct BfArgs {
     const uint16_t *res;     // resident side, tiled bf16 copy (see k_prep_bf16)
@@ -51,7 +49,16 @@ struct BfArgs {
     int64_t partial_stride;
 };
 
-// LDS layout of a stage: row r (0..255 streamed, 256..511 resident) occupies 64 bytes = four
+// Workgroup shapes (WJ = waves along the resident side, each owning 128 resident rows; four waves
+// along the streamed side, each owning 64 of the tile's 256 streamed points):
+//   WJ = 2: 512 threads, 256 x 256 tile, ring of 4 stages x 32 KB, one workgroup per CU;
+//   WJ = 1: 256 threads, 256 x 128 tile, ring of 3 stages x 24 KB, two workgroups per CU, which
+//           run out of phase: one's tile epilogue (vector ALU only) and barrier waits are covered by
+//           the other's MFMAs, at the price of 1.5x the operand traffic per flop.  Measured slower
+//           (8.8 against 7.9 ms at n = m = 70000, d = 784): the operand traffic costs more than the
+//           overlap brings.  Kept selectable (FS_BF16_WJ=1) for experiments.
+//
+// LDS layout of a stage: row r (0..255 streamed, then the resident rows) occupies 64 bytes = four
 // 16-byte pieces; piece p is stored at position p ^ ((r >> 1) & 3), which makes the 8 lanes that
 // the LDS serves per cycle hit 8 different 16-byte bank groups when they read one MFMA fragment.
 // The derived bf16 copies in HBM already have this layout in 1 KB tiles (16 rows x 32 coordinates),
@@ -61,21 +68,29 @@ struct BfArgs {
 // Schedule of one stage g in every wave (F0/F1 = fragment registers of the two 16-wide k-steps):
 //     4 MFMA on F0(g) | read F1(g) | 4 MFMA on F0(g) | 4 MFMA on F1(g) |
 //     wait "stage g+1 landed" + barrier | read F0(g+1) | 4 MFMA on F1(g)
-// with the direct loads of stage g+3 issued between the first MFMAs by ONE of the two waves of
-// every SIMD (alternating per stage): VMEM issue blocks the wave when the L1 path is busy (a stage
-// is 32 KB = ~630 cycles at 52 B/clk/CU), and the sibling wave keeps the MFMA pipe busy meanwhile.
-// The barrier and the LDS latency of the next fragments hide behind the last MFMAs.
+// with the direct loads of stage g + NS - 1 (this wave's 1 KB pieces and its quarter of the bias
+// tile) issued one by one between the first MFMAs.  The barrier and the LDS latency of the next
+// fragments hide behind the last MFMAs.
 // Ceiling: with random operands the matrix cores sustain ~1.83 PFLOP/s here (a loop of nothing but
 // this MFMA: 2.42 PFLOP/s on constant operands, 1.83 on uniform random ones), i.e. the chip is
 // power-limited well below the 2.5 PFLOP/s peak that the roofline fraction is quoted against.
-__global__ __launch_bounds__(NT, 1) void k_lse_bf16(BfArgs a)
+template <int WJ, int NS>
+__global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a)
 {
-    __shared__ __attribute__((aligned(1024))) unsigned char ring[NSTAGE * STAGE_BYTES];   // 131,072 B
+    constexpr int BJ = 128 * WJ;                 // resident rows per workgroup
+    constexpr int ROWS = BI + BJ;
+    constexpr int STAGE_BYTES = ROWS * KC * 2;   // 32 KB / 24 KB
+    constexpr int NW = 4 * WJ;                   // waves
+    constexpr int PPW = (ROWS / 16) / NW;        // 1 KB pieces of a stage per wave: 4 / 6
+    constexpr int NPW = PPW + 1;                 // ... plus its share of the bias tile
+    constexpr int D = NS - 1;                    // stages in flight
+    static_assert((ROWS / 16) % NW == 0 && NPW <= 12 && D >= 2 && D <= 3, "pipeline shape");
+    __shared__ __attribute__((aligned(1024))) unsigned char ring[NS * STAGE_BYTES];
     __shared__ __attribute__((aligned(256))) float bias_ring[NBIAS][BI];                 // 8,192 B
 
     // ---- which (resident tile, split) this workgroup owns.  Workgroups go to XCDs round-robin;
     // each XCD gets a contiguous, equally long run of the work list, which is ordered in patches of
-    // 8 resident tiles x 8 splits (clipped at the edges), so that the ~32 workgroups running on an
+    // 8 resident tiles x 8 splits (clipped at the edges), so that the workgroups running on an
     // XCD at any time share their panels through that XCD's L2.
     const int b = blockIdx.x;
     const int total = a.n_jtiles * a.splits;
@@ -117,33 +132,26 @@ __global__ __launch_bounds__(NT, 1) void k_lse_bf16(BfArgs a)
     const unsigned bias_off = (unsigned)(size_t)&bias_ring[0][0];
 
     // The bf16 copies are stored as 1 KB tiles (16 rows x 32 coordinates, already swizzled), tile
-    // (row block rb, chunk ch) at byte ((rb * n_chunks + ch) << 10): a stage is 32 linear 1 KB
-    // copies, four per wave (segments 8q + w; 0..15 streamed rows, 16..31 resident rows).
+    // (row block rb, chunk ch) at byte ((rb * n_chunks + ch) << 10): a stage is ROWS/16 linear
+    // 1 KB copies, PPW per wave (pieces q NW + w; 0..15 streamed rows, then the resident rows).
     const unsigned char *res_tiles =
-        reinterpret_cast<const unsigned char *>(a.res) + (((int64_t)jtile * 16 * n_chunks) << 10) + l * 16;
+        reinterpret_cast<const unsigned char *>(a.res) + (((int64_t)jtile * (BJ / 16) * n_chunks) << 10) + l * 16;
     const unsigned char *str_tiles = reinterpret_cast<const unsigned char *>(a.str) + l * 16;
 
-    // Loads of a stage are issued by the four waves whose resident-side index wj equals the stage
-    // parity (one wave per SIMD), nine pieces each: eight 1 KB tiles (segments 4q + wi) and 256 B
-    // of bias.  A wave that stalls on the L1 path while issuing leaves the MFMA pipe of its SIMD to
-    // its sibling wave, which issues nothing during that stage.
-    int pg = wj, pch = wj, pt = t_begin;   // next stage this wave issues: number, chunk, tile
-    while (pch >= n_chunks) {
-        pch -= n_chunks;
-        ++pt;
-    }
-    auto issue_piece = [&](int q) {      // q = 0..7: 1 KB of points, q = 8: bias, then advance by two stages
-        if (q < 8) {
-            const int sidx = 4 * q + wi;
-            const unsigned char *src = q < 4 ? str_tiles + ((((int64_t)pt * 16 + sidx) * n_chunks + pch) << 10)
-                                             : res_tiles + ((((int64_t)(sidx - 16)) * n_chunks + pch) << 10);
-            dma16(src, ring_off + (pg & (NSTAGE - 1)) * STAGE_BYTES + sidx * 1024);
+    int pg = 0, pch = 0, pt = t_begin;   // next stage this wave issues: number, chunk, tile
+    auto issue_piece = [&](int q) {      // q < PPW: 1 KB of points, q == PPW: bias, then advance to the next stage
+        if (q < PPW) {
+            const int sidx = q * NW + w;
+            const unsigned char *src = sidx < 16 ? str_tiles + ((((int64_t)pt * 16 + sidx) * n_chunks + pch) << 10)
+                                                 : res_tiles + ((((int64_t)(sidx - 16)) * n_chunks + pch) << 10);
+            dma16(src, ring_off + (pg % NS) * STAGE_BYTES + sidx * 1024);
         } else {
+            // (with two waves per streamed quarter both write the same 256 bytes: harmless, and every
+            // wave has the same number of loads in flight)
             dma4(a.bias + (int64_t)pt * BI + wi * 64 + l, bias_off + (pg & (NBIAS - 1)) * (BI * 4) + wi * 256);
-            pg += 2;
-            pch += 2;
-            while (pch >= n_chunks) {
-                pch -= n_chunks;
+            ++pg;
+            if (++pch == n_chunks) {
+                pch = 0;
                 ++pt;
             }
         }
@@ -162,24 +170,28 @@ __global__ __launch_bounds__(NT, 1) void k_lse_bf16(BfArgs a)
     const int pk0 = ((0 + lh) ^ sw) * 16, pk1 = ((2 + lh) ^ sw) * 16;
     bf8 a0[2], b0[4], a1[2], b1[4];
     auto read_frags = [&](bf8(&af)[2], bf8(&bf)[4], int stage, int pk) {
-        const unsigned char *sb = ring + (stage & (NSTAGE - 1)) * STAGE_BYTES + pk;
+        const unsigned char *sb = ring + (stage % NS) * STAGE_BYTES + pk;
 #pragma unroll
         for (int it = 0; it < 2; ++it) af[it] = *reinterpret_cast<const bf8 *>(sb + offA + it * 32 * 64);
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt) bf[jt] = *reinterpret_cast<const bf8 *>(sb + offB + jt * 32 * 64);
     };
-
-    // ---- prologue: three stages in flight, stage 0 landed, its first fragments on the way ----
-    // (even waves issue stages 0 and 2, odd waves stage 1)
-    while (pg < 3 && pg < G)
-#pragma unroll
-        for (int q = 0; q < 9; ++q) issue_piece(q);
-    if (wj == 0) {
-        if (G > 2)
-            asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+    // this wave's loads of stage `upto` and older have landed, given that it has issued stages up to `issued`
+    auto wait_landed = [&](int upto, int issued) {
+        const int newer = issued - upto;   // whole stages issued after `upto`
+        if (newer >= 2)
+            wait_vm<2 * NPW>();
+        else if (newer == 1)
+            wait_vm<NPW>();
         else
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
+            wait_vm<0>();
+    };
+
+    // ---- prologue: D stages in flight, stage 0 landed, its first fragments on the way ----
+    while (pg < D && pg < G)
+#pragma unroll
+        for (int q = 0; q < NPW; ++q) issue_piece(q);
+    wait_landed(0, pg - 1);
     lds_done_barrier();
     read_frags(a0, b0, 0, pk0);
 
@@ -194,14 +206,13 @@ __global__ __launch_bounds__(NT, 1) void k_lse_bf16(BfArgs a)
                 for (int r = 0; r < 16; ++r) acc[it][jt][r] = 0.0f;
 
         for (int ch = 0; ch < n_chunks; ++ch, ++g) {
-            // this wave issues stage g+3 now iff the parities match; it is then also the one that
-            // issued stage g+1 and has to see it landed before the barrier below
-            const bool mine = ((g + 1) & 1) == wj;
-            const bool issue = mine && g + 3 < G;
+            // Stage g + D goes to the ring slot of stage g - 1, which nobody reads any more: every
+            // wave had its reads of that stage back before it passed the barrier of stage g - 1.
+            const bool issue = g + D < G;
 #define FS_MFMA(IT, JT, AF, BF) acc[IT][JT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(AF[IT], BF[JT], acc[IT][JT], 0, 0, 0)
 #define FS_PIECE(Q)                          \
     __builtin_amdgcn_sched_barrier(0);       \
-    if (issue) issue_piece(Q);               \
+    if (Q < NPW && issue) issue_piece(Q);    \
     __builtin_amdgcn_sched_barrier(0)
             // (only F0(g) is pending here, so the wait the compiler puts before the first MFMA is
             // exactly "F0 has arrived"; F1 is requested behind the first MFMA group)
@@ -222,24 +233,15 @@ __global__ __launch_bounds__(NT, 1) void k_lse_bf16(BfArgs a)
             FS_MFMA(1, 2, a0, b0);
             FS_PIECE(6);
             FS_MFMA(1, 3, a0, b0);
-            FS_PIECE(7);
             FS_MFMA(0, 0, a1, b1);
-            FS_PIECE(8);
             FS_MFMA(0, 1, a1, b1);
             FS_MFMA(0, 2, a1, b1);
             FS_MFMA(0, 3, a1, b1);
             __builtin_amdgcn_sched_barrier(0);
             if (g + 1 < G) {
-                if (mine) {
-                    // stage g+1 (issued by this wave) has landed: the only newer loads of this wave
-                    // are the nine pieces of stage g+3 issued above
-                    if (issue)
-                        asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
-                    else
-                        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                }
-                // ... and after the barrier for all waves; everyone has also finished reading stage
-                // g-1 (whose ring slot the loads of stage g+3 go to), and F0 may be refilled
+                // this wave's pieces of stage g+1 have landed ...
+                wait_landed(g + 1, pg - 1);
+                // ... and after the barrier everybody's; F0 may be refilled
                 lds_done_barrier();
                 read_frags(a0, b0, g + 1, pk0);
             }
@@ -308,7 +310,7 @@ __global__ __launch_bounds__(NT, 1) void k_lse_bf16(BfArgs a)
 
     // ---- merge the 2 lane halves x 4 streamed-side waves of every resident row -------------
     lds_done_barrier();   // the ring is free: reuse it for the merge
-    float2 *red = reinterpret_cast<float2 *>(ring);   // [BJ][8]
+    float2 *red = reinterpret_cast<float2 *>(ring);   // [BJ][8]: 4 streamed-side waves x 2 lane halves per row
 #pragma unroll
     for (int jt = 0; jt < 4; ++jt) red[(128 * wj + 32 * jt + lr) * 8 + 2 * wi + lh] = make_float2(mrun[jt], srun[jt]);
     __syncthreads();
@@ -330,17 +332,20 @@ __global__ __launch_bounds__(NT, 1) void k_lse_bf16(BfArgs a)
 
 fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out)
 {
+    const char *env = getenv("FS_BF16_WJ");   // experiments: force the workgroup shape
+    const int wj = env ? (env[0] == '1' ? 1 : 2) : 2;
+    const int bj = 128 * wj, per_cu = wj == 2 ? 1 : 2;
     BfArgs a{};
     a.res = res->pts_b;
     a.str = str->pts_b;
     a.bias = str->bias_f;
     a.kp = P->kp;
     a.cscale = (float)(2.0 * kLog2e / eps);
-    a.n_jtiles = (int)ceil_div(res->cnt, BJ);
+    a.n_jtiles = (int)ceil_div(res->cnt, bj);
     a.n_itiles = (int)ceil_div(str->cnt, BI);
-    // One workgroup per CU at a time.  Pick the number of splits of the streamed side that
-    // minimises  rounds x tiles-per-workgroup  (rounds = ceil(workgroups / CUs)), i.e. the time
-    // including the idle tail of the last round; prefer fewer, longer workgroups on near-ties.
+    // Pick the number of splits of the streamed side that minimises  rounds x tiles-per-workgroup
+    // (rounds = ceil(workgroups / workgroups the chip holds at a time)), i.e. the time including the
+    // idle tail of the last round; prefer fewer, longer workgroups on near-ties.
     {
         int best_s = 1;
         double best_cost = 1e300;
@@ -350,7 +355,7 @@ fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
             int tps = (int)ceil_div(a.n_itiles, sp);
             int seff = (int)ceil_div(a.n_itiles, tps);
             if (seff != sp) continue;
-            double rounds = (double)ceil_div((int64_t)a.n_jtiles * seff, c->num_cu);
+            double rounds = (double)ceil_div((int64_t)a.n_jtiles * seff, (int64_t)c->num_cu * per_cu);
             double cost = rounds * (tps + 0.25);   // 0.25: pipeline fill and merge of a workgroup
             if (cost < best_cost * 0.99) {
                 best_cost = cost;
@@ -364,11 +369,14 @@ fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
     const int per = (total + 7) / 8;
     a.partial = (double2 *)P->partial;
     a.partial_stride = res->cnt_pad;
-    if ((int64_t)a.n_jtiles * BJ > res->cnt_pad || (int64_t)a.n_itiles * BI > str->cnt_pad ||
+    if ((int64_t)a.n_jtiles * bj > res->cnt_pad || (int64_t)a.n_itiles * BI > str->cnt_pad ||
         (size_t)a.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp & 31) != 0 || a.kp < 32)
         return fail(c, FS_ERR_DEVICE, "internal: bf16 launch shape exceeds the padded buffers");
     prof_begin(c, (double)res->cnt * (double)str->cnt);
-    hipLaunchKernelGGL(k_lse_bf16, dim3((unsigned)(per * 8)), dim3(NT), 0, c->stream, a);
+    if (wj == 2)
+        hipLaunchKernelGGL((k_lse_bf16<2, 4>), dim3((unsigned)(per * 8)), dim3(512), 0, c->stream, a);
+    else
+        hipLaunchKernelGGL((k_lse_bf16<1, 3>), dim3((unsigned)(per * 8)), dim3(256), 0, c->stream, a);
     prof_end(c);
     FS_HIP(c, hipGetLastError());
     *splits_out = a.splits;
