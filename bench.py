@@ -57,7 +57,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path is single-GPU; "
-              "see DESIGN.md for how it would shard). Use --gpus 1.", file=sys.stderr)
+              "sharding over GPUs is a design note only). Use --gpus 1.", file=sys.stderr)
         return 2
 
     import numpy as np
