@@ -84,6 +84,16 @@ def main() -> int:
     xf = prob.x.float()
     a_col = prob.a.unsqueeze(1)
 
+    apply_ms = {"apply_plan": [], "apply_plan_T": []}
+
+    def timed(key, fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        r = fn()
+        e1.record()
+        apply_ms[key].append((e0, e1))
+        return r
+
     def step():
         f.zero_()
         g.zero_()
@@ -96,8 +106,8 @@ def main() -> int:
         er, ec = ctx.fs_marginal_err(prob, w.eps_end, f, g)
         grad = None
         if can_apply:
-            PY = ctx.fs_apply_plan(prob, w.eps_end, f, g, V)
-            ctx.fs_apply_plan_T(prob, w.eps_end, f, g, U)
+            PY = timed("apply_plan", lambda: ctx.fs_apply_plan(prob, w.eps_end, f, g, V))
+            timed("apply_plan_T", lambda: ctx.fs_apply_plan_T(prob, w.eps_end, f, g, U))
             if V.shape[1] == w.d:
                 grad = 2.0 * (a_col * xf - PY)     # Cor. 4 (elementwise assembly)
         return er, ec, grad
@@ -121,6 +131,9 @@ def main() -> int:
     avg_ms, launches, pairs = ctx.fs_profile_read()
     ctx.fs_profile_enable(False)
 
+    # the two plan applications of a step, timed on torch's stream (the library's stream is the same one)
+    apply_avg = {k: (sum(a.elapsed_time(b) for a, b in v[-args.steps:]) / max(1, len(v[-args.steps:])) if v else None)
+                 for k, v in apply_ms.items()}
     ms_per_step = elapsed * 1e3 / args.steps
     iters = w.total_iters
     value = iters * args.steps / elapsed
@@ -157,6 +170,8 @@ def main() -> int:
                    "eps_end": w.eps_end, "stages": w.n_stages, "iters_per_stage": w.iters, "schedule": args.schedule,
                    "step": "row_norms + solve + marginal_err + apply_plan + apply_plan_T + grad"},
         "marginal_err": {"row": er, "col": ec},
+        "apply_ms": {"apply_plan": apply_avg["apply_plan"], "apply_plan_T": apply_avg["apply_plan_T"],
+                     "p": int(V.shape[1]), "flop_per_call": 2.0 * w.n * w.m * (w.d + int(V.shape[1]))},
         "roofline": roof,
     }
 
