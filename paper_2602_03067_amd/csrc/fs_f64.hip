@@ -25,7 +25,6 @@ namespace {
 
 typedef double d4 __attribute__((ext_vector_type(4)));
 
-constexpr int BR = 64;     // resident rows per workgroup
 constexpr int IT = 1;      // 16-point streamed blocks per wave (two were slower: 0.77 vs 0.72 ms at d = 64)
 constexpr int BC = 64 * IT;   // streamed points per tile
 constexpr int KC = 32;     // contraction chunk staged for the streamed points
@@ -62,9 +61,12 @@ struct PassArgs {
 // in and out around every group of MFMAs)
 // NCT: 16-column blocks of the value matrix this launch produces (1..4); transport-vector products
 // (one column) then do a quarter of the second contraction
-template <bool APPLY, bool HAD = false, int NCT = 4>
-__global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
+// JT: 16-row resident blocks per workgroup (4: 64 rows; 2: 32 rows, which lets the plan application
+// run two workgroups per CU without parking accumulators in AGPRs)
+template <bool APPLY, bool HAD = false, int NCT = 4, int JT = 4>
+__global__ __launch_bounds__(256, (APPLY && JT == 4) ? 1 : 2) void k_pass_f64(PassArgs a)
 {
+    constexpr int BR = 16 * JT;   // resident rows per workgroup
     __shared__ double res_lds[BR * LDR];          // 33,280 B; reused for the final merge
     __shared__ double str_lds[BC * LDS_];         // 16,896 B
     __shared__ double bias_lds[BC];
@@ -96,16 +98,16 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
         }
     }
 
-    float mrun[4], srun[4];
-    d4 O[APPLY ? 4 : 1][APPLY ? NCT : 1];
+    float mrun[JT], srun[JT];
+    d4 O[APPLY ? JT : 1][APPLY ? NCT : 1];
 #pragma unroll
-    for (int jt = 0; jt < 4; ++jt) {
+    for (int jt = 0; jt < JT; ++jt) {
         mrun[jt] = kNegInit;
         srun[jt] = 0.0f;
     }
     if constexpr (APPLY) {
 #pragma unroll
-        for (int jt = 0; jt < 4; ++jt)
+        for (int jt = 0; jt < JT; ++jt)
 #pragma unroll
             for (int ct = 0; ct < NCT; ++ct) O[jt][ct] = d4{0.0, 0.0, 0.0, 0.0};
     }
@@ -116,8 +118,12 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
     // Staging of one (tile, chunk) stage goes through registers: its global loads are issued
     // before the MFMAs of the previous stage and stored to LDS after them, so the memory latency
     // is covered by matrix work.
-    double2 pre_s[4 * IT], pre_r[4], pre_a[HAD ? 4 : 1];
+    double2 pre_s[4 * IT], pre_r[JT], pre_a[HAD ? JT : 1];
     double pre_b = 0.0;
+    // value rows of the tile go through registers too, except in the Hadamard variant, which has
+    // no registers to spare and loads them between the barriers instead
+    constexpr bool VPRE = APPLY && !HAD;
+    float pre_v[VPRE ? BC * PCH / 256 : 1];
     auto fetch = [&](int t, int ch) {
         const int64_t col0 = (int64_t)t * BC;
         const int kc0 = ch * KC;
@@ -128,7 +134,7 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
             const int cidx = e >> 4, kk = (e & 15) * 2;
             pre_s[q] = make_double2(0.0, 0.0);   // zero beyond kp
             if (kk < kw) pre_s[q] = *reinterpret_cast<const double2 *>(a.str + (col0 + cidx) * kp + kc0 + kk);
-            if (!res_cached && q < 4) {
+            if (!res_cached && q < JT) {
                 pre_r[q] = make_double2(0.0, 0.0);
                 if (kk < kw) pre_r[q] = *reinterpret_cast<const double2 *>(a.res + (row0 + cidx) * kp + kc0 + kk);
                 if constexpr (HAD) {
@@ -140,15 +146,26 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
             }
         }
         if (ch == 0 && tid < BC) pre_b = a.bias[col0 + tid];
+        if constexpr (VPRE) {
+            if (ch == 0) {
+#pragma unroll
+                for (int q = 0; q < BC * PCH / 256; ++q) {
+                    const int e = tid + 256 * q;
+                    const int cidx = e >> 6, cc = e & 63;
+                    const int64_t j = col0 + cidx;
+                    pre_v[q] = (j < a.n_str && a.p0 + cc < a.p) ? a.V[j * a.ldv + a.p0 + cc] : 0.0f;
+                }
+            }
+        }
     };
-    auto stash = [&](int ch) {
+    auto stash = [&](int ch, int t_cur) {
 #pragma unroll
         for (int q = 0; q < 4 * IT; ++q) {
             const int e = tid + 256 * q;
             const int cidx = e >> 4, kk = (e & 15) * 2;
             str_lds[cidx * LDS_ + kk] = pre_s[q].x;
             str_lds[cidx * LDS_ + kk + 1] = pre_s[q].y;
-            if (!res_cached && q < 4) {
+            if (!res_cached && q < JT) {
                 res_lds[cidx * LDR + kk] = pre_r[q].x;
                 res_lds[cidx * LDR + kk + 1] = pre_r[q].y;
                 if constexpr (HAD) {
@@ -158,17 +175,32 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
             }
         }
         if (ch == 0 && tid < BC) bias_lds[tid] = pre_b;
+        if constexpr (VPRE) {
+            if (ch == 0) {
+#pragma unroll
+                for (int q = 0; q < BC * PCH / 256; ++q) vt[tid + 256 * q] = pre_v[q];
+            }
+        } else if constexpr (APPLY) {
+            if (ch == 0) {
+                const int64_t col0 = (int64_t)t_cur * BC;
+                for (int e = tid; e < BC * PCH; e += 256) {
+                    const int cidx = e >> 6, cc = e & 63;
+                    const int64_t j = col0 + cidx;
+                    vt[e] = (j < a.n_str && a.p0 + cc < a.p) ? a.V[j * a.ldv + a.p0 + cc] : 0.0f;
+                }
+            }
+        }
     };
     if (t_begin < t_end) fetch(t_begin, 0);
 
     for (int t = t_begin; t < t_end; ++t) {
         const int64_t col0 = (int64_t)t * BC;
-        d4 acc[IT][4];
-        d4 accW[HAD ? IT : 1][HAD ? 4 : 1];   // <hadA row, streamed point> (Hadamard weights)
+        d4 acc[IT][JT];
+        d4 accW[HAD ? IT : 1][HAD ? JT : 1];   // <hadA row, streamed point> (Hadamard weights)
 #pragma unroll
         for (int it = 0; it < IT; ++it)
 #pragma unroll
-            for (int jt = 0; jt < 4; ++jt) {
+            for (int jt = 0; jt < JT; ++jt) {
                 acc[it][jt] = d4{0.0, 0.0, 0.0, 0.0};
                 if constexpr (HAD) accW[it][jt] = d4{0.0, 0.0, 0.0, 0.0};
             }
@@ -177,16 +209,7 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
             const int kc0 = ch * KC;
             const int kw = min(KC, kp - kc0);
             __syncthreads();   // previous chunk (and the previous tile's epilogue) is done with LDS
-            stash(ch);
-            if (ch == 0) {
-                if constexpr (APPLY) {
-                    for (int e = tid; e < BC * PCH; e += 256) {
-                        int cidx = e >> 6, cc = e & 63;
-                        int64_t j = col0 + cidx;
-                        vt[e] = (j < a.n_str && a.p0 + cc < a.p) ? a.V[j * a.ldv + a.p0 + cc] : 0.0f;
-                    }
-                }
-            }
+            stash(ch, t);
             __syncthreads();
             if (ch + 1 < n_chunks)
                 fetch(t, ch + 1);
@@ -197,24 +220,24 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
             const double *sb = res_lds + lj * LDR + kbase + lg;
             const double *sw = had_lds + lj * LDR + kbase + lg;
             auto kstep = [&](int kk) {
-                double av[IT], bv[4];
+                double av[IT], bv[JT];
 #pragma unroll
                 for (int it = 0; it < IT; ++it) av[it] = sa[it * 16 * LDS_ + kk];
 #pragma unroll
-                for (int jt = 0; jt < 4; ++jt) bv[jt] = sb[jt * 16 * LDR + kk];
+                for (int jt = 0; jt < JT; ++jt) bv[jt] = sb[jt * 16 * LDR + kk];
 #pragma unroll
                 for (int it = 0; it < IT; ++it)
 #pragma unroll
-                    for (int jt = 0; jt < 4; ++jt)
+                    for (int jt = 0; jt < JT; ++jt)
                         acc[it][jt] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[it], bv[jt], acc[it][jt], 0, 0, 0);
                 if constexpr (HAD) {
-                    double wv[4];
+                    double wv[JT];
 #pragma unroll
-                    for (int jt = 0; jt < 4; ++jt) wv[jt] = sw[jt * 16 * LDR + kk];
+                    for (int jt = 0; jt < JT; ++jt) wv[jt] = sw[jt * 16 * LDR + kk];
 #pragma unroll
                     for (int it = 0; it < IT; ++it)
 #pragma unroll
-                        for (int jt = 0; jt < 4; ++jt)
+                        for (int jt = 0; jt < JT; ++jt)
                             accW[it][jt] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[it], wv[jt], accW[it][jt], 0, 0, 0);
                 }
             };
@@ -240,7 +263,7 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
 
             if constexpr (!APPLY) {
 #pragma unroll
-                for (int jt = 0; jt < 4; ++jt) {
+                for (int jt = 0; jt < JT; ++jt) {
                     double s[4];
                     float mx = kNegInit;
 #pragma unroll
@@ -258,11 +281,11 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
                     mrun[jt] = mnew;
                 }
             } else {
-                double s[4][4];
-                float mx[4];
+                double s[JT][4];
+                float mx[JT];
                 bool raise = false;
 #pragma unroll
-                for (int jt = 0; jt < 4; ++jt) {
+                for (int jt = 0; jt < JT; ++jt) {
                     float m = kNegInit;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
@@ -279,7 +302,7 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
                 if (__any(raise)) {
                     // rare: lift the (integer) stabilisers and rescale sums and accumulators exactly
 #pragma unroll
-                    for (int jt = 0; jt < 4; ++jt) {
+                    for (int jt = 0; jt < JT; ++jt) {
                         float mnew = fmaxf(mrun[jt], ceilf(mx[jt]));
                         float scale = fast_exp2(mrun[jt] - mnew);
                         srun[jt] *= scale;
@@ -294,7 +317,7 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
                     }
                 }
 #pragma unroll
-                for (int jt = 0; jt < 4; ++jt) {
+                for (int jt = 0; jt < JT; ++jt) {
                     double md = (double)mrun[jt];
                     double E[4];
                     float csum = 0.0f;
@@ -324,12 +347,12 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
     if constexpr (APPLY) {
         if (lg == 0) {
 #pragma unroll
-            for (int jt = 0; jt < 4; ++jt) mw[w][16 * jt + lj] = mrun[jt];
+            for (int jt = 0; jt < JT; ++jt) mw[w][16 * jt + lj] = mrun[jt];
         }
     } else {
         // per-lane maxima differ: reduce them over the lane groups first
 #pragma unroll
-        for (int jt = 0; jt < 4; ++jt) {
+        for (int jt = 0; jt < JT; ++jt) {
             float m = mrun[jt];
             m = fmaxf(m, __shfl_xor(m, 16, 64));
             m = fmaxf(m, __shfl_xor(m, 32, 64));
@@ -340,7 +363,7 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
     }
     __syncthreads();
 #pragma unroll
-    for (int jt = 0; jt < 4; ++jt) {
+    for (int jt = 0; jt < JT; ++jt) {
         int r = 16 * jt + lj;
         float M = fmaxf(fmaxf(mw[0][r], mw[1][r]), fmaxf(mw[2][r], mw[3][r]));
         sred[r][4 * w + lg] = srun[jt] * fast_exp2(mrun[jt] - M);
@@ -350,7 +373,7 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
         for (int ww = 0; ww < 4; ++ww) {
             if (w == ww) {
 #pragma unroll
-                for (int jt = 0; jt < 4; ++jt)
+                for (int jt = 0; jt < JT; ++jt)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         int row = 16 * jt + 4 * r + lg;
@@ -381,11 +404,13 @@ __global__ __launch_bounds__(256, APPLY ? 1 : 2) void k_pass_f64(PassArgs a)
     }
 }
 
-PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str)
+constexpr int kLseJT = 4, kApplyJT = 2;   // resident blocks per workgroup of the two passes
+
+PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str, int br)
 {
     PassShape s;
-    s.rows_per_block = BR;
-    s.row_blocks = (int)ceil_div(n_res, BR);
+    s.rows_per_block = br;
+    s.row_blocks = (int)ceil_div(n_res, br);
     int n_tiles = (int)ceil_div(n_str, BC);
     int target = 2 * c->num_cu;
     int splits = (int)ceil_div(target, s.row_blocks);
@@ -402,7 +427,7 @@ PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str)
 
 fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out)
 {
-    PassShape s = shape_f64(c, res->cnt, str->cnt);
+    PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kLseJT);
     PassArgs a{};
     a.res = res->pts_d;
     a.str = str->pts_d;
@@ -413,11 +438,11 @@ fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, d
     a.tiles_per_split = (int)(s.cols_per_split / BC);
     a.partial = (double2 *)P->partial;
     a.partial_stride = res->cnt_pad;
-    if ((int64_t)s.row_blocks * BR > res->cnt_pad || (int64_t)a.n_tiles * BC > str->cnt_pad ||
+    if ((int64_t)s.row_blocks * s.rows_per_block > res->cnt_pad || (int64_t)a.n_tiles * BC > str->cnt_pad ||
         (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp & 3) != 0)
         return fail(c, FS_ERR_DEVICE, "internal: fp64 launch shape exceeds the padded buffers");
     prof_begin(c, (double)res->cnt * (double)str->cnt);
-    hipLaunchKernelGGL((k_pass_f64<false, false>), dim3((unsigned)s.row_blocks, (unsigned)s.splits), dim3(256), 0, c->stream, a);
+    hipLaunchKernelGGL((k_pass_f64<false, false, 4, kLseJT>), dim3((unsigned)s.row_blocks, (unsigned)s.splits), dim3(256), 0, c->stream, a);
     prof_end(c);
     FS_HIP(c, hipGetLastError());
     *splits_out = s.splits;
@@ -428,14 +453,14 @@ size_t f64_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t d, int64
 {
     (void)d;
     (void)p;
-    PassShape s = shape_f64(c, n_res, n_str);
+    PassShape s = shape_f64(c, n_res, n_str, 16 * kApplyJT);
     return (size_t)s.splits * (size_t)round_up(n_res, 1024) * PCH * 4;
 }
 
 fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, const float *V,
                     int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out, const float *hadA, int64_t lda)
 {
-    PassShape s = shape_f64(c, res->cnt, str->cnt);
+    PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kApplyJT);
     PassArgs a{};
     a.res = res->pts_d;
     a.str = str->pts_d;
@@ -455,7 +480,7 @@ fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str,
     a.lda = lda;
     a.n_res = res->cnt;
     a.d = (int)P->d;
-    if ((int64_t)s.row_blocks * BR > res->cnt_pad || (int64_t)a.n_tiles * BC > str->cnt_pad ||
+    if ((int64_t)s.row_blocks * s.rows_per_block > res->cnt_pad || (int64_t)a.n_tiles * BC > str->cnt_pad ||
         (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp & 3) != 0 ||
         (size_t)s.splits * res->cnt_pad * PCH * 4 > P->extra_bytes)
         return fail(c, FS_ERR_DEVICE, "internal: fp64 apply launch shape exceeds the padded buffers");
@@ -463,7 +488,7 @@ fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str,
         a.p0 = p0;
         const dim3 grid((unsigned)s.row_blocks, (unsigned)s.splits);
         const int nct = (int)ceil_div((p - p0 < PCH ? p - p0 : (int64_t)PCH), 16);
-#define FS_F64_APPLY(H, N) hipLaunchKernelGGL((k_pass_f64<true, H, N>), grid, dim3(256), 0, c->stream, a)
+#define FS_F64_APPLY(H, N) hipLaunchKernelGGL((k_pass_f64<true, H, N, kApplyJT>), grid, dim3(256), 0, c->stream, a)
         if (hadA) {
             switch (nct) {
             case 1: FS_F64_APPLY(true, 1); break;
