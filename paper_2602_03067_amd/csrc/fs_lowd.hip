@@ -256,6 +256,20 @@ __global__ __launch_bounds__(kBlock, 2) void k_lse_lowd_split(SplitArgs a)
             b[r][MK][5] = q[2];
         }
     };
+    const int t_begin = blockIdx.y * tiles_per_split;
+    const int t_end = min(n_tiles, t_begin + tiles_per_split);
+    const Unit *gsrc = reinterpret_cast<const Unit *>(str);
+
+    // a tile is a linear 16 KS TJ / 8 byte copy, moved by direct global -> LDS loads (no registers)
+    const unsigned tile_off = (unsigned)(size_t)&tile[0][0];
+    auto fetch = [&](int t, int bufi) {
+#pragma unroll
+        for (int q = 0; q < UPT; ++q)
+            dma16(gsrc + (int64_t)t * (TJ * NP) + q * kBlock + tid, tile_off + (bufi * (TJ * NP) + q * kBlock + w * 64) * 16);
+    };
+    // the first tile is on its way while the resident operands are built
+    if (t_begin < t_end) fetch(t_begin, 0);
+
     const __bf16 one = (__bf16)1.0f, zero = (__bf16)0.0f;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -298,18 +312,6 @@ __global__ __launch_bounds__(kBlock, 2) void k_lse_lowd_split(SplitArgs a)
         set_max(r, -kNegInit);
     }
 
-    const int t_begin = blockIdx.y * tiles_per_split;
-    const int t_end = min(n_tiles, t_begin + tiles_per_split);
-    const Unit *gsrc = reinterpret_cast<const Unit *>(str);
-
-    // a tile is a linear 16 KS TJ / 8 byte copy, moved by direct global -> LDS loads (no registers)
-    const unsigned tile_off = (unsigned)(size_t)&tile[0][0];
-    auto fetch = [&](int t, int bufi) {
-#pragma unroll
-        for (int q = 0; q < UPT; ++q)
-            dma16(gsrc + (int64_t)t * (TJ * NP) + q * kBlock + tid, tile_off + (bufi * (TJ * NP) + q * kBlock + w * 64) * 16);
-    };
-    if (t_begin < t_end) fetch(t_begin, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
@@ -572,20 +574,44 @@ void launch_apply_d(dim3 grid, hipStream_t st, const S *res, const S *str, const
     case 15: { constexpr int DD = 15; CALL; } break; default: { constexpr int DD = 16; CALL; } break;   \
     }
 
-PassShape shape_for(const Ctx *c, int64_t n_res, int64_t n_str, int rows_per_block, int tj = kTJ)
+// Column splits of a streaming pass.  Model (in units of the time a CU needs for one tile): a CU
+// works through its ceil(W / CUs) workgroups one tile at a time (the vector ALU is the shared
+// resource, two resident workgroups only interleave), and every round of 2 CUs workgroups pays
+// the start-up and wind-down latency of a workgroup (resident operands, first tile, merge,
+// partial store: ~5 us measured, about 7 tile times of the split kernel) once:
+//     cost(s) = ceil(W / CUs) * tiles_per_split + ceil(W / (2 CUs)) * startup + 0.3 s,   W = row_blocks * s
+// (the last term: the merge kernel that follows reads s records per row).
+// Among the split counts within 2 % of the cheapest the one closest to 32 workgroups per CU from
+// below is taken (finer load balance at large sizes; measured at n = m = 262144), else the smallest.
+// One tile per workgroup, which filling the chip 32 times over used to give at n ~ 10^4, made the
+// pass four times slower than this choice.  FS_LOWD_SPLITS=<s> overrides (experiments only).
+PassShape shape_for(const Ctx *c, int64_t n_res, int64_t n_str, int rows_per_block, int tj = kTJ, int startup_tiles = 7)
 {
     PassShape s;
     s.rows_per_block = rows_per_block;
     s.row_blocks = (int)ceil_div(n_res, s.rows_per_block);
-    int n_tiles = (int)ceil_div(n_str, tj);
-    // measured at n = m = 262144: the pass time falls from 12.2 ms at 4 workgroups per CU to a
-    // plateau of ~10.6 ms at 24..64 (more waves to hide LDS latency, finer load balance)
-    int target = 32 * c->num_cu;
-    int splits = (int)ceil_div(target, s.row_blocks);
-    if (splits > n_tiles) splits = n_tiles;
-    if (splits > max_splits(n_res)) splits = max_splits(n_res);
-    if (splits < 1) splits = 1;
-    int tps = (int)ceil_div(n_tiles, splits);
+    const int n_tiles = (int)ceil_div(n_str, tj);
+    int smax = n_tiles < max_splits(n_res) ? n_tiles : max_splits(n_res);
+    if (smax < 1) smax = 1;
+    int legacy = (int)ceil_div(32 * c->num_cu, s.row_blocks);
+    if (legacy > smax) legacy = smax;
+    auto cost = [&](int sp) {
+        const int64_t tps = ceil_div(n_tiles, sp);
+        const int64_t w = (int64_t)s.row_blocks * ceil_div(n_tiles, tps);
+        return (double)(ceil_div(w, c->num_cu) * tps + ceil_div(w, 2 * c->num_cu) * startup_tiles) + 0.3 * (double)(w / s.row_blocks);
+    };
+    double best = cost(1);
+    for (int sp = 2; sp <= smax; ++sp) best = cost(sp) < best ? cost(sp) : best;
+    int splits = 0;
+    for (int sp = legacy; sp >= 1 && !splits; --sp)
+        if (cost(sp) <= 1.02 * best) splits = sp;
+    for (int sp = legacy + 1; sp <= smax && !splits; ++sp)
+        if (cost(sp) <= 1.02 * best) splits = sp;
+    if (const char *e = getenv("FS_LOWD_SPLITS")) {
+        const int v = atoi(e);
+        if (v >= 1) splits = v < smax ? v : smax;
+    }
+    const int tps = (int)ceil_div(n_tiles, splits);
     s.splits = (int)ceil_div(n_tiles, tps);
     s.cols_per_split = (int64_t)tps * tj;
     return s;

@@ -342,6 +342,14 @@ __global__ void k_bias_from_user(const float *pot_user, int64_t cnt, double inv_
     }
 }
 
+// Rescaling of a split's sums to the common maximum.  Every streaming kernel keeps integer-valued
+// running maxima (and -3e38 for "nothing seen"), so the factor 2^(m_k - M) is an exact ldexp.
+__device__ inline double rescale_split(double v, double mk, double M)
+{
+    const double dlt = mk - M;
+    return dlt >= -1100.0 ? ldexp(v, (int)dlt) : 0.0;   // also 0 for a NaN difference (-inf - -inf)
+}
+
 // ---- merge the per-split (max, sum) statistics of a streaming pass -----------------------
 //   LSE_2 = M + log2(sum_k s_k 2^(m_k - M)),  pot_new = -eps * ln2 * LSE_2      (Alg. 1, last lines)
 // and, as asked: store pot_new, the bias for the pass that streams this side next, the
@@ -359,14 +367,16 @@ __global__ __launch_bounds__(256) void k_finalize(const double2 *partial, int64_
     double dev = 0.0;
     if (i < cnt) {
         double M = -INFINITY;
+#pragma unroll 8
         for (int k = 0; k < splits; ++k) {
             double mk = partial[(int64_t)k * stride + i].x;
             M = mk > M ? mk : M;
         }
         double S = 0.0;
+#pragma unroll 8
         for (int k = 0; k < splits; ++k) {
             double2 ms = partial[(int64_t)k * stride + i];
-            S += ms.y * exp2(ms.x - M);
+            S += rescale_split(ms.y, ms.x, M);
         }
         // fhat = -eps * LSE (Alg. 1), f = fhat + alpha (Prop. 1)
         double pot_new = -eps * kLn2 * (M + log2(S)) + res_norm[i];
@@ -417,14 +427,16 @@ __global__ __launch_bounds__(256) void k_value_terms(const double2 *partial, int
     double t[3] = {0.0, 0.0, 0.0};
     if (i < cnt) {
         double M = -INFINITY;
+#pragma unroll 8
         for (int k = 0; k < splits; ++k) {
             double mk = partial[(int64_t)k * stride + i].x;
             M = mk > M ? mk : M;
         }
         double S = 0.0;
+#pragma unroll 8
         for (int k = 0; k < splits; ++k) {
             double2 ms = partial[(int64_t)k * stride + i];
-            S += ms.y * exp2(ms.x - M);
+            S += rescale_split(ms.y, ms.x, M);
         }
         const double pot_new = -eps * kLn2 * (M + log2(S)) + res_norm[i];
         const double wi = w ? (double)w[i] : exp(log_uniform);
@@ -468,6 +480,7 @@ __global__ void k_apply_finalize(const double2 *partial, int64_t stride, const f
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= cnt) return;
     double M = -INFINITY;
+#pragma unroll 8
     for (int k = 0; k < splits; ++k) {
         double mk = partial[(int64_t)k * stride + i].x;
         M = mk > M ? mk : M;
@@ -480,15 +493,16 @@ __global__ void k_apply_finalize(const double2 *partial, int64_t stride, const f
         double acc = 0.0;
         for (int k = 0; k < splits; ++k) {
             double2 ms = partial[(int64_t)k * stride + i];
-            acc += exp2(ms.x - M) * (double)opart[((int64_t)k * opart_stride + i) * PC + c];
+            acc += rescale_split((double)opart[((int64_t)k * opart_stride + i) * PC + c], ms.x, M);
         }
         out[i * ldo + p0 + c] = (float)(fac * acc);
     }
     if (mass_out && p0 == 0) {
         double S = 0.0;
+#pragma unroll 8
         for (int k = 0; k < splits; ++k) {
             double2 ms = partial[(int64_t)k * stride + i];
-            S += exp2(ms.x - M) * ms.y;
+            S += rescale_split(ms.y, ms.x, M);
         }
         mass_out[i] = (float)(fac * S);
     }
