@@ -71,15 +71,25 @@ __global__ __launch_bounds__(256) void k_coord_sums(const void *pts, int dtype, 
     }
 }
 
-// stage 2: mean[k] = (sum of partX[.][k] + sum of partY[.][k]) / (n + m), one thread per coordinate
-__global__ void k_mean_final(const double *partX, const double *partY, int blocks, double inv_cnt, double *mean)
+// stage 2: mean[k] = (sum of partX[.][k] + sum of partY[.][k]) / (n + m).  One block of 256: thread
+// (group g, coordinate k) sums the blocks b = g mod 16, then coordinate k's 16 group sums are added
+// in a fixed order.  Also clears `zeroed` (the slot the next kernels take a maximum into).
+__global__ __launch_bounds__(256) void k_mean_final(const double *partX, const double *partY, int blocks, double inv_cnt,
+                                                    double *mean, double *zeroed)
 {
-    int k = threadIdx.x;
-    if (k >= kLowdMaxD) return;
+    static_assert(kLowdMaxD == 16, "thread mapping below");
+    __shared__ double sh[16][kLowdMaxD];
+    const int k = threadIdx.x & 15, g = threadIdx.x >> 4;
     double s = 0.0;
-    for (int b = 0; b < blocks; ++b) s += partX[(int64_t)b * kLowdMaxD + k];
-    for (int b = 0; b < blocks; ++b) s += partY[(int64_t)b * kLowdMaxD + k];
-    mean[k] = s * inv_cnt;
+    for (int b = g; b < blocks; b += 16) s += partX[(int64_t)b * kLowdMaxD + k] + partY[(int64_t)b * kLowdMaxD + k];
+    sh[g][k] = s;
+    __syncthreads();
+    if (threadIdx.x < kLowdMaxD) {
+        double t = 0.0;
+        for (int q = 0; q < 16; ++q) t += sh[q][threadIdx.x];
+        mean[threadIdx.x] = t * inv_cnt;
+    }
+    if (threadIdx.x == 0) *zeroed = 0.0;
 }
 
 // piece d of a streamed-role split record: the bias in three bf16 pieces, then the three ones
@@ -96,10 +106,11 @@ __device__ inline uint4 split_bias_piece(float bias)
 //      float (rounded once) and double (exact difference), each with its own squared norms ----
 __global__ void k_prep_lowd(const void *pts, int dtype, int64_t cnt, int64_t cnt_pad, int d, int64_t ld, int dp, int dpd,
                             const double *mean, float *packed, double *packed_d, double *norm_f, double *norm,
-                            uint16_t *split, int ks)
+                            uint16_t *split, int ks, unsigned long long *rho_max_bits)
 {
+    // launched with exactly cnt_pad threads (cnt_pad is a multiple of the block size)
+    __shared__ double shmax[256];
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= cnt_pad) return;
     float *o = packed + i * dp;
     double *od = packed_d + i * dpd;
     double nf = 0.0, nd = 0.0;
@@ -133,6 +144,15 @@ __global__ void k_prep_lowd(const void *pts, int dtype, int64_t cnt, int64_t cnt
             rec[split_piece_pos(ks, i, k)] = u;
         }
     }
+    // largest squared norm after centring, over both clouds: non-negative doubles order like their
+    // bit patterns, and a maximum does not depend on the order of the atomics
+    shmax[threadIdx.x] = nd;
+    __syncthreads();
+    for (int st = 128; st > 0; st >>= 1) {
+        if ((int)threadIdx.x < st) shmax[threadIdx.x] = fmax(shmax[threadIdx.x], shmax[threadIdx.x + st]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0 && shmax[0] > 0.0) atomicMax(rho_max_bits, (unsigned long long)__double_as_longlong(shmax[0]));
 }
 
 // ---- "precise" split records (d <= 3) from the float64 copy; layout of the six 16-byte pieces
@@ -182,22 +202,6 @@ __global__ void k_prep_split_precise(const double *packed_d, int64_t cnt_pad, in
         rec[2 + k] = make_uint4(bf16_pair(ry[k][0], ry[k][1]), bf16_pair(ry[k][2], Y1[k]), bf16_pair(Y1[k], Y1[k]),
                                 bf16_pair(ry[k][0], ry[k][1]));
     rec[5] = make_uint4(0u, 0u, bf16_pair(z, ry[0][0]), bf16_pair(ry[1][0], ry[2][0]));
-}
-
-// largest entry of two arrays, by one block (max is order independent, so this is deterministic)
-__global__ __launch_bounds__(256) void k_max2(const double *a, int64_t na, const double *b, int64_t nb, double *dst)
-{
-    __shared__ double sh[256];
-    double m = 0.0;
-    for (int64_t i = threadIdx.x; i < na; i += 256) m = fmax(m, a[i]);
-    for (int64_t i = threadIdx.x; i < nb; i += 256) m = fmax(m, b[i]);
-    sh[threadIdx.x] = m;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if ((int)threadIdx.x < s) sh[threadIdx.x] = fmax(sh[threadIdx.x], sh[threadIdx.x + s]);
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) *dst = sh[0];
 }
 
 // ---- float64 derived copy (fp64 matrix-core path) ----------------------------------------
@@ -583,14 +587,13 @@ fs_status launch_prepare(Ctx *c, const fs_problem *p, Prepared *P)
                            partX);
         hipLaunchKernelGGL(k_coord_sums, dim3(half), dim3(256), 0, c->stream, p->y, dtype, p->m, (int)p->d, p->ldy,
                            partY);
-        hipLaunchKernelGGL(k_mean_final, dim3(1), dim3(64), 0, c->stream, partX, partY, half,
-                           1.0 / (double)(p->n + p->m), P->mean);
+        hipLaunchKernelGGL(k_mean_final, dim3(1), dim3(256), 0, c->stream, partX, partY, half,
+                           1.0 / (double)(p->n + p->m), P->mean, P->scalars + 7);
         for (auto &s : in)
             hipLaunchKernelGGL(k_prep_lowd, dim3((unsigned)ceil_div(s.S->cnt_pad, 256)), dim3(256), 0, c->stream, s.pts,
                                dtype, s.S->cnt, s.S->cnt_pad, (int)p->d, s.ld, P->dp, P->dpd, P->mean, s.S->packed,
-                               s.S->packed_d, s.S->norm_f, s.S->norm, s.S->split, P->ks);
-        hipLaunchKernelGGL(k_max2, dim3(1), dim3(256), 0, c->stream, P->X.norm, P->X.cnt, P->Y.norm, P->Y.cnt,
-                           P->scalars + 7);
+                               s.S->packed_d, s.S->norm_f, s.S->norm, s.S->split, P->ks,
+                               reinterpret_cast<unsigned long long *>(P->scalars + 7));
         FS_HIP(c, hipGetLastError());
         // the host chooses the score precision of each half-step from this number
         FS_HIP(c, hipMemcpyAsync(&P->rho_max, P->scalars + 7, sizeof(double), hipMemcpyDeviceToHost, c->stream));
