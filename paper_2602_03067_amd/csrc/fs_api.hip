@@ -526,16 +526,33 @@ fs_status fs_solve_symmetric(fs_ctx *ctx, const fs_problem *prob, float eps_in, 
     for (int t = 0; t < iters; ++t) {
         const bool last = t == iters - 1;
         int splits_f = 1, splits_g = 1;
+        const double eps_bias = last ? 0.0 : eps;
+        if (P.path == Path::LowD) {
+            // both passes in one launch and both merges in another, when the half-steps run on the
+            // split-record kernels: at small n an iteration is bound by launch latency
+            bool done = false;
+            P.partial = first_partial;
+            if ((st = lowd_lse_pair(c, &P, eps, first_partial, second_partial, &splits_f, &splits_g, &done)) != FS_OK)
+                return st;
+            if (done) {
+                const bool pr = lowd_precise(&P, eps);
+                if ((st = launch_finalize_pair(c, &P, &P.X, pr ? P.X.norm : P.X.norm_f, first_partial, splits_f,
+                                               last ? f : nullptr, &P.Y, pr ? P.Y.norm : P.Y.norm_f, second_partial,
+                                               splits_g, last ? g : nullptr, eps, eps_bias, 0.5)) != FS_OK)
+                    return st;
+                continue;
+            }
+        }
         P.partial = first_partial;
         if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits_f)) != FS_OK) return st;   // Eq. 4: from the old g
         P.partial = second_partial;
         if ((st = run_lse(c, &P, &P.Y, &P.X, eps, &splits_g)) != FS_OK) return st;   // Eq. 5: from the old f
         // only now are the potentials (and the biases the next iteration streams) replaced
         P.partial = first_partial;
-        if ((st = finalize(c, &P, &P.X, splits_f, eps, last ? 0.0 : eps, last ? f : nullptr, nullptr, 0.5)) != FS_OK)
+        if ((st = finalize(c, &P, &P.X, splits_f, eps, eps_bias, last ? f : nullptr, nullptr, 0.5)) != FS_OK)
             return st;
         P.partial = second_partial;
-        if ((st = finalize(c, &P, &P.Y, splits_g, eps, last ? 0.0 : eps, last ? g : nullptr, nullptr, 0.5)) != FS_OK)
+        if ((st = finalize(c, &P, &P.Y, splits_g, eps, eps_bias, last ? g : nullptr, nullptr, 0.5)) != FS_OK)
             return st;
     }
     return FS_OK;

@@ -214,6 +214,9 @@ fs_status launch_bias_from_user(Ctx *c, Prepared *P, Side *side, const float *po
 fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, const double *res_norm, int splits,
                           double eps_cur, double eps_next_bias, float *user_out, double *abs_dev_sum,
                           double mix = 1.0, double *save_old = nullptr);
+fs_status launch_finalize_pair(Ctx *c, const Prepared *P, Side *X, const double *norm_x, const void *partial_x, int splits_x,
+                               float *f_out, Side *Y, const double *norm_y, const void *partial_y, int splits_y,
+                               float *g_out, double eps_cur, double eps_next_bias, double mix);
 fs_status launch_export_f32(Ctx *c, const double *src, int64_t cnt, float *dst);
 fs_status launch_value_terms(Ctx *c, const Prepared *P, const Side *res, const double *res_norm, const Side *str,
                              int splits, double eps, double *scratch, double *dst);
@@ -238,6 +241,9 @@ PassShape lowd_shape(const Ctx *c, int64_t n_res, int64_t n_str);
 bool lowd_precise(const Prepared *P, double eps);
 fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,
                    int *splits_out);
+// both half-steps of an averaged iteration (Eq. 4-5) in one launch; *done = false: not applicable
+fs_status lowd_lse_pair(Ctx *c, const Prepared *P, double eps, void *partial_x, void *partial_y, int *splits_x,
+                        int *splits_y, bool *done);
 size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t p);
 // had_A != nullptr: Hadamard-weighted transport (Alg. 5), every plan entry times <had_A row i, centred
 // streamed point j>; had_A is [res->cnt][lda] floats.

@@ -216,12 +216,14 @@ struct SplitArgs {
     double gx;              // precise: grid of the leading digit of c x
     int d, dp;
     int tiles_per_split, n_tiles;
+    int row_blocks, splits;  // extent of this pass in the grid
     double2 *partial;
     int64_t partial_stride;
 };
 
+// one workgroup of the pass: row block bx, column split by
 template <int KS, int R, int TJ, int CH, bool PRECISE>
-__global__ __launch_bounds__(kBlock, 2) void k_lse_lowd_split(SplitArgs a)
+__device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx, const int by)
 {
     constexpr int NP = 2 * KS;               // 16-byte pieces per record
     constexpr int UPT = TJ * NP / kBlock;    // pieces each thread moves per tile
@@ -238,7 +240,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_lse_lowd_split(SplitArgs a)
     double2 *__restrict__ partial = a.partial;
     const int64_t partial_stride = a.partial_stride;
     const uint16_t *__restrict__ str = a.str;
-    const int64_t row0 = (int64_t)blockIdx.x * (128 * R) + w * (32 * R);
+    const int64_t row0 = (int64_t)bx * (128 * R) + w * (32 * R);
     // the piece with the ones and the max slots: piece d = 2 (KS-1) + (d & 1) in the fp32 record,
     // piece 1 in the precise one
     constexpr int MK = PRECISE ? 0 : KS - 1;
@@ -256,7 +258,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_lse_lowd_split(SplitArgs a)
             b[r][MK][5] = q[2];
         }
     };
-    const int t_begin = blockIdx.y * tiles_per_split;
+    const int t_begin = by * tiles_per_split;
     const int t_end = min(n_tiles, t_begin + tiles_per_split);
     const Unit *gsrc = reinterpret_cast<const Unit *>(str);
 
@@ -436,8 +438,26 @@ __global__ __launch_bounds__(kBlock, 2) void k_lse_lowd_split(SplitArgs a)
         const float mo = __shfl_xor(m, 32), so = __shfl_xor(sv, 32);
         const float M = fmaxf(m, mo);
         const float S = sv * fast_exp2(m - M) + so * fast_exp2(mo - M);
-        if (lh == 0) partial[(int64_t)blockIdx.y * partial_stride + row0 + 32 * r + lj] = make_double2((double)M, (double)S);
+        if (lh == 0) partial[(int64_t)by * partial_stride + row0 + 32 * r + lj] = make_double2((double)M, (double)S);
     }
+}
+
+template <int KS, int R, int TJ, int CH, bool PRECISE>
+__global__ __launch_bounds__(kBlock, 2) void k_lse_lowd_split(SplitArgs a)
+{
+    lse_split_body<KS, R, TJ, CH, PRECISE>(a, blockIdx.x, blockIdx.y);
+}
+
+// Both half-steps of one iteration of the averaged schedule (Eq. 4-5) in one launch: they read the
+// same old potentials, so the row blocks of the f-pass (a0) and of the g-pass (a1) share a grid;
+// grid.y covers the larger of the two split counts.
+template <int KS, int R, int TJ, int CH, bool PRECISE>
+__global__ __launch_bounds__(kBlock, 2) void k_lse_lowd_split_pair(SplitArgs a0, SplitArgs a1)
+{
+    const bool second = (int)blockIdx.x >= a0.row_blocks;   // uniform over the workgroup
+    const SplitArgs &a = second ? a1 : a0;
+    if ((int)blockIdx.y >= a.splits) return;
+    lse_split_body<KS, R, TJ, CH, PRECISE>(a, (int)blockIdx.x - (second ? a0.row_blocks : 0), blockIdx.y);
 }
 
 // ---- plan application (Alg. 2 / Alg. 4): the same pass with a value accumulator ----------
@@ -675,64 +695,133 @@ static bool precise_on_matrix_cores(const Prepared *P, const Side *res, const Si
     return q <= 1.0 && bias_bound < 2097152.0 * q;
 }
 
+// Arguments of a split-record pass (res resident, str streamed) writing its records to `partial`;
+// false when this half-step does not run on the split-record kernels (float64 scores off the
+// matrix cores) or its shape does not fit the padded copies (*st says which).
+static bool split_pass_args(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, void *partial,
+                            SplitArgs *a, bool *precise_out, fs_status *st)
+{
+    *st = FS_OK;
+    const bool precise = lowd_precise(P, eps);
+    double gx = 0.0;
+    if (precise && !precise_on_matrix_cores(P, res, str, eps, &gx)) return false;
+    const PassShape s = shape_for(c, res->cnt, str->cnt, 128 * kSplitR, kSplitTJ);
+    const int n_tiles = (int)ceil_div(str->cnt, kSplitTJ);
+    // host-side shape checks: every access of the kernel stays inside the padded copies
+    if ((int64_t)s.row_blocks * s.rows_per_block > res->cnt_pad || (int64_t)n_tiles * kSplitTJ > str->cnt_pad ||
+        (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (!precise && P->ks != split_ksteps(P->d)) ||
+        (!precise && (P->ks < 1 || P->ks > 9))) {
+        *st = fail(c, FS_ERR_DEVICE, "internal: low-d launch shape exceeds the padded buffers");
+        return false;
+    }
+    *a = SplitArgs{};
+    a->cscale = 2.0 * kLog2e / eps;
+    a->d = (int)P->d;
+    a->tiles_per_split = (int)(s.cols_per_split / kSplitTJ);
+    a->n_tiles = n_tiles;
+    a->row_blocks = s.row_blocks;
+    a->splits = s.splits;
+    a->partial = (double2 *)partial;
+    a->partial_stride = res->cnt_pad;
+    if (precise) {
+        a->res = res->packed_d;
+        a->dp = P->dpd;
+        a->str = str->split_p;
+        a->gx = gx;
+    } else {
+        a->res = res->packed;
+        a->dp = P->dp;
+        a->str = str->split;
+    }
+    *precise_out = precise;
+    return true;
+}
+
+template <int KS>
+void launch_lse_split_pair(dim3 grid, hipStream_t st, const SplitArgs &a0, const SplitArgs &a1)
+{
+    hipLaunchKernelGGL((k_lse_lowd_split_pair<KS, kSplitR, kSplitTJ, kSplitCH, false>), grid, dim3(kBlock), 0, st, a0, a1);
+}
+
+#define FS_SPLIT_KS_DISPATCH(ks, CALL)                                                                       \
+    switch (ks) {                                                                                            \
+    case 1: { constexpr int KS_ = 1; CALL; } break;                                                          \
+    case 2: { constexpr int KS_ = 2; CALL; } break;                                                          \
+    case 3: { constexpr int KS_ = 3; CALL; } break;                                                          \
+    case 4: { constexpr int KS_ = 4; CALL; } break;                                                          \
+    case 5: { constexpr int KS_ = 5; CALL; } break;                                                          \
+    case 6: { constexpr int KS_ = 6; CALL; } break;                                                          \
+    case 7: { constexpr int KS_ = 7; CALL; } break;                                                          \
+    case 8: { constexpr int KS_ = 8; CALL; } break;                                                          \
+    default: { constexpr int KS_ = 9; CALL; } break;                                                         \
+    }
+
 fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out)
 {
     // fp32-accuracy half-steps run on the bf16 matrix cores from the split records; float64-score
     // ones too when d <= 3 (precise records), else on the vector ALU
-    const bool precise = lowd_precise(P, eps);
-    double gx = 0.0;
-    const bool valu = precise && !precise_on_matrix_cores(P, res, str, eps, &gx);
-    const int tj = valu ? kTJ : kSplitTJ;
-    PassShape s = valu ? lowd_shape(c, res->cnt, str->cnt) : shape_for(c, res->cnt, str->cnt, 128 * kSplitR, tj);
-    const int n_tiles = (int)ceil_div(str->cnt, tj);
-    const int tps = (int)(s.cols_per_split / tj);
-    // host-side shape checks: every access of the kernel stays inside the padded copies
-    if ((int64_t)s.row_blocks * s.rows_per_block > res->cnt_pad || (int64_t)n_tiles * tj > str->cnt_pad ||
-        (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (!precise && P->ks != split_ksteps(P->d)))
+    SplitArgs a;
+    bool precise = false;
+    fs_status st;
+    if (split_pass_args(c, P, res, str, eps, P->partial, &a, &precise, &st)) {
+        const dim3 grid((unsigned)a.row_blocks, (unsigned)a.splits);
+        prof_begin(c, (double)res->cnt * (double)str->cnt, precise ? 1 : 0);
+        if (precise) {
+            hipLaunchKernelGGL((k_lse_lowd_split<3, kSplitR, kSplitTJ, kSplitCH, true>), grid, dim3(kBlock), 0, c->stream, a);
+        } else {
+            FS_SPLIT_KS_DISPATCH(P->ks, (launch_lse_split<KS_>(grid, c->stream, a)));
+        }
+        prof_end(c);
+        FS_HIP(c, hipGetLastError());
+        *splits_out = a.splits;
+        return FS_OK;
+    }
+    if (st != FS_OK) return st;
+    // float64 scores on the vector ALU
+    PassShape s = lowd_shape(c, res->cnt, str->cnt);
+    const int n_tiles = (int)ceil_div(str->cnt, kTJ);
+    const int tps = (int)(s.cols_per_split / kTJ);
+    if ((int64_t)s.row_blocks * s.rows_per_block > res->cnt_pad || (int64_t)n_tiles * kTJ > str->cnt_pad ||
+        (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes)
         return fail(c, FS_ERR_DEVICE, "internal: low-d launch shape exceeds the padded buffers");
     const double cscale = 2.0 * kLog2e / eps;
     dim3 grid((unsigned)s.row_blocks, (unsigned)s.splits);
     double2 *part = (double2 *)P->partial;
-    prof_begin(c, (double)res->cnt * (double)str->cnt, precise ? 1 : 0);
-    if (valu) {
-        const int R = s.rows_per_block / kBlock;
-        FS_LOWD_DISPATCH((int)P->d, (launch_lse_d<DD>(R, grid, c->stream, res->packed_d, str->packed_d, cscale, tps, n_tiles,
-                                                      part, res->cnt_pad)));
-    } else {
-        SplitArgs a{};
-        a.cscale = cscale;
-        a.d = (int)P->d;
-        a.tiles_per_split = tps;
-        a.n_tiles = n_tiles;
-        a.partial = part;
-        a.partial_stride = res->cnt_pad;
-        if (precise) {
-            a.res = res->packed_d;
-            a.dp = P->dpd;
-            a.str = str->split_p;
-            a.gx = gx;
-            hipLaunchKernelGGL((k_lse_lowd_split<3, kSplitR, kSplitTJ, kSplitCH, true>), grid, dim3(kBlock), 0, c->stream, a);
-        } else {
-            a.res = res->packed;
-            a.dp = P->dp;
-            a.str = str->split;
-            switch (P->ks) {
-            case 1: launch_lse_split<1>(grid, c->stream, a); break;
-            case 2: launch_lse_split<2>(grid, c->stream, a); break;
-            case 3: launch_lse_split<3>(grid, c->stream, a); break;
-            case 4: launch_lse_split<4>(grid, c->stream, a); break;
-            case 5: launch_lse_split<5>(grid, c->stream, a); break;
-            case 6: launch_lse_split<6>(grid, c->stream, a); break;
-            case 7: launch_lse_split<7>(grid, c->stream, a); break;
-            case 8: launch_lse_split<8>(grid, c->stream, a); break;
-            case 9: launch_lse_split<9>(grid, c->stream, a); break;
-            default: prof_end(c); return fail(c, FS_ERR_DEVICE, "internal: split record length");
-            }
-        }
-    }
+    prof_begin(c, (double)res->cnt * (double)str->cnt, 1);
+    const int R = s.rows_per_block / kBlock;
+    FS_LOWD_DISPATCH((int)P->d, (launch_lse_d<DD>(R, grid, c->stream, res->packed_d, str->packed_d, cscale, tps, n_tiles,
+                                                  part, res->cnt_pad)));
     prof_end(c);
     FS_HIP(c, hipGetLastError());
     *splits_out = s.splits;
+    return FS_OK;
+}
+
+// The f-pass (records to partial_x) and the g-pass (records to partial_y) of one iteration of the
+// averaged schedule (Eq. 4-5) in ONE launch.  *done = false (nothing launched) when the half-steps
+// of this problem do not run on the split-record kernels; the caller then runs them one by one.
+fs_status lowd_lse_pair(Ctx *c, const Prepared *P, double eps, void *partial_x, void *partial_y, int *splits_x,
+                        int *splits_y, bool *done)
+{
+    *done = false;
+    SplitArgs ax, ay;
+    bool px = false, py = false;
+    fs_status st;
+    if (!split_pass_args(c, P, &P->X, &P->Y, eps, partial_x, &ax, &px, &st)) return st;
+    if (!split_pass_args(c, P, &P->Y, &P->X, eps, partial_y, &ay, &py, &st)) return st;
+    if (px != py) return FS_OK;
+    const dim3 grid((unsigned)(ax.row_blocks + ay.row_blocks), (unsigned)(ax.splits > ay.splits ? ax.splits : ay.splits));
+    prof_begin(c, 2.0 * (double)P->X.cnt * (double)P->Y.cnt, px ? 1 : 0);
+    if (px) {
+        hipLaunchKernelGGL((k_lse_lowd_split_pair<3, kSplitR, kSplitTJ, kSplitCH, true>), grid, dim3(kBlock), 0, c->stream, ax, ay);
+    } else {
+        FS_SPLIT_KS_DISPATCH(P->ks, (launch_lse_split_pair<KS_>(grid, c->stream, ax, ay)));
+    }
+    prof_end(c);
+    FS_HIP(c, hipGetLastError());
+    *splits_x = ax.splits;
+    *splits_y = ay.splits;
+    *done = true;
     return FS_OK;
 }
 

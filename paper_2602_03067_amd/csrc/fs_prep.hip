@@ -358,48 +358,74 @@ __device__ inline double rescale_split(double v, double mk, double M)
 //   LSE_2 = M + log2(sum_k s_k 2^(m_k - M)),  pot_new = -eps * ln2 * LSE_2      (Alg. 1, last lines)
 // and, as asked: store pot_new, the bias for the pass that streams this side next, the
 // unshifted potential for the caller, or the marginal deviation |w e^((pot_old-pot_new)/eps) - w|.
-__global__ __launch_bounds__(256) void k_finalize(const double2 *partial, int64_t stride, int splits, int64_t cnt,
-                                                  double eps, double inv_eps_next, const float *w,
-                                                  double log_uniform, const double *res_norm, double *pot,
-                                                  BiasSink sink, float *user_out, double *dev_part, double mix,
-                                                  double *save_old)
+struct FinalizeArgs {
+    const double2 *partial;
+    int64_t stride;
+    int splits;
+    int64_t cnt;
+    double eps, inv_eps_next;
+    const float *w;
+    double log_uniform;
+    const double *res_norm;
+    double *pot;
+    BiasSink sink;
+    float *user_out;
+    double *dev_part;
+    double mix;
+    double *save_old;
+    int blocks;   // workgroups of this side
+};
+
+__device__ __forceinline__ void finalize_body(const FinalizeArgs &a, const int bx)
 {
     // dev_part == nullptr: store the update.  dev_part != nullptr: measure the marginal deviation
     // only, unless save_old is given: then measure AND store, keeping the old potential in save_old.
     __shared__ double sh[256];
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t i = (int64_t)bx * 256 + threadIdx.x;
     double dev = 0.0;
-    if (i < cnt) {
+    if (i < a.cnt) {
         double M = -INFINITY;
 #pragma unroll 8
-        for (int k = 0; k < splits; ++k) {
-            double mk = partial[(int64_t)k * stride + i].x;
+        for (int k = 0; k < a.splits; ++k) {
+            double mk = a.partial[(int64_t)k * a.stride + i].x;
             M = mk > M ? mk : M;
         }
         double S = 0.0;
 #pragma unroll 8
-        for (int k = 0; k < splits; ++k) {
-            double2 ms = partial[(int64_t)k * stride + i];
+        for (int k = 0; k < a.splits; ++k) {
+            double2 ms = a.partial[(int64_t)k * a.stride + i];
             S += rescale_split(ms.y, ms.x, M);
         }
         // fhat = -eps * LSE (Alg. 1), f = fhat + alpha (Prop. 1)
-        double pot_new = -eps * kLn2 * (M + log2(S)) + res_norm[i];
-        if (mix != 1.0) pot_new = (1.0 - mix) * pot[i] + mix * pot_new;   // averaged schedule (Eq. 4-5)
-        if (dev_part) {
-            double wi = w ? (double)w[i] : exp(log_uniform);
-            dev = fabs(wi * exp((pot[i] - pot_new) / eps) - wi);   // Prop. 3: r = a exp((fhat - fhat+)/eps)
+        double pot_new = -a.eps * kLn2 * (M + log2(S)) + a.res_norm[i];
+        if (a.mix != 1.0) pot_new = (1.0 - a.mix) * a.pot[i] + a.mix * pot_new;   // averaged schedule (Eq. 4-5)
+        if (a.dev_part) {
+            double wi = a.w ? (double)a.w[i] : exp(a.log_uniform);
+            dev = fabs(wi * exp((a.pot[i] - pot_new) / a.eps) - wi);   // Prop. 3: r = a exp((fhat - fhat+)/eps)
         }
-        if (!dev_part || save_old) {
-            if (save_old) save_old[i] = pot[i];
-            pot[i] = pot_new;
-            if (inv_eps_next > 0.0) store_bias(sink, i, pot_new, inv_eps_next, w ? log((double)w[i]) : log_uniform);
-            if (user_out) user_out[i] = (float)pot_new;
+        if (!a.dev_part || a.save_old) {
+            if (a.save_old) a.save_old[i] = a.pot[i];
+            a.pot[i] = pot_new;
+            if (a.inv_eps_next > 0.0)
+                store_bias(a.sink, i, pot_new, a.inv_eps_next, a.w ? log((double)a.w[i]) : a.log_uniform);
+            if (a.user_out) a.user_out[i] = (float)pot_new;
         }
     }
-    if (dev_part) {
+    if (a.dev_part) {
         double t = block_sum_256(dev, sh);
-        if (threadIdx.x == 0) dev_part[blockIdx.x] = t;
+        if (threadIdx.x == 0) a.dev_part[bx] = t;
     }
+}
+
+__global__ __launch_bounds__(256) void k_finalize(FinalizeArgs a) { finalize_body(a, blockIdx.x); }
+
+// the merges of the two passes of an averaged iteration (Eq. 4-5) in one launch
+__global__ __launch_bounds__(256) void k_finalize_pair(FinalizeArgs a0, FinalizeArgs a1)
+{
+    if ((int)blockIdx.x < a0.blocks)
+        finalize_body(a0, blockIdx.x);
+    else
+        finalize_body(a1, (int)blockIdx.x - a0.blocks);
 }
 
 __global__ void k_export_f32(const double *src, int64_t cnt, float *dst)
@@ -641,16 +667,51 @@ fs_status launch_bias_from_user(Ctx *c, Prepared *P, Side *side, const float *po
     return FS_OK;
 }
 
+static FinalizeArgs finalize_args(const Prepared *P, const void *partial, Side *res, const double *res_norm, int splits,
+                                  double eps_cur, double eps_next_bias, float *user_out, double *dev_part, double mix,
+                                  double *save_old)
+{
+    FinalizeArgs a{};
+    a.partial = (const double2 *)partial;
+    a.stride = res->cnt_pad;
+    a.splits = splits;
+    a.cnt = res->cnt;
+    a.eps = eps_cur;
+    a.inv_eps_next = eps_next_bias > 0.0 ? 1.0 / eps_next_bias : 0.0;
+    a.w = res->w;
+    a.log_uniform = res->log_uniform;
+    a.res_norm = res_norm;
+    a.pot = res->pot;
+    a.sink = sink_of(P, res, eps_next_bias);
+    a.user_out = user_out;
+    a.dev_part = dev_part;
+    a.mix = mix;
+    a.save_old = save_old;
+    a.blocks = (int)ceil_div(res->cnt, 256);
+    return a;
+}
+
 fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, const double *res_norm, int splits, double eps_cur,
                           double eps_next_bias, float *user_out, double *abs_dev_sum, double mix, double *save_old)
 {
-    const unsigned blocks = (unsigned)ceil_div(res->cnt, 256);
     double *dev_part = abs_dev_sum ? P->dev_part : nullptr;   // per-block sums of the marginal deviation
-    hipLaunchKernelGGL(k_finalize, dim3(blocks), dim3(256), 0, c->stream, (const double2 *)P->partial, res->cnt_pad,
-                       splits, res->cnt, eps_cur, eps_next_bias > 0.0 ? 1.0 / eps_next_bias : 0.0, res->w,
-                       res->log_uniform, res_norm, res->pot, sink_of(P, res, eps_next_bias), user_out, dev_part, mix, save_old);
+    const FinalizeArgs a = finalize_args(P, P->partial, res, res_norm, splits, eps_cur, eps_next_bias, user_out, dev_part,
+                                         mix, save_old);
+    hipLaunchKernelGGL(k_finalize, dim3((unsigned)a.blocks), dim3(256), 0, c->stream, a);
     if (abs_dev_sum)
-        hipLaunchKernelGGL(k_sum_to, dim3(1), dim3(256), 0, c->stream, dev_part, (int64_t)blocks, abs_dev_sum);
+        hipLaunchKernelGGL(k_sum_to, dim3(1), dim3(256), 0, c->stream, dev_part, (int64_t)a.blocks, abs_dev_sum);
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
+// merges of the f-pass (records in partial_x) and of the g-pass (partial_y) in one launch
+fs_status launch_finalize_pair(Ctx *c, const Prepared *P, Side *X, const double *norm_x, const void *partial_x, int splits_x,
+                               float *f_out, Side *Y, const double *norm_y, const void *partial_y, int splits_y,
+                               float *g_out, double eps_cur, double eps_next_bias, double mix)
+{
+    const FinalizeArgs ax = finalize_args(P, partial_x, X, norm_x, splits_x, eps_cur, eps_next_bias, f_out, nullptr, mix, nullptr);
+    const FinalizeArgs ay = finalize_args(P, partial_y, Y, norm_y, splits_y, eps_cur, eps_next_bias, g_out, nullptr, mix, nullptr);
+    hipLaunchKernelGGL(k_finalize_pair, dim3((unsigned)(ax.blocks + ay.blocks)), dim3(256), 0, c->stream, ax, ay);
     FS_HIP(c, hipGetLastError());
     return FS_OK;
 }

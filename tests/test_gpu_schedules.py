@@ -32,6 +32,9 @@ def _problem(rng, n, m, d, scale):
 
 @pytest.mark.parametrize("n,m,d,eps,iters", [(300, 421, 3, 0.25, 25), (1030, 700, 2, 0.05, 12),   # low-d passes
                                              (260, 300, 8, 0.5, 10),
+                                             # very different split counts of the two passes that share a launch
+                                             (2100, 150, 3, 0.2, 6), (77, 6000, 3, 0.3, 6),
+                                             (500, 900, 3, 0.01, 8),   # float64-score half-steps
                                              (200, 333, 40, 2.0, 15), (130, 257, 64, 1.0, 8)])     # fp64 MFMA pass
 def test_symmetric_fp32_mode(ctx, oracle, n, m, d, eps, iters):
     rng = np.random.default_rng(1000 * n + m + d)
