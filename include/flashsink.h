@@ -56,14 +56,20 @@ typedef enum { FS_F32 = 0, FS_BF16 = 1 } fs_dtype;
 
 /*
  * Arithmetic of the score tile 2<x_i, y_j>:
- *  FS_COMPUTE_FP32       d <= 16: fp32 vector ALU on coordinates centred at the common
- *                        mean (the cost is translation invariant); d > 16: the
+ *  FS_COMPUTE_FP32       true fp32 products or better.  d <= 16: coordinates centred at the
+ *                        common mean (the cost is translation invariant), products
+ *                        summed at fp32 accuracy from bf16-split operands, float64-grade
+ *                        scores where fp32 ones cannot hold the tolerance; d > 16: the
  *                        contraction runs on the fp64 matrix cores, because at
  *                        |score| ~ 1e3 fp32 products cannot hold 1e-4 absolute.
  *                        Potentials agree with a float64 reference to 1e-4*eps.
  *  FS_COMPUTE_BF16_MFMA  x, y rounded to bfloat16 (RNE), products on the bf16 matrix
  *                        cores with fp32 accumulation; norms are taken from the
  *                        rounded points.  Needs d >= 16.  Agreement 2e-2*eps.
+ *                        Plan application in this mode also rounds the plan entries
+ *                        (relative to each row's largest) and V to bfloat16 for the
+ *                        second contraction; agreement 2e-2 relative (Frobenius).
+ *                        fs_hvp needs FS_COMPUTE_FP32.
  */
 typedef enum { FS_COMPUTE_FP32 = 0, FS_COMPUTE_BF16_MFMA = 1 } fs_compute;
 

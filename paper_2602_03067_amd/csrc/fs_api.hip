@@ -260,8 +260,7 @@ fs_status apply_common(Ctx *c, const fs_problem *prob, float eps, const float *f
     switch (choose_path(prob)) {
     case Path::LowD: extra = lowd_apply_ws(c, n_res, n_str, p); break;
     case Path::F64: extra = f64_apply_ws(c, n_res, n_str, prob->d, p); break;
-    case Path::BF16:
-        return fail(c, FS_ERR_UNSUPPORTED, "plan application is not available in bf16 mode; use FS_COMPUTE_FP32");
+    case Path::BF16: extra = bf16_apply_ws(c, n_res, n_str); break;
     }
     if ((st = prepare(c, prob, &P, extra, &P.extra)) != FS_OK) return st;
     P.extra_bytes = extra;
@@ -272,7 +271,7 @@ fs_status apply_common(Ctx *c, const fs_problem *prob, float eps, const float *f
     switch (P.path) {
     case Path::LowD: return lowd_apply(c, &P, res, str, eps, V, p, ldv, out, ldo, mass);
     case Path::F64: return f64_apply(c, &P, res, str, eps, V, p, ldv, out, ldo, mass);
-    case Path::BF16: break;
+    case Path::BF16: return bf16_apply(c, &P, res, str, eps, V, p, ldv, out, ldo, mass);
     }
     return FS_ERR_UNSUPPORTED;
 }

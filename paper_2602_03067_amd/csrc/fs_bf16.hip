@@ -47,6 +47,9 @@ struct BfArgs {
     int n_jtiles, n_itiles, splits, tiles_per_split;
     double2 *partial;
     int64_t partial_stride;
+    // plan application only
+    const unsigned char *vimg;   // [n_itiles] value images (see k_vimg_bf16)
+    float *opart;                // [splits][partial_stride][PC]
 };
 
 // Workgroup shapes (WJ = waves along the resident side, each owning 128 resident rows; four waves
@@ -74,19 +77,39 @@ struct BfArgs {
 // Ceiling: with random operands the matrix cores sustain ~1.83 PFLOP/s here (a loop of nothing but
 // this MFMA: 2.42 PFLOP/s on constant operands, 1.83 on uniform random ones), i.e. the chip is
 // power-limited well below the 2.5 PFLOP/s peak that the roofline fraction is quoted against.
-template <int WJ, int NS>
+//
+// PC > 0 is the plan application (Alg. 2 / Alg. 4) in this mode: a fused matmul - softmax - matmul.
+// A wave then owns JTW = 2 blocks of 32 resident rows (64 x 64 scores per tile, 256 x 128 per
+// workgroup), which leaves registers for the output accumulators O[resident row][PC value columns].
+// After the contraction over d the exponentials exp2(score - max) of a tile are rounded to bf16 IN
+// the accumulator layout, which is exactly the B operand of a second MFMA whose contraction runs
+// over the streamed points:   O^T[c][j] += sum_i Vt[c][i] E[i][j].   The value rows of the tile
+// arrive as a bf16 image Vt[c][i] (rows padded to 520 bytes: conflict-free 8-byte fragment reads)
+// by direct loads issued at the start of the tile's contraction.  The running max of a resident
+// row is common to the two lane halves here (the second MFMA sums over them).
+constexpr int kVRow = 520;                       // bytes per value column in the LDS image (256 points + pad)
+constexpr int kVImgBytes(int pc) { return (pc * kVRow + 1023) / 1024 * 1024; }
+
+template <int WJ, int NS, int JTW, int PC>
 __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a)
 {
-    constexpr int BJ = 128 * WJ;                 // resident rows per workgroup
+    constexpr bool APPLY = PC > 0;
+    constexpr int BJ = 32 * JTW * WJ;            // resident rows per workgroup
     constexpr int ROWS = BI + BJ;
     constexpr int STAGE_BYTES = ROWS * KC * 2;   // 32 KB / 24 KB
     constexpr int NW = 4 * WJ;                   // waves
-    constexpr int PPW = (ROWS / 16) / NW;        // 1 KB pieces of a stage per wave: 4 / 6
+    constexpr int PPW = (ROWS / 16) / NW;        // 1 KB pieces of a stage per wave
     constexpr int NPW = PPW + 1;                 // ... plus its share of the bias tile
     constexpr int D = NS - 1;                    // stages in flight
+    constexpr int NCB = APPLY ? PC / 32 : 1;     // 32-column blocks of the value matrix
+    constexpr int VIMG = APPLY ? kVImgBytes(PC) : 16;
+    constexpr int NVP = VIMG / 1024;             // 1 KB pieces of a value image
     static_assert((ROWS / 16) % NW == 0 && NPW <= 12 && D >= 2 && D <= 3, "pipeline shape");
+    static_assert(JTW == 4 || JTW == 2, "MFMA schedules below");
+    static_assert(!APPLY || (PC % 32 == 0 && BJ * PC * 4 + BJ * 64 <= NS * STAGE_BYTES), "merge buffers fit the ring");
     __shared__ __attribute__((aligned(1024))) unsigned char ring[NS * STAGE_BYTES];
     __shared__ __attribute__((aligned(256))) float bias_ring[NBIAS][BI];                 // 8,192 B
+    __shared__ __attribute__((aligned(1024))) unsigned char vimg[VIMG];
 
     // ---- which (resident tile, split) this workgroup owns.  Workgroups go to XCDs round-robin;
     // each XCD gets a contiguous, equally long run of the work list, which is ordered in patches of
@@ -130,6 +153,7 @@ __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a
 
     const unsigned ring_off = (unsigned)(size_t)ring;
     const unsigned bias_off = (unsigned)(size_t)&bias_ring[0][0];
+    const unsigned vimg_off = (unsigned)(size_t)vimg;
 
     // The bf16 copies are stored as 1 KB tiles (16 rows x 32 coordinates, already swizzled), tile
     // (row block rb, chunk ch) at byte ((rb * n_chunks + ch) << 10): a stage is ROWS/16 linear
@@ -157,26 +181,36 @@ __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a
         }
     };
 
-    float mrun[4], srun[4];
+    float mrun[JTW], srun[JTW];
+    f16v O[APPLY ? JTW : 1][NCB];
 #pragma unroll
-    for (int jt = 0; jt < 4; ++jt) {
+    for (int jt = 0; jt < JTW; ++jt) {
         mrun[jt] = kNegInit;
         srun[jt] = 0.0f;
+    }
+    if constexpr (APPLY) {
+#pragma unroll
+        for (int jt = 0; jt < JTW; ++jt)
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) O[jt][cb][r] = 0.0f;
     }
 
     // fragment addressing inside a stage
     const int sw = (lr >> 1) & 3;
-    const int offA = (64 * wi + lr) * 64, offB = (BI + 128 * wj + lr) * 64;
+    const int offA = (64 * wi + lr) * 64, offB = (BI + 32 * JTW * wj + lr) * 64;
     const int pk0 = ((0 + lh) ^ sw) * 16, pk1 = ((2 + lh) ^ sw) * 16;
-    bf8 a0[2], b0[4], a1[2], b1[4];
-    auto read_frags = [&](bf8(&af)[2], bf8(&bf)[4], int stage, int pk) {
+    bf8 a0[2], b0[JTW], a1[2], b1[JTW];
+    auto read_frags = [&](bf8(&af)[2], bf8(&bf)[JTW], int stage, int pk) {
         const unsigned char *sb = ring + (stage % NS) * STAGE_BYTES + pk;
 #pragma unroll
         for (int it = 0; it < 2; ++it) af[it] = *reinterpret_cast<const bf8 *>(sb + offA + it * 32 * 64);
 #pragma unroll
-        for (int jt = 0; jt < 4; ++jt) bf[jt] = *reinterpret_cast<const bf8 *>(sb + offB + jt * 32 * 64);
+        for (int jt = 0; jt < JTW; ++jt) bf[jt] = *reinterpret_cast<const bf8 *>(sb + offB + jt * 32 * 64);
     };
     // this wave's loads of stage `upto` and older have landed, given that it has issued stages up to `issued`
+    // (loads of a value image issued in between only make these waits stricter)
     auto wait_landed = [&](int upto, int issued) {
         const int newer = issued - upto;   // whole stages issued after `upto`
         if (newer >= 2)
@@ -185,6 +219,18 @@ __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a
             wait_vm<NPW>();
         else
             wait_vm<0>();
+    };
+    int vstamp = 0;   // pg when this wave issued its pieces of the current tile's value image
+    auto issue_vimg = [&](int t) {
+        if constexpr (APPLY) {
+            const unsigned char *src = reinterpret_cast<const unsigned char *>(a.vimg) + (int64_t)t * VIMG + l * 16;
+#pragma unroll
+            for (int q = 0; q * NW < NVP; ++q) {
+                const int pidx = q * NW + w;
+                if (pidx < NVP) dma16(src + pidx * 1024, vimg_off + pidx * 1024);
+            }
+            vstamp = pg;
+        }
     };
 
     // ---- prologue: D stages in flight, stage 0 landed, its first fragments on the way ----
@@ -197,11 +243,11 @@ __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a
 
     int g = 0;
     for (int t = t_begin; t < t_end; ++t) {
-        f16v acc[2][4];
+        f16v acc[2][JTW];
 #pragma unroll
         for (int it = 0; it < 2; ++it)
 #pragma unroll
-            for (int jt = 0; jt < 4; ++jt)
+            for (int jt = 0; jt < JTW; ++jt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[it][jt][r] = 0.0f;
 
@@ -214,29 +260,45 @@ __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a
     __builtin_amdgcn_sched_barrier(0);       \
     if (Q < NPW && issue) issue_piece(Q);    \
     __builtin_amdgcn_sched_barrier(0)
-            // (only F0(g) is pending here, so the wait the compiler puts before the first MFMA is
-            // exactly "F0 has arrived"; F1 is requested behind the first MFMA group)
-            FS_MFMA(0, 0, a0, b0);
-            FS_PIECE(0);
-            FS_MFMA(0, 1, a0, b0);
-            FS_PIECE(1);
-            FS_MFMA(0, 2, a0, b0);
-            FS_PIECE(2);
-            FS_MFMA(0, 3, a0, b0);
-            __builtin_amdgcn_sched_barrier(0);
-            read_frags(a1, b1, g, pk1);
-            FS_PIECE(3);
-            FS_MFMA(1, 0, a0, b0);
-            FS_PIECE(4);
-            FS_MFMA(1, 1, a0, b0);
-            FS_PIECE(5);
-            FS_MFMA(1, 2, a0, b0);
-            FS_PIECE(6);
-            FS_MFMA(1, 3, a0, b0);
-            FS_MFMA(0, 0, a1, b1);
-            FS_MFMA(0, 1, a1, b1);
-            FS_MFMA(0, 2, a1, b1);
-            FS_MFMA(0, 3, a1, b1);
+            if constexpr (JTW == 4) {
+                // (only F0(g) is pending here, so the wait the compiler puts before the first MFMA is
+                // exactly "F0 has arrived"; F1 is requested behind the first MFMA group)
+                FS_MFMA(0, 0, a0, b0);
+                FS_PIECE(0);
+                FS_MFMA(0, 1, a0, b0);
+                FS_PIECE(1);
+                FS_MFMA(0, 2, a0, b0);
+                FS_PIECE(2);
+                FS_MFMA(0, 3, a0, b0);
+                __builtin_amdgcn_sched_barrier(0);
+                read_frags(a1, b1, g, pk1);
+                FS_PIECE(3);
+                FS_MFMA(1, 0, a0, b0);
+                FS_PIECE(4);
+                FS_MFMA(1, 1, a0, b0);
+                FS_PIECE(5);
+                FS_MFMA(1, 2, a0, b0);
+                FS_PIECE(6);
+                FS_MFMA(1, 3, a0, b0);
+                FS_MFMA(0, 0, a1, b1);
+                FS_MFMA(0, 1, a1, b1);
+                FS_MFMA(0, 2, a1, b1);
+                FS_MFMA(0, 3, a1, b1);
+            } else {
+                FS_MFMA(0, 0, a0, b0);
+                FS_PIECE(0);
+                FS_MFMA(0, 1, a0, b0);
+                __builtin_amdgcn_sched_barrier(0);
+                read_frags(a1, b1, g, pk1);
+                FS_PIECE(1);
+                FS_MFMA(1, 0, a0, b0);
+                FS_PIECE(2);
+                FS_MFMA(1, 1, a0, b0);
+                FS_PIECE(3);
+                FS_MFMA(0, 0, a1, b1);
+                FS_PIECE(4);
+                FS_MFMA(0, 1, a1, b1);
+            }
             __builtin_amdgcn_sched_barrier(0);
             if (g + 1 < G) {
                 // this wave's pieces of stage g+1 have landed ...
@@ -245,11 +307,23 @@ __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a
                 lds_done_barrier();
                 read_frags(a0, b0, g + 1, pk0);
             }
+            if constexpr (APPLY) {
+                // every wave is past the previous tile's use of the value image now
+                if (ch == 0) {
+                    if (g + 1 >= G) lds_done_barrier();
+                    issue_vimg(t);
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);
-            FS_MFMA(1, 0, a1, b1);
-            FS_MFMA(1, 1, a1, b1);
-            FS_MFMA(1, 2, a1, b1);
-            FS_MFMA(1, 3, a1, b1);
+            if constexpr (JTW == 4) {
+                FS_MFMA(1, 0, a1, b1);
+                FS_MFMA(1, 1, a1, b1);
+                FS_MFMA(1, 2, a1, b1);
+                FS_MFMA(1, 3, a1, b1);
+            } else {
+                FS_MFMA(1, 0, a1, b1);
+                FS_MFMA(1, 1, a1, b1);
+            }
 #undef FS_MFMA
 #undef FS_PIECE
         }
@@ -269,51 +343,159 @@ __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a
                 bias[it][4 * g4 + 2] = bv.z;
                 bias[it][4 * g4 + 3] = bv.w;
             }
-        float csum[4];
-        bool bad = false;
+        if constexpr (!APPLY) {
+            float csum[JTW];
+            bool bad = false;
 #pragma unroll
-        for (int jt = 0; jt < 4; ++jt) {
-            const float m = mrun[jt];
-            float s0 = 0.0f, s1 = 0.0f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                s0 += fast_exp2(fmaf(acc[0][jt][r], a.cscale, bias[0][r]) - m);
-                s1 += fast_exp2(fmaf(acc[1][jt][r], a.cscale, bias[1][r]) - m);
-            }
-            csum[jt] = s0 + s1;
-            bad = bad || !(csum[jt] < kLazyMax);
-        }
-        if (__any(bad)) {
-#pragma unroll
-            for (int jt = 0; jt < 4; ++jt) {
-                float mx = kNegInit;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    mx = fmaxf(mx, fmaf(acc[0][jt][r], a.cscale, bias[0][r]));
-                    mx = fmaxf(mx, fmaf(acc[1][jt][r], a.cscale, bias[1][r]));
-                }
-                float mnew = fmaxf(mrun[jt], ceilf(mx));
+            for (int jt = 0; jt < JTW; ++jt) {
+                const float m = mrun[jt];
                 float s0 = 0.0f, s1 = 0.0f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    s0 += fast_exp2(fmaf(acc[0][jt][r], a.cscale, bias[0][r]) - mnew);
-                    s1 += fast_exp2(fmaf(acc[1][jt][r], a.cscale, bias[1][r]) - mnew);
+                    s0 += fast_exp2(fmaf(acc[0][jt][r], a.cscale, bias[0][r]) - m);
+                    s1 += fast_exp2(fmaf(acc[1][jt][r], a.cscale, bias[1][r]) - m);
                 }
                 csum[jt] = s0 + s1;
-                srun[jt] *= fast_exp2(mrun[jt] - mnew);
-                mrun[jt] = mnew;
+                bad = bad || !(csum[jt] < kLazyMax);
             }
-        }
+            if (__any(bad)) {
 #pragma unroll
-        for (int jt = 0; jt < 4; ++jt) srun[jt] += csum[jt];
+                for (int jt = 0; jt < JTW; ++jt) {
+                    float mx = kNegInit;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        mx = fmaxf(mx, fmaf(acc[0][jt][r], a.cscale, bias[0][r]));
+                        mx = fmaxf(mx, fmaf(acc[1][jt][r], a.cscale, bias[1][r]));
+                    }
+                    float mnew = fmaxf(mrun[jt], ceilf(mx));
+                    float s0 = 0.0f, s1 = 0.0f;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        s0 += fast_exp2(fmaf(acc[0][jt][r], a.cscale, bias[0][r]) - mnew);
+                        s1 += fast_exp2(fmaf(acc[1][jt][r], a.cscale, bias[1][r]) - mnew);
+                    }
+                    csum[jt] = s0 + s1;
+                    srun[jt] *= fast_exp2(mrun[jt] - mnew);
+                    mrun[jt] = mnew;
+                }
+            }
+#pragma unroll
+            for (int jt = 0; jt < JTW; ++jt) srun[jt] += csum[jt];
+        } else {
+            // scores in place of the accumulators
+#pragma unroll
+            for (int it = 0; it < 2; ++it)
+#pragma unroll
+                for (int jt = 0; jt < JTW; ++jt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[it][jt][r] = fmaf(acc[it][jt][r], a.cscale, bias[it][r]);
+            // the stabiliser must keep every exponential representable in bf16 next to the row's
+            // largest one and the fp32 sums finite: lift it when a score exceeds it by more than 60
+            bool lift = false;
+            float mx[JTW];
+#pragma unroll
+            for (int jt = 0; jt < JTW; ++jt) {
+                float m = kNegInit;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) m = fmaxf(m, fmaxf(acc[0][jt][r], acc[1][jt][r]));
+                m = fmaxf(m, __shfl_xor(m, 32, 64));   // common to the two lane halves of the row
+                mx[jt] = m;
+                lift = lift || (m > mrun[jt] + 60.0f);
+            }
+            if (__any(lift)) {
+#pragma unroll
+                for (int jt = 0; jt < JTW; ++jt) {
+                    const float mnew = fmaxf(mrun[jt], ceilf(mx[jt]));
+                    const float scale = fast_exp2(mrun[jt] - mnew);   // exact power of two (or 0)
+                    srun[jt] *= scale;
+                    mrun[jt] = mnew;
+                    // accumulator column n = lr is this lane's resident row: one factor per lane
+#pragma unroll
+                    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) O[jt][cb][r] *= scale;
+                }
+            }
+            // this wave's pieces of the value image have landed, then everybody's
+            {
+                const int newer = pg - vstamp;
+                if (newer >= 2)
+                    wait_vm<2 * NPW>();
+                else if (newer == 1)
+                    wait_vm<NPW>();
+                else
+                    wait_vm<0>();
+            }
+            lds_done_barrier();
+#pragma unroll
+            for (int it = 0; it < 2; ++it)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    // A fragments: Vt[c = 32 cb + lr][the eight streamed points of this lane half]
+                    bf8 vf[NCB];
+#pragma unroll
+                    for (int cb = 0; cb < NCB; ++cb) {
+                        const unsigned char *vp = vimg + (32 * cb + lr) * kVRow + 2 * (64 * wi + 32 * it + 16 * s + 4 * lh);
+                        const uint2 lo = *reinterpret_cast<const uint2 *>(vp);
+                        const uint2 hi = *reinterpret_cast<const uint2 *>(vp + 16);
+                        const uint4 u = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                        vf[cb] = *reinterpret_cast<const bf8 *>(&u);
+                    }
+#pragma unroll
+                    for (int jt = 0; jt < JTW; ++jt) {
+                        bf8 e;
+                        float part = 0.0f;
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) {
+                            const float ev = fast_exp2(acc[it][jt][8 * s + q] - mrun[jt]);
+                            part += ev;
+                            e[q] = (__bf16)ev;
+                        }
+                        srun[jt] += part;
+#pragma unroll
+                        for (int cb = 0; cb < NCB; ++cb)
+                            O[jt][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[cb], e, O[jt][cb], 0, 0, 0);
+                    }
+                }
+        }
     }
 
     // ---- merge the 2 lane halves x 4 streamed-side waves of every resident row -------------
     lds_done_barrier();   // the ring is free: reuse it for the merge
     float2 *red = reinterpret_cast<float2 *>(ring);   // [BJ][8]: 4 streamed-side waves x 2 lane halves per row
 #pragma unroll
-    for (int jt = 0; jt < 4; ++jt) red[(128 * wj + 32 * jt + lr) * 8 + 2 * wi + lh] = make_float2(mrun[jt], srun[jt]);
+    for (int jt = 0; jt < JTW; ++jt)
+        red[(32 * JTW * wj + 32 * jt + lr) * 8 + 2 * wi + lh] = make_float2(mrun[jt], srun[jt]);
     __syncthreads();
+    if constexpr (APPLY) {
+        // output accumulators: scaled to the row's common max and added wave by wave (fixed order)
+        float *obuf = reinterpret_cast<float *>(ring + BJ * 64);   // [BJ][PC]
+        for (int ww = 0; ww < 4; ++ww) {
+            if (wi == ww) {
+#pragma unroll
+                for (int jt = 0; jt < JTW; ++jt) {
+                    const int j = 32 * JTW * wj + 32 * jt + lr;
+                    float M = kNegInit;
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) M = fmaxf(M, red[j * 8 + k].x);
+                    const float sc = fast_exp2(mrun[jt] - M);
+#pragma unroll
+                    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int cc = 32 * cb + 8 * (r >> 2) + 4 * lh + (r & 3);
+                            const float v = O[jt][cb][r] * sc;
+                            obuf[j * PC + cc] = ww == 0 ? v : obuf[j * PC + cc] + v;
+                        }
+                }
+            }
+            __syncthreads();
+        }
+        for (int e = tid; e < BJ * PC; e += 256 * WJ) {
+            const int j = e / PC, cc = e - j * PC;
+            a.opart[((int64_t)split * a.partial_stride + row0 + j) * PC + cc] = obuf[e];
+        }
+    }
     if (tid < BJ) {
         float M = kNegInit;
 #pragma unroll
@@ -327,6 +509,46 @@ __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a
         a.partial[(int64_t)split * a.partial_stride + row0 + tid] = make_double2((double)M, S);
     }
 }
+
+// Value image of every streamed tile for the plan application: bf16 Vt[c][i], c < pc value columns
+// starting at p0, i < 256 points of tile t, rows of kVRow bytes, one image per img_bytes; zero
+// outside the matrix.  (The pad bytes are copied to LDS with the rest and never read.)
+__global__ __launch_bounds__(BI) void k_vimg_bf16(const float *V, int64_t ldv, int64_t n_str, int p0, int p, int pc,
+                                                   int img_bytes, unsigned char *img)
+{
+    const int i = threadIdx.x;
+    const int64_t row = (int64_t)blockIdx.x * BI + i;
+    unsigned char *dst = img + (int64_t)blockIdx.x * img_bytes;
+    for (int cc = 0; cc < pc; ++cc) {
+        const float v = (row < n_str && p0 + cc < p) ? V[row * ldv + p0 + cc] : 0.0f;
+        *reinterpret_cast<__bf16 *>(dst + cc * kVRow + 2 * i) = (__bf16)v;
+    }
+}
+
+// Number of splits of the streamed side that minimises  rounds x tiles-per-workgroup
+// (rounds = ceil(workgroups / workgroups the chip holds at a time)), i.e. the time including the
+// idle tail of the last round; prefer fewer, longer workgroups on near-ties.
+int choose_splits(const Ctx *c, int n_jtiles, int n_itiles, int cap, int per_cu)
+{
+    int best_s = 1;
+    double best_cost = 1e300;
+    const int smax = n_itiles < cap ? n_itiles : cap;
+    for (int sp = 1; sp <= smax; ++sp) {
+        int tps = (int)ceil_div(n_itiles, sp);
+        int seff = (int)ceil_div(n_itiles, tps);
+        if (seff != sp) continue;
+        double rounds = (double)ceil_div((int64_t)n_jtiles * seff, (int64_t)c->num_cu * per_cu);
+        double cost = rounds * (tps + 0.25);   // 0.25: pipeline fill and merge of a workgroup
+        if (cost < best_cost * 0.99) {
+            best_cost = cost;
+            best_s = sp;
+        }
+    }
+    return best_s;
+}
+
+constexpr int kApplyPC = 64;    // value columns per application pass
+constexpr int kApplyBJ = 128;   // resident rows per workgroup of the application kernel
 
 }  // namespace
 
@@ -343,28 +565,8 @@ fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
     a.cscale = (float)(2.0 * kLog2e / eps);
     a.n_jtiles = (int)ceil_div(res->cnt, bj);
     a.n_itiles = (int)ceil_div(str->cnt, BI);
-    // Pick the number of splits of the streamed side that minimises  rounds x tiles-per-workgroup
-    // (rounds = ceil(workgroups / workgroups the chip holds at a time)), i.e. the time including the
-    // idle tail of the last round; prefer fewer, longer workgroups on near-ties.
-    {
-        int best_s = 1;
-        double best_cost = 1e300;
-        const int cap = max_splits(res->cnt);
-        const int smax = a.n_itiles < cap ? a.n_itiles : cap;
-        for (int sp = 1; sp <= smax; ++sp) {
-            int tps = (int)ceil_div(a.n_itiles, sp);
-            int seff = (int)ceil_div(a.n_itiles, tps);
-            if (seff != sp) continue;
-            double rounds = (double)ceil_div((int64_t)a.n_jtiles * seff, (int64_t)c->num_cu * per_cu);
-            double cost = rounds * (tps + 0.25);   // 0.25: pipeline fill and merge of a workgroup
-            if (cost < best_cost * 0.99) {
-                best_cost = cost;
-                best_s = sp;
-            }
-        }
-        a.splits = best_s;
-        a.tiles_per_split = (int)ceil_div(a.n_itiles, best_s);
-    }
+    a.splits = choose_splits(c, a.n_jtiles, a.n_itiles, max_splits(res->cnt), per_cu);
+    a.tiles_per_split = (int)ceil_div(a.n_itiles, a.splits);
     const int total = a.n_jtiles * a.splits;
     const int per = (total + 7) / 8;
     a.partial = (double2 *)P->partial;
@@ -374,12 +576,60 @@ fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
         return fail(c, FS_ERR_DEVICE, "internal: bf16 launch shape exceeds the padded buffers");
     prof_begin(c, (double)res->cnt * (double)str->cnt);
     if (wj == 2)
-        hipLaunchKernelGGL((k_lse_bf16<2, 4>), dim3((unsigned)(per * 8)), dim3(512), 0, c->stream, a);
+        hipLaunchKernelGGL((k_lse_bf16<2, 4, 4, 0>), dim3((unsigned)(per * 8)), dim3(512), 0, c->stream, a);
     else
-        hipLaunchKernelGGL((k_lse_bf16<1, 3>), dim3((unsigned)(per * 8)), dim3(256), 0, c->stream, a);
+        hipLaunchKernelGGL((k_lse_bf16<1, 3, 4, 0>), dim3((unsigned)(per * 8)), dim3(256), 0, c->stream, a);
     prof_end(c);
     FS_HIP(c, hipGetLastError());
     *splits_out = a.splits;
+    return FS_OK;
+}
+
+// workspace of bf16_apply: [splits][rows][kApplyPC] float accumulators, then the value images
+size_t bf16_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str)
+{
+    const int n_jtiles = (int)ceil_div(n_res, kApplyBJ), n_itiles = (int)ceil_div(n_str, BI);
+    const int splits = choose_splits(c, n_jtiles, n_itiles, max_splits(n_res), 1);
+    const size_t opart = (size_t)splits * (size_t)round_up(n_res, 1024) * kApplyPC * 4;
+    return ((opart + 1023) & ~size_t(1023)) + (size_t)n_itiles * kVImgBytes(kApplyPC);
+}
+
+fs_status bf16_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, const float *V, int64_t p,
+                     int64_t ldv, float *out, int64_t ldo, float *mass_out)
+{
+    BfArgs a{};
+    a.res = res->pts_b;
+    a.str = str->pts_b;
+    a.bias = str->bias_f;
+    a.kp = P->kp;
+    a.cscale = (float)(2.0 * kLog2e / eps);
+    a.n_jtiles = (int)ceil_div(res->cnt, kApplyBJ);
+    a.n_itiles = (int)ceil_div(str->cnt, BI);
+    a.splits = choose_splits(c, a.n_jtiles, a.n_itiles, max_splits(res->cnt), 1);
+    a.tiles_per_split = (int)ceil_div(a.n_itiles, a.splits);
+    a.partial = (double2 *)P->partial;
+    a.partial_stride = res->cnt_pad;
+    const size_t opart_bytes = ((size_t)a.splits * res->cnt_pad * kApplyPC * 4 + 1023) & ~size_t(1023);
+    const size_t vimg_bytes = (size_t)a.n_itiles * kVImgBytes(kApplyPC);
+    a.opart = reinterpret_cast<float *>(P->extra);
+    unsigned char *vimg = reinterpret_cast<unsigned char *>(P->extra) + opart_bytes;
+    a.vimg = vimg;
+    // host-side shape checks: every access of the kernels stays inside the padded buffers
+    if ((int64_t)a.n_jtiles * kApplyBJ > res->cnt_pad || (int64_t)a.n_itiles * BI > str->cnt_pad ||
+        (size_t)a.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp & 31) != 0 || a.kp < 32 ||
+        opart_bytes + vimg_bytes > P->extra_bytes || !P->extra)
+        return fail(c, FS_ERR_DEVICE, "internal: bf16 apply launch shape exceeds the padded buffers");
+    const int total = a.n_jtiles * a.splits;
+    const int per = (total + 7) / 8;
+    for (int p0 = 0; p0 < p; p0 += kApplyPC) {
+        hipLaunchKernelGGL(k_vimg_bf16, dim3((unsigned)a.n_itiles), dim3(BI), 0, c->stream, V, ldv, str->cnt, p0, (int)p,
+                           kApplyPC, kVImgBytes(kApplyPC), vimg);
+        hipLaunchKernelGGL((k_lse_bf16<2, 4, 2, kApplyPC>), dim3((unsigned)(per * 8)), dim3(512), 0, c->stream, a);
+        FS_HIP(c, hipGetLastError());
+        fs_status st = launch_apply_finalize(c, P, res, res->norm, a.splits, eps, a.opart, kApplyPC, p0, (int)p, out, ldo,
+                                             mass_out);
+        if (st != FS_OK) return st;
+    }
     return FS_OK;
 }
 

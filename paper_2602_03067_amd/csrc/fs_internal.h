@@ -262,6 +262,10 @@ fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str,
 // fs_bf16.hip
 fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,
                    int *splits_out);
+// plan application in bf16 mode (Alg. 2 / Alg. 4): workspace bytes and the pass itself
+size_t bf16_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str);
+fs_status bf16_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, const float *V, int64_t p,
+                     int64_t ldv, float *out, int64_t ldo, float *mass_out);
 
 // profiling helpers (fs_api.hip)
 void prof_begin(Ctx *c, double pairs, int kind = 0);

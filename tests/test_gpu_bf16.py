@@ -134,3 +134,59 @@ def test_full_size_sampled(ctx, oracle, name, iters):
     er, ec = ctx.fs_marginal_err(prob, eps, f, g)
     say("%s full: err_row=%.4e err_col=%.4e" % (name, er, ec))
     assert ec <= 1e-3 and 0.0 <= er < 2.0
+
+
+TOL_APPLY_A = 2e-2    # relative Frobenius error against the oracle on the inputs as given
+TOL_APPLY_B = 6e-3    # ... on the bf16-rounded points (what is left: bf16 plan entries and values)
+
+
+@pytest.mark.parametrize("n,m,d,p", [(1, 1, 16, 1), (130, 70, 20, 1), (200, 333, 64, 5), (257, 600, 40, 70),
+                                     (64, 64, 96, 64), (300, 1100, 784, 64), (1500, 129, 128, 33)])
+def test_apply_shapes_bf16_mode(ctx, oracle, n, m, d, p):
+    """Plan application (Alg. 2 / Alg. 4) in bf16 mode: both directions, with the plan's mass,
+    ragged sizes, several streamed tiles and more than one pass of 64 value columns."""
+    rng = np.random.default_rng(13 * n + m + d + p)
+    x, y, a, b = _rand_problem(rng, n, m, d)
+    eps = float(np.float32(0.5))
+    xb, yb = workloads.to_bf16_round(x), workloads.to_bf16_round(y)
+    fo, go = oracle.solve(xb, yb, a, b, eps, eps, 1, 3)
+    f32 = (fo + 0.05 * rng.standard_normal(n)).astype(np.float32)
+    g32 = go.astype(np.float32)
+    V = rng.standard_normal((m, p)).astype(np.float32)
+    U = rng.standard_normal((n, p)).astype(np.float32)
+    say("bf16 path apply n=%d m=%d d=%d p=%d" % (n, m, d, p))
+    prob = make_problem(x, y, a, b, compute=BF)
+    out, mass = ctx.fs_apply_plan(prob, eps, dev(f32), dev(g32), dev(V), want_mass=True)
+    outT, massT = ctx.fs_apply_plan_T(prob, eps, dev(f32), dev(g32), dev(U), want_mass=True)
+    torch.cuda.synchronize()
+    for tag, xs, ys, tol in (("given", x, y, TOL_APPLY_A), ("bf16-rounded", xb, yb, TOL_APPLY_B)):
+        want, r = oracle.apply_plan(xs, ys, a, b, eps, f32, g32, V, return_mass=True)
+        wantT, c = oracle.apply_plan_T(xs, ys, a, b, eps, f32, g32, U, return_mass=True)
+        e1 = np.linalg.norm(host(out) - want) / np.linalg.norm(want)
+        e2 = np.linalg.norm(host(outT) - wantT) / np.linalg.norm(wantT)
+        em = max(np.abs(host(mass) / r - 1).max(), np.abs(host(massT) / c - 1).max())
+        say("  vs oracle on %s inputs: PV %.3e  PtU %.3e  mass %.3e" % (tag, e1, e2, em))
+        assert e1 <= tol and e2 <= tol and em <= tol
+
+
+def test_apply_bf16_mode_large_score_spread(ctx, oracle):
+    """Small eps: the plan is close to an assignment and the running max moves by hundreds between
+    tiles, so the accumulators are rescaled many times."""
+    rng = np.random.default_rng(77)
+    n, m, d, p = 700, 900, 64, 64
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    y = (rng.standard_normal((m, d)) + 1.0).astype(np.float32)
+    a = np.full(n, 1.0 / n, dtype=np.float32)
+    b = np.full(m, 1.0 / m, dtype=np.float32)
+    eps = float(np.float32(0.5))
+    xb, yb = workloads.to_bf16_round(x), workloads.to_bf16_round(y)
+    fo, go = oracle.solve(xb, yb, a, b, eps, eps, 1, 20)
+    f32, g32 = fo.astype(np.float32), go.astype(np.float32)
+    say("bf16 path apply, score spread: n=%d m=%d d=%d eps=%g" % (n, m, d, eps))
+    prob = make_problem(x, y, a, b, compute=BF)
+    PY, r = ctx.fs_apply_plan(prob, eps, dev(f32), dev(g32), dev(y), want_mass=True)
+    want, r_o = oracle.apply_plan(xb, yb, a, b, eps, f32, g32, y, return_mass=True)
+    e1 = np.linalg.norm(host(PY) - want) / np.linalg.norm(want)
+    em = np.abs(host(r) / r_o - 1).max()
+    say("  PY %.3e  mass %.3e" % (e1, em))
+    assert e1 <= TOL_APPLY_B and em <= TOL_APPLY_B
