@@ -209,6 +209,22 @@ fs_status fs_apply_plan_T(fs_ctx *ctx, const fs_problem *prob, float eps, const 
                           int64_t ldo, float *c_out);
 
 /*
+ * Gradient of the entropic OT value with respect to the points of one cloud, for ANY
+ * potentials, assembled inside the library on top of one plan application (Cor. 4; the
+ * appendix on gradients for the induced-marginal form):
+ *   fs_grad_x:  T = P y (n x d),   mode 0:  2 (diag(a) x - T)
+ *                                  mode 1:  2 (diag(r) x - T),  r = P 1 the plan's own row marginal
+ *                                  mode 2:  x - diag(a)^-1 T    displacement to the barycentric image
+ *   fs_grad_y:  T = P^T x (m x d), the same with b, c = P^T 1 and y.
+ * grad: rows x d floats (ldg >= d), device, written; it may not overlap an input.  d <= 4096.
+ * With bfloat16 point storage the other cloud is widened to float in the workspace first.
+ */
+fs_status fs_grad_x(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, const float *g,
+                    int32_t mode, float *grad, int64_t ldg);
+fs_status fs_grad_y(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, const float *g,
+                    int32_t mode, float *grad, int64_t ldg);
+
+/*
  * Hessian-vector product G = T A of the entropic OT value with respect to the source
  * cloud x (Thm. 5): the matrix-free Schur-complement / conjugate-gradient oracle of
  * App. E, built on streamed applications of the plan that (f, g) induce:

@@ -22,7 +22,7 @@ FS_COMPUTE_FP32, FS_COMPUTE_BF16_MFMA = 0, 1
 EXPORTS = (
     "fs_create", "fs_destroy", "fs_status_str", "fs_last_error", "fs_version", "fs_row_norms",
     "fs_update_f", "fs_update_g", "fs_solve", "fs_solve_symmetric", "fs_solve_tol", "fs_marginal_err", "fs_ot_value", "fs_apply_plan",
-    "fs_apply_plan_T", "fs_hvp", "fs_profile_enable", "fs_profile_read",
+    "fs_apply_plan_T", "fs_grad_x", "fs_grad_y", "fs_hvp", "fs_profile_enable", "fs_profile_read",
 )
 
 
@@ -76,6 +76,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fs_ot_value.argtypes = [vp, PP, f32, vp, vp, ctypes.POINTER(ctypes.c_double)]
     lib.fs_apply_plan.argtypes = [vp, PP, f32, vp, vp, vp, i64, i64, vp, i64, vp]
     lib.fs_apply_plan_T.argtypes = [vp, PP, f32, vp, vp, vp, i64, i64, vp, i64, vp]
+    lib.fs_grad_x.argtypes = [vp, PP, f32, vp, vp, i32, vp, i64]
+    lib.fs_grad_y.argtypes = [vp, PP, f32, vp, vp, i32, vp, i64]
     lib.fs_hvp.argtypes = [vp, PP, f32, vp, vp, vp, i64, f32, f32, i32, vp, i64, ctypes.POINTER(i32)]
     lib.fs_profile_enable.argtypes = [vp, i32]
     lib.fs_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64),
@@ -243,6 +245,20 @@ class Context:
     def fs_apply_plan_T(self, prob: Problem, eps: float, f, g, U, want_mass: bool = False):
         return self._apply(self.lib.fs_apply_plan_T, "fs_apply_plan_T", prob, eps, f, g, U, prob.m,
                            prob.n, want_mass)
+
+    def _grad(self, fn, name, prob: Problem, eps: float, f, g, mode: int, rows: int) -> torch.Tensor:
+        _dev_f32(f, "f", (prob.n,))
+        _dev_f32(g, "g", (prob.m,))
+        out = torch.empty(rows, prob.d, dtype=torch.float32, device=f.device)
+        self._check(fn(self.h, ctypes.byref(prob.c), eps, _ptr(f), _ptr(g), int(mode), _ptr(out), prob.d), name)
+        return out
+
+    def fs_grad_x(self, prob: Problem, eps: float, f, g, mode: int = 0) -> torch.Tensor:
+        """Gradient with respect to x (n x d); mode 0: 2(diag(a)x - Py), 1: with r = P1, 2: x - (Py)/a."""
+        return self._grad(self.lib.fs_grad_x, "fs_grad_x", prob, eps, f, g, mode, prob.n)
+
+    def fs_grad_y(self, prob: Problem, eps: float, f, g, mode: int = 0) -> torch.Tensor:
+        return self._grad(self.lib.fs_grad_y, "fs_grad_y", prob, eps, f, g, mode, prob.m)
 
     def fs_hvp(self, prob: Problem, eps: float, f: torch.Tensor, g: torch.Tensor, A: torch.Tensor,
                tau: float, eta: float, max_cg: int) -> Tuple[torch.Tensor, int]:

@@ -236,6 +236,42 @@ fs_status run_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, d
     return FS_ERR_UNSUPPORTED;
 }
 
+// Plan application in two phases, so that a caller can place data in the workspace in between:
+// apply_begin validates, sizes the workspace (with `tail_bytes` more for the caller, at *tail),
+// prepares the problem and the biases of both sides; apply_run streams.
+fs_status apply_begin(Ctx *c, const fs_problem *prob, float eps, const float *f, const float *g, int64_t p,
+                      bool transposed, size_t tail_bytes, Prepared *P, char **tail)
+{
+    fs_status st;
+    const int64_t n_res = transposed ? prob->m : prob->n;
+    const int64_t n_str = transposed ? prob->n : prob->m;
+    size_t extra = 0;
+    switch (choose_path(prob)) {
+    case Path::LowD: extra = lowd_apply_ws(c, n_res, n_str, p); break;
+    case Path::F64: extra = f64_apply_ws(c, n_res, n_str, prob->d, p); break;
+    case Path::BF16: extra = bf16_apply_ws(c, n_res, n_str); break;
+    }
+    extra = (extra + 255) & ~size_t(255);
+    if ((st = prepare(c, prob, P, extra + tail_bytes, &P->extra)) != FS_OK) return st;
+    P->extra_bytes = extra;
+    if (tail) *tail = P->extra + extra;
+    if ((st = launch_bias_from_user(c, P, &P->X, f, eps)) != FS_OK) return st;
+    return launch_bias_from_user(c, P, &P->Y, g, eps);
+}
+
+fs_status apply_run(Ctx *c, Prepared *P, float eps, bool transposed, const float *V, int64_t p, int64_t ldv, float *out,
+                    int64_t ldo, float *mass)
+{
+    Side *res = transposed ? &P->Y : &P->X;
+    Side *str = transposed ? &P->X : &P->Y;
+    switch (P->path) {
+    case Path::LowD: return lowd_apply(c, P, res, str, eps, V, p, ldv, out, ldo, mass);
+    case Path::F64: return f64_apply(c, P, res, str, eps, V, p, ldv, out, ldo, mass);
+    case Path::BF16: return bf16_apply(c, P, res, str, eps, V, p, ldv, out, ldo, mass);
+    }
+    return FS_ERR_UNSUPPORTED;
+}
+
 fs_status apply_common(Ctx *c, const fs_problem *prob, float eps, const float *f, const float *g,
                        const float *V, int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass,
                        bool transposed)
@@ -254,26 +290,48 @@ fs_status apply_common(Ctx *c, const fs_problem *prob, float eps, const float *f
         overlap(out, (size_t)((out_rows - 1) * ldo + p) * 4, g, (size_t)prob->m * 4))
         return fail(c, FS_ERR_INVALID_ARG, "out overlaps an input");
     Prepared P;
-    int64_t n_res = transposed ? prob->m : prob->n;
-    int64_t n_str = transposed ? prob->n : prob->m;
-    size_t extra = 0;
-    switch (choose_path(prob)) {
-    case Path::LowD: extra = lowd_apply_ws(c, n_res, n_str, p); break;
-    case Path::F64: extra = f64_apply_ws(c, n_res, n_str, prob->d, p); break;
-    case Path::BF16: extra = bf16_apply_ws(c, n_res, n_str); break;
+    if ((st = apply_begin(c, prob, eps, f, g, p, transposed, 0, &P, nullptr)) != FS_OK) return st;
+    return apply_run(c, &P, eps, transposed, V, p, ldv, out, ldo, mass);
+}
+
+// a9: gradient of the OT value with respect to one cloud, assembled in the library on top of
+// the plan applied to the other cloud
+fs_status grad_common(Ctx *c, const fs_problem *prob, float eps, const float *f, const float *g, int32_t mode,
+                      float *grad, int64_t ldg, bool wrt_y)
+{
+    fs_status st = validate_problem(c, prob);
+    if (st != FS_OK) return st;
+    if ((st = validate_eps(c, eps)) != FS_OK) return st;
+    if (!f || !g) return fail(c, FS_ERR_INVALID_ARG, "f or g is NULL");
+    if (mode < 0 || mode > 2) return fail(c, FS_ERR_INVALID_ARG, "mode must be 0, 1 or 2");
+    const int64_t d = prob->d;
+    if (d > 4096 || ldg < d) return fail(c, FS_ERR_BAD_SHAPE, "need d <= 4096 and ldg >= d");
+    const int64_t rows = wrt_y ? prob->m : prob->n;          // the cloud differentiated
+    const int64_t orows = wrt_y ? prob->n : prob->m;         // the cloud the plan is applied to
+    const size_t gbytes = (size_t)((rows - 1) * ldg + d) * 4;
+    if ((st = check_out(c, prob, grad, gbytes, "grad")) != FS_OK) return st;
+    if (overlap(grad, gbytes, f, (size_t)prob->n * 4) || overlap(grad, gbytes, g, (size_t)prob->m * 4))
+        return fail(c, FS_ERR_INVALID_ARG, "grad overlaps an input");
+    const void *opts = wrt_y ? prob->x : prob->y;
+    const int64_t old = wrt_y ? prob->ldx : prob->ldy;
+    const bool convert = prob->dtype != FS_F32;              // the value matrix of an application is float
+    const size_t mass_bytes = ((size_t)rows * 4 + 255) & ~size_t(255);
+    const size_t tail_bytes = mass_bytes + (convert ? (size_t)orows * d * 4 : 0);
+    Prepared P;
+    char *tail = nullptr;
+    if ((st = apply_begin(c, prob, eps, f, g, d, wrt_y, tail_bytes, &P, &tail)) != FS_OK) return st;
+    float *mass = reinterpret_cast<float *>(tail);
+    const float *V = static_cast<const float *>(opts);
+    int64_t ldv = old;
+    if (convert) {
+        float *vf = reinterpret_cast<float *>(tail + mass_bytes);
+        if ((st = launch_pts_to_f32(c, opts, prob->dtype, orows, d, old, vf)) != FS_OK) return st;
+        V = vf;
+        ldv = d;
     }
-    if ((st = prepare(c, prob, &P, extra, &P.extra)) != FS_OK) return st;
-    P.extra_bytes = extra;
-    if ((st = launch_bias_from_user(c, &P, &P.X, f, eps)) != FS_OK) return st;
-    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps)) != FS_OK) return st;
-    Side *res = transposed ? &P.Y : &P.X;
-    Side *str = transposed ? &P.X : &P.Y;
-    switch (P.path) {
-    case Path::LowD: return lowd_apply(c, &P, res, str, eps, V, p, ldv, out, ldo, mass);
-    case Path::F64: return f64_apply(c, &P, res, str, eps, V, p, ldv, out, ldo, mass);
-    case Path::BF16: return bf16_apply(c, &P, res, str, eps, V, p, ldv, out, ldo, mass);
-    }
-    return FS_ERR_UNSUPPORTED;
+    if ((st = apply_run(c, &P, eps, wrt_y, V, d, ldv, grad, ldg, mode == 1 ? mass : nullptr)) != FS_OK) return st;
+    return launch_grad_assemble(c, grad, ldg, wrt_y ? prob->y : prob->x, prob->dtype, wrt_y ? prob->ldy : prob->ldx, rows, d,
+                                wrt_y ? prob->b : prob->a, mass, mode);
 }
 
 }  // namespace
@@ -626,6 +684,18 @@ fs_status fs_apply_plan_T(fs_ctx *ctx, const fs_problem *prob, float eps, const 
                           const float *U, int64_t p, int64_t ldu, float *out, int64_t ldo, float *c_out)
 {
     return apply_common(reinterpret_cast<Ctx *>(ctx), prob, eps, f, g, U, p, ldu, out, ldo, c_out, true);
+}
+
+fs_status fs_grad_x(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, const float *g, int32_t mode,
+                    float *grad, int64_t ldg)
+{
+    return grad_common(reinterpret_cast<Ctx *>(ctx), prob, eps, f, g, mode, grad, ldg, false);
+}
+
+fs_status fs_grad_y(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, const float *g, int32_t mode,
+                    float *grad, int64_t ldg)
+{
+    return grad_common(reinterpret_cast<Ctx *>(ctx), prob, eps, f, g, mode, grad, ldg, true);
 }
 
 fs_status fs_hvp(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, const float *g, const float *A,

@@ -218,6 +218,9 @@ fs_status launch_finalize_pair(Ctx *c, const Prepared *P, Side *X, const double 
                                float *f_out, Side *Y, const double *norm_y, const void *partial_y, int splits_y,
                                float *g_out, double eps_cur, double eps_next_bias, double mix);
 fs_status launch_export_f32(Ctx *c, const double *src, int64_t cnt, float *dst);
+fs_status launch_pts_to_f32(Ctx *c, const void *pts, int dtype, int64_t rows, int64_t d, int64_t ld, float *dst);
+fs_status launch_grad_assemble(Ctx *c, float *g, int64_t ldg, const void *pts, int dtype, int64_t ld, int64_t rows,
+                               int64_t d, const float *w, const float *mass, int mode);
 fs_status launch_value_terms(Ctx *c, const Prepared *P, const Side *res, const double *res_norm, const Side *str,
                              int splits, double eps, double *scratch, double *dst);
 fs_status launch_row_norms(Ctx *c, const void *pts, int dtype, int64_t rows, int64_t d, int64_t ld,

@@ -577,6 +577,55 @@ fs_status launch_apply_finalize(Ctx *c, const Prepared *P, const Side *res, cons
     return FS_OK;
 }
 
+// float copy of a point matrix (bf16 storage) for use as the value matrix of a plan application
+__global__ void k_pts_to_f32(const void *pts, int dtype, int64_t rows, int64_t d, int64_t ld, float *dst)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= rows * d) return;
+    const int64_t i = e / d, k = e - i * d;
+    dst[e] = load_pt(pts, dtype, i * ld + k);
+}
+
+// Gradient assembly on top of T = (plan applied to the other cloud), in place in `g` (rows x d):
+//   mode 0: 2 (w_i z_i - T_i)        Cor. 4, w the given weights (uniform 1/rows when NULL)
+//   mode 1: 2 (mass_i z_i - T_i)     the same with the plan's own marginal (appendix on gradients)
+//   mode 2: z_i - T_i / w_i          displacement to the barycentric image
+__global__ void k_grad_assemble(float *g, int64_t ldg, const void *pts, int dtype, int64_t ld, int64_t rows, int64_t d,
+                                const float *w, double uniform_w, const float *mass, int mode)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= rows * d) return;
+    const int64_t i = e / d, k = e - i * d;
+    const double z = (double)load_pt(pts, dtype, i * ld + k);
+    const double t = (double)g[i * ldg + k];
+    const double wi = w ? (double)w[i] : uniform_w;
+    double r;
+    if (mode == 0)
+        r = 2.0 * (wi * z - t);
+    else if (mode == 1)
+        r = 2.0 * ((double)mass[i] * z - t);
+    else
+        r = z - t / wi;
+    g[i * ldg + k] = (float)r;
+}
+
+fs_status launch_pts_to_f32(Ctx *c, const void *pts, int dtype, int64_t rows, int64_t d, int64_t ld, float *dst)
+{
+    hipLaunchKernelGGL(k_pts_to_f32, dim3((unsigned)ceil_div(rows * d, 256)), dim3(256), 0, c->stream, pts, dtype, rows, d,
+                       ld, dst);
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
+fs_status launch_grad_assemble(Ctx *c, float *g, int64_t ldg, const void *pts, int dtype, int64_t ld, int64_t rows,
+                               int64_t d, const float *w, const float *mass, int mode)
+{
+    hipLaunchKernelGGL(k_grad_assemble, dim3((unsigned)ceil_div(rows * d, 256)), dim3(256), 0, c->stream, g, ldg, pts, dtype,
+                       ld, rows, d, w, 1.0 / (double)rows, mass, mode);
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
 fs_status launch_export_f32(Ctx *c, const double *src, int64_t cnt, float *dst)
 {
     hipLaunchKernelGGL(k_export_f32, dim3((unsigned)ceil_div(cnt, 256)), dim3(256), 0, c->stream, src, cnt, dst);

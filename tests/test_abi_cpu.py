@@ -137,6 +137,19 @@ def test_apply_validation(lib, hctx):
     assert lib.fs_apply_plan(*args(4, 4, 4)) == 7                  # valid: reaches device stage
 
 
+def test_grad_validation(lib, hctx):
+    p = _prob()
+    args = lambda mode, ldg, out=1 << 22, f=1 << 21: (hctx, ctypes.byref(p), F(0.1), P(f), P(1 << 20), mode, P(out), ldg)
+    assert lib.fs_grad_x(*args(3, 3)) == 1                         # unknown mode
+    assert lib.fs_grad_y(*args(-1, 3)) == 1
+    assert lib.fs_grad_x(*args(0, 2)) == 2                         # ldg < d
+    assert lib.fs_grad_x(*args(0, 3, out=None)) == 1
+    assert lib.fs_grad_x(*args(0, 3, out=4096)) == 1               # grad on top of x
+    assert lib.fs_grad_x(*args(0, 3, out=(1 << 21) + 8)) == 1      # grad on top of f
+    assert lib.fs_grad_x(*args(0, 3)) == 7                         # valid: reaches device stage
+    assert lib.fs_grad_y(*args(2, 5)) == 7
+
+
 def test_row_norms_validation(lib, hctx):
     assert lib.fs_row_norms(hctx, None, 0, 4, 3, 3, P(1 << 20)) == 1
     assert lib.fs_row_norms(hctx, P(4096), 0, 0, 3, 3, P(1 << 20)) == 2
