@@ -270,3 +270,29 @@ def test_full_size_lowdim_sampled_rows(ctx, oracle):
     f_plus = host(ctx.fs_update_f(prob, eps, g))[rows]
     r_gpu = w.a[rows].astype(np.float64) * np.exp((host(f)[rows] - f_plus) / eps)
     np.testing.assert_allclose(r_gpu, r_or, rtol=5e-4)
+
+
+@pytest.mark.parametrize("n,m,d", [(1500000, 1048576 + 77, 2), (3000000, 130, 5)])
+def test_million_points_sampled_rows(ctx, oracle, n, m, d):
+    """Sizes well beyond the bench's: one f-update and one g-update (more than 10^12 pairs in the
+    first case), checked by the oracle on 64 sampled rows and columns."""
+    rng = np.random.default_rng(n + m + d)
+    x = rng.random((n, d)).astype(np.float32)
+    y = (rng.random((m, d)) * 0.8 + 0.1).astype(np.float32)
+    a = np.full(n, 1.0 / n, dtype=np.float32)
+    b = rng.random(m).astype(np.float32) + 0.5
+    b /= b.sum()
+    eps = float(np.float32(0.05))
+    g0 = (0.1 * rng.standard_normal(m)).astype(np.float32)
+    say("large sizes: update_f / update_g n=%d m=%d d=%d" % (n, m, d))
+    prob = make_problem(x, y, a, b)
+    f1 = ctx.fs_update_f(prob, eps, dev(g0))
+    g1 = ctx.fs_update_g(prob, eps, f1)
+    torch.cuda.synchronize()
+    f1h = host(f1)
+    rows = np.sort(rng.choice(n, size=64, replace=False))
+    cols = np.sort(rng.choice(m, size=64, replace=False))
+    ef = max_err_over_eps(f1h[rows], oracle.update_f(x, y, b, eps, g0, rows=rows), eps)
+    eg = max_err_over_eps(host(g1)[cols], oracle.update_g(x, y, a, eps, f1h, cols=cols), eps)
+    say("  sampled max|df|/eps=%.3e max|dg|/eps=%.3e" % (ef, eg))
+    assert np.isfinite(f1h).all() and ef <= TOL and eg <= TOL
