@@ -502,40 +502,51 @@ __global__ __launch_bounds__(256) void k_weighted_sums(int64_t cnt, const float 
 
 // merge the splits of an application pass and apply the epilogue of Alg. 2:
 //   out_i = a_i * exp(fhat_i/eps + m_i) * O_i   with everything in base 2;  mass_i = same with s.
-__global__ void k_apply_finalize(const double2 *partial, int64_t stride, const float *opart, int64_t opart_stride,
-                                 int PC, int splits, int64_t cnt, double inv_eps, const float *w, double log_uniform,
-                                 const double *pot, const double *res_norm, int p0, int p, float *out, int64_t ldo,
-                                 float *mass_out)
+// A block of 256 threads covers 256 / PC rows; thread (row, c) produces one output entry, so the
+// reads of the [splits][rows][PC] accumulators are contiguous; the row's max and factor are
+// computed once (by its thread c = 0) and shared.  PC divides 256.
+__global__ __launch_bounds__(256) void k_apply_finalize(const double2 *partial, int64_t stride, const float *opart,
+                                                        int64_t opart_stride, int PC, int splits, int64_t cnt,
+                                                        double inv_eps, const float *w, double log_uniform,
+                                                        const double *pot, const double *res_norm, int p0, int p,
+                                                        float *out, int64_t ldo, float *mass_out)
 {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= cnt) return;
-    double M = -INFINITY;
+    __shared__ double shM[256], shFac[256];
+    const int rows_per_block = 256 / PC;
+    const int rl = threadIdx.x / PC, c = threadIdx.x - rl * PC;
+    const int64_t i = (int64_t)blockIdx.x * rows_per_block + rl;
+    if (c == 0 && i < cnt) {
+        double M = -INFINITY;
 #pragma unroll 8
+        for (int k = 0; k < splits; ++k) {
+            double mk = partial[(int64_t)k * stride + i].x;
+            M = mk > M ? mk : M;
+        }
+        double lw = w ? log((double)w[i]) : log_uniform;
+        // row factor  a_i * exp(fhat_i/eps + m_i): add the exponents BEFORE exponentiating
+        const double fac = exp2(((pot[i] - res_norm[i]) * inv_eps + lw) * kLog2e + M);
+        shM[rl] = M;
+        shFac[rl] = fac;
+        if (mass_out && p0 == 0) {
+            double S = 0.0;
+#pragma unroll 8
+            for (int k = 0; k < splits; ++k) {
+                double2 ms = partial[(int64_t)k * stride + i];
+                S += rescale_split(ms.y, ms.x, M);
+            }
+            mass_out[i] = (float)(fac * S);
+        }
+    }
+    __syncthreads();
+    if (i >= cnt || p0 + c >= p) return;
+    const double M = shM[rl];
+    double acc = 0.0;
+#pragma unroll 4
     for (int k = 0; k < splits; ++k) {
-        double mk = partial[(int64_t)k * stride + i].x;
-        M = mk > M ? mk : M;
+        const double mk = partial[(int64_t)k * stride + i].x;
+        acc += rescale_split((double)opart[((int64_t)k * opart_stride + i) * PC + c], mk, M);
     }
-    double lw = w ? log((double)w[i]) : log_uniform;
-    // row factor  a_i * exp(fhat_i/eps + m_i): add the exponents BEFORE exponentiating
-    double fac = exp2(((pot[i] - res_norm[i]) * inv_eps + lw) * kLog2e + M);
-    for (int c = 0; c < PC; ++c) {
-        if (p0 + c >= p) break;
-        double acc = 0.0;
-        for (int k = 0; k < splits; ++k) {
-            double2 ms = partial[(int64_t)k * stride + i];
-            acc += rescale_split((double)opart[((int64_t)k * opart_stride + i) * PC + c], ms.x, M);
-        }
-        out[i * ldo + p0 + c] = (float)(fac * acc);
-    }
-    if (mass_out && p0 == 0) {
-        double S = 0.0;
-#pragma unroll 8
-        for (int k = 0; k < splits; ++k) {
-            double2 ms = partial[(int64_t)k * stride + i];
-            S += rescale_split(ms.y, ms.x, M);
-        }
-        mass_out[i] = (float)(fac * S);
-    }
+    out[i * ldo + p0 + c] = (float)(shFac[rl] * acc);
 }
 
 // `eps`: the eps of the pass that will stream these biases
@@ -570,7 +581,8 @@ fs_status launch_apply_finalize(Ctx *c, const Prepared *P, const Side *res, cons
                                 double eps, const float *opart, int PC, int p0, int p, float *out, int64_t ldo,
                                 float *mass_out)
 {
-    hipLaunchKernelGGL(k_apply_finalize, dim3((unsigned)ceil_div(res->cnt, 256)), dim3(256), 0, c->stream,
+    if (PC < 1 || PC > 256 || 256 % PC != 0) return fail(c, FS_ERR_DEVICE, "internal: accumulator width of the application merge");
+    hipLaunchKernelGGL(k_apply_finalize, dim3((unsigned)ceil_div(res->cnt, 256 / PC)), dim3(256), 0, c->stream,
                        (const double2 *)P->partial, res->cnt_pad, opart, res->cnt_pad, PC, splits, res->cnt, 1.0 / eps,
                        res->w, res->log_uniform, res->pot, res_norm, p0, p, out, ldo, mass_out);
     FS_HIP(c, hipGetLastError());
