@@ -1,0 +1,119 @@
+"""GPU edge cases of the C ABI against the float64 oracle: row strides larger than the row,
+a context on a stream of its own, one context reused over problems of different sizes and paths
+(workspace regrowth), very small eps in low dimension."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_03067_amd import binding
+from tests._gpu_common import dev, host, max_err_over_eps, say
+
+pytestmark = pytest.mark.gpu
+BF = binding.FS_COMPUTE_BF16_MFMA
+
+
+def _cloud(rng, n, m, d, scale):
+    x = (rng.standard_normal((n, d)) * scale).astype(np.float32)
+    y = (rng.standard_normal((m, d)) * scale + 0.3 * scale).astype(np.float32)
+    a = rng.random(n) + 0.1
+    a = (a / a.sum()).astype(np.float32)
+    b = rng.random(m) + 0.1
+    b = (b / b.sum()).astype(np.float32)
+    return x, y, a, b
+
+
+def _strided(arr, extra):
+    """Device tensor whose rows are `extra` elements apart more than their length (junk in between)."""
+    rows, cols = arr.shape
+    buf = torch.full((rows, cols + extra), 1.0e30, dtype=torch.float32, device="cuda:0")
+    view = buf[:, :cols]
+    view.copy_(torch.from_numpy(arr))
+    assert view.stride(0) == cols + extra
+    return view
+
+
+@pytest.mark.parametrize("d,compute,tol", [(3, "fp32", 1e-4), (9, "fp32", 1e-4), (40, "fp32", 1e-4), (48, "bf16", 2e-2)])
+def test_row_strides_larger_than_the_rows(oracle, d, compute, tol):
+    rng = np.random.default_rng(100 + d)
+    n, m, p = 333, 290, 5
+    x, y, a, b = _cloud(rng, n, m, d, 1.0 / np.sqrt(d))
+    eps = float(np.float32(0.3))
+    g0 = (0.2 * rng.standard_normal(m)).astype(np.float32)
+    V = rng.standard_normal((m, p)).astype(np.float32)
+    say("strided inputs d=%d %s" % (d, compute))
+    ctx = binding.Context(0)
+    prob = binding.Problem(_strided(x, 3), _strided(y, 7), dev(a), dev(b), BF if compute == "bf16" else binding.FS_COMPUTE_FP32)
+    f1 = ctx.fs_update_f(prob, eps, dev(g0))
+    g1 = ctx.fs_update_g(prob, eps, f1)
+    f1h = host(f1)
+    ef = max_err_over_eps(f1h, oracle.update_f(x, y, b, eps, g0), eps)
+    eg = max_err_over_eps(host(g1), oracle.update_g(x, y, a, eps, f1h.astype(np.float32)), eps)
+    out = host(ctx.fs_apply_plan(prob, eps, f1, g1, _strided(V, 2)))
+    want = oracle.apply_plan(x, y, a, b, eps, f1h.astype(np.float32), host(g1).astype(np.float32), V)
+    ea = np.linalg.norm(out - want) / np.linalg.norm(want)
+    say("  max|df|/eps=%.3e max|dg|/eps=%.3e apply rel=%.3e" % (ef, eg, ea))
+    assert ef <= tol and eg <= tol and ea <= max(tol, 2e-4)
+    ctx.close()
+
+
+def test_context_on_its_own_stream(oracle):
+    rng = np.random.default_rng(7)
+    n, m, d = 500, 400, 3
+    x, y, a, b = _cloud(rng, n, m, d, 1.0)
+    eps = float(np.float32(0.2))
+    say("context bound to a non-default stream")
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        ctx = binding.Context(0, stream)
+        prob = binding.Problem(dev(x), dev(y), dev(a), dev(b))
+        f = torch.zeros(n, device="cuda:0")
+        g = torch.zeros(m, device="cuda:0")
+        ctx.fs_solve(prob, eps, eps, 1, 7, f, g)
+    stream.synchronize()
+    fo, go = oracle.solve(x, y, a, b, eps, eps, 1, 7)
+    assert max_err_over_eps(host(f), fo, eps) <= 1e-4 and max_err_over_eps(host(g), go, eps) <= 1e-4
+    ctx.close()
+
+
+def test_one_context_many_problems(oracle):
+    """The workspace grows and is laid out anew per call: small, large, another path, small again."""
+    rng = np.random.default_rng(11)
+    ctx = binding.Context(0)
+    for (n, m, d, compute, tol) in ((50, 60, 3, "fp32", 1e-4), (3000, 2500, 3, "fp32", 1e-4), (300, 200, 64, "fp32", 1e-4),
+                                    (600, 700, 64, "bf16", 2e-2), (40, 30, 2, "fp32", 1e-4), (900, 1000, 16, "fp32", 1e-4)):
+        x, y, a, b = _cloud(rng, n, m, d, 1.0 / np.sqrt(d))
+        eps = float(np.float32(0.25))
+        say("same context: n=%d m=%d d=%d %s" % (n, m, d, compute))
+        prob = binding.Problem(dev(x), dev(y), dev(a), dev(b), BF if compute == "bf16" else binding.FS_COMPUTE_FP32)
+        f = torch.zeros(n, device="cuda:0")
+        g = torch.zeros(m, device="cuda:0")
+        ctx.fs_solve(prob, eps, eps, 1, 4, f, g)
+        fo, go = oracle.solve(x, y, a, b, eps, eps, 1, 4)
+        ef, eg = max_err_over_eps(host(f), fo, eps), max_err_over_eps(host(g), go, eps)
+        say("  max|df|/eps=%.3e max|dg|/eps=%.3e" % (ef, eg))
+        assert ef <= tol and eg <= tol
+    ctx.close()
+
+
+@pytest.mark.parametrize("d,eps", [(3, 2e-3), (2, 5e-4), (8, 2e-3)])
+def test_very_small_eps_low_dimension(oracle, d, eps):
+    """Scores of several thousand (base 2): float64-score half-steps, on the matrix cores where the
+    fixed grids cover the biases (d <= 3) and on the vector ALU otherwise."""
+    rng = np.random.default_rng(31 + d)
+    n, m = 700, 650
+    x = rng.random((n, d)).astype(np.float32)
+    y = rng.random((m, d)).astype(np.float32)
+    a = np.full(n, 1.0 / n, dtype=np.float32)
+    b = np.full(m, 1.0 / m, dtype=np.float32)
+    eps = float(np.float32(eps))
+    say("very small eps: d=%d eps=%g" % (d, eps))
+    ctx = binding.Context(0)
+    prob = binding.Problem(dev(x), dev(y), dev(a), dev(b))
+    f = torch.zeros(n, device="cuda:0")
+    g = torch.zeros(m, device="cuda:0")
+    ctx.fs_solve(prob, eps, eps, 1, 5, f, g)
+    fo, go = oracle.solve(x, y, a, b, eps, eps, 1, 5)
+    ef, eg = max_err_over_eps(host(f), fo, eps), max_err_over_eps(host(g), go, eps)
+    say("  max|df|/eps=%.3e max|dg|/eps=%.3e" % (ef, eg))
+    assert ef <= 1e-4 and eg <= 1e-4
+    ctx.close()
