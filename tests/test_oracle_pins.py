@@ -460,6 +460,43 @@ def test_barycentric_projection_at_convergence(oracle):
 
 
 # ----------------------------------------------------------------------------------------
+# Gradient of the OT value with respect to the points (Section 2.2, Cor. 4): by the envelope
+# theorem the derivative of the converged value only sees the cost, so central differences of
+# the VALUE (computed from a dense plan, no plan application involved) must reproduce
+# 2 (diag(a) x - P y) and 2 (diag(b) y - P^T x) built from the oracle's plan applications.
+# ----------------------------------------------------------------------------------------
+def test_gradient_is_the_derivative_of_the_converged_value(oracle):
+    rng = np.random.default_rng(77)
+    n, m, d = 6, 7, 2
+    x, y, a, b = _problem(rng, n, m, d)
+    eps = _e(0.5)
+
+    def value(xx, yy):
+        f, g = oracle.solve(xx, yy, a, b, eps, eps, 1, 4000)
+        C = ((xx[:, None, :] - yy[None, :, :]) ** 2).sum(-1)
+        P = a[:, None] * b[None, :] * np.exp((f[:, None] + g[None, :] - C) / eps)
+        assert abs(P.sum() - 1.0) < 1e-10 and np.abs(P.sum(1) - a).max() < 1e-10      # converged
+        return (P * C).sum() + eps * (P * np.log(P / (a[:, None] * b[None, :]))).sum()   # Eq. 1
+
+    f, g = oracle.solve(x, y, a, b, eps, eps, 1, 4000)
+    PY = oracle.apply_plan(x, y, a, b, eps, f, g, y)
+    PtX = oracle.apply_plan_T(x, y, a, b, eps, f, g, x)
+    gx = 2.0 * (a[:, None] * x - PY)
+    gy = 2.0 * (b[:, None] * y - PtX)
+    h = 1e-5
+    for (i, k) in ((0, 0), (3, 1), (5, 0)):
+        xp, xm = x.copy(), x.copy()
+        xp[i, k] += h
+        xm[i, k] -= h
+        assert abs((value(xp, y) - value(xm, y)) / (2 * h) - gx[i, k]) < 2e-6
+    for (j, k) in ((1, 1), (6, 0)):
+        yp, ym = y.copy(), y.copy()
+        yp[j, k] += h
+        ym[j, k] -= h
+        assert abs((value(x, yp) - value(x, ym)) / (2 * h) - gy[j, k]) < 2e-6
+
+
+# ----------------------------------------------------------------------------------------
 # P10: the online LSE recurrence of App. D.3 reproduces the two-pass LSE for any tiling
 # ----------------------------------------------------------------------------------------
 @pytest.mark.parametrize("tile", [1, 3, 8, 50])
