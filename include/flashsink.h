@@ -17,10 +17,14 @@
  *    float.  The shift by the squared norms (Prop. 1) is internal.
  *  - a == NULL / b == NULL means uniform weights 1/n, 1/m.  Weights must be
  *    positive; a zero weight removes its point from every sum (log 0 = -inf).
- *  - All work is enqueued on the stream given to fs_create; calls return
- *    without synchronising, except fs_marginal_err (it returns host scalars)
- *    and calls that have to grow the context's workspace (they synchronise the
- *    stream once, before the old workspace is released).
+ *  - All work is enqueued on the stream given to fs_create.  The streaming passes
+ *    are never waited for, except by the calls that return host values
+ *    (fs_marginal_err, fs_ot_value, fs_solve_tol, fs_profile_read).  An entry
+ *    point may synchronise the stream briefly in its prologue: for d <= 16 it
+ *    reads back a few scalars (largest squared norm, size of the given
+ *    potentials) that select the score arithmetic, fs_hvp reads back the scalars
+ *    of its conjugate-gradient loop, and a call that has to grow the context's
+ *    workspace synchronises once before the old workspace is released.
  *  - Errors are reported by status code only; nothing throws or aborts.
  *    Argument validation happens on the host before any launch.  The message
  *    of the last failure on a context is available from fs_last_error.
