@@ -219,12 +219,26 @@ struct SplitArgs {
     int row_blocks, splits;  // extent of this pass in the grid
     double2 *partial;
     int64_t partial_stride;
+    // plan application (PC > 0): value matrix [n_str][ldv], its columns p0 .. p0+PC-1 of p, and the
+    // [splits][partial_stride][PC] accumulators
+    const float *V;
+    int64_t ldv, n_str;
+    int p0, p;
+    float *opart;
 };
 
-// one workgroup of the pass: row block bx, column split by
-template <int KS, int R, int TJ, int CH, bool PRECISE>
+// one workgroup of the pass: row block bx, column split by.
+// PC > 0 makes it the plan application (Alg. 2 / Alg. 4) for PC value columns: every exponential
+// also multiplies the value row of its streamed point, which all lanes of a half-wave share (a
+// lane's registers are streamed points, its lane index the resident row), so the value row comes
+// as one broadcast LDS read per exponential and the products stay on the vector ALU in fp32.
+template <int KS, int R, int TJ, int CH, bool PRECISE, int PC = 0, int PCU = PC>
 __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx, const int by)
 {
+    // PCU <= PC: value columns actually wanted (the others are neither multiplied nor stored)
+    constexpr bool APPLY = PC > 0;
+    static_assert(PC == 0 || PC == 4, "one float4 of values per streamed point");
+    __shared__ __attribute__((aligned(16))) float vtile[APPLY ? 2 : 1][APPLY ? TJ * PC : 4];
     constexpr int NP = 2 * KS;               // 16-byte pieces per record
     constexpr int UPT = TJ * NP / kBlock;    // pieces each thread moves per tile
     constexpr int NG = TJ / 32;              // groups of 32 streamed points per tile
@@ -249,6 +263,13 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
 
     bf8 b[R][KS];
     float mrun[R], srun[R], stile[R];
+    float orun[APPLY ? R : 1][APPLY ? PC : 1], otile[APPLY ? R : 1][APPLY ? PC : 1];
+    if constexpr (APPLY) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int c = 0; c < PC; ++c) orun[r][c] = otile[r][c] = 0.0f;
+    }
     auto set_max = [&](int r, float neg_m) {   // slots 3..5 of that piece <- pieces of -max
         __bf16 q[3];
         split3(neg_m, q);
@@ -264,10 +285,23 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
 
     // a tile is a linear 16 KS TJ / 8 byte copy, moved by direct global -> LDS loads (no registers)
     const unsigned tile_off = (unsigned)(size_t)&tile[0][0];
+    const unsigned vtile_off = (unsigned)(size_t)&vtile[0][0];
     auto fetch = [&](int t, int bufi) {
 #pragma unroll
         for (int q = 0; q < UPT; ++q)
             dma16(gsrc + (int64_t)t * (TJ * NP) + q * kBlock + tid, tile_off + (bufi * (TJ * NP) + q * kBlock + w * 64) * 16);
+        if constexpr (APPLY) {
+            // value rows of the tile, one dword per lane; entries outside the matrix are read from a
+            // valid address instead (their exponentials are zero / their columns are not stored)
+#pragma unroll
+            for (int q = 0; q < TJ * PC / kBlock; ++q) {
+                const int e = q * kBlock + tid;
+                const int64_t j = (int64_t)t * TJ + e / PC;
+                const int cc = a.p0 + e % PC;
+                const float *src = a.V + (j < a.n_str ? j : 0) * a.ldv + (cc < a.p ? cc : a.p0);
+                dma4(src, vtile_off + (bufi * (TJ * PC) + q * kBlock + w * 64) * 4);
+            }
+        }
     };
     // the first tile is on its way while the resident operands are built
     if (t_begin < t_end) fetch(t_begin, 0);
@@ -337,7 +371,7 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
     // exponentials of step s, the matrix pipe computes step s + 1, its KS instructions spread evenly
     // between them.  (Instructions of one wave overlap across the two pipes only if they alternate
     // at this grain; a wave that issues its MFMAs back to back stalls the vector ALU.)
-    auto chunk_sums = [&](const Unit *tl, int c0, float(&csum)[R]) {
+    auto chunk_sums = [&](const Unit *tl, const float *vt, int c0, float(&csum)[R], float(&co)[APPLY ? R : 1][APPLY ? PC : 1]) {
         constexpr int NS = CH * R;
         bf8 av[2][KS];
         f16v dd[2];
@@ -366,9 +400,26 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
                     dd[sn & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[gn & 1][ks], b[rn][ks], ks == 0 ? z : dd[sn & 1], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 const int e0 = 16 * ks / KS, e1 = 16 * (ks + 1) / KS;
-                float part = fast_exp2(dd[st & 1][e0]);
+                float part = 0.0f;
 #pragma unroll
-                for (int e = e0 + 1; e < e1; ++e) part += fast_exp2(dd[st & 1][e]);
+                for (int e = e0; e < e1; ++e) {
+                    const float ev = fast_exp2(dd[st & 1][e]);
+                    part = e == e0 ? ev : part + ev;
+                    if constexpr (APPLY) {
+                        // register e of lane half lh is streamed point 8 (e / 4) + 4 lh + e % 4 of group c0 + g
+                        const float4 vv = *reinterpret_cast<const float4 *>(vt + (32 * (c0 + g) + 8 * (e >> 2) + 4 * lh + (e & 3)) * PC);
+                        const float vcol[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+                        for (int c = 0; c < PC; ++c) {
+                            if (c >= PCU)
+                                co[r][c] = 0.0f;
+                            else if (g == 0 && e == 0)
+                                co[r][c] = ev * vcol[c];
+                            else
+                                co[r][c] = fmaf(ev, vcol[c], co[r][c]);
+                        }
+                    }
+                }
                 acc = ks == 0 ? part : acc + part;
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -380,10 +431,21 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
     for (int t = t_begin; t < t_end; ++t) {
         if (t + 1 < t_end) fetch(t + 1, buf ^ 1);   // that buffer was last read before the previous barrier
         const Unit *tl = tile[buf];
+        const float *vt = vtile[APPLY ? buf : 0];
 #pragma unroll 1
         for (int c0 = 0; c0 < NG; c0 += CH) {
             float csum[R];
-            chunk_sums(tl, c0, csum);
+            float co[APPLY ? R : 1][APPLY ? PC : 1];
+            chunk_sums(tl, vt, c0, csum, co);
+            if constexpr (APPLY) {
+                // pin the products to this point: left alone, the compiler sinks all of them behind the
+                // branch below (they are only needed when the chunk is accepted) and keeps 64
+                // exponentials and 64 value rows alive for that, in scratch memory
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < PC; ++c) asm volatile("" ::"v"(co[r][c]));
+            }
             bool bad = false;
 #pragma unroll
             for (int r = 0; r < R; ++r) bad = bad || !(csum[r] < kLazyMax);
@@ -413,18 +475,38 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
                     const float scale = fast_exp2(mrun[r] - mnew);
                     srun[r] *= scale;
                     stile[r] *= scale;
+                    if constexpr (APPLY) {
+#pragma unroll
+                        for (int c = 0; c < PC; ++c) {
+                            orun[r][c] *= scale;
+                            otile[r][c] *= scale;
+                        }
+                    }
                     mrun[r] = mnew;
                     set_max(r, -mnew);
                 }
-                chunk_sums(tl, c0, csum);   // all exponents are <= 0 now: no second check
+                chunk_sums(tl, vt, c0, csum, co);   // all exponents are <= 0 now: no second check
             }
 #pragma unroll
-            for (int r = 0; r < R; ++r) stile[r] += csum[r];
+            for (int r = 0; r < R; ++r) {
+                stile[r] += csum[r];
+                if constexpr (APPLY) {
+#pragma unroll
+                    for (int c = 0; c < PC; ++c) otile[r][c] += co[r][c];
+                }
+            }
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             srun[r] += stile[r];
             stile[r] = 0.0f;
+            if constexpr (APPLY) {
+#pragma unroll
+                for (int c = 0; c < PC; ++c) {
+                    orun[r][c] += otile[r][c];
+                    otile[r][c] = 0.0f;
+                }
+            }
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of the next tile has landed
         __syncthreads();
@@ -439,6 +521,15 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
         const float M = fmaxf(m, mo);
         const float S = sv * fast_exp2(m - M) + so * fast_exp2(mo - M);
         if (lh == 0) partial[(int64_t)by * partial_stride + row0 + 32 * r + lj] = make_double2((double)M, (double)S);
+        if constexpr (APPLY) {
+            float4 o;
+            o.x = orun[r][0] * fast_exp2(m - M) + __shfl_xor(orun[r][0], 32) * fast_exp2(mo - M);
+            o.y = orun[r][1] * fast_exp2(m - M) + __shfl_xor(orun[r][1], 32) * fast_exp2(mo - M);
+            o.z = orun[r][2] * fast_exp2(m - M) + __shfl_xor(orun[r][2], 32) * fast_exp2(mo - M);
+            o.w = orun[r][3] * fast_exp2(m - M) + __shfl_xor(orun[r][3], 32) * fast_exp2(mo - M);
+            if (lh == 0)
+                *reinterpret_cast<float4 *>(a.opart + ((int64_t)by * partial_stride + row0 + 32 * r + lj) * PC) = o;
+        }
     }
 }
 
@@ -446,6 +537,13 @@ template <int KS, int R, int TJ, int CH, bool PRECISE>
 __global__ __launch_bounds__(kBlock, 2) void k_lse_lowd_split(SplitArgs a)
 {
     lse_split_body<KS, R, TJ, CH, PRECISE>(a, blockIdx.x, blockIdx.y);
+}
+
+// plan application on the split records (PC value columns per launch)
+template <int KS, int R, int TJ, int CH, bool PRECISE, int PC, int PCU>
+__global__ __launch_bounds__(kBlock, 2) void k_apply_lowd_split(SplitArgs a)
+{
+    lse_split_body<KS, R, TJ, CH, PRECISE, PC, PCU>(a, blockIdx.x, blockIdx.y);
 }
 
 // Both half-steps of one iteration of the averaged schedule (Eq. 4-5) in one launch: they read the
@@ -828,13 +926,70 @@ fs_status lowd_lse_pair(Ctx *c, const Prepared *P, double eps, void *partial_x, 
 size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t p)
 {
     (void)p;
-    PassShape s = shape_for(c, n_res, n_str, kBlock);
-    return (size_t)s.splits * (size_t)round_up(n_res, 1024) * kApplyPC * 4;
+    // the larger of the two launch shapes an application can take (split records / vector ALU)
+    const PassShape s1 = shape_for(c, n_res, n_str, kBlock);
+    const PassShape s2 = shape_for(c, n_res, n_str, 128 * kSplitR, kSplitTJ);
+    const int splits = s1.splits > s2.splits ? s1.splits : s2.splits;
+    return (size_t)splits * (size_t)round_up(n_res, 1024) * kApplyPC * 4;
+}
+
+// `cols`: value columns of this launch that exist (1..kApplyPC).  A single column (transport-vector
+// products) has a kernel of its own for the short records: 8.9 against 13.9 ms at n = m = 262144; a
+// three-column variant measured slower than the four-column one (15.9 ms) and is not built.
+template <int KS>
+void launch_apply_split(dim3 grid, hipStream_t st, const SplitArgs &a, int cols)
+{
+    if constexpr (KS <= 3) {
+        if (cols == 1) {
+            hipLaunchKernelGGL((k_apply_lowd_split<KS, kSplitR, kSplitTJ, kSplitCH, false, kApplyPC, 1>), grid, dim3(kBlock), 0, st, a);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((k_apply_lowd_split<KS, kSplitR, kSplitTJ, kSplitCH, false, kApplyPC, kApplyPC>), grid, dim3(kBlock), 0, st, a);
 }
 
 fs_status lowd_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, const float *V,
                      int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out, const float *had_A, int64_t lda)
 {
+    float *opart = (float *)P->extra;
+    // Plain applications run on the split records (scores on the matrix cores, as in the LSE pass);
+    // the Hadamard-weighted form and float64 scores outside the matrix cores' reach stay on the
+    // vector-ALU kernel below.
+    if (!had_A) {
+        SplitArgs a;
+        bool precise = false;
+        fs_status st;
+        if (split_pass_args(c, P, res, str, eps, P->partial, &a, &precise, &st)) {
+            if ((size_t)a.splits * res->cnt_pad * kApplyPC * 4 > P->extra_bytes || !opart)
+                return fail(c, FS_ERR_DEVICE, "internal: low-d apply workspace");
+            a.V = V;
+            a.ldv = ldv;
+            a.n_str = str->cnt;
+            a.p = (int)p;
+            a.opart = opart;
+            const dim3 grid((unsigned)a.row_blocks, (unsigned)a.splits);
+            for (int p0 = 0; p0 < p; p0 += kApplyPC) {
+                a.p0 = p0;
+                const int cols = (int)(p - p0 < kApplyPC ? p - p0 : kApplyPC);
+                if (precise) {
+                    if (cols == 1)
+                        hipLaunchKernelGGL((k_apply_lowd_split<3, kSplitR, kSplitTJ, kSplitCH, true, kApplyPC, 1>), grid,
+                                           dim3(kBlock), 0, c->stream, a);
+                    else
+                        hipLaunchKernelGGL((k_apply_lowd_split<3, kSplitR, kSplitTJ, kSplitCH, true, kApplyPC, kApplyPC>), grid,
+                                           dim3(kBlock), 0, c->stream, a);
+                } else {
+                    FS_SPLIT_KS_DISPATCH(P->ks, (launch_apply_split<KS_>(grid, c->stream, a, cols)));
+                }
+                FS_HIP(c, hipGetLastError());
+                st = launch_apply_finalize(c, P, res, precise ? res->norm : res->norm_f, a.splits, eps, opart, kApplyPC, p0,
+                                           (int)p, out, ldo, mass_out);
+                if (st != FS_OK) return st;
+            }
+            return FS_OK;
+        }
+        if (st != FS_OK) return st;
+    }
     PassShape s = shape_for(c, res->cnt, str->cnt, kBlock);
     const int n_tiles = (int)ceil_div(str->cnt, kTJ);
     const int tps = (int)(s.cols_per_split / kTJ);
@@ -845,7 +1000,6 @@ fs_status lowd_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str
     const double cscale = 2.0 * kLog2e / eps;
     const bool precise = lowd_precise(P, eps);
     dim3 grid((unsigned)s.row_blocks, (unsigned)s.splits);
-    float *opart = (float *)P->extra;
     for (int p0 = 0; p0 < p; p0 += kApplyPC) {
         if (precise) {
             FS_LOWD_DISPATCH((int)P->d, (launch_apply_d<double, DD>(grid, c->stream, res->packed_d, str->packed_d, V, ldv,
