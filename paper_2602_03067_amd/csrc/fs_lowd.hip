@@ -235,7 +235,7 @@ struct SplitArgs {
 template <int KS, int R, int TJ, int CH, bool PRECISE, int PC = 0, int PCU = PC>
 __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx, const int by)
 {
-    // PCU <= PC: value columns actually wanted (the others are neither multiplied nor stored)
+    // PCU <= PC: value columns actually wanted (the others are not multiplied; zeros are stored for them)
     constexpr bool APPLY = PC > 0;
     static_assert(PC == 0 || PC == 4, "one float4 of values per streamed point");
     __shared__ __attribute__((aligned(16))) float vtile[APPLY ? 2 : 1][APPLY ? TJ * PC : 4];
