@@ -255,8 +255,8 @@ fs_status apply_begin(Ctx *c, const fs_problem *prob, float eps, const float *f,
     if ((st = prepare(c, prob, P, extra + tail_bytes, &P->extra)) != FS_OK) return st;
     P->extra_bytes = extra;
     if (tail) *tail = P->extra + extra;
-    if ((st = launch_bias_from_user(c, P, &P->X, f, eps)) != FS_OK) return st;
-    return launch_bias_from_user(c, P, &P->Y, g, eps);
+    if ((st = launch_bias_from_user(c, P, &P->X, f, eps, true, false)) != FS_OK) return st;
+    return launch_bias_from_user(c, P, &P->Y, g, eps, false, true);
 }
 
 fs_status apply_run(Ctx *c, Prepared *P, float eps, bool transposed, const float *V, int64_t p, int64_t ldv, float *out,
@@ -577,8 +577,8 @@ fs_status fs_solve_symmetric(fs_ctx *ctx, const fs_problem *prob, float eps_in, 
     const size_t second = sizing.partial_bytes;
     char *second_partial = nullptr;
     if ((st = prepare(c, prob, &P, second, &second_partial)) != FS_OK) return st;
-    if ((st = launch_bias_from_user(c, &P, &P.X, f, eps)) != FS_OK) return st;
-    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.X, f, eps, true, false)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps, false, true)) != FS_OK) return st;
     void *const first_partial = P.partial;
     for (int t = 0; t < iters; ++t) {
         const bool last = t == iters - 1;
@@ -626,8 +626,8 @@ fs_status fs_marginal_err(fs_ctx *ctx, const fs_problem *prob, float eps, const 
     Prepared P;
     P.force_precise = true;   // a measurement: always the accurate score arithmetic
     if ((st = prepare(c, prob, &P, 0, nullptr)) != FS_OK) return st;
-    if ((st = launch_bias_from_user(c, &P, &P.X, f, eps)) != FS_OK) return st;
-    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.X, f, eps, true, false)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps, false, true)) != FS_OK) return st;
     if ((st = launch_fill_f64(c, P.scalars, 0.0, 8)) != FS_OK) return st;
     int splits = 1;
     if (err_row_l1) {
@@ -658,8 +658,8 @@ fs_status fs_ot_value(fs_ctx *ctx, const fs_problem *prob, float eps, const floa
     const size_t scratch_bytes = (3 * (size_t)ceil_div(prob->n, 256) + 2 * (size_t)ceil_div(prob->m, 256)) * 8;
     char *scratch = nullptr;
     if ((st = prepare(c, prob, &P, scratch_bytes, &scratch)) != FS_OK) return st;
-    if ((st = launch_bias_from_user(c, &P, &P.X, f, eps)) != FS_OK) return st;
-    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.X, f, eps, true, false)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps, false, true)) != FS_OK) return st;
     int splits = 1;
     if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits)) != FS_OK) return st;
     const double *nrm = (P.path == Path::LowD && !lowd_precise(&P, eps)) ? P.X.norm_f : P.X.norm;
@@ -725,8 +725,8 @@ fs_status fs_hvp(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f,
     if ((st = prepare(c, prob, &P, apply_ws + hvp_scratch_bytes(prob->n, prob->m, prob->d), &extra)) != FS_OK) return st;
     P.extra = extra;
     P.extra_bytes = apply_ws;
-    if ((st = launch_bias_from_user(c, &P, &P.X, f, eps)) != FS_OK) return st;
-    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.X, f, eps, true, false)) != FS_OK) return st;
+    if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps, false, true)) != FS_OK) return st;
     int iters = 0;
     st = hvp_run(c, &P, static_cast<const float *>(prob->x), prob->ldx, static_cast<const float *>(prob->y), prob->ldy,
                  (double)eps, A, lda, (double)tau, (double)eta, max_cg, out, ldo, extra + apply_ws, &iters);

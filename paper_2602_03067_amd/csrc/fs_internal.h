@@ -83,7 +83,7 @@ __device__ inline void split3d(double v, __bf16 (&p)[3])   // three bf16 pieces 
 // gy = 2^(Ey-7) with 2^Ey > max |y_k| (from rho_max, the largest squared norm after centring) and
 // gx = 2^(Ex-7) with 2^Ex > (2 log2e/eps) max |x_k|; leading digits are multiples of the grid with
 // at most 8 significant bits.
-inline void split_grids(double rho_max, double eps, double *gx, double *gy)
+__host__ __device__ inline void split_grids(double rho_max, double eps, double *gx, double *gy)
 {
     const double r = sqrt(rho_max > 1e-60 ? rho_max : 1e-60);
     *gy = exp2(floor(log2(r)) + 1.0 - 7.0);
@@ -206,7 +206,11 @@ struct PassShape {
 
 // fs_prep.hip
 fs_status launch_prepare(Ctx *c, const fs_problem *p, Prepared *P);
-fs_status launch_bias_from_user(Ctx *c, Prepared *P, Side *side, const float *pot_user, double eps);
+// `first` / `last`: an entry point that brings in both potentials passes (true, false) and then
+// (false, true); the low-d read-back of the sizes that choose the score arithmetic (largest squared
+// norm, size of the biases) happens once, in the call with last = true.
+fs_status launch_bias_from_user(Ctx *c, Prepared *P, Side *side, const float *pot_user, double eps, bool first = true,
+                                bool last = true);
 // `res_norm` is the norm array matching the coordinates the pass used (Side::norm or norm_f).
 // `mix`: the new potential is (1 - mix) * old + mix * update (1: plain update, 1/2: averaged schedule).
 // `abs_dev_sum` != nullptr measures the marginal deviation instead of storing the update; with

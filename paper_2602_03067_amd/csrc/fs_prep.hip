@@ -56,9 +56,18 @@ __global__ void k_row_norms(const void *pts, int dtype, int64_t rows, int64_t d,
 
 // ---- common mean of both clouds (low-d path), deterministic two-stage reduction ---------
 // stage 1: block b writes the coordinate sums of its slice to part[b][0..15]
-__global__ __launch_bounds__(256) void k_coord_sums(const void *pts, int dtype, int64_t rows, int d, int64_t ld,
-                                                    double *part)
+// (blockIdx.y: 0 = the x cloud, 1 = the y cloud)
+struct CloudIn {
+    const void *pts;
+    int64_t rows, ld;
+    double *part;
+};
+__global__ __launch_bounds__(256) void k_coord_sums(CloudIn c0, CloudIn c1, int dtype, int d)
 {
+    const CloudIn &cl = blockIdx.y ? c1 : c0;
+    const void *pts = cl.pts;
+    const int64_t rows = cl.rows, ld = cl.ld;
+    double *part = cl.part;
     __shared__ double sh[256];
     double acc[kLowdMaxD];
     for (int k = 0; k < kLowdMaxD; ++k) acc[k] = 0.0;
@@ -73,7 +82,7 @@ __global__ __launch_bounds__(256) void k_coord_sums(const void *pts, int dtype, 
 
 // stage 2: mean[k] = (sum of partX[.][k] + sum of partY[.][k]) / (n + m).  One block of 256: thread
 // (group g, coordinate k) sums the blocks b = g mod 16, then coordinate k's 16 group sums are added
-// in a fixed order.  Also clears `zeroed` (the slot the next kernels take a maximum into).
+// in a fixed order.  Also clears zeroed[0..2] (the slots the next kernels take maxima into).
 __global__ __launch_bounds__(256) void k_mean_final(const double *partX, const double *partY, int blocks, double inv_cnt,
                                                     double *mean, double *zeroed)
 {
@@ -89,7 +98,7 @@ __global__ __launch_bounds__(256) void k_mean_final(const double *partX, const d
         for (int q = 0; q < 16; ++q) t += sh[q][threadIdx.x];
         mean[threadIdx.x] = t * inv_cnt;
     }
-    if (threadIdx.x == 0) *zeroed = 0.0;
+    if (threadIdx.x < 3) zeroed[threadIdx.x] = 0.0;
 }
 
 // piece d of a streamed-role split record: the bias in three bf16 pieces, then the three ones
@@ -104,11 +113,25 @@ __device__ inline uint4 split_bias_piece(float bias)
 
 // ---- low-d derived copies: coordinates centred at the common mean, packed with a bias slot;
 //      float (rounded once) and double (exact difference), each with its own squared norms ----
-__global__ void k_prep_lowd(const void *pts, int dtype, int64_t cnt, int64_t cnt_pad, int d, int64_t ld, int dp, int dpd,
-                            const double *mean, float *packed, double *packed_d, double *norm_f, double *norm,
-                            uint16_t *split, int ks, unsigned long long *rho_max_bits)
+// (blockIdx.y: 0 = the x cloud, 1 = the y cloud; a cloud's cnt_pad is a multiple of the block size, so a
+// block is either entirely inside it or leaves as a whole)
+struct PrepLowdSide {
+    const void *pts;
+    int64_t cnt, cnt_pad, ld;
+    float *packed;
+    double *packed_d, *norm_f, *norm;
+    uint16_t *split;
+};
+__global__ __launch_bounds__(256) void k_prep_lowd(PrepLowdSide s0, PrepLowdSide s1, int dtype, int d, int dp, int dpd,
+                                                   const double *mean, int ks, unsigned long long *rho_max_bits)
 {
-    // launched with exactly cnt_pad threads (cnt_pad is a multiple of the block size)
+    const PrepLowdSide &sd = blockIdx.y ? s1 : s0;
+    if ((int64_t)blockIdx.x * 256 >= sd.cnt_pad) return;
+    const void *pts = sd.pts;
+    const int64_t cnt = sd.cnt, ld = sd.ld;
+    float *packed = sd.packed;
+    double *packed_d = sd.packed_d, *norm_f = sd.norm_f, *norm = sd.norm;
+    uint16_t *split = sd.split;
     __shared__ double shmax[256];
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     float *o = packed + i * dp;
@@ -183,10 +206,18 @@ __device__ inline uint2 split_precise_bias_residual(double bias, double q)
     return make_uint2(bf16_pair(rb[0], rb[1]), bf16_pair(rb[2], (__bf16)0.0f));
 }
 
-__global__ void k_prep_split_precise(const double *packed_d, int64_t cnt_pad, int d, int dpd, double gy, uint16_t *out)
+// `rho_max`: device scalar (largest squared norm after centring): the grid comes from it
+// (blockIdx.y: 0 = the x cloud, 1 = the y cloud)
+__global__ void k_prep_split_precise(const double *packed_d0, int64_t cnt_pad0, uint16_t *out0, const double *packed_d1,
+                                     int64_t cnt_pad1, uint16_t *out1, int d, int dpd, const double *rho_max)
 {
+    const double *packed_d = blockIdx.y ? packed_d1 : packed_d0;
+    const int64_t cnt_pad = blockIdx.y ? cnt_pad1 : cnt_pad0;
+    uint16_t *out = blockIdx.y ? out1 : out0;
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= cnt_pad) return;
+    double gx_unused, gy;
+    split_grids(*rho_max, 1.0, &gx_unused, &gy);
     __bf16 Y1[3], ry[3][3];
     for (int k = 0; k < 3; ++k) {
         const double y = k < d ? packed_d[i * dpd + k] : 0.0;
@@ -278,8 +309,10 @@ struct BiasSink {
     float *packed;          // LowD float copy: packed[i*dp + d], shifted by norm_f
     uint16_t *split;        // LowD split records (same value as the float copy), ks > 0
     int ks;
-    uint16_t *split_p;      // LowD precise split records (d <= 3) and the grid of their bias digits
-    double q;
+    uint16_t *split_p;      // LowD precise split records (d <= 3) and the grid of their bias digits:
+    double q;               // q itself, or (q == 0) the device scalar rho_max and the eps it is derived from
+    const double *rho_dev;
+    double q_eps;
     double *packed_d;       // LowD double copy: packed_d[i*dpd + d], shifted by norm
     int dp, dpd, d;
     float *bias_f;          // BF16 path
@@ -300,9 +333,15 @@ __device__ inline void store_bias(const BiasSink &s, int64_t i, double pot, doub
     }
     if (s.packed_d) s.packed_d[i * s.dpd + s.d] = b;
     if (s.split_p) {
+        double q = s.q;
+        if (!(q > 0.0)) {
+            double gx, gy;
+            split_grids(*s.rho_dev, s.q_eps, &gx, &gy);
+            q = gx * gy;
+        }
         uint4 *rec = reinterpret_cast<uint4 *>(s.split_p) + i * 6;
-        rec[1] = split_precise_bias_digits(b, s.q);
-        *reinterpret_cast<uint2 *>(rec + 5) = split_precise_bias_residual(b, s.q);
+        rec[1] = split_precise_bias_digits(b, q);
+        *reinterpret_cast<uint2 *>(rec + 5) = split_precise_bias_residual(b, q);
     }
     if (s.bias_f) s.bias_f[i] = (float)b;
     if (s.bias_d) s.bias_d[i] = b;
@@ -550,14 +589,22 @@ __global__ __launch_bounds__(256) void k_apply_finalize(const double2 *partial, 
 }
 
 // `eps`: the eps of the pass that will stream these biases
-BiasSink sink_of(const Prepared *P, const Side *s, double eps)
+// `rho_on_device`: the host does not know rho_max yet (prologue of an entry call): the kernel
+// derives the grid from the device scalar
+BiasSink sink_of(const Prepared *P, const Side *s, double eps, bool rho_on_device = false)
 {
     BiasSink k{};
     k.split_p = s->split_p;
     if (s->split_p && eps > 0.0) {
-        double gx, gy;
-        split_grids(P->rho_max, eps, &gx, &gy);
-        k.q = gx * gy;
+        if (rho_on_device) {
+            k.q = 0.0;
+            k.rho_dev = P->scalars + 7;
+            k.q_eps = eps;
+        } else {
+            double gx, gy;
+            split_grids(P->rho_max, eps, &gx, &gy);
+            k.q = gx * gy;
+        }
     } else {
         k.split_p = nullptr;
     }
@@ -670,28 +717,26 @@ fs_status launch_prepare(Ctx *c, const fs_problem *p, Prepared *P)
         const int half = 128;
         double *partX = P->mean + kLowdMaxD;
         double *partY = partX + (size_t)half * kLowdMaxD;
-        hipLaunchKernelGGL(k_coord_sums, dim3(half), dim3(256), 0, c->stream, p->x, dtype, p->n, (int)p->d, p->ldx,
-                           partX);
-        hipLaunchKernelGGL(k_coord_sums, dim3(half), dim3(256), 0, c->stream, p->y, dtype, p->m, (int)p->d, p->ldy,
-                           partY);
+        const CloudIn cx{p->x, p->n, p->ldx, partX}, cy{p->y, p->m, p->ldy, partY};
+        hipLaunchKernelGGL(k_coord_sums, dim3(half, 2), dim3(256), 0, c->stream, cx, cy, dtype, (int)p->d);
+        // (also clears scalars[5..7]: the sizes of the biases and the largest squared norm, all taken by atomic maxima)
         hipLaunchKernelGGL(k_mean_final, dim3(1), dim3(256), 0, c->stream, partX, partY, half,
-                           1.0 / (double)(p->n + p->m), P->mean, P->scalars + 7);
-        for (auto &s : in)
-            hipLaunchKernelGGL(k_prep_lowd, dim3((unsigned)ceil_div(s.S->cnt_pad, 256)), dim3(256), 0, c->stream, s.pts,
-                               dtype, s.S->cnt, s.S->cnt_pad, (int)p->d, s.ld, P->dp, P->dpd, P->mean, s.S->packed,
-                               s.S->packed_d, s.S->norm_f, s.S->norm, s.S->split, P->ks,
-                               reinterpret_cast<unsigned long long *>(P->scalars + 7));
-        FS_HIP(c, hipGetLastError());
-        // the host chooses the score precision of each half-step from this number
-        FS_HIP(c, hipMemcpyAsync(&P->rho_max, P->scalars + 7, sizeof(double), hipMemcpyDeviceToHost, c->stream));
-        FS_HIP(c, hipStreamSynchronize(c->stream));
-        if (p->d <= 3) {   // the grid of the precise records' leading digits depends on rho_max
-            double gx, gy;
-            split_grids(P->rho_max, 1.0, &gx, &gy);
-            for (auto &s : in)
-                hipLaunchKernelGGL(k_prep_split_precise, dim3((unsigned)ceil_div(s.S->cnt_pad, 256)), dim3(256), 0,
-                                   c->stream, s.S->packed_d, s.S->cnt_pad, (int)p->d, P->dpd, gy, s.S->split_p);
+                           1.0 / (double)(p->n + p->m), P->mean, P->scalars + 5);
+        const int64_t pad_max = P->X.cnt_pad > P->Y.cnt_pad ? P->X.cnt_pad : P->Y.cnt_pad;
+        PrepLowdSide sd[2];
+        for (int k = 0; k < 2; ++k) {
+            const Side *S = in[k].S;
+            sd[k] = PrepLowdSide{in[k].pts, S->cnt, S->cnt_pad, in[k].ld, S->packed, S->packed_d, S->norm_f, S->norm, S->split};
         }
+        hipLaunchKernelGGL(k_prep_lowd, dim3((unsigned)ceil_div(pad_max, 256), 2), dim3(256), 0, c->stream, sd[0], sd[1], dtype,
+                           (int)p->d, P->dp, P->dpd, P->mean, P->ks, reinterpret_cast<unsigned long long *>(P->scalars + 7));
+        // (the host reads rho_max back together with the sizes of the biases, see launch_bias_from_user)
+        P->rho_max = -1.0;
+        if (p->d <= 3)   // the grid of the precise records' leading digits depends on rho_max
+            hipLaunchKernelGGL(k_prep_split_precise, dim3((unsigned)ceil_div(pad_max, 256), 2), dim3(256), 0, c->stream,
+                               P->X.packed_d, P->X.cnt_pad, P->X.split_p, P->Y.packed_d, P->Y.cnt_pad, P->Y.split_p, (int)p->d,
+                               P->dpd, P->scalars + 7);
+        FS_HIP(c, hipGetLastError());
     } else if (P->path == Path::F64) {
         for (auto &s : in)
             hipLaunchKernelGGL(k_prep_f64, dim3((unsigned)ceil_div(s.S->cnt_pad, 4)), dim3(256), 0, c->stream, s.pts,
@@ -705,25 +750,30 @@ fs_status launch_prepare(Ctx *c, const fs_problem *p, Prepared *P)
     return FS_OK;
 }
 
-fs_status launch_bias_from_user(Ctx *c, Prepared *P, Side *side, const float *pot_user, double eps)
+fs_status launch_bias_from_user(Ctx *c, Prepared *P, Side *side, const float *pot_user, double eps, bool first, bool last)
 {
     // low-d problems: the size of the bias enters the choice of the score precision (lowd_precise),
-    // so it is measured where a caller's potential comes in (one 8-byte read-back per entry call)
+    // so it is measured where a caller's potential comes in; it is read back together with the
+    // largest squared norm, once per entry call (three doubles)
     unsigned long long *absmax = nullptr;
     if (P->path == Path::LowD) {
         absmax = reinterpret_cast<unsigned long long *>(P->scalars + 5);   // scalars[5], [6]
-        fs_status st = launch_fill_f64(c, P->scalars + 5, 0.0, 2);
-        if (st != FS_OK) return st;
+        if (first && !(P->rho_max < 0.0)) {   // (a fresh prologue has cleared them already)
+            fs_status st = launch_fill_f64(c, P->scalars + 5, 0.0, 2);
+            if (st != FS_OK) return st;
+        }
     }
     hipLaunchKernelGGL(k_bias_from_user, dim3((unsigned)ceil_div(side->cnt, 256)), dim3(256), 0, c->stream, pot_user,
-                       side->cnt, 1.0 / eps, side->w, side->log_uniform, side->pot, sink_of(P, side, eps), absmax);
+                       side->cnt, 1.0 / eps, side->w, side->log_uniform, side->pot, sink_of(P, side, eps, P->rho_max < 0.0),
+                       absmax);
     FS_HIP(c, hipGetLastError());
-    if (absmax) {
-        double mag[2] = {0.0, 0.0};
-        FS_HIP(c, hipMemcpyAsync(mag, P->scalars + 5, 2 * sizeof(double), hipMemcpyDeviceToHost, c->stream));
+    if (absmax && last) {
+        double h[3] = {0.0, 0.0, 0.0};   // |log w| part, potential part, rho_max
+        FS_HIP(c, hipMemcpyAsync(h, P->scalars + 5, sizeof h, hipMemcpyDeviceToHost, c->stream));
         FS_HIP(c, hipStreamSynchronize(c->stream));
-        if (mag[0] > P->logw_mag) P->logw_mag = mag[0];
-        if (mag[1] * eps > P->pot_mag_eps) P->pot_mag_eps = mag[1] * eps;
+        if (h[0] > P->logw_mag) P->logw_mag = h[0];
+        if (h[1] * eps > P->pot_mag_eps) P->pot_mag_eps = h[1] * eps;
+        P->rho_max = h[2];
     }
     return FS_OK;
 }
