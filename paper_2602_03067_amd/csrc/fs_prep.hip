@@ -483,6 +483,20 @@ __global__ __launch_bounds__(256) void k_sum_to(const double *part, int64_t cnt,
     if (threadIdx.x == 0) *dst = t;
 }
 
+// the five sums of the dual objective's terms in one launch: block k < 3 sums pr[k][0..br), block 3 + k
+// sums ps[k][0..bs), each in a fixed order
+__global__ __launch_bounds__(256) void k_sum_value_terms(const double *pr, int64_t br, const double *ps, int64_t bs, double *dst)
+{
+    __shared__ double sh[256];
+    const int k = blockIdx.x;
+    const double *part = k < 3 ? pr + (int64_t)k * br : ps + (int64_t)(k - 3) * bs;
+    const int64_t cnt = k < 3 ? br : bs;
+    double acc = 0.0;
+    for (int64_t i = threadIdx.x; i < cnt; i += 256) acc += part[i];
+    const double t = block_sum_256(acc, sh);
+    if (threadIdx.x == 0) dst[k] = t;
+}
+
 // ---- terms of the dual objective (App. B) -------------------------------------------------
 // After an LSE pass over `res`: mass_i = w_i exp((pot_i - pot_i^+)/eps) is the row sum of the plan
 // that the CURRENT potentials induce (Prop. 3).  Block sums of mass_i, w_i pot_i and w_i go to
@@ -837,10 +851,7 @@ fs_status launch_value_terms(Ctx *c, const Prepared *P, const Side *res, const d
     hipLaunchKernelGGL(k_value_terms, dim3(br), dim3(256), 0, c->stream, (const double2 *)P->partial, res->cnt_pad, splits,
                        res->cnt, eps, res->w, res->log_uniform, res_norm, res->pot, pr);
     hipLaunchKernelGGL(k_weighted_sums, dim3(bs), dim3(256), 0, c->stream, str->cnt, str->w, str->log_uniform, str->pot, ps);
-    for (int k = 0; k < 3; ++k)
-        hipLaunchKernelGGL(k_sum_to, dim3(1), dim3(256), 0, c->stream, pr + (size_t)k * br, (int64_t)br, dst + k);
-    for (int k = 0; k < 2; ++k)
-        hipLaunchKernelGGL(k_sum_to, dim3(1), dim3(256), 0, c->stream, ps + (size_t)k * bs, (int64_t)bs, dst + 3 + k);
+    hipLaunchKernelGGL(k_sum_value_terms, dim3(5), dim3(256), 0, c->stream, pr, (int64_t)br, ps, (int64_t)bs, dst);
     FS_HIP(c, hipGetLastError());
     return FS_OK;
 }
