@@ -195,6 +195,19 @@ fs_status fs_ot_value(fs_ctx *ctx, const fs_problem *prob, float eps, const floa
                       const float *g /* device */, double *value /* host */);
 
 /*
+ * Debiased Sinkhorn divergence  S = OT(a,b) - OT(a,a)/2 - OT(b,b)/2  (Section 4.2 uses it as the
+ * loss of the downstream tasks): each term is the dual value (fs_ot_value) after `iters`
+ * alternating iterations from zero potentials at eps -- three fs_solve + fs_ot_value runs inside
+ * the library.  f (n floats), g (m floats), device: receive the potentials of the cross term.
+ * value: HOST double; terms: NULL or three HOST doubles receiving OT(a,b), OT(a,a), OT(b,b).
+ * Synchronises the stream.  The potentials of the self terms live in a second, grow-only buffer
+ * of the context (2 max(n, m) floats).
+ */
+fs_status fs_divergence(fs_ctx *ctx, const fs_problem *prob, float eps, int32_t iters,
+                        float *f /* device */, float *g /* device */, double *value /* host */,
+                        double *terms /* host, nullable */);
+
+/*
  * out = P V with P_ij = a_i b_j exp((f_i + g_j - C_ij)/eps) for ANY potentials
  * (Prop. 3, Alg. 2): one streaming pass, P never stored.
  * V: m x p (ldv), out: n x p (ldo), r_out: NULL or n floats receiving P 1_m.

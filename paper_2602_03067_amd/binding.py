@@ -21,7 +21,7 @@ FS_COMPUTE_FP32, FS_COMPUTE_BF16_MFMA = 0, 1
 
 EXPORTS = (
     "fs_create", "fs_destroy", "fs_status_str", "fs_last_error", "fs_version", "fs_row_norms",
-    "fs_update_f", "fs_update_g", "fs_solve", "fs_solve_symmetric", "fs_solve_tol", "fs_marginal_err", "fs_ot_value", "fs_apply_plan",
+    "fs_update_f", "fs_update_g", "fs_solve", "fs_solve_symmetric", "fs_solve_tol", "fs_marginal_err", "fs_ot_value", "fs_divergence", "fs_apply_plan",
     "fs_apply_plan_T", "fs_grad_x", "fs_grad_y", "fs_hvp", "fs_profile_enable", "fs_profile_read",
 )
 
@@ -74,6 +74,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fs_solve_tol.argtypes = [vp, PP, f32, i32, i32, f32, vp, vp, ctypes.POINTER(i32), ctypes.POINTER(f32)]
     lib.fs_marginal_err.argtypes = [vp, PP, f32, vp, vp, ctypes.POINTER(f32), ctypes.POINTER(f32)]
     lib.fs_ot_value.argtypes = [vp, PP, f32, vp, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.fs_divergence.argtypes = [vp, PP, f32, i32, vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.fs_apply_plan.argtypes = [vp, PP, f32, vp, vp, vp, i64, i64, vp, i64, vp]
     lib.fs_apply_plan_T.argtypes = [vp, PP, f32, vp, vp, vp, i64, i64, vp, i64, vp]
     lib.fs_grad_x.argtypes = [vp, PP, f32, vp, vp, i32, vp, i64]
@@ -208,6 +209,16 @@ class Context:
         self._check(self.lib.fs_ot_value(self.h, ctypes.byref(prob.c), eps, _ptr(f), _ptr(g), ctypes.byref(v)),
                     "fs_ot_value")
         return v.value
+
+    def fs_divergence(self, prob: Problem, eps: float, iters: int):
+        """Debiased Sinkhorn divergence; returns (value, (OT(a,b), OT(a,a), OT(b,b)), f, g)."""
+        f = torch.empty(prob.n, dtype=torch.float32, device=prob.x.device)
+        g = torch.empty(prob.m, dtype=torch.float32, device=prob.x.device)
+        v = ctypes.c_double()
+        t = (ctypes.c_double * 3)()
+        self._check(self.lib.fs_divergence(self.h, ctypes.byref(prob.c), eps, int(iters), _ptr(f), _ptr(g), ctypes.byref(v), t),
+                    "fs_divergence")
+        return v.value, (t[0], t[1], t[2]), f, g
 
     def fs_solve_symmetric(self, prob: Problem, eps: float, iters: int, f: torch.Tensor,
                            g: torch.Tensor) -> None:

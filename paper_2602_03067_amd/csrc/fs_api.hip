@@ -397,6 +397,7 @@ fs_status fs_destroy(fs_ctx *ctx)
         (void)hipStreamSynchronize(c->stream);
         for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
         if (c->ws) (void)hipFree(c->ws);
+        if (c->aux) (void)hipFree(c->aux);
     }
     delete c;
     return FS_OK;
@@ -671,6 +672,72 @@ fs_status fs_ot_value(fs_ctx *ctx, const fs_problem *prob, float eps, const floa
     FS_HIP(c, hipStreamSynchronize(c->stream));
     // App. B: <a,f> + <b,g> - eps (sum_ij P_ij - sum_ij a_i b_j)
     *value = h[1] + h[3] - (double)eps * (h[0] - h[2] * h[4]);
+    return FS_OK;
+}
+
+fs_status fs_divergence(fs_ctx *ctx, const fs_problem *prob, float eps, int32_t iters, float *f, float *g, double *value,
+                        double *terms)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    fs_status st = validate_problem(c, prob);
+    if (st != FS_OK) return st;
+    if ((st = validate_eps(c, eps)) != FS_OK) return st;
+    if (iters < 1) return fail(c, FS_ERR_BAD_EPS, "need iters >= 1");
+    if (!value) return fail(c, FS_ERR_INVALID_ARG, "value is NULL");
+    if ((st = check_out(c, prob, f, (size_t)prob->n * 4, "f")) != FS_OK) return st;
+    if ((st = check_out(c, prob, g, (size_t)prob->m * 4, "g")) != FS_OK) return st;
+    if (overlap(f, (size_t)prob->n * 4, g, (size_t)prob->m * 4)) return fail(c, FS_ERR_INVALID_ARG, "f overlaps g");
+    if (c->device < 0) return fail(c, FS_ERR_DEVICE, "host-only context: arguments are valid, nothing was launched");
+    FS_HIP(c, hipSetDevice(c->device));
+    // potentials of the two self-terms: the entry points called below lay the workspace out anew, so
+    // these live in a buffer of their own
+    const int64_t big = prob->n > prob->m ? prob->n : prob->m;
+    const size_t need = (size_t)2 * big * sizeof(float);
+    if (need > c->aux_bytes) {
+        FS_HIP(c, hipStreamSynchronize(c->stream));
+        if (c->aux) {
+            FS_HIP(c, hipFree(c->aux));
+            c->aux = nullptr;
+            c->aux_bytes = 0;
+        }
+        void *pnew = nullptr;
+        hipError_t e = hipMalloc(&pnew, need);
+        if (e != hipSuccess) return fail(c, FS_ERR_ALLOC, "buffer of %zu bytes: %s", need, hipGetErrorString(e));
+        c->aux = (char *)pnew;
+        c->aux_bytes = need;
+    }
+    float *sf = reinterpret_cast<float *>(c->aux), *sg = sf + big;
+    double v[3] = {0.0, 0.0, 0.0};
+    // cross term: OT(a, b)
+    FS_HIP(c, hipMemsetAsync(f, 0, (size_t)prob->n * 4, c->stream));
+    FS_HIP(c, hipMemsetAsync(g, 0, (size_t)prob->m * 4, c->stream));
+    if ((st = fs_solve(ctx, prob, eps, eps, 1, iters, f, g)) != FS_OK) return st;
+    if ((st = fs_ot_value(ctx, prob, eps, f, g, &v[0])) != FS_OK) return st;
+    // self terms: OT(a, a) and OT(b, b)
+    for (int k = 0; k < 2; ++k) {
+        fs_problem self = *prob;
+        if (k == 0) {
+            self.y = prob->x;
+            self.m = prob->n;
+            self.ldy = prob->ldx;
+            self.b = prob->a;
+        } else {
+            self.x = prob->y;
+            self.n = prob->m;
+            self.ldx = prob->ldy;
+            self.a = prob->b;
+        }
+        FS_HIP(c, hipMemsetAsync(sf, 0, (size_t)self.n * 4, c->stream));
+        FS_HIP(c, hipMemsetAsync(sg, 0, (size_t)self.m * 4, c->stream));
+        if ((st = fs_solve(ctx, &self, eps, eps, 1, iters, sf, sg)) != FS_OK) return st;
+        if ((st = fs_ot_value(ctx, &self, eps, sf, sg, &v[1 + k])) != FS_OK) return st;
+    }
+    *value = v[0] - 0.5 * v[1] - 0.5 * v[2];
+    if (terms) {
+        terms[0] = v[0];
+        terms[1] = v[1];
+        terms[2] = v[2];
+    }
     return FS_OK;
 }
 

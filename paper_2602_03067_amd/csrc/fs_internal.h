@@ -106,6 +106,9 @@ struct Ctx {
     // grow-only device workspace
     char *ws = nullptr;
     size_t ws_bytes = 0;
+    // grow-only second buffer for entry points that call other entry points (which lay the workspace out anew)
+    char *aux = nullptr;
+    size_t aux_bytes = 0;
     std::string err;
     // profiling of the streaming LSE launches
     bool prof_on = false;

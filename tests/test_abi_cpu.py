@@ -150,6 +150,19 @@ def test_grad_validation(lib, hctx):
     assert lib.fs_grad_y(*args(2, 5)) == 7
 
 
+def test_divergence_validation(lib, hctx):
+    p = _prob()
+    v = ctypes.c_double()
+    args = lambda iters, f=1 << 21, g=1 << 22, val=ctypes.byref(v): (hctx, ctypes.byref(p), F(0.1), iters, P(f) if f else None,
+                                                                     P(g) if g else None, val, None)
+    assert lib.fs_divergence(*args(0)) == 3                        # needs at least one iteration
+    assert lib.fs_divergence(*args(5, val=None)) == 1
+    assert lib.fs_divergence(*args(5, f=None)) == 1
+    assert lib.fs_divergence(*args(5, g=(1 << 21) + 8)) == 1       # g on top of f
+    assert lib.fs_divergence(*args(5, f=4096)) == 1                # f on top of x
+    assert lib.fs_divergence(*args(5)) == 7                        # valid: reaches device stage
+
+
 def test_row_norms_validation(lib, hctx):
     assert lib.fs_row_norms(hctx, None, 0, 4, 3, 3, P(1 << 20)) == 1
     assert lib.fs_row_norms(hctx, P(4096), 0, 0, 3, 3, P(1 << 20)) == 2

@@ -92,3 +92,29 @@ def test_debiased_divergence_from_three_solves(ctx, oracle):
     say("  divergence gpu=%.8f oracle=%.8f" % (total_gpu, total_ref))
     assert total_gpu > 0.0
     assert abs(total_gpu - total_ref) <= 2e-5 * (abs(total_ref) + eps)
+
+
+@pytest.mark.parametrize("n,m,d,eps,iters", [(350, 290, 3, 0.2, 40), (180, 410, 24, 0.5, 15)])
+def test_divergence_entry_point(ctx, oracle, n, m, d, eps, iters):
+    """fs_divergence against the oracle's three solves and dual values; called twice, the second time on
+    a smaller problem, so that the buffer kept between calls is exercised."""
+    rng = np.random.default_rng(5 * n + d)
+    eps = float(np.float32(eps))
+    for (nn, mm) in ((n, m), (n // 2 + 1, m // 3 + 2)):
+        x, y, a, b = _problem(rng, nn, mm, d, 1.0 if d <= 16 else 0.4)
+        say("fs_divergence n=%d m=%d d=%d eps=%g iters=%d" % (nn, mm, d, eps, iters))
+        ref_terms = []
+        for (p, q, wp, wq) in ((x, y, a, b), (x, x, a, a), (y, y, b, b)):
+            fo, go = oracle.solve(p, q, wp, wq, eps, eps, 1, iters)
+            ref_terms.append(oracle.objectives(p, q, wp, wq, eps, fo, go)[1])
+            if p is x and q is y:
+                f_ref, g_ref = fo, go
+        ref = ref_terms[0] - 0.5 * ref_terms[1] - 0.5 * ref_terms[2]
+        value, terms, f, g = ctx.fs_divergence(make_problem(x, y, a, b), eps, iters)
+        say("  gpu=%.8f oracle=%.8f terms gpu=%s" % (value, ref, ["%.6f" % t for t in terms]))
+        assert max_err_over_eps(host(f), f_ref, eps) <= 1e-4 and max_err_over_eps(host(g), g_ref, eps) <= 1e-4
+        for t, r in zip(terms, ref_terms):
+            assert abs(t - r) <= 2e-5 * (abs(r) + eps)
+        assert value == terms[0] - 0.5 * terms[1] - 0.5 * terms[2]
+        assert value > 0.0
+        assert abs(value - ref) <= 4e-5 * (max(abs(r) for r in ref_terms) + eps)
