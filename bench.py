@@ -28,7 +28,7 @@ PEAKS = {"bf16": 2.5e15, "f64": 78.6e12}
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this script on the default size of each workload, scaled by what the same counters read for a
 # 1 GiB device copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); the summaries are under profiles/.
-MEASURED_TRAFFIC = {"lowdim_anneal": 191.85e6, "mnist_shape": 16260.33e6, "embedding": 4384.09e6,
+MEASURED_TRAFFIC = {"lowdim_anneal": 191.85e6, "mnist_shape": 16258.16e6, "embedding": 4384.08e6,
                     "transport_grad": 77.18e6}
 
 
