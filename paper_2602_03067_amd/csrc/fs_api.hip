@@ -148,7 +148,7 @@ size_t layout(const Ctx *c, const fs_problem *p, Prepared *P, char *base, size_t
             S.split_p = (base && p->d <= 3) ? (uint16_t *)(base + o) : nullptr;
             break;
         case Path::F64:
-            P->kp = (int)round_up(p->d, 4);
+            P->kp = (int)round_up(p->d, 32);
             o = A.take((size_t)S.cnt_pad * P->kp * 8);
             S.pts_d = base ? (double *)(base + o) : nullptr;
             o = A.take((size_t)S.cnt_pad * 8);

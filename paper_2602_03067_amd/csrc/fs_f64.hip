@@ -24,13 +24,17 @@ namespace fs {
 namespace {
 
 typedef double d4 __attribute__((ext_vector_type(4)));
+typedef double d2 __attribute__((ext_vector_type(2)));   // staging registers: a plain vector type, so that they stay registers
 
-constexpr int IT = 1;      // 16-point streamed blocks per wave (two were slower: 0.77 vs 0.72 ms at d = 64)
-constexpr int BC = 64 * IT;   // streamed points per tile
+constexpr int BC = 64;      // streamed points per tile: one 16-point block per wave (two per wave were slower)
 constexpr int KC = 32;     // contraction chunk staged for the streamed points
 constexpr int KRES = 64;   // resident coordinates kept in LDS across the pass
-constexpr int LDR = KRES + 1;   // odd leading dimensions: conflict-free 8-byte column reads
-constexpr int LDS_ = KC + 1;
+// leading dimensions = 2 (mod 32) doubles: the 32 lanes of a half-wave (16 points x 2 adjacent
+// coordinates) then read 32 different 8-byte bank pairs, and rows stay 16-byte aligned for the
+// 128-bit stores of the staging
+constexpr int LDR = KRES + 2;
+constexpr int LDS_ = KC + 2;
+constexpr int kReadAhead = 8;   // the operand reads run one contraction step ahead of the MFMAs: slack behind the arrays
 constexpr int PCH = 64;    // value columns per application pass
 
 __device__ inline float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
@@ -39,7 +43,8 @@ struct PassArgs {
     const double *res;       // [res_pad][kp]
     const double *str;       // [str_pad][kp]
     const double *bias;      // [str_pad], base-2 bias of the streamed points (-inf on padding)
-    int kp;
+    int kp;                  // row stride of res / str: coordinates rounded up to KC, zero filled
+    int kc;                  // contraction length: coordinates rounded up to 8
     double cscale;           // 2 log2(e) / eps
     int tiles_per_split, n_tiles;
     double2 *partial;        // [splits][partial_stride] (max, sum)
@@ -67,32 +72,36 @@ template <bool APPLY, bool HAD = false, int NCT = 4, int JT = 4>
 __global__ __launch_bounds__(256, (APPLY && JT == 4) ? 1 : 2) void k_pass_f64(PassArgs a)
 {
     constexpr int BR = 16 * JT;   // resident rows per workgroup
-    __shared__ double res_lds[BR * LDR];          // 33,280 B; reused for the final merge
-    __shared__ double str_lds[BC * LDS_];         // 16,896 B
-    __shared__ double bias_lds[BC];
+    // Two buffers for the streamed chunk: the next stage is stored while other waves may still be
+    // reading the current one, which leaves one barrier per stage.  The Hadamard variant keeps one
+    // buffer (and a second barrier) so that two workgroups still fit in a CU's LDS.
+    constexpr int NSB = HAD ? 1 : 2;
+    constexpr int kStrBuf = BC * LDS_;
+    __shared__ __attribute__((aligned(16))) double res_lds[BR * LDR + kReadAhead];   // 33.8 KB (JT = 4); reused for the final merge
+    __shared__ __attribute__((aligned(16))) double str_lds[NSB * kStrBuf + kReadAhead];  // 17.4 KB per buffer
+    __shared__ double bias_lds[3][BC];            // by tile number mod 3 (a tile's epilogue may run after the next stage is stored)
     __shared__ float vt[APPLY ? BC * PCH : 1];    // 16,384 B (application)
-    __shared__ double had_lds[HAD ? BR * LDR : 1];  // 33,280 B: rows of hadA, laid out like res_lds
+    __shared__ __attribute__((aligned(16))) double had_lds[HAD ? BR * LDR + kReadAhead : 1];  // rows of hadA, laid out like res_lds
     __shared__ float mw[4][BR];                   // per-wave running max (final merge)
     __shared__ float sred[BR][17];                // per-(wave, lane group) sums (final merge)
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, l = tid & 63, lg = l >> 4, lj = l & 15;
-    const int kp = a.kp;
+    const int kld = a.kp;         // row stride of the records: a multiple of KC, zero beyond the coordinates
+    const int kc = a.kc;          // contraction length: coordinates rounded up to 8
     const int64_t row0 = (int64_t)blockIdx.x * BR;
-    const bool res_cached = kp <= KRES;
-    const int n_chunks = (kp + KC - 1) / KC;
+    const bool res_cached = kc <= KRES;
+    const int n_chunks = (kc + KC - 1) / KC;
 
     if (res_cached) {
-        const int per_row = kp >> 1;   // double2 per row
+        const int per_row = kc >> 1;   // double2 per row
         for (int e = tid; e < BR * per_row; e += 256) {
             int r = e / per_row, kk = (e - r * per_row) * 2;
-            double2 v = *reinterpret_cast<const double2 *>(a.res + (row0 + r) * kp + kk);
-            res_lds[r * LDR + kk] = v.x;
-            res_lds[r * LDR + kk + 1] = v.y;
+            *reinterpret_cast<d2 *>(res_lds + r * LDR + kk) = *reinterpret_cast<const d2 *>(a.res + (row0 + r) * kld + kk);
         }
         if constexpr (HAD) {
-            for (int e = tid; e < BR * kp; e += 256) {
-                int r = e / kp, kk = e - r * kp;
+            for (int e = tid; e < BR * kc; e += 256) {
+                int r = e / kc, kk = e - r * kc;
                 had_lds[r * LDR + kk] = (row0 + r < a.n_res && kk < a.d) ? (double)a.hadA[(row0 + r) * a.lda + kk] : 0.0;
             }
         }
@@ -117,29 +126,30 @@ __global__ __launch_bounds__(256, (APPLY && JT == 4) ? 1 : 2) void k_pass_f64(Pa
 
     // Staging of one (tile, chunk) stage goes through registers: its global loads are issued
     // before the MFMAs of the previous stage and stored to LDS after them, so the memory latency
-    // is covered by matrix work.
-    double2 pre_s[4 * IT], pre_r[JT], pre_a[HAD ? JT : 1];
+    // is covered by matrix work.  Addresses are a uniform base plus a per-thread offset that never
+    // changes: thread (point tid / 16 of every group of 16 points, coordinates 2 (tid % 16) ..+1).
+    d2 pre_s[4], pre_r[JT], pre_a[HAD ? JT : 1];
     double pre_b = 0.0;
     // value rows of the tile go through registers too, except in the Hadamard variant, which has
     // no registers to spare and loads them between the barriers instead
     constexpr bool VPRE = APPLY && !HAD;
     float pre_v[VPRE ? BC * PCH / 256 : 1];
-    auto fetch = [&](int t, int ch) {
+    const int sp = tid >> 4, sk = (tid & 15) * 2;
+    const int toff = sp * kld + sk;
+    auto fetch = [&](int t, int ch) __attribute__((always_inline)) {
         const int64_t col0 = (int64_t)t * BC;
         const int kc0 = ch * KC;
-        const int kw = min(KC, kp - kc0);
+        const double *gs = a.str + col0 * kld + kc0;
 #pragma unroll
-        for (int q = 0; q < 4 * IT; ++q) {
-            const int e = tid + 256 * q;
-            const int cidx = e >> 4, kk = (e & 15) * 2;
-            pre_s[q] = make_double2(0.0, 0.0);   // zero beyond kp
-            if (kk < kw) pre_s[q] = *reinterpret_cast<const double2 *>(a.str + (col0 + cidx) * kp + kc0 + kk);
-            if (!res_cached && q < JT) {
-                pre_r[q] = make_double2(0.0, 0.0);
-                if (kk < kw) pre_r[q] = *reinterpret_cast<const double2 *>(a.res + (row0 + cidx) * kp + kc0 + kk);
+        for (int q = 0; q < 4; ++q) pre_s[q] = *reinterpret_cast<const d2 *>(gs + (int64_t)(16 * q) * kld + toff);
+        if (!res_cached) {
+            const double *gr = a.res + row0 * kld + kc0;
+#pragma unroll
+            for (int q = 0; q < JT; ++q) {
+                pre_r[q] = *reinterpret_cast<const d2 *>(gr + (int64_t)(16 * q) * kld + toff);
                 if constexpr (HAD) {
-                    const int64_t rr = row0 + cidx;
-                    const int k0 = kc0 + kk;
+                    const int64_t rr = row0 + 16 * q + sp;
+                    const int k0 = kc0 + sk;
                     pre_a[q].x = (rr < a.n_res && k0 < a.d) ? (double)a.hadA[rr * a.lda + k0] : 0.0;
                     pre_a[q].y = (rr < a.n_res && k0 + 1 < a.d) ? (double)a.hadA[rr * a.lda + k0 + 1] : 0.0;
                 }
@@ -158,23 +168,20 @@ __global__ __launch_bounds__(256, (APPLY && JT == 4) ? 1 : 2) void k_pass_f64(Pa
             }
         }
     };
-    auto stash = [&](int ch, int t_cur) {
+    // store the fetched stage: streamed chunk into buffer `buf`, the resident chunk (when it is not
+    // cached) into columns [32 buf, 32 buf + 32) of its rows, bias and values of a tile's first stage
+    auto stash = [&](int buf, int t_st, int ch, int tile_mod3) __attribute__((always_inline)) {
+        double *sd = str_lds + buf * kStrBuf + sp * LDS_ + sk;
 #pragma unroll
-        for (int q = 0; q < 4 * IT; ++q) {
-            const int e = tid + 256 * q;
-            const int cidx = e >> 4, kk = (e & 15) * 2;
-            str_lds[cidx * LDS_ + kk] = pre_s[q].x;
-            str_lds[cidx * LDS_ + kk + 1] = pre_s[q].y;
-            if (!res_cached && q < JT) {
-                res_lds[cidx * LDR + kk] = pre_r[q].x;
-                res_lds[cidx * LDR + kk + 1] = pre_r[q].y;
-                if constexpr (HAD) {
-                    had_lds[cidx * LDR + kk] = pre_a[q].x;
-                    had_lds[cidx * LDR + kk + 1] = pre_a[q].y;
-                }
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<d2 *>(sd + 16 * q * LDS_) = pre_s[q];
+        if (!res_cached) {
+#pragma unroll
+            for (int q = 0; q < JT; ++q) {
+                *reinterpret_cast<d2 *>(res_lds + (16 * q + sp) * LDR + KC * buf + sk) = pre_r[q];
+                if constexpr (HAD) *reinterpret_cast<d2 *>(had_lds + (16 * q + sp) * LDR + KC * buf + sk) = pre_a[q];
             }
         }
-        if (ch == 0 && tid < BC) bias_lds[tid] = pre_b;
+        if (ch == 0 && tid < BC) bias_lds[tile_mod3][tid] = pre_b;
         if constexpr (VPRE) {
             if (ch == 0) {
 #pragma unroll
@@ -182,7 +189,7 @@ __global__ __launch_bounds__(256, (APPLY && JT == 4) ? 1 : 2) void k_pass_f64(Pa
             }
         } else if constexpr (APPLY) {
             if (ch == 0) {
-                const int64_t col0 = (int64_t)t_cur * BC;
+                const int64_t col0 = (int64_t)t_st * BC;
                 for (int e = tid; e < BC * PCH; e += 256) {
                     const int cidx = e >> 6, cc = e & 63;
                     const int64_t j = col0 + cidx;
@@ -191,155 +198,196 @@ __global__ __launch_bounds__(256, (APPLY && JT == 4) ? 1 : 2) void k_pass_f64(Pa
             }
         }
     };
-    if (t_begin < t_end) fetch(t_begin, 0);
 
-    for (int t = t_begin; t < t_end; ++t) {
-        const int64_t col0 = (int64_t)t * BC;
-        d4 acc[IT][JT];
-        d4 accW[HAD ? IT : 1][HAD ? JT : 1];   // <hadA row, streamed point> (Hadamard weights)
+    d4 acc[JT];
+    d4 accW[HAD ? JT : 1];   // <hadA row, streamed point> (Hadamard weights)
+    auto zero_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int it = 0; it < IT; ++it)
+        for (int jt = 0; jt < JT; ++jt) {
+            acc[jt] = d4{0.0, 0.0, 0.0, 0.0};
+            if constexpr (HAD) accW[jt] = d4{0.0, 0.0, 0.0, 0.0};
+        }
+    };
+
+    // ---- tile epilogue: scores of this lane = cscale * acc + bias of its four streamed points
+    auto epilogue = [&](int tile_mod3) __attribute__((always_inline)) {
+        const int sp0 = 16 * w;   // first streamed point of this wave's block within the tile
+        double bias[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bias[r] = bias_lds[tile_mod3][sp0 + 4 * r + lg];
+
+        if constexpr (!APPLY) {
 #pragma unroll
             for (int jt = 0; jt < JT; ++jt) {
-                acc[it][jt] = d4{0.0, 0.0, 0.0, 0.0};
-                if constexpr (HAD) accW[it][jt] = d4{0.0, 0.0, 0.0, 0.0};
-            }
-
-        for (int ch = 0; ch < n_chunks; ++ch) {
-            const int kc0 = ch * KC;
-            const int kw = min(KC, kp - kc0);
-            __syncthreads();   // previous chunk (and the previous tile's epilogue) is done with LDS
-            stash(ch, t);
-            __syncthreads();
-            if (ch + 1 < n_chunks)
-                fetch(t, ch + 1);
-            else if (t + 1 < t_end)
-                fetch(t + 1, 0);
-            const int kbase = res_cached ? kc0 : 0;
-            const double *sa = str_lds + (16 * IT * w + lj) * LDS_ + lg;
-            const double *sb = res_lds + lj * LDR + kbase + lg;
-            const double *sw = had_lds + lj * LDR + kbase + lg;
-            auto kstep = [&](int kk) {
-                double av[IT], bv[JT];
+                double sc[4];
+                float mx = kNegInit;
 #pragma unroll
-                for (int it = 0; it < IT; ++it) av[it] = sa[it * 16 * LDS_ + kk];
-#pragma unroll
-                for (int jt = 0; jt < JT; ++jt) bv[jt] = sb[jt * 16 * LDR + kk];
-#pragma unroll
-                for (int it = 0; it < IT; ++it)
-#pragma unroll
-                    for (int jt = 0; jt < JT; ++jt)
-                        acc[it][jt] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[it], bv[jt], acc[it][jt], 0, 0, 0);
-                if constexpr (HAD) {
-                    double wv[JT];
-#pragma unroll
-                    for (int jt = 0; jt < JT; ++jt) wv[jt] = sw[jt * 16 * LDR + kk];
-#pragma unroll
-                    for (int it = 0; it < IT; ++it)
-#pragma unroll
-                        for (int jt = 0; jt < JT; ++jt)
-                            accW[it][jt] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[it], wv[jt], accW[it][jt], 0, 0, 0);
+                for (int r = 0; r < 4; ++r) {
+                    sc[r] = fma(acc[jt][r], a.cscale, bias[r]);
+                    mx = fmaxf(mx, (float)sc[r]);
                 }
-            };
-            if (kw == KC) {
-                // full chunk: unrolled, so that the accumulators stay where the MFMAs want them
-                // for all eight steps (in the rolled loop below the compiler moves all of them
-                // between AGPRs and VGPRs in every iteration when it has to use AGPRs)
+                float mnew = fmaxf(mrun[jt], ceilf(mx));
+                float scale = fast_exp2(mrun[jt] - mnew);
+                double md = (double)mnew;
+                float csum = 0.0f;
 #pragma unroll
-                for (int kk = 0; kk < KC; kk += 4) kstep(kk);
-            } else {
-                for (int kk = 0; kk < kw; kk += 4) kstep(kk);
+                for (int r = 0; r < 4; ++r) csum += fast_exp2((float)(sc[r] - md));
+                srun[jt] = fmaf(srun[jt], scale, csum);
+                mrun[jt] = mnew;
             }
-        }
-
-        // ---- tile epilogue, one 16-point streamed block at a time: scores of this lane =
-        //      cscale * acc + bias of its four streamed points
+        } else {
+            double sc[JT][4];
+            float mx[JT];
+            bool raise = false;
 #pragma unroll
-        for (int it = 0; it < IT; ++it) {
-            const int sp0 = 16 * IT * w + 16 * it;   // first streamed point of this block within the tile
-            double bias[4];
+            for (int jt = 0; jt < JT; ++jt) {
+                float m = kNegInit;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) bias[r] = bias_lds[sp0 + 4 * r + lg];
-
-            if constexpr (!APPLY) {
+                for (int r = 0; r < 4; ++r) {
+                    sc[jt][r] = fma(acc[jt][r], a.cscale, bias[r]);
+                    m = fmaxf(m, (float)sc[jt][r]);
+                }
+                // the stabiliser of a resident row must be common to the four lane groups,
+                // because the second MFMA sums over them
+                m = fmaxf(m, __shfl_xor(m, 16, 64));
+                m = fmaxf(m, __shfl_xor(m, 32, 64));
+                mx[jt] = m;
+                raise = raise || (m > mrun[jt] + 40.0f);
+            }
+            if (__any(raise)) {
+                // rare: lift the (integer) stabilisers and rescale sums and accumulators exactly
 #pragma unroll
                 for (int jt = 0; jt < JT; ++jt) {
-                    double s[4];
-                    float mx = kNegInit;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        s[r] = fma(acc[it][jt][r], a.cscale, bias[r]);
-                        mx = fmaxf(mx, (float)s[r]);
-                    }
-                    float mnew = fmaxf(mrun[jt], ceilf(mx));
+                    float mnew = fmaxf(mrun[jt], ceilf(mx[jt]));
                     float scale = fast_exp2(mrun[jt] - mnew);
-                    double md = (double)mnew;
-                    float csum = 0.0f;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) csum += fast_exp2((float)(s[r] - md));
-                    srun[jt] = fmaf(srun[jt], scale, csum);
+                    srun[jt] *= scale;
                     mrun[jt] = mnew;
-                }
-            } else {
-                double s[JT][4];
-                float mx[JT];
-                bool raise = false;
-#pragma unroll
-                for (int jt = 0; jt < JT; ++jt) {
-                    float m = kNegInit;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        s[jt][r] = fma(acc[it][jt][r], a.cscale, bias[r]);
-                        m = fmaxf(m, (float)s[jt][r]);
-                    }
-                    // the stabiliser of a resident row must be common to the four lane groups,
-                    // because the second MFMA sums over them
-                    m = fmaxf(m, __shfl_xor(m, 16, 64));
-                    m = fmaxf(m, __shfl_xor(m, 32, 64));
-                    mx[jt] = m;
-                    raise = raise || (m > mrun[jt] + 40.0f);
-                }
-                if (__any(raise)) {
-                    // rare: lift the (integer) stabilisers and rescale sums and accumulators exactly
+                        // accumulator register r holds resident row 4r + lg of this column block
+                        double scd = (double)__shfl(scale, 4 * r + lg, 64);
 #pragma unroll
-                    for (int jt = 0; jt < JT; ++jt) {
-                        float mnew = fmaxf(mrun[jt], ceilf(mx[jt]));
-                        float scale = fast_exp2(mrun[jt] - mnew);
-                        srun[jt] *= scale;
-                        mrun[jt] = mnew;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            // accumulator register r holds resident row 4r + lg of this column block
-                            double sc = (double)__shfl(scale, 4 * r + lg, 64);
-#pragma unroll
-                            for (int ct = 0; ct < NCT; ++ct) O[jt][ct][r] *= sc;
-                        }
+                        for (int ct = 0; ct < NCT; ++ct) O[jt][ct][r] *= scd;
                     }
                 }
+            }
 #pragma unroll
-                for (int jt = 0; jt < JT; ++jt) {
-                    double md = (double)mrun[jt];
-                    double E[4];
-                    float csum = 0.0f;
+            for (int jt = 0; jt < JT; ++jt) {
+                double md = (double)mrun[jt];
+                double E[4];
+                float csum = 0.0f;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        float e = fast_exp2((float)(s[jt][r] - md));
-                        csum += e;
-                        E[r] = (double)e;
-                        if constexpr (HAD) E[r] *= accW[it][jt][r];
-                    }
-                    srun[jt] += csum;
+                for (int r = 0; r < 4; ++r) {
+                    float e = fast_exp2((float)(sc[jt][r] - md));
+                    csum += e;
+                    E[r] = (double)e;
+                    if constexpr (HAD) E[r] *= accW[jt][r];
+                }
+                srun[jt] += csum;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
+                for (int r = 0; r < 4; ++r) {
 #pragma unroll
-                        for (int ct = 0; ct < NCT; ++ct) {
-                            double vv = (double)vt[(sp0 + 4 * r + lg) * PCH + 16 * ct + lj];
-                            O[jt][ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(E[r], vv, O[jt][ct], 0, 0, 0);
-                        }
+                    for (int ct = 0; ct < NCT; ++ct) {
+                        double vv = (double)vt[(sp0 + 4 * r + lg) * PCH + 16 * ct + lj];
+                        O[jt][ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(E[r], vv, O[jt][ct], 0, 0, 0);
                     }
                 }
             }
         }
+    };
+
+    // ---- the stages (tile, chunk) of this workgroup's split, in order ---------------------------
+    auto advance = [&](int &t, int &ch, int &m3) __attribute__((always_inline)) {
+        if (++ch == n_chunks) {
+            ch = 0;
+            ++t;
+            m3 = m3 == 2 ? 0 : m3 + 1;
+        }
+    };
+    int t = t_begin, ch = 0, m3 = 0;     // stage being contracted (m3: its tile's number mod 3)
+    int tn = t, chn = 0, m3n = 0;        // stage stored next
+    advance(tn, chn, m3n);
+    int par = 0;                         // buffer of the stage being contracted
+    if (t < t_end) {
+        fetch(t, 0);
+        stash(0, t, 0, 0);
+    }
+    __syncthreads();
+    if (tn < t_end) fetch(tn, chn);
+    zero_acc();
+
+    while (t < t_end) {
+        const int kc0 = ch * KC;
+        const int kw = min(KC, kc - kc0);
+        const int kbase = res_cached ? kc0 : KC * par;
+        const double *sa = str_lds + par * kStrBuf + (16 * w + lj) * LDS_ + lg;
+        const double *sb = res_lds + lj * LDR + kbase + lg;
+        const double *sw = had_lds + lj * LDR + kbase + lg;
+        // Operands of contraction step k+1 are read from LDS before the MFMAs of step k are
+        // issued (two register sets, ping-pong): otherwise every group of MFMAs starts by
+        // waiting out the LDS latency with an idle matrix pipe.  The last trip reads one step
+        // past the chunk (never used; it stays inside the arrays' slack).
+        double av0, av1, bv0[JT], bv1[JT], wv0[HAD ? JT : 1], wv1[HAD ? JT : 1];
+        auto rd = [&](int kk, double &av, double (&bv)[JT], double (&wv)[HAD ? JT : 1]) {
+            av = sa[kk];
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt) bv[jt] = sb[jt * 16 * LDR + kk];
+            if constexpr (HAD) {
+#pragma unroll
+                for (int jt = 0; jt < JT; ++jt) wv[jt] = sw[jt * 16 * LDR + kk];
+            }
+        };
+        auto mm = [&](double av, const double (&bv)[JT], const double (&wv)[HAD ? JT : 1]) {
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt) acc[jt] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv[jt], acc[jt], 0, 0, 0);
+            if constexpr (HAD) {
+#pragma unroll
+                for (int jt = 0; jt < JT; ++jt) accW[jt] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, wv[jt], accW[jt], 0, 0, 0);
+            }
+        };
+        rd(0, av0, bv0, wv0);
+        for (int kk = 0; kk < kw; kk += 8) {   // kw is a multiple of 8
+            rd(kk + 4, av1, bv1, wv1);
+            __builtin_amdgcn_sched_barrier(0);
+            mm(av0, bv0, wv0);
+            __builtin_amdgcn_sched_barrier(0);
+            rd(kk + 8, av0, bv0, wv0);
+            __builtin_amdgcn_sched_barrier(0);
+            mm(av1, bv1, wv1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        const bool last = ch == n_chunks - 1;
+        if constexpr (APPLY) {
+            // the epilogue reads the tile's values and bias, which the store below replaces
+            if (last) {
+                epilogue(m3);
+                zero_acc();
+                __syncthreads();
+            } else if (NSB == 1) {
+                __syncthreads();
+            }
+        } else if (NSB == 1) {
+            __syncthreads();
+        }
+        if (tn < t_end) stash(NSB == 2 ? par ^ 1 : 0, tn, chn, m3n);
+        __syncthreads();
+        int t2 = tn, ch2 = chn, m32 = m3n;
+        advance(t2, ch2, m32);
+        if (t2 < t_end) fetch(t2, ch2);
+        if constexpr (!APPLY) {
+            if (last) {
+                epilogue(m3);
+                zero_acc();
+            }
+        }
+        t = tn;
+        ch = chn;
+        m3 = m3n;
+        tn = t2;
+        chn = ch2;
+        m3n = m32;
+        if (NSB == 2) par ^= 1;
     }
 
     // ---- merge the 4 waves x 4 lane groups of every resident row ---------------------------
@@ -433,13 +481,14 @@ fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, d
     a.str = str->pts_d;
     a.bias = str->bias_d;
     a.kp = P->kp;
+    a.kc = (int)round_up(P->d, 8);
     a.cscale = 2.0 * kLog2e / eps;
     a.n_tiles = (int)ceil_div(str->cnt, BC);
     a.tiles_per_split = (int)(s.cols_per_split / BC);
     a.partial = (double2 *)P->partial;
     a.partial_stride = res->cnt_pad;
     if ((int64_t)s.row_blocks * s.rows_per_block > res->cnt_pad || (int64_t)a.n_tiles * BC > str->cnt_pad ||
-        (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp & 3) != 0)
+        (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp % KC) != 0 || a.kc > a.kp)
         return fail(c, FS_ERR_DEVICE, "internal: fp64 launch shape exceeds the padded buffers");
     prof_begin(c, (double)res->cnt * (double)str->cnt);
     hipLaunchKernelGGL((k_pass_f64<false, false, 4, kLseJT>), dim3((unsigned)s.row_blocks, (unsigned)s.splits), dim3(256), 0, c->stream, a);
@@ -466,6 +515,7 @@ fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str,
     a.str = str->pts_d;
     a.bias = str->bias_d;
     a.kp = P->kp;
+    a.kc = (int)round_up(P->d, 8);
     a.cscale = 2.0 * kLog2e / eps;
     a.n_tiles = (int)ceil_div(str->cnt, BC);
     a.tiles_per_split = (int)(s.cols_per_split / BC);
@@ -481,7 +531,7 @@ fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str,
     a.n_res = res->cnt;
     a.d = (int)P->d;
     if ((int64_t)s.row_blocks * s.rows_per_block > res->cnt_pad || (int64_t)a.n_tiles * BC > str->cnt_pad ||
-        (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp & 3) != 0 ||
+        (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp % KC) != 0 || a.kc > a.kp ||
         (size_t)s.splits * res->cnt_pad * PCH * 4 > P->extra_bytes)
         return fail(c, FS_ERR_DEVICE, "internal: fp64 apply launch shape exceeds the padded buffers");
     for (int p0 = 0; p0 < p; p0 += PCH) {
