@@ -15,8 +15,8 @@
 // in A-operand layout for the second contraction  O[j][c] += sum_i E[i][j] V[i][c]  (k = l/16
 // <-> i = 4r + k), so P never leaves the registers.
 //
-// Workgroup: 256 threads = 4 waves; 64 resident rows (4 column blocks j of 16) x tiles of 64
-// streamed points (16 per wave).  The resident block lives in LDS for the whole pass when
+// Workgroup: 4 or 8 waves; 64 (LSE) or 32 (application) resident rows in column blocks j of 16 x
+// tiles of 16 streamed points per wave.  The resident block lives in LDS for the whole pass when
 // d <= 64; streamed points go through LDS in contraction chunks of 32.
 #include "fs_internal.h"
 
@@ -26,7 +26,6 @@ namespace {
 typedef double d4 __attribute__((ext_vector_type(4)));
 typedef double d2 __attribute__((ext_vector_type(2)));   // staging registers: a plain vector type, so that they stay registers
 
-constexpr int BC = 64;      // streamed points per tile: one 16-point block per wave (two per wave were slower)
 constexpr int KC = 32;     // contraction chunk staged for the streamed points
 constexpr int KRES = 64;   // resident coordinates kept in LDS across the pass
 // leading dimensions = 2 (mod 32) doubles: the 32 lanes of a half-wave (16 points x 2 adjacent
@@ -34,7 +33,7 @@ constexpr int KRES = 64;   // resident coordinates kept in LDS across the pass
 // 128-bit stores of the staging
 constexpr int LDR = KRES + 2;
 constexpr int LDS_ = KC + 2;
-constexpr int kReadAhead = 8;   // the operand reads run one contraction step ahead of the MFMAs: slack behind the arrays
+constexpr int kReadAhead = 16;  // the operand reads run one contraction step ahead of the MFMAs: slack behind the arrays
 constexpr int PCH = 64;    // value columns per application pass
 
 __device__ inline float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
@@ -61,29 +60,32 @@ struct PassArgs {
     int d;                   // real number of coordinates (columns of hadA)
 };
 
-// (two workgroups per CU for the LSE pass: with at most 256 registers per lane the compiler keeps
-// the MFMA accumulators in ordinary VGPRs; with more it parks them in AGPRs and copies all of them
-// in and out around every group of MFMAs)
+// (never more than 256 registers per lane: with at most 256 the compiler keeps the MFMA
+// accumulators in ordinary VGPRs; with more it parks them in AGPRs and copies all of them in and
+// out around every group of MFMAs.  The LSE pass needs ~120 and 52 KB of LDS: three workgroups per CU.)
 // NCT: 16-column blocks of the value matrix this launch produces (1..4); transport-vector products
 // (one column) then do a quarter of the second contraction
 // JT: 16-row resident blocks per workgroup (4: 64 rows; 2: 32 rows, which lets the plan application
 // run two workgroups per CU without parking accumulators in AGPRs)
-template <bool APPLY, bool HAD = false, int NCT = 4, int JT = 4>
-__global__ __launch_bounds__(256, (APPLY && JT == 4) ? 1 : 2) void k_pass_f64(PassArgs a)
+// NW: waves per workgroup; a wave owns 16 streamed points of every tile (two 16-point blocks per
+// wave were slower), so a tile has 16 NW points.  The LSE pass runs 8 waves over one resident
+// block (4 waves per SIMD with two workgroups per CU), the application 4.
+template <bool APPLY, bool HAD = false, int NCT = 4, int JT = 4, int NW = 4>
+__global__ __launch_bounds__(64 * NW, 2) void k_pass_f64(PassArgs a)
 {
+    constexpr int NT = 64 * NW;   // threads
+    constexpr int BC = 16 * NW;   // streamed points per tile
     constexpr int BR = 16 * JT;   // resident rows per workgroup
-    // Two buffers for the streamed chunk: the next stage is stored while other waves may still be
-    // reading the current one, which leaves one barrier per stage.  The Hadamard variant keeps one
-    // buffer (and a second barrier) so that two workgroups still fit in a CU's LDS.
-    constexpr int NSB = HAD ? 1 : 2;
-    constexpr int kStrBuf = BC * LDS_;
     __shared__ __attribute__((aligned(16))) double res_lds[BR * LDR + kReadAhead];   // 33.8 KB (JT = 4); reused for the final merge
-    __shared__ __attribute__((aligned(16))) double str_lds[NSB * kStrBuf + kReadAhead];  // 17.4 KB per buffer
-    __shared__ double bias_lds[3][BC];            // by tile number mod 3 (a tile's epilogue may run after the next stage is stored)
+    __shared__ __attribute__((aligned(16))) double str_lds[BC * LDS_ + kReadAhead];  // 17.4 KB: 16 points per wave, wave-private
+    __shared__ double bias_lds[BC];
     __shared__ float vt[APPLY ? BC * PCH : 1];    // 16,384 B (application)
     __shared__ __attribute__((aligned(16))) double had_lds[HAD ? BR * LDR + kReadAhead : 1];  // rows of hadA, laid out like res_lds
-    __shared__ float mw[4][BR];                   // per-wave running max (final merge)
-    __shared__ float sred[BR][17];                // per-(wave, lane group) sums (final merge)
+    // final merge: per-wave running max and per-(wave, lane group) sums, on top of the streamed
+    // staging area, which is free by then (this keeps the LSE pass at three workgroups per CU)
+    static_assert(sizeof(float) * (NW * BR + BR * (4 * NW + 1)) <= sizeof(double) * BC * LDS_, "merge scratch exceeds the staging area");
+    float (*mw)[BR] = reinterpret_cast<float (*)[BR]>(str_lds);
+    float (*sred)[4 * NW + 1] = reinterpret_cast<float (*)[4 * NW + 1]>(reinterpret_cast<float *>(str_lds) + NW * BR);
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, l = tid & 63, lg = l >> 4, lj = l & 15;
@@ -95,12 +97,12 @@ __global__ __launch_bounds__(256, (APPLY && JT == 4) ? 1 : 2) void k_pass_f64(Pa
 
     if (res_cached) {
         const int per_row = kc >> 1;   // double2 per row
-        for (int e = tid; e < BR * per_row; e += 256) {
+        for (int e = tid; e < BR * per_row; e += NT) {
             int r = e / per_row, kk = (e - r * per_row) * 2;
             *reinterpret_cast<d2 *>(res_lds + r * LDR + kk) = *reinterpret_cast<const d2 *>(a.res + (row0 + r) * kld + kk);
         }
         if constexpr (HAD) {
-            for (int e = tid; e < BR * kc; e += 256) {
+            for (int e = tid; e < BR * kc; e += NT) {
                 int r = e / kc, kk = e - r * kc;
                 had_lds[r * LDR + kk] = (row0 + r < a.n_res && kk < a.d) ? (double)a.hadA[(row0 + r) * a.lda + kk] : 0.0;
             }
@@ -126,74 +128,82 @@ __global__ __launch_bounds__(256, (APPLY && JT == 4) ? 1 : 2) void k_pass_f64(Pa
 
     // Staging of one (tile, chunk) stage goes through registers: its global loads are issued
     // before the MFMAs of the previous stage and stored to LDS after them, so the memory latency
-    // is covered by matrix work.  Addresses are a uniform base plus a per-thread offset that never
-    // changes: thread (point tid / 16 of every group of 16 points, coordinates 2 (tid % 16) ..+1).
-    d2 pre_s[4], pre_r[JT], pre_a[HAD ? JT : 1];
+    // is covered by matrix work.  Everything that belongs to the streamed points (coordinates,
+    // bias, value rows) is WAVE-PRIVATE: a wave loads, stores and reads only its own 16 points, so
+    // program order within the wave is all the synchronisation these need.  When the resident rows
+    // fit in LDS for the whole pass (d <= 64) the loop therefore has no barrier at all, and the
+    // four waves drift apart freely, which lets one wave's epilogue overlap the others' MFMAs.
+    // Only a resident block that has to be staged chunk by chunk (d > 64) is shared: it alternates
+    // between the two column halves of res_lds, with one barrier per stage.
+    // Addresses are a uniform base plus a per-thread offset that never changes.
+    constexpr int RP = NT / 16;        // resident rows one staging pass of the workgroup covers
+    constexpr int NRQ = BR / RP;       // passes per resident chunk
+    static_assert(BR % RP == 0 && NRQ >= 1, "resident block and workgroup size do not match");
+    d2 pre_s[4], pre_r[NRQ], pre_a[HAD ? NRQ : 1];
     double pre_b = 0.0;
     // value rows of the tile go through registers too, except in the Hadamard variant, which has
-    // no registers to spare and loads them between the barriers instead
+    // no registers to spare and loads them at the store instead
     constexpr bool VPRE = APPLY && !HAD;
-    float pre_v[VPRE ? BC * PCH / 256 : 1];
-    const int sp = tid >> 4, sk = (tid & 15) * 2;
-    const int toff = sp * kld + sk;
+    float pre_v[VPRE ? 16 : 1];
+    const int sk = (l & 15) * 2;                  // coordinate pair of this thread within a chunk
+    const int toff_s = (16 * w + lg) * kld + sk;  // streamed: point 16 w + 4 q + lg of the tile
+    const int sp = tid >> 4;
+    const int toff_r = sp * kld + sk;             // resident: row (NT / 16) q + sp of the block
     auto fetch = [&](int t, int ch) __attribute__((always_inline)) {
         const int64_t col0 = (int64_t)t * BC;
         const int kc0 = ch * KC;
         const double *gs = a.str + col0 * kld + kc0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) pre_s[q] = *reinterpret_cast<const d2 *>(gs + (int64_t)(16 * q) * kld + toff);
+        for (int q = 0; q < 4; ++q) pre_s[q] = *reinterpret_cast<const d2 *>(gs + (int64_t)(4 * q) * kld + toff_s);
         if (!res_cached) {
             const double *gr = a.res + row0 * kld + kc0;
 #pragma unroll
-            for (int q = 0; q < JT; ++q) {
-                pre_r[q] = *reinterpret_cast<const d2 *>(gr + (int64_t)(16 * q) * kld + toff);
+            for (int q = 0; q < NRQ; ++q) {
+                pre_r[q] = *reinterpret_cast<const d2 *>(gr + (int64_t)(RP * q) * kld + toff_r);
                 if constexpr (HAD) {
-                    const int64_t rr = row0 + 16 * q + sp;
+                    const int64_t rr = row0 + RP * q + sp;
                     const int k0 = kc0 + sk;
                     pre_a[q].x = (rr < a.n_res && k0 < a.d) ? (double)a.hadA[rr * a.lda + k0] : 0.0;
                     pre_a[q].y = (rr < a.n_res && k0 + 1 < a.d) ? (double)a.hadA[rr * a.lda + k0 + 1] : 0.0;
                 }
             }
         }
-        if (ch == 0 && tid < BC) pre_b = a.bias[col0 + tid];
+        if (ch == 0 && l < 16) pre_b = a.bias[col0 + 16 * w + l];
         if constexpr (VPRE) {
             if (ch == 0) {
 #pragma unroll
-                for (int q = 0; q < BC * PCH / 256; ++q) {
-                    const int e = tid + 256 * q;
-                    const int cidx = e >> 6, cc = e & 63;
-                    const int64_t j = col0 + cidx;
-                    pre_v[q] = (j < a.n_str && a.p0 + cc < a.p) ? a.V[j * a.ldv + a.p0 + cc] : 0.0f;
+                for (int q = 0; q < 16; ++q) {
+                    const int64_t j = col0 + 16 * w + q;
+                    pre_v[q] = (j < a.n_str && a.p0 + l < a.p) ? a.V[j * a.ldv + a.p0 + l] : 0.0f;
                 }
             }
         }
     };
-    // store the fetched stage: streamed chunk into buffer `buf`, the resident chunk (when it is not
-    // cached) into columns [32 buf, 32 buf + 32) of its rows, bias and values of a tile's first stage
-    auto stash = [&](int buf, int t_st, int ch, int tile_mod3) __attribute__((always_inline)) {
-        double *sd = str_lds + buf * kStrBuf + sp * LDS_ + sk;
+    // store the fetched stage; `half` = column half of res_lds the shared resident chunk goes to
+    auto stash = [&](int half, int t_st, int ch) __attribute__((always_inline)) {
+        double *sd = str_lds + (16 * w + lg) * LDS_ + sk;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) *reinterpret_cast<d2 *>(sd + 16 * q * LDS_) = pre_s[q];
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<d2 *>(sd + 4 * q * LDS_) = pre_s[q];
         if (!res_cached) {
 #pragma unroll
-            for (int q = 0; q < JT; ++q) {
-                *reinterpret_cast<d2 *>(res_lds + (16 * q + sp) * LDR + KC * buf + sk) = pre_r[q];
-                if constexpr (HAD) *reinterpret_cast<d2 *>(had_lds + (16 * q + sp) * LDR + KC * buf + sk) = pre_a[q];
+            for (int q = 0; q < NRQ; ++q) {
+                *reinterpret_cast<d2 *>(res_lds + (RP * q + sp) * LDR + KC * half + sk) = pre_r[q];
+                if constexpr (HAD) *reinterpret_cast<d2 *>(had_lds + (RP * q + sp) * LDR + KC * half + sk) = pre_a[q];
             }
         }
-        if (ch == 0 && tid < BC) bias_lds[tile_mod3][tid] = pre_b;
+        if (ch == 0 && l < 16) bias_lds[16 * w + l] = pre_b;
         if constexpr (VPRE) {
             if (ch == 0) {
 #pragma unroll
-                for (int q = 0; q < BC * PCH / 256; ++q) vt[tid + 256 * q] = pre_v[q];
+                for (int q = 0; q < 16; ++q) vt[(16 * w + q) * PCH + l] = pre_v[q];
             }
         } else if constexpr (APPLY) {
             if (ch == 0) {
                 const int64_t col0 = (int64_t)t_st * BC;
-                for (int e = tid; e < BC * PCH; e += 256) {
-                    const int cidx = e >> 6, cc = e & 63;
-                    const int64_t j = col0 + cidx;
-                    vt[e] = (j < a.n_str && a.p0 + cc < a.p) ? a.V[j * a.ldv + a.p0 + cc] : 0.0f;
+#pragma unroll 4
+                for (int q = 0; q < 16; ++q) {
+                    const int64_t j = col0 + 16 * w + q;
+                    vt[(16 * w + q) * PCH + l] = (j < a.n_str && a.p0 + l < a.p) ? a.V[j * a.ldv + a.p0 + l] : 0.0f;
                 }
             }
         }
@@ -210,13 +220,16 @@ __global__ __launch_bounds__(256, (APPLY && JT == 4) ? 1 : 2) void k_pass_f64(Pa
     };
 
     // ---- tile epilogue: scores of this lane = cscale * acc + bias of its four streamed points
-    auto epilogue = [&](int tile_mod3) __attribute__((always_inline)) {
+    auto epilogue = [&]() __attribute__((always_inline)) {
         const int sp0 = 16 * w;   // first streamed point of this wave's block within the tile
         double bias[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) bias[r] = bias_lds[tile_mod3][sp0 + 4 * r + lg];
+        for (int r = 0; r < 4; ++r) bias[r] = bias_lds[sp0 + 4 * r + lg];
 
         if constexpr (!APPLY) {
+            // every tile lifts the running max (an integer) to the ceiling of its largest score
+            // (the lazy scheme of the application below was measured slower here: 0.605 against
+            // 0.587 ms at n = m = 16384, d = 64, with one check per block, 0.623 with one per tile)
 #pragma unroll
             for (int jt = 0; jt < JT; ++jt) {
                 double sc[4];
@@ -235,61 +248,67 @@ __global__ __launch_bounds__(256, (APPLY && JT == 4) ? 1 : 2) void k_pass_f64(Pa
                 srun[jt] = fmaf(srun[jt], scale, csum);
                 mrun[jt] = mnew;
             }
-        } else {
-            double sc[JT][4];
-            float mx[JT];
-            bool raise = false;
+            return;
+        }
+        // Lazy stabiliser: the running max (an integer) is not tracked tile by tile.  The
+        // exponentials are taken against the current one and their sum is checked against 2^60;
+        // only when that fails (the first tile, and the few times a row meets much larger scores)
+        // is the max lifted to the ceiling of the tile's largest score, the running sums rescaled
+        // by the exact power of two and the tile's exponentials redone.  Terms below 2^-126 of a
+        // sum that has held a term above 1/2 are lost, which is far below fp32 resolution.
 #pragma unroll
-            for (int jt = 0; jt < JT; ++jt) {
+        for (int jt = 0; jt < JT; ++jt) {
+            double sc[4];
+            float e[4];
+            double md = (double)mrun[jt];
+            float csum = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                sc[r] = fma(acc[jt][r], a.cscale, bias[r]);
+                e[r] = fast_exp2((float)(sc[r] - md));
+                csum += e[r];
+            }
+            if (__any(!(csum < 0x1p60f))) {
                 float m = kNegInit;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    sc[jt][r] = fma(acc[jt][r], a.cscale, bias[r]);
-                    m = fmaxf(m, (float)sc[jt][r]);
+                for (int r = 0; r < 4; ++r) m = fmaxf(m, (float)sc[r]);
+                if constexpr (APPLY) {
+                    // the stabiliser of a resident row must be common to the four lane groups,
+                    // because the second MFMA sums over them
+                    m = fmaxf(m, __shfl_xor(m, 16, 64));
+                    m = fmaxf(m, __shfl_xor(m, 32, 64));
                 }
-                // the stabiliser of a resident row must be common to the four lane groups,
-                // because the second MFMA sums over them
-                m = fmaxf(m, __shfl_xor(m, 16, 64));
-                m = fmaxf(m, __shfl_xor(m, 32, 64));
-                mx[jt] = m;
-                raise = raise || (m > mrun[jt] + 40.0f);
-            }
-            if (__any(raise)) {
-                // rare: lift the (integer) stabilisers and rescale sums and accumulators exactly
-#pragma unroll
-                for (int jt = 0; jt < JT; ++jt) {
-                    float mnew = fmaxf(mrun[jt], ceilf(mx[jt]));
-                    float scale = fast_exp2(mrun[jt] - mnew);
-                    srun[jt] *= scale;
-                    mrun[jt] = mnew;
+                const float mnew = fmaxf(mrun[jt], ceilf(m));
+                const float scale = fast_exp2(mrun[jt] - mnew);
+                srun[jt] *= scale;
+                mrun[jt] = mnew;
+                if constexpr (APPLY) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         // accumulator register r holds resident row 4r + lg of this column block
-                        double scd = (double)__shfl(scale, 4 * r + lg, 64);
+                        const double scd = (double)__shfl(scale, 4 * r + lg, 64);
 #pragma unroll
                         for (int ct = 0; ct < NCT; ++ct) O[jt][ct][r] *= scd;
                     }
                 }
-            }
-#pragma unroll
-            for (int jt = 0; jt < JT; ++jt) {
-                double md = (double)mrun[jt];
-                double E[4];
-                float csum = 0.0f;
+                md = (double)mnew;
+                csum = 0.0f;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    float e = fast_exp2((float)(sc[jt][r] - md));
-                    csum += e;
-                    E[r] = (double)e;
-                    if constexpr (HAD) E[r] *= accW[jt][r];
+                    e[r] = fast_exp2((float)(sc[r] - md));
+                    csum += e[r];
                 }
-                srun[jt] += csum;
+            }
+            srun[jt] += csum;
+            if constexpr (APPLY) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
+                    double E = (double)e[r];
+                    if constexpr (HAD) E *= accW[jt][r];
 #pragma unroll
                     for (int ct = 0; ct < NCT; ++ct) {
                         double vv = (double)vt[(sp0 + 4 * r + lg) * PCH + 16 * ct + lj];
-                        O[jt][ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(E[r], vv, O[jt][ct], 0, 0, 0);
+                        O[jt][ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(E, vv, O[jt][ct], 0, 0, 0);
                     }
                 }
             }
@@ -297,22 +316,21 @@ __global__ __launch_bounds__(256, (APPLY && JT == 4) ? 1 : 2) void k_pass_f64(Pa
     };
 
     // ---- the stages (tile, chunk) of this workgroup's split, in order ---------------------------
-    auto advance = [&](int &t, int &ch, int &m3) __attribute__((always_inline)) {
+    auto advance = [&](int &t, int &ch) __attribute__((always_inline)) {
         if (++ch == n_chunks) {
             ch = 0;
             ++t;
-            m3 = m3 == 2 ? 0 : m3 + 1;
         }
     };
-    int t = t_begin, ch = 0, m3 = 0;     // stage being contracted (m3: its tile's number mod 3)
-    int tn = t, chn = 0, m3n = 0;        // stage stored next
-    advance(tn, chn, m3n);
-    int par = 0;                         // buffer of the stage being contracted
+    int t = t_begin, ch = 0;     // stage being contracted
+    int tn = t, chn = 0;         // stage stored next
+    advance(tn, chn);
+    int par = 0;                 // column half of a staged resident chunk
     if (t < t_end) {
         fetch(t, 0);
-        stash(0, t, 0, 0);
+        stash(0, t, 0);
     }
-    __syncthreads();
+    __syncthreads();             // resident rows (cached or first chunk) are in place
     if (tn < t_end) fetch(tn, chn);
     zero_acc();
 
@@ -320,7 +338,7 @@ __global__ __launch_bounds__(256, (APPLY && JT == 4) ? 1 : 2) void k_pass_f64(Pa
         const int kc0 = ch * KC;
         const int kw = min(KC, kc - kc0);
         const int kbase = res_cached ? kc0 : KC * par;
-        const double *sa = str_lds + par * kStrBuf + (16 * w + lj) * LDS_ + lg;
+        const double *sa = str_lds + (16 * w + lj) * LDS_ + lg;
         const double *sb = res_lds + lj * LDR + kbase + lg;
         const double *sw = had_lds + lj * LDR + kbase + lg;
         // Operands of contraction step k+1 are read from LDS before the MFMAs of step k are
@@ -357,37 +375,23 @@ __global__ __launch_bounds__(256, (APPLY && JT == 4) ? 1 : 2) void k_pass_f64(Pa
             __builtin_amdgcn_sched_barrier(0);
         }
 
-        const bool last = ch == n_chunks - 1;
-        if constexpr (APPLY) {
-            // the epilogue reads the tile's values and bias, which the store below replaces
-            if (last) {
-                epilogue(m3);
-                zero_acc();
-                __syncthreads();
-            } else if (NSB == 1) {
-                __syncthreads();
-            }
-        } else if (NSB == 1) {
-            __syncthreads();
+        if (ch == n_chunks - 1) {
+            epilogue();
+            zero_acc();
         }
-        if (tn < t_end) stash(NSB == 2 ? par ^ 1 : 0, tn, chn, m3n);
-        __syncthreads();
-        int t2 = tn, ch2 = chn, m32 = m3n;
-        advance(t2, ch2, m32);
+        // the wave is done reading its part of the staging arrays: store the next stage
+        __builtin_amdgcn_wave_barrier();
+        if (tn < t_end) stash(par ^ 1, tn, chn);
+        __builtin_amdgcn_wave_barrier();
+        if (!res_cached) __syncthreads();   // uniform over the workgroup: the shared resident chunk
+        int t2 = tn, ch2 = chn;
+        advance(t2, ch2);
         if (t2 < t_end) fetch(t2, ch2);
-        if constexpr (!APPLY) {
-            if (last) {
-                epilogue(m3);
-                zero_acc();
-            }
-        }
         t = tn;
         ch = chn;
-        m3 = m3n;
         tn = t2;
         chn = ch2;
-        m3n = m32;
-        if (NSB == 2) par ^= 1;
+        par ^= 1;
     }
 
     // ---- merge the 4 waves x 4 lane groups of every resident row ---------------------------
@@ -413,19 +417,23 @@ __global__ __launch_bounds__(256, (APPLY && JT == 4) ? 1 : 2) void k_pass_f64(Pa
 #pragma unroll
     for (int jt = 0; jt < JT; ++jt) {
         int r = 16 * jt + lj;
-        float M = fmaxf(fmaxf(mw[0][r], mw[1][r]), fmaxf(mw[2][r], mw[3][r]));
+        float M = mw[0][r];
+#pragma unroll
+        for (int ww = 1; ww < NW; ++ww) M = fmaxf(M, mw[ww][r]);
         sred[r][4 * w + lg] = srun[jt] * fast_exp2(mrun[jt] - M);
     }
     if constexpr (APPLY) {
         double *obuf = res_lds;   // [BR][PCH] doubles = 32 KB <= sizeof(res_lds)
-        for (int ww = 0; ww < 4; ++ww) {
+        for (int ww = 0; ww < NW; ++ww) {
             if (w == ww) {
 #pragma unroll
                 for (int jt = 0; jt < JT; ++jt)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         int row = 16 * jt + 4 * r + lg;
-                        float M = fmaxf(fmaxf(mw[0][row], mw[1][row]), fmaxf(mw[2][row], mw[3][row]));
+                        float M = mw[0][row];
+#pragma unroll
+                        for (int w2 = 1; w2 < NW; ++w2) M = fmaxf(M, mw[w2][row]);
                         double sc = (double)fast_exp2(mw[w][row] - M);
 #pragma unroll
                         for (int ct = 0; ct < NCT; ++ct) {
@@ -437,37 +445,41 @@ __global__ __launch_bounds__(256, (APPLY && JT == 4) ? 1 : 2) void k_pass_f64(Pa
             }
             __syncthreads();
         }
-        for (int e = tid; e < BR * PCH; e += 256) {
+        for (int e = tid; e < BR * PCH; e += NT) {
             int r = e >> 6, cc = e & 63;
             a.opart[((int64_t)blockIdx.y * a.partial_stride + row0 + r) * PCH + cc] = cc < 16 * NCT ? (float)obuf[e] : 0.0f;
         }
     }
     __syncthreads();
     if (tid < BR) {
-        float M = fmaxf(fmaxf(mw[0][tid], mw[1][tid]), fmaxf(mw[2][tid], mw[3][tid]));
+        float M = mw[0][tid];
+#pragma unroll
+        for (int ww = 1; ww < NW; ++ww) M = fmaxf(M, mw[ww][tid]);
         double S = 0.0;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) S += (double)sred[tid][k];
+        for (int k = 0; k < 4 * NW; ++k) S += (double)sred[tid][k];
         a.partial[(int64_t)blockIdx.y * a.partial_stride + row0 + tid] = make_double2((double)M, S);
     }
 }
 
 constexpr int kLseJT = 4, kApplyJT = 2;   // resident blocks per workgroup of the two passes
+constexpr int kLseNW = 8, kApplyNW = 4;   // waves per workgroup
+constexpr int kWgPerCu = 2;               // as in the kernel's launch bounds
 
-PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str, int br)
+PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str, int br, int bc)
 {
     PassShape s;
     s.rows_per_block = br;
     s.row_blocks = (int)ceil_div(n_res, br);
-    int n_tiles = (int)ceil_div(n_str, BC);
-    int target = 2 * c->num_cu;
+    int n_tiles = (int)ceil_div(n_str, bc);
+    int target = kWgPerCu * c->num_cu;
     int splits = (int)ceil_div(target, s.row_blocks);
     if (splits > n_tiles) splits = n_tiles;
     if (splits > max_splits(n_res)) splits = max_splits(n_res);
     if (splits < 1) splits = 1;
     int tps = (int)ceil_div(n_tiles, splits);
     s.splits = (int)ceil_div(n_tiles, tps);
-    s.cols_per_split = (int64_t)tps * BC;
+    s.cols_per_split = (int64_t)tps * bc;
     return s;
 }
 
@@ -475,7 +487,8 @@ PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str, int br)
 
 fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out)
 {
-    PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kLseJT);
+    PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kLseJT, 16 * kLseNW);
+    constexpr int BC = 16 * kLseNW;
     PassArgs a{};
     a.res = res->pts_d;
     a.str = str->pts_d;
@@ -491,7 +504,8 @@ fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, d
         (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp % KC) != 0 || a.kc > a.kp)
         return fail(c, FS_ERR_DEVICE, "internal: fp64 launch shape exceeds the padded buffers");
     prof_begin(c, (double)res->cnt * (double)str->cnt);
-    hipLaunchKernelGGL((k_pass_f64<false, false, 4, kLseJT>), dim3((unsigned)s.row_blocks, (unsigned)s.splits), dim3(256), 0, c->stream, a);
+    hipLaunchKernelGGL((k_pass_f64<false, false, 4, kLseJT, kLseNW>), dim3((unsigned)s.row_blocks, (unsigned)s.splits), dim3(64 * kLseNW), 0,
+                       c->stream, a);
     prof_end(c);
     FS_HIP(c, hipGetLastError());
     *splits_out = s.splits;
@@ -502,14 +516,15 @@ size_t f64_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t d, int64
 {
     (void)d;
     (void)p;
-    PassShape s = shape_f64(c, n_res, n_str, 16 * kApplyJT);
+    PassShape s = shape_f64(c, n_res, n_str, 16 * kApplyJT, 16 * kApplyNW);
     return (size_t)s.splits * (size_t)round_up(n_res, 1024) * PCH * 4;
 }
 
 fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, const float *V,
                     int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out, const float *hadA, int64_t lda)
 {
-    PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kApplyJT);
+    PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kApplyJT, 16 * kApplyNW);
+    constexpr int BC = 16 * kApplyNW;
     PassArgs a{};
     a.res = res->pts_d;
     a.str = str->pts_d;
@@ -538,7 +553,7 @@ fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str,
         a.p0 = p0;
         const dim3 grid((unsigned)s.row_blocks, (unsigned)s.splits);
         const int nct = (int)ceil_div((p - p0 < PCH ? p - p0 : (int64_t)PCH), 16);
-#define FS_F64_APPLY(H, N) hipLaunchKernelGGL((k_pass_f64<true, H, N, kApplyJT>), grid, dim3(256), 0, c->stream, a)
+#define FS_F64_APPLY(H, N) hipLaunchKernelGGL((k_pass_f64<true, H, N, kApplyJT, kApplyNW>), grid, dim3(64 * kApplyNW), 0, c->stream, a)
         if (hadA) {
             switch (nct) {
             case 1: FS_F64_APPLY(true, 1); break;
