@@ -146,6 +146,12 @@ size_t layout(const Ctx *c, const fs_problem *p, Prepared *P, char *base, size_t
             S.split = (base && P->ks) ? (uint16_t *)(base + o) : nullptr;
             o = A.take(p->d <= 3 ? (size_t)S.cnt_pad * 96 : 0);
             S.split_p = (base && p->d <= 3) ? (uint16_t *)(base + o) : nullptr;
+            // d > 3: float64-score half-steps run on the fp64 matrix cores, from records of that path
+            P->kp = 32;
+            o = A.take(p->d > 3 ? (size_t)S.cnt_pad * P->kp * 8 : 0);
+            S.pts_d = (base && p->d > 3) ? (double *)(base + o) : nullptr;
+            o = A.take(p->d > 3 ? (size_t)S.cnt_pad * 8 : 0);
+            S.bias_d = (base && p->d > 3) ? (double *)(base + o) : nullptr;
             break;
         case Path::F64:
             P->kp = (int)round_up(p->d, 32);

@@ -485,7 +485,7 @@ PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str, int br, int bc)
 
 }  // namespace
 
-fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out)
+fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out, int prof_kind)
 {
     PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kLseJT, 16 * kLseNW);
     constexpr int BC = 16 * kLseNW;
@@ -503,7 +503,7 @@ fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, d
     if ((int64_t)s.row_blocks * s.rows_per_block > res->cnt_pad || (int64_t)a.n_tiles * BC > str->cnt_pad ||
         (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp % KC) != 0 || a.kc > a.kp)
         return fail(c, FS_ERR_DEVICE, "internal: fp64 launch shape exceeds the padded buffers");
-    prof_begin(c, (double)res->cnt * (double)str->cnt);
+    prof_begin(c, (double)res->cnt * (double)str->cnt, prof_kind);
     hipLaunchKernelGGL((k_pass_f64<false, false, 4, kLseJT, kLseNW>), dim3((unsigned)s.row_blocks, (unsigned)s.splits), dim3(64 * kLseNW), 0,
                        c->stream, a);
     prof_end(c);

@@ -857,7 +857,7 @@ void launch_lse_split_pair(dim3 grid, hipStream_t st, const SplitArgs &a0, const
 fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out)
 {
     // fp32-accuracy half-steps run on the bf16 matrix cores from the split records; float64-score
-    // ones too when d <= 3 (precise records), else on the vector ALU
+    // ones too when d <= 3 (precise records); other float64-score half-steps are handled further down
     SplitArgs a;
     bool precise = false;
     fs_status st;
@@ -875,7 +875,9 @@ fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
         return FS_OK;
     }
     if (st != FS_OK) return st;
-    // float64 scores on the vector ALU
+    // float64 scores outside the reach of the split records: on the fp64 matrix cores for d > 3 (from
+    // the centred float64 records the prologue wrote for that kernel), else on the vector ALU
+    if (res->pts_d && str->pts_d && str->bias_d) return f64_lse(c, P, res, str, eps, splits_out, 1);
     PassShape s = lowd_shape(c, res->cnt, str->cnt);
     const int n_tiles = (int)ceil_div(str->cnt, kTJ);
     const int tps = (int)(s.cols_per_split / kTJ);
@@ -926,11 +928,13 @@ fs_status lowd_lse_pair(Ctx *c, const Prepared *P, double eps, void *partial_x, 
 size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t p)
 {
     (void)p;
-    // the larger of the two launch shapes an application can take (split records / vector ALU)
+    // the largest of the launch shapes an application can take (split records / vector ALU / fp64 matrix cores)
     const PassShape s1 = shape_for(c, n_res, n_str, kBlock);
     const PassShape s2 = shape_for(c, n_res, n_str, 128 * kSplitR, kSplitTJ);
     const int splits = s1.splits > s2.splits ? s1.splits : s2.splits;
-    return (size_t)splits * (size_t)round_up(n_res, 1024) * kApplyPC * 4;
+    const size_t own = (size_t)splits * (size_t)round_up(n_res, 1024) * kApplyPC * 4;
+    const size_t f64 = f64_apply_ws(c, n_res, n_str, kLowdMaxD, p);
+    return own > f64 ? own : f64;
 }
 
 // `cols`: value columns of this launch that exist (1..kApplyPC).  A single column (transport-vector
@@ -990,6 +994,9 @@ fs_status lowd_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str
         }
         if (st != FS_OK) return st;
     }
+    // float64 scores at d > 3 (plain or Hadamard-weighted): the fp64 matrix-core application
+    if (lowd_precise(P, eps) && res->pts_d && str->pts_d && str->bias_d)
+        return f64_apply(c, P, res, str, eps, V, p, ldv, out, ldo, mass_out, had_A, lda);
     PassShape s = shape_for(c, res->cnt, str->cnt, kBlock);
     const int n_tiles = (int)ceil_div(str->cnt, kTJ);
     const int tps = (int)(s.cols_per_split / kTJ);

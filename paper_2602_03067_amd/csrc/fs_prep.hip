@@ -121,8 +121,9 @@ struct PrepLowdSide {
     float *packed;
     double *packed_d, *norm_f, *norm;
     uint16_t *split;
+    double *pts_d, *bias_d;   // d > 3: records of the fp64 matrix-core pass ([cnt_pad][kp] centred coordinates, bias), else null
 };
-__global__ __launch_bounds__(256) void k_prep_lowd(PrepLowdSide s0, PrepLowdSide s1, int dtype, int d, int dp, int dpd,
+__global__ __launch_bounds__(256) void k_prep_lowd(PrepLowdSide s0, PrepLowdSide s1, int dtype, int d, int dp, int dpd, int kp,
                                                    const double *mean, int ks, unsigned long long *rho_max_bits)
 {
     const PrepLowdSide &sd = blockIdx.y ? s1 : s0;
@@ -151,6 +152,11 @@ __global__ __launch_bounds__(256) void k_prep_lowd(PrepLowdSide s0, PrepLowdSide
     }
     o[d] = -INFINITY;   // bias slots: padding rows never contribute; real rows are set per half-step
     od[d] = -INFINITY;
+    if (sd.pts_d) {
+        double *op = sd.pts_d + i * kp;
+        for (int k = 0; k < kp; ++k) op[k] = k < d ? od[k] : 0.0;
+        sd.bias_d[i] = -INFINITY;
+    }
     norm_f[i] = nf;
     norm[i] = nd;
     if (split) {   // streamed-role split record of the float copy
@@ -740,10 +746,11 @@ fs_status launch_prepare(Ctx *c, const fs_problem *p, Prepared *P)
         PrepLowdSide sd[2];
         for (int k = 0; k < 2; ++k) {
             const Side *S = in[k].S;
-            sd[k] = PrepLowdSide{in[k].pts, S->cnt, S->cnt_pad, in[k].ld, S->packed, S->packed_d, S->norm_f, S->norm, S->split};
+            sd[k] = PrepLowdSide{in[k].pts, S->cnt, S->cnt_pad, in[k].ld, S->packed, S->packed_d, S->norm_f, S->norm, S->split,
+                                 S->pts_d,   S->bias_d};
         }
         hipLaunchKernelGGL(k_prep_lowd, dim3((unsigned)ceil_div(pad_max, 256), 2), dim3(256), 0, c->stream, sd[0], sd[1], dtype,
-                           (int)p->d, P->dp, P->dpd, P->mean, P->ks, reinterpret_cast<unsigned long long *>(P->scalars + 7));
+                           (int)p->d, P->dp, P->dpd, P->kp, P->mean, P->ks, reinterpret_cast<unsigned long long *>(P->scalars + 7));
         // (the host reads rho_max back together with the sizes of the biases, see launch_bias_from_user)
         P->rho_max = -1.0;
         if (p->d <= 3)   // the grid of the precise records' leading digits depends on rho_max

@@ -98,7 +98,7 @@ def test_one_context_many_problems(oracle):
 @pytest.mark.parametrize("d,eps", [(3, 2e-3), (2, 5e-4), (8, 2e-3)])
 def test_very_small_eps_low_dimension(oracle, d, eps):
     """Scores of several thousand (base 2): float64-score half-steps, on the matrix cores where the
-    fixed grids cover the biases (d <= 3) and on the vector ALU otherwise."""
+    fixed grids cover the biases (d <= 3) and on the fp64 matrix cores at larger d."""
     rng = np.random.default_rng(31 + d)
     n, m = 700, 650
     x = rng.random((n, d)).astype(np.float32)

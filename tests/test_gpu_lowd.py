@@ -296,3 +296,53 @@ def test_million_points_sampled_rows(ctx, oracle, n, m, d):
     eg = max_err_over_eps(host(g1)[cols], oracle.update_g(x, y, a, eps, f1h, cols=cols), eps)
     say("  sampled max|df|/eps=%.3e max|dg|/eps=%.3e" % (ef, eg))
     assert np.isfinite(f1h).all() and ef <= TOL and eg <= TOL
+
+
+@pytest.mark.parametrize("n,m,d,p", [(300, 421, 4, 1), (129, 1000, 7, 5), (1100, 260, 12, 70), (640, 700, 16, 64)])
+def test_float64_scores_above_three_dimensions(ctx, oracle, n, m, d, p):
+    """3 < d <= 16 with float64 scores (forced here; on its own the library takes them at small eps and
+    on long runs): half-steps, both plan applications and the Hessian-vector product then run on the
+    fp64 matrix-core kernels, from centred float64 records of the low-dimension prologue."""
+    from oracle import hvp_dense
+    rng = np.random.default_rng(5 * n + m + d)
+    x, y, a, b = _rand_problem(rng, n, m, d)
+    eps = float(np.float32(0.5))
+    fo, go = oracle.solve(x, y, a, b, eps, eps, 1, 30)
+    f32 = (fo + 0.02 * rng.standard_normal(n)).astype(np.float32)
+    g32 = go.astype(np.float32)
+    V = rng.standard_normal((m, p)).astype(np.float32)
+    U = rng.standard_normal((n, p)).astype(np.float32)
+    A = rng.standard_normal((n, d)).astype(np.float32)
+    say("float64 scores forced, n=%d m=%d d=%d p=%d" % (n, m, d, p))
+    prob = make_problem(x, y, a, b)
+    old = os.environ.get("FS_LOWD_SCORE")
+    os.environ["FS_LOWD_SCORE"] = "f64"
+    try:
+        f_gpu = host(ctx.fs_update_f(prob, eps, dev(g32)))
+        g_gpu = host(ctx.fs_update_g(prob, eps, dev(f32)))
+        out, mass = ctx.fs_apply_plan(prob, eps, dev(f32), dev(g32), dev(V), want_mass=True)
+        outT, massT = ctx.fs_apply_plan_T(prob, eps, dev(f32), dev(g32), dev(U), want_mass=True)
+        fs, gs = torch.zeros(n, device="cuda:0"), torch.zeros(m, device="cuda:0")
+        ctx.fs_solve_symmetric(prob, eps, 6, fs, gs)
+        G, k = ctx.fs_hvp(prob, eps, dev(fo.astype(np.float32)), dev(g32), dev(A), 1e-5, 1e-6, 400)
+    finally:
+        if old is None:
+            os.environ.pop("FS_LOWD_SCORE", None)
+        else:
+            os.environ["FS_LOWD_SCORE"] = old
+    assert max_err_over_eps(f_gpu, oracle.update_f(x, y, b, eps, g32), eps) <= TOL
+    assert max_err_over_eps(g_gpu, oracle.update_g(x, y, a, eps, f32), eps) <= TOL
+    want, r = oracle.apply_plan(x, y, a, b, eps, f32, g32, V, return_mass=True)
+    wantT, c = oracle.apply_plan_T(x, y, a, b, eps, f32, g32, U, return_mass=True)
+    for got, ref in ((host(out), want), (host(outT), wantT)):
+        assert np.linalg.norm(got - ref) <= 2e-4 * np.linalg.norm(ref)
+        assert np.abs(got - ref).max() <= 1e-3 * np.abs(ref).max()
+    np.testing.assert_allclose(host(mass), r, rtol=2e-4)
+    np.testing.assert_allclose(host(massT), c, rtol=2e-4)
+    fso, gso = oracle.solve_symmetric(x, y, a, b, eps, 6)
+    assert max_err_over_eps(host(fs), fso, eps) <= TOL and max_err_over_eps(host(gs), gso, eps) <= TOL
+    fh = fo.astype(np.float32).astype(np.float64)
+    wantG = hvp_dense.hvp(x, y, a, b, eps, fh, g32.astype(np.float64), A, tau=1e-5)
+    rel = np.linalg.norm(host(G) - wantG) / np.linalg.norm(wantG)
+    say("  hvp: %d CG iterations, rel. error %.3e" % (k, rel))
+    assert rel <= 1e-4
