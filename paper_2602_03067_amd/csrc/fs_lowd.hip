@@ -661,10 +661,14 @@ template <int D>
 void launch_lse_d(int R, dim3 grid, hipStream_t st, const double *res, const double *str, double cscale, int tps,
                   int n_tiles, double2 *partial, int64_t stride)
 {
-    if (R == 2)
-        hipLaunchKernelGGL((k_lse_lowd<double, D, 2>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride);
-    else
-        hipLaunchKernelGGL((k_lse_lowd<double, D, 1>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride);
+    // float64 scores on the vector ALU exist for d <= 3 only (above, those half-steps run on the fp64
+    // matrix cores and never come here)
+    if constexpr (D <= 3) {
+        if (R == 2)
+            hipLaunchKernelGGL((k_lse_lowd<double, D, 2>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride);
+        else
+            hipLaunchKernelGGL((k_lse_lowd<double, D, 1>), grid, dim3(kBlock), 0, st, res, str, cscale, tps, n_tiles, partial, stride);
+    }
 }
 
 template <typename S, int D>
@@ -672,12 +676,15 @@ void launch_apply_d(dim3 grid, hipStream_t st, const S *res, const S *str, const
                     int64_t n_str, S cscale, int tps, int n_tiles, double2 *partial, int64_t stride, float *opart,
                     const float *had_A, int64_t lda, int64_t n_res)
 {
-    if (had_A)
-        hipLaunchKernelGGL((k_apply_lowd<S, D, kApplyPC, true>), grid, dim3(kBlock), 0, st, res, str, V, ldv, p0, p, n_str,
-                           cscale, tps, n_tiles, partial, stride, opart, stride, had_A, lda, n_res);
-    else
-        hipLaunchKernelGGL((k_apply_lowd<S, D, kApplyPC, false>), grid, dim3(kBlock), 0, st, res, str, V, ldv, p0, p, n_str,
-                           cscale, tps, n_tiles, partial, stride, opart, stride, had_A, lda, n_res);
+    // (the float64 form exists for d <= 3 only, see launch_lse_d)
+    if constexpr (sizeof(S) == 4 || D <= 3) {
+        if (had_A)
+            hipLaunchKernelGGL((k_apply_lowd<S, D, kApplyPC, true>), grid, dim3(kBlock), 0, st, res, str, V, ldv, p0, p, n_str,
+                               cscale, tps, n_tiles, partial, stride, opart, stride, had_A, lda, n_res);
+        else
+            hipLaunchKernelGGL((k_apply_lowd<S, D, kApplyPC, false>), grid, dim3(kBlock), 0, st, res, str, V, ldv, p0, p, n_str,
+                               cscale, tps, n_tiles, partial, stride, opart, stride, had_A, lda, n_res);
+    }
 }
 
 #define FS_LOWD_DISPATCH(D_, CALL)                                                                       \
@@ -878,6 +885,7 @@ fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
     // float64 scores outside the reach of the split records: on the fp64 matrix cores for d > 3 (from
     // the centred float64 records the prologue wrote for that kernel), else on the vector ALU
     if (res->pts_d && str->pts_d && str->bias_d) return f64_lse(c, P, res, str, eps, splits_out, 1);
+    if (P->d > 3) return fail(c, FS_ERR_DEVICE, "internal: float64-score pass at d > 3 without its records");
     PassShape s = lowd_shape(c, res->cnt, str->cnt);
     const int n_tiles = (int)ceil_div(str->cnt, kTJ);
     const int tps = (int)(s.cols_per_split / kTJ);
@@ -997,6 +1005,7 @@ fs_status lowd_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str
     // float64 scores at d > 3 (plain or Hadamard-weighted): the fp64 matrix-core application
     if (lowd_precise(P, eps) && res->pts_d && str->pts_d && str->bias_d)
         return f64_apply(c, P, res, str, eps, V, p, ldv, out, ldo, mass_out, had_A, lda);
+    if (P->d > 3 && lowd_precise(P, eps)) return fail(c, FS_ERR_DEVICE, "internal: float64-score application at d > 3 without its records");
     PassShape s = shape_for(c, res->cnt, str->cnt, kBlock);
     const int n_tiles = (int)ceil_div(str->cnt, kTJ);
     const int tps = (int)(s.cols_per_split / kTJ);
