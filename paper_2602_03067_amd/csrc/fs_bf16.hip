@@ -142,7 +142,9 @@ __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a
     }
 
     const int tid = threadIdx.x;
-    const int w = tid >> 6, l = tid & 63;
+    // (the wave number as a scalar: stage, piece and address arithmetic of the loads below then runs on
+    // the scalar unit instead of taking vector-ALU issue slots from the MFMA loop)
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63;
     const int wi = w & 3, wj = w >> 2;
     const int lh = l >> 5, lr = l & 31;
     const int n_chunks = a.kp / KC;
@@ -159,8 +161,9 @@ __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a
     // (row block rb, chunk ch) at byte ((rb * n_chunks + ch) << 10): a stage is ROWS/16 linear
     // 1 KB copies, PPW per wave (pieces q NW + w; 0..15 streamed rows, then the resident rows).
     const unsigned char *res_tiles =
-        reinterpret_cast<const unsigned char *>(a.res) + (((int64_t)jtile * (BJ / 16) * n_chunks) << 10) + l * 16;
-    const unsigned char *str_tiles = reinterpret_cast<const unsigned char *>(a.str) + l * 16;
+        reinterpret_cast<const unsigned char *>(a.res) + (((int64_t)jtile * (BJ / 16) * n_chunks) << 10);
+    const unsigned char *str_tiles = reinterpret_cast<const unsigned char *>(a.str);
+    const unsigned l16 = l * 16, l4 = l * 4;
 
     int pg = 0, pch = 0, pt = t_begin;   // next stage this wave issues: number, chunk, tile
     auto issue_piece = [&](int q) {      // q < PPW: 1 KB of points, q == PPW: bias, then advance to the next stage
@@ -168,11 +171,11 @@ __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a
             const int sidx = q * NW + w;
             const unsigned char *src = sidx < 16 ? str_tiles + ((((int64_t)pt * 16 + sidx) * n_chunks + pch) << 10)
                                                  : res_tiles + ((((int64_t)(sidx - 16)) * n_chunks + pch) << 10);
-            dma16(src, ring_off + (pg % NS) * STAGE_BYTES + sidx * 1024);
+            dma16s(src, l16, ring_off + (pg % NS) * STAGE_BYTES + sidx * 1024);
         } else {
             // (with two waves per streamed quarter both write the same 256 bytes: harmless, and every
             // wave has the same number of loads in flight)
-            dma4(a.bias + (int64_t)pt * BI + wi * 64 + l, bias_off + (pg & (NBIAS - 1)) * (BI * 4) + wi * 256);
+            dma4s(a.bias + (int64_t)pt * BI + wi * 64, l4, bias_off + (pg & (NBIAS - 1)) * (BI * 4) + wi * 256);
             ++pg;
             if (++pch == n_chunks) {
                 pch = 0;
@@ -223,11 +226,11 @@ __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a
     int vstamp = 0;   // pg when this wave issued its pieces of the current tile's value image
     auto issue_vimg = [&](int t) {
         if constexpr (APPLY) {
-            const unsigned char *src = reinterpret_cast<const unsigned char *>(a.vimg) + (int64_t)t * VIMG + l * 16;
+            const unsigned char *src = reinterpret_cast<const unsigned char *>(a.vimg) + (int64_t)t * VIMG;
 #pragma unroll
             for (int q = 0; q * NW < NVP; ++q) {
                 const int pidx = q * NW + w;
-                if (pidx < NVP) dma16(src + pidx * 1024, vimg_off + pidx * 1024);
+                if (pidx < NVP) dma16s(src + pidx * 1024, l16, vimg_off + pidx * 1024);
             }
             vstamp = pg;
         }

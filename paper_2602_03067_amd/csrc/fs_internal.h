@@ -53,6 +53,19 @@ __device__ inline void dma4(const void *g, unsigned lds_off)
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(g), "s"(m) : "memory", "m0");
 }
 
+// The same with a wave-uniform base address (it stays in scalar registers, and so does all the
+// arithmetic that leads to it) and a per-lane byte offset.
+__device__ inline void dma16s(const void *g_uniform, unsigned lane_off, unsigned lds_off)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(g_uniform), "s"(lds_off)
+                 : "memory", "m0");
+}
+__device__ inline void dma4s(const void *g_uniform, unsigned lane_off, unsigned lds_off)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(lane_off), "s"(g_uniform), "s"(lds_off)
+                 : "memory", "m0");
+}
+
 inline int split_ksteps(int64_t d) { return (int)(8 * d + 6 + 15) / 16; }   // 1..9 for d = 1..16
 // Position (in 16-byte units) of piece `piece` inside the record of point `point`: 64-byte records
 // (ks = 2) are rotated so that the eight lanes the LDS serves per cycle read eight different bank
