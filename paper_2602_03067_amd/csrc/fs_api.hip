@@ -253,7 +253,7 @@ fs_status apply_begin(Ctx *c, const fs_problem *prob, float eps, const float *f,
     const int64_t n_str = transposed ? prob->n : prob->m;
     size_t extra = 0;
     switch (choose_path(prob)) {
-    case Path::LowD: extra = lowd_apply_ws(c, n_res, n_str, p); break;
+    case Path::LowD: extra = lowd_apply_ws(c, n_res, n_str, prob->d, p); break;
     case Path::F64: extra = f64_apply_ws(c, n_res, n_str, prob->d, p); break;
     case Path::BF16: extra = bf16_apply_ws(c, n_res, n_str); break;
     }
@@ -791,8 +791,8 @@ fs_status fs_hvp(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f,
         return fail(c, FS_ERR_INVALID_ARG, "out overlaps an input");
     Prepared P;
     const bool lowd = choose_path(prob) == Path::LowD;
-    const size_t ws_f = lowd ? lowd_apply_ws(c, prob->n, prob->m, prob->d) : f64_apply_ws(c, prob->n, prob->m, prob->d, prob->d);
-    const size_t ws_g = lowd ? lowd_apply_ws(c, prob->m, prob->n, prob->d) : f64_apply_ws(c, prob->m, prob->n, prob->d, prob->d);
+    const size_t ws_f = lowd ? lowd_apply_ws(c, prob->n, prob->m, prob->d, prob->d) : f64_apply_ws(c, prob->n, prob->m, prob->d, prob->d);
+    const size_t ws_g = lowd ? lowd_apply_ws(c, prob->m, prob->n, prob->d, prob->d) : f64_apply_ws(c, prob->m, prob->n, prob->d, prob->d);
     const size_t apply_ws = ((ws_f > ws_g ? ws_f : ws_g) + 255) & ~size_t(255);
     char *extra = nullptr;
     if ((st = prepare(c, prob, &P, apply_ws + hvp_scratch_bytes(prob->n, prob->m, prob->d), &extra)) != FS_OK) return st;

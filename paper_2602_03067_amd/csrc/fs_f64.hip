@@ -466,20 +466,38 @@ constexpr int kLseJT = 4, kApplyJT = 2;   // resident blocks per workgroup of th
 constexpr int kLseNW = 8, kApplyNW = 4;   // waves per workgroup
 constexpr int kWgPerCu = 2;               // as in the kernel's launch bounds
 
-PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str, int br, int bc)
+// Launch shape: row blocks x splits of the streamed side.  The split count minimises a makespan
+// model in units of the time a CU needs for one tile: workgroups are dealt to the CUs evenly, a CU
+// with w of them takes w (tiles per split + start-up) tile times (two resident workgroups share the
+// matrix pipe, so each runs at half speed; one alone cannot fill the CU and is charged 1.4x), and
+// every split adds a record per row to the merge.  Filling "twice the CUs" regardless of the size, as
+// the first version did, gave e.g. 628 workgroups on 512 slots at n = 10000: a second round at a
+// quarter of the chip.
+PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str, int br, int bc, int64_t kc)
 {
     PassShape s;
     s.rows_per_block = br;
     s.row_blocks = (int)ceil_div(n_res, br);
-    int n_tiles = (int)ceil_div(n_str, bc);
-    int target = kWgPerCu * c->num_cu;
-    int splits = (int)ceil_div(target, s.row_blocks);
-    if (splits > n_tiles) splits = n_tiles;
-    if (splits > max_splits(n_res)) splits = max_splits(n_res);
-    if (splits < 1) splits = 1;
-    int tps = (int)ceil_div(n_tiles, splits);
-    s.splits = (int)ceil_div(n_tiles, tps);
-    s.cols_per_split = (int64_t)tps * bc;
+    const int n_tiles = (int)ceil_div(n_str, bc);
+    int cap = max_splits(n_res);
+    if (cap > n_tiles) cap = n_tiles;
+    if (cap < 1) cap = 1;
+    const double startup = 64.0 / (double)(kc < 8 ? 8 : kc);   // ~5 us of start-up and wind-down in tile times
+    double best = 0.0;
+    int best_tps = n_tiles;
+    for (int sp = 1; sp <= cap; ++sp) {
+        const int tps = (int)ceil_div(n_tiles, sp);
+        const int eff = (int)ceil_div(n_tiles, tps);
+        if (eff != sp) continue;   // the same shape as a smaller count
+        const int64_t w = ceil_div((int64_t)s.row_blocks * eff, (int64_t)c->num_cu);
+        const double cost = (double)w * ((double)tps + startup) * (w < kWgPerCu ? 1.4 : 1.0) + 0.02 * eff;
+        if (sp == 1 || cost < best * 0.995) {
+            best = cost;
+            best_tps = tps;
+        }
+    }
+    s.splits = (int)ceil_div(n_tiles, best_tps);
+    s.cols_per_split = (int64_t)best_tps * bc;
     return s;
 }
 
@@ -487,7 +505,7 @@ PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str, int br, int bc)
 
 fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out, int prof_kind)
 {
-    PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kLseJT, 16 * kLseNW);
+    PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kLseJT, 16 * kLseNW, P->d);
     constexpr int BC = 16 * kLseNW;
     PassArgs a{};
     a.res = res->pts_d;
@@ -514,16 +532,15 @@ fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, d
 
 size_t f64_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t d, int64_t p)
 {
-    (void)d;
     (void)p;
-    PassShape s = shape_f64(c, n_res, n_str, 16 * kApplyJT, 16 * kApplyNW);
+    PassShape s = shape_f64(c, n_res, n_str, 16 * kApplyJT, 16 * kApplyNW, d);
     return (size_t)s.splits * (size_t)round_up(n_res, 1024) * PCH * 4;
 }
 
 fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, const float *V,
                     int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out, const float *hadA, int64_t lda)
 {
-    PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kApplyJT, 16 * kApplyNW);
+    PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kApplyJT, 16 * kApplyNW, P->d);
     constexpr int BC = 16 * kApplyNW;
     PassArgs a{};
     a.res = res->pts_d;

@@ -267,7 +267,7 @@ fs_status lowd_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
 // both half-steps of an averaged iteration (Eq. 4-5) in one launch; *done = false: not applicable
 fs_status lowd_lse_pair(Ctx *c, const Prepared *P, double eps, void *partial_x, void *partial_y, int *splits_x,
                         int *splits_y, bool *done);
-size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t p);
+size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t d, int64_t p);
 // had_A != nullptr: Hadamard-weighted transport (Alg. 5), every plan entry times <had_A row i, centred
 // streamed point j>; had_A is [res->cnt][lda] floats.
 fs_status lowd_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,

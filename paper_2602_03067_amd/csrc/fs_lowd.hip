@@ -933,15 +933,14 @@ fs_status lowd_lse_pair(Ctx *c, const Prepared *P, double eps, void *partial_x, 
     return FS_OK;
 }
 
-size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t p)
+size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t d, int64_t p)
 {
-    (void)p;
     // the largest of the launch shapes an application can take (split records / vector ALU / fp64 matrix cores)
     const PassShape s1 = shape_for(c, n_res, n_str, kBlock);
     const PassShape s2 = shape_for(c, n_res, n_str, 128 * kSplitR, kSplitTJ);
     const int splits = s1.splits > s2.splits ? s1.splits : s2.splits;
     const size_t own = (size_t)splits * (size_t)round_up(n_res, 1024) * kApplyPC * 4;
-    const size_t f64 = f64_apply_ws(c, n_res, n_str, kLowdMaxD, p);
+    const size_t f64 = d > 3 ? f64_apply_ws(c, n_res, n_str, d, p) : 0;
     return own > f64 ? own : f64;
 }
 
