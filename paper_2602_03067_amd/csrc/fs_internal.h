@@ -174,7 +174,9 @@ struct Side {
     uint16_t *split = nullptr;
     // LowD, d <= 3: "precise" split records [cnt_pad][48] bf16 built from the float64 copy
     uint16_t *split_p = nullptr;
-    // F64: double [cnt_pad][kp], kp = round_up(d, 32) (zero filled), bias in bias_d[cnt_pad]
+    // F64: double [cnt_pad][kp], kp = round_up(d, 32) (zero filled), bias in bias_d[cnt_pad].
+    // LowD with d > 3 keeps the same two arrays (centred coordinates, kp = 32) for its float64-score
+    // passes, which run on the fp64 matrix-core kernels.
     double *pts_d = nullptr;
     double *bias_d = nullptr;
     // BF16: uint16 [cnt_pad][kp], kp = round_up(d, 32), bias in bias_f[cnt_pad]
