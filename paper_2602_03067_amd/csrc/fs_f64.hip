@@ -70,9 +70,12 @@ struct PassArgs {
 // NW: waves per workgroup; a wave owns 16 streamed points of every tile (two 16-point blocks per
 // wave were slower), so a tile has 16 NW points.  The LSE pass runs 8 waves over one resident
 // block (4 waves per SIMD with two workgroups per CU), the application 4.
-template <bool APPLY, bool HAD = false, int NCT = 4, int JT = 4, int NW = 4>
+// LAZY: the stabiliser of the epilogue (see there); the LSE pass uses it for the short contractions it
+// runs on behalf of the low-dimension path, whose scores spread little.
+template <bool APPLY, bool HAD = false, int NCT = 4, int JT = 4, int NW = 4, bool LAZY = APPLY>
 __global__ __launch_bounds__(64 * NW, 2) void k_pass_f64(PassArgs a)
 {
+    static_assert(LAZY || !APPLY, "the application has the lazy stabiliser only");
     constexpr int NT = 64 * NW;   // threads
     constexpr int BC = 16 * NW;   // streamed points per tile
     constexpr int BR = 16 * JT;   // resident rows per workgroup
@@ -226,10 +229,11 @@ __global__ __launch_bounds__(64 * NW, 2) void k_pass_f64(PassArgs a)
 #pragma unroll
         for (int r = 0; r < 4; ++r) bias[r] = bias_lds[sp0 + 4 * r + lg];
 
-        if constexpr (!APPLY) {
+        if constexpr (!LAZY) {
             // every tile lifts the running max (an integer) to the ceiling of its largest score
-            // (the lazy scheme of the application below was measured slower here: 0.605 against
-            // 0.587 ms at n = m = 16384, d = 64, with one check per block, 0.623 with one per tile)
+            // (at d = 64 the lazy scheme below was measured slower: 0.605 against 0.587 ms at n = m = 16384
+            // with one check per block, 0.623 with one per tile; scores that spread over hundreds of
+            // base-2 units send some lane of the wave through its recompute path in many tiles)
 #pragma unroll
             for (int jt = 0; jt < JT; ++jt) {
                 double sc[4];
@@ -522,8 +526,11 @@ fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, d
         (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp % KC) != 0 || a.kc > a.kp)
         return fail(c, FS_ERR_DEVICE, "internal: fp64 launch shape exceeds the padded buffers");
     prof_begin(c, (double)res->cnt * (double)str->cnt, prof_kind);
-    hipLaunchKernelGGL((k_pass_f64<false, false, 4, kLseJT, kLseNW>), dim3((unsigned)s.row_blocks, (unsigned)s.splits), dim3(64 * kLseNW), 0,
-                       c->stream, a);
+    const dim3 grid((unsigned)s.row_blocks, (unsigned)s.splits);
+    if (P->path == Path::LowD)
+        hipLaunchKernelGGL((k_pass_f64<false, false, 4, kLseJT, kLseNW, true>), grid, dim3(64 * kLseNW), 0, c->stream, a);
+    else
+        hipLaunchKernelGGL((k_pass_f64<false, false, 4, kLseJT, kLseNW, false>), grid, dim3(64 * kLseNW), 0, c->stream, a);
     prof_end(c);
     FS_HIP(c, hipGetLastError());
     *splits_out = s.splits;
