@@ -179,3 +179,17 @@ def test_no_gpu_means_loud_failure(lib):
     assert lib.fs_create(ctypes.byref(h), 0, None) == 7
     with pytest.raises(RuntimeError):
         binding.Context(0)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; --gpus 2 (or a multi-rank environment) ends with a message, before
+    anything touches a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+    env = dict(os.environ, WORLD_SIZE="4")
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py")], capture_output=True, text=True, timeout=120, env=env)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr
