@@ -346,3 +346,39 @@ def test_float64_scores_above_three_dimensions(ctx, oracle, n, m, d, p):
     rel = np.linalg.norm(host(G) - wantG) / np.linalg.norm(wantG)
     say("  hvp: %d CG iterations, rel. error %.3e" % (k, rel))
     assert rel <= 1e-4
+
+
+def test_float64_scores_above_three_dimensions_many_blocks(ctx, oracle):
+    """The same kernels at a size with hundreds of row blocks and several splits (n = 30000, m = 21000,
+    d = 8, float64 scores forced), checked by the oracle on sampled rows and columns."""
+    rng = np.random.default_rng(77)
+    n, m, d = 30000, 21000, 8
+    x = rng.random((n, d)).astype(np.float32)
+    y = (rng.random((m, d)) * 0.9 + 0.05).astype(np.float32)
+    a = rng.random(n) + 0.5
+    a = (a / a.sum()).astype(np.float32)
+    b = rng.random(m) + 0.5
+    b = (b / b.sum()).astype(np.float32)
+    eps = float(np.float32(0.05))
+    g = (0.1 * rng.standard_normal(m)).astype(np.float32)
+    f = (0.1 * rng.standard_normal(n)).astype(np.float32)
+    rows = np.sort(rng.choice(n, 200, replace=False))
+    cols = np.sort(rng.choice(m, 200, replace=False))
+    say("float64 scores forced at n=%d m=%d d=%d, sampled rows" % (n, m, d))
+    prob = make_problem(x, y, a, b)
+    old = os.environ.get("FS_LOWD_SCORE")
+    os.environ["FS_LOWD_SCORE"] = "f64"
+    try:
+        f_gpu = host(ctx.fs_update_f(prob, eps, dev(g)))
+        g_gpu = host(ctx.fs_update_g(prob, eps, dev(f)))
+        V = rng.standard_normal((m, 3)).astype(np.float32)
+        out = host(ctx.fs_apply_plan(prob, eps, dev(f_gpu), dev(g), dev(V)))
+    finally:
+        if old is None:
+            os.environ.pop("FS_LOWD_SCORE", None)
+        else:
+            os.environ["FS_LOWD_SCORE"] = old
+    assert max_err_over_eps(f_gpu[rows], oracle.update_f(x, y, b, eps, g, rows=rows), eps) <= TOL
+    assert max_err_over_eps(g_gpu[cols], oracle.update_g(x, y, a, eps, f, cols=cols), eps) <= TOL
+    want = oracle.apply_plan(x, y, a, b, eps, f_gpu, g, V, rows=rows)
+    assert np.linalg.norm(out[rows] - want) <= 2e-4 * np.linalg.norm(want)
