@@ -154,6 +154,15 @@ def main() -> int:
         dtype = "f32"
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = MEASURED_TRAFFIC.get(w.name) if args.n is None else None
+    # the same launch in the other units the workload list asks for: pair evaluations (= exponentials) per
+    # second, and the measured HBM traffic as a rate and as a fraction of the 8 TB/s peak (far from it: the
+    # pass is not HBM-bound; the re-reads of the streamed cloud are served by L2 and the memory-side cache)
+    rates = {"pair_evals_per_s": pairs / (avg_ms * 1e-3), "exp2_per_s": pairs / (avg_ms * 1e-3)}
+    if roof["traffic"]:
+        rates["hbm_GB_per_s"] = roof["traffic"] / (avg_ms * 1e-3) / 1e9
+        rates["hbm_frac_of_peak"] = rates["hbm_GB_per_s"] / 8000.0
+        # one half-step reads both clouds and one potential and writes the other potential
+        rates["algorithmic_min_bytes"] = float((w.n + w.m) * (w.d * (2 if w.compute == "bf16_mfma" else 4) + 4))
     roof["kernel"] = "streaming LSE half-step"
     roof["avg_launch_ms"] = avg_ms
     roof["launches"] = launches
@@ -171,6 +180,7 @@ def main() -> int:
         "apply_ms": {"grad_x": apply_avg["grad_x"], "grad_x_value_columns": w.d,
                      "apply_plan_T": apply_avg["apply_plan_T"], "apply_plan_T_value_columns": int(U.shape[1])},
         "roofline": roof,
+        "rates": rates,
     }
 
     # ---- the float64 oracle on the host cores, on a bounded sample -------------------------
