@@ -49,7 +49,7 @@ typedef enum {
     FS_ERR_INVALID_ARG = 1, /* null pointer, aliasing, bad enum value                  */
     FS_ERR_BAD_SHAPE = 2,   /* n, m, d, p <= 0, ld < d, sizes beyond the supported max */
     FS_ERR_BAD_EPS = 3,     /* eps <= 0 or not finite, n_stages < 1, iters < 0         */
-    FS_ERR_BAD_WEIGHTS = 4, /* reserved for explicit weight validation                 */
+    FS_ERR_BAD_WEIGHTS = 4, /* fs_check_weights: a weight <= 0 or not finite, sum != 1 */
     FS_ERR_UNSUPPORTED = 5, /* dtype/compute combination not available                 */
     FS_ERR_ALLOC = 6,       /* device allocation failed                                */
     FS_ERR_DEVICE = 7       /* a HIP call failed (message in fs_last_error)            */
@@ -193,6 +193,16 @@ fs_status fs_marginal_err(fs_ctx *ctx, const fs_problem *prob, float eps, const 
  */
 fs_status fs_ot_value(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f /* device */,
                       const float *g /* device */, double *value /* host */);
+
+/*
+ * Optional check of the weights (Section 2 takes a and b in the open simplex; the entry points
+ * above do not check this, because it costs a pass over the weights): FS_ERR_BAD_WEIGHTS if a
+ * weight is not positive and finite, or if a or b does not sum to 1 within tol; FS_OK otherwise.
+ * NULL weights (uniform) pass.  sum_a, sum_b: NULL or HOST doubles that receive the sums.
+ * Synchronises the stream when there is something to check.
+ */
+fs_status fs_check_weights(fs_ctx *ctx, const fs_problem *prob, float tol, double *sum_a /* host, nullable */,
+                           double *sum_b /* host, nullable */);
 
 /*
  * Debiased Sinkhorn divergence  S = OT(a,b) - OT(a,a)/2 - OT(b,b)/2  (Section 4.2 uses it as the

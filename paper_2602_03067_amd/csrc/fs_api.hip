@@ -340,6 +340,24 @@ fs_status grad_common(Ctx *c, const fs_problem *prob, float eps, const float *f,
                                 wrt_y ? prob->b : prob->a, mass, mode);
 }
 
+// the context's second buffer (kept across the entry points that lay the workspace out anew), at least `need` bytes
+fs_status ensure_aux(Ctx *c, size_t need)
+{
+    if (need <= c->aux_bytes) return FS_OK;
+    FS_HIP(c, hipStreamSynchronize(c->stream));
+    if (c->aux) {
+        FS_HIP(c, hipFree(c->aux));
+        c->aux = nullptr;
+        c->aux_bytes = 0;
+    }
+    void *pnew = nullptr;
+    hipError_t e = hipMalloc(&pnew, need);
+    if (e != hipSuccess) return fail(c, FS_ERR_ALLOC, "buffer of %zu bytes: %s", need, hipGetErrorString(e));
+    c->aux = (char *)pnew;
+    c->aux_bytes = need;
+    return FS_OK;
+}
+
 }  // namespace
 }  // namespace fs
 
@@ -681,6 +699,35 @@ fs_status fs_ot_value(fs_ctx *ctx, const fs_problem *prob, float eps, const floa
     return FS_OK;
 }
 
+fs_status fs_check_weights(fs_ctx *ctx, const fs_problem *prob, float tol, double *sum_a, double *sum_b)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    fs_status st = validate_problem(c, prob);
+    if (st != FS_OK) return st;
+    if (!(tol >= 0.0f) || !(tol < INFINITY)) return fail(c, FS_ERR_INVALID_ARG, "tol must be finite and >= 0");
+    if (sum_a) *sum_a = 1.0;
+    if (sum_b) *sum_b = 1.0;
+    if (!prob->a && !prob->b) return FS_OK;   // uniform weights on both sides
+    if (c->device < 0) return fail(c, FS_ERR_DEVICE, "host-only context: arguments are valid, nothing was launched");
+    FS_HIP(c, hipSetDevice(c->device));
+    const size_t ba = (size_t)ceil_div(prob->n, 256), bb = (size_t)ceil_div(prob->m, 256);
+    if ((st = ensure_aux(c, (2 * (ba + bb) + 4) * sizeof(double))) != FS_OK) return st;
+    double *res = reinterpret_cast<double *>(c->aux), *scratch = res + 4;
+    double h[4] = {1.0, 0.0, 1.0, 0.0};
+    if (prob->a && (st = launch_weight_stats(c, prob->a, prob->n, scratch, res)) != FS_OK) return st;
+    if (prob->b && (st = launch_weight_stats(c, prob->b, prob->m, scratch + 2 * ba, res + 2)) != FS_OK) return st;
+    if (prob->a) FS_HIP(c, hipMemcpyAsync(h, res, 2 * sizeof(double), hipMemcpyDeviceToHost, c->stream));
+    if (prob->b) FS_HIP(c, hipMemcpyAsync(h + 2, res + 2, 2 * sizeof(double), hipMemcpyDeviceToHost, c->stream));
+    FS_HIP(c, hipStreamSynchronize(c->stream));
+    if (sum_a) *sum_a = h[0];
+    if (sum_b) *sum_b = h[2];
+    if (h[1] > 0.0) return fail(c, FS_ERR_BAD_WEIGHTS, "%.0f weights of a are not positive and finite", h[1]);
+    if (h[3] > 0.0) return fail(c, FS_ERR_BAD_WEIGHTS, "%.0f weights of b are not positive and finite", h[3]);
+    if (fabs(h[0] - 1.0) > (double)tol) return fail(c, FS_ERR_BAD_WEIGHTS, "a sums to %.9g", h[0]);
+    if (fabs(h[2] - 1.0) > (double)tol) return fail(c, FS_ERR_BAD_WEIGHTS, "b sums to %.9g", h[2]);
+    return FS_OK;
+}
+
 fs_status fs_divergence(fs_ctx *ctx, const fs_problem *prob, float eps, int32_t iters, float *f, float *g, double *value,
                         double *terms)
 {
@@ -698,20 +745,7 @@ fs_status fs_divergence(fs_ctx *ctx, const fs_problem *prob, float eps, int32_t 
     // potentials of the two self-terms: the entry points called below lay the workspace out anew, so
     // these live in a buffer of their own
     const int64_t big = prob->n > prob->m ? prob->n : prob->m;
-    const size_t need = (size_t)2 * big * sizeof(float);
-    if (need > c->aux_bytes) {
-        FS_HIP(c, hipStreamSynchronize(c->stream));
-        if (c->aux) {
-            FS_HIP(c, hipFree(c->aux));
-            c->aux = nullptr;
-            c->aux_bytes = 0;
-        }
-        void *pnew = nullptr;
-        hipError_t e = hipMalloc(&pnew, need);
-        if (e != hipSuccess) return fail(c, FS_ERR_ALLOC, "buffer of %zu bytes: %s", need, hipGetErrorString(e));
-        c->aux = (char *)pnew;
-        c->aux_bytes = need;
-    }
+    if ((st = ensure_aux(c, (size_t)2 * big * sizeof(float))) != FS_OK) return st;
     float *sf = reinterpret_cast<float *>(c->aux), *sg = sf + big;
     double v[3] = {0.0, 0.0, 0.0};
     // cross term: OT(a, b)

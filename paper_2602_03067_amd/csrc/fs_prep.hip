@@ -540,6 +540,25 @@ __global__ __launch_bounds__(256) void k_value_terms(const double2 *partial, int
     }
 }
 
+// block sums of the weights (part[0][.]) and of the indicator "not positive and finite" (part[1][.])
+__global__ __launch_bounds__(256) void k_weight_stats(const float *w, int64_t cnt, double *part)
+{
+    __shared__ double sh[256];
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    double t[2] = {0.0, 0.0};
+    if (i < cnt) {
+        const float v = w[i];
+        const bool ok = v > 0.0f && v < INFINITY;
+        t[0] = ok ? (double)v : 0.0;
+        t[1] = ok ? 0.0 : 1.0;
+    }
+    for (int k = 0; k < 2; ++k) {
+        double s = block_sum_256(t[k], sh);
+        if (threadIdx.x == 0) part[(int64_t)k * gridDim.x + blockIdx.x] = s;
+        __syncthreads();
+    }
+}
+
 // block sums of w_i pot_i and w_i: part[0][.], part[1][.]
 __global__ __launch_bounds__(256) void k_weighted_sums(int64_t cnt, const float *w, double log_uniform, const double *pot,
                                                        double *part)
@@ -844,6 +863,18 @@ fs_status launch_finalize_pair(Ctx *c, const Prepared *P, Side *X, const double 
     const FinalizeArgs ax = finalize_args(P, partial_x, X, norm_x, splits_x, eps_cur, eps_next_bias, f_out, nullptr, mix, nullptr);
     const FinalizeArgs ay = finalize_args(P, partial_y, Y, norm_y, splits_y, eps_cur, eps_next_bias, g_out, nullptr, mix, nullptr);
     hipLaunchKernelGGL(k_finalize_pair, dim3((unsigned)(ax.blocks + ay.blocks)), dim3(256), 0, c->stream, ax, ay);
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
+// dst[0] <- sum of the weights, dst[1] <- how many of them are not positive and finite; `scratch` holds
+// 2 * blocks doubles
+fs_status launch_weight_stats(Ctx *c, const float *w, int64_t cnt, double *scratch, double *dst)
+{
+    const unsigned nb = (unsigned)ceil_div(cnt, 256);
+    hipLaunchKernelGGL(k_weight_stats, dim3(nb), dim3(256), 0, c->stream, w, cnt, scratch);
+    hipLaunchKernelGGL(k_sum_to, dim3(1), dim3(256), 0, c->stream, scratch, (int64_t)nb, dst);
+    hipLaunchKernelGGL(k_sum_to, dim3(1), dim3(256), 0, c->stream, scratch + nb, (int64_t)nb, dst + 1);
     FS_HIP(c, hipGetLastError());
     return FS_OK;
 }

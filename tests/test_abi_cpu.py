@@ -181,6 +181,19 @@ def test_no_gpu_means_loud_failure(lib):
         binding.Context(0)
 
 
+def test_check_weights_validation(lib, hctx):
+    sa, sb = ctypes.c_double(), ctypes.c_double()
+    p = _prob()
+    assert lib.fs_check_weights(hctx, None, F(1e-5), None, None) == 1
+    assert lib.fs_check_weights(hctx, ctypes.byref(p), F(-1.0), None, None) == 1
+    assert lib.fs_check_weights(hctx, ctypes.byref(p), F(float("nan")), None, None) == 1
+    # uniform weights on both sides: nothing to check, also without a device
+    assert lib.fs_check_weights(hctx, ctypes.byref(p), F(1e-5), ctypes.byref(sa), ctypes.byref(sb)) == 0
+    assert sa.value == 1.0 and sb.value == 1.0
+    q = _prob(a=1 << 24)
+    assert lib.fs_check_weights(hctx, ctypes.byref(q), F(1e-5), None, None) == 7   # valid: reaches device stage
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py measures one GPU; --gpus 2 (or a multi-rank environment) ends with a message, before
     anything touches a device."""

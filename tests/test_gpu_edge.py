@@ -117,3 +117,32 @@ def test_very_small_eps_low_dimension(oracle, d, eps):
     say("  max|df|/eps=%.3e max|dg|/eps=%.3e" % (ef, eg))
     assert ef <= 1e-4 and eg <= 1e-4
     ctx.close()
+
+
+def test_check_weights(oracle):
+    """fs_check_weights: sums in float64 of the float weights, FS_ERR_BAD_WEIGHTS for a weight that is not
+    positive, and for a sum off by more than the tolerance."""
+    rng = np.random.default_rng(3)
+    n, m, d = 5000, 777, 3
+    x = rng.random((n, d)).astype(np.float32)
+    y = rng.random((m, d)).astype(np.float32)
+    a = rng.random(n) + 0.1
+    a = (a / a.sum()).astype(np.float32)
+    b = np.full(m, 1.0 / m, dtype=np.float32)
+    say("check_weights n=%d m=%d" % (n, m))
+    ctx = binding.Context(0)
+    sa, sb = ctx.fs_check_weights(binding.Problem(dev(x), dev(y), dev(a), dev(b)), 1e-5)
+    assert abs(sa - a.astype(np.float64).sum()) <= 1e-12 and abs(sb - b.astype(np.float64).sum()) <= 1e-12
+    assert ctx.fs_check_weights(binding.Problem(dev(x), dev(y), None, dev(b)), 1e-5)[0] == 1.0
+    bad = a.copy()
+    bad[1234] = 0.0
+    with pytest.raises(binding.FlashSinkError) as e:
+        ctx.fs_check_weights(binding.Problem(dev(x), dev(y), dev(bad), dev(b)), 1e-5)
+    assert e.value.status == 4
+    with pytest.raises(binding.FlashSinkError) as e:
+        ctx.fs_check_weights(binding.Problem(dev(x), dev(y), dev(a), dev((b * 1.01).astype(np.float32))), 1e-5)
+    assert e.value.status == 4
+    bad[1234] = np.nan
+    with pytest.raises(binding.FlashSinkError):
+        ctx.fs_check_weights(binding.Problem(dev(x), dev(y), dev(bad), None), 1e-5)
+    ctx.close()
