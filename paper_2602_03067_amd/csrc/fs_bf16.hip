@@ -18,8 +18,6 @@
 // the row-wise LSE runs inside the lane; lanes/waves are merged once per workgroup.
 #include "fs_internal.h"
 
-#include <stdlib.h>
-
 
 namespace fs {
 namespace {
@@ -59,7 +57,7 @@ struct BfArgs {
 //           run out of phase: one's tile epilogue (vector ALU only) and barrier waits are covered by
 //           the other's MFMAs, at the price of 1.5x the operand traffic per flop.  Measured slower
 //           (8.8 against 7.9 ms at n = m = 70000, d = 784): the operand traffic costs more than the
-//           overlap brings.  Kept selectable (FS_BF16_WJ=1) for experiments.
+//           overlap brings.  The LSE pass is built with WJ = 2 only; the template keeps the parameter.
 //
 // LDS layout of a stage: row r (0..255 streamed, then the resident rows) occupies 64 bytes = four
 // 16-byte pieces; piece p is stored at position p ^ ((r >> 1) & 3), which makes the 8 lanes that
@@ -557,9 +555,8 @@ constexpr int kApplyBJ = 128;   // resident rows per workgroup of the applicatio
 
 fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out)
 {
-    const char *env = getenv("FS_BF16_WJ");   // experiments: force the workgroup shape
-    const int wj = env ? (env[0] == '1' ? 1 : 2) : 2;
-    const int bj = 128 * wj, per_cu = wj == 2 ? 1 : 2;
+    // (a 256 x 128 workgroup tile, two workgroups per CU, was measured slower and is not built)
+    const int bj = 256, per_cu = 1;
     BfArgs a{};
     a.res = res->pts_b;
     a.str = str->pts_b;
@@ -578,10 +575,7 @@ fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
         (size_t)a.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp & 31) != 0 || a.kp < 32)
         return fail(c, FS_ERR_DEVICE, "internal: bf16 launch shape exceeds the padded buffers");
     prof_begin(c, (double)res->cnt * (double)str->cnt);
-    if (wj == 2)
-        hipLaunchKernelGGL((k_lse_bf16<2, 4, 4, 0>), dim3((unsigned)(per * 8)), dim3(512), 0, c->stream, a);
-    else
-        hipLaunchKernelGGL((k_lse_bf16<1, 3, 4, 0>), dim3((unsigned)(per * 8)), dim3(256), 0, c->stream, a);
+    hipLaunchKernelGGL((k_lse_bf16<2, 4, 4, 0>), dim3((unsigned)(per * 8)), dim3(512), 0, c->stream, a);
     prof_end(c);
     FS_HIP(c, hipGetLastError());
     *splits_out = a.splits;

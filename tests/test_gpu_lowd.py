@@ -382,3 +382,30 @@ def test_float64_scores_above_three_dimensions_many_blocks(ctx, oracle):
     assert max_err_over_eps(g_gpu[cols], oracle.update_g(x, y, a, eps, f, cols=cols), eps) <= TOL
     want = oracle.apply_plan(x, y, a, b, eps, f_gpu, g, V, rows=rows)
     assert np.linalg.norm(out[rows] - want) <= 2e-4 * np.linalg.norm(want)
+
+
+@pytest.mark.parametrize("hook,value", [("FS_LOWD_SPLITS", "1"), ("FS_LOWD_SPLITS", "7"), ("FS_LOWD_PRECISE", "valu")])
+def test_alternative_launch_shapes_and_kernels_agree(ctx, oracle, hook, value):
+    """The library's experiment switches (a forced split count of the streamed side; float64 scores on the
+    vector ALU instead of the precise split records) must give the same potentials: a cross-check of the
+    split merge and of the two float64-score kernels at d <= 3."""
+    rng = np.random.default_rng(41)
+    n, m, d = 1500, 5000, 3
+    x, y, a, b = _rand_problem(rng, n, m, d)
+    eps = float(np.float32(0.01))   # small enough for float64 scores
+    g = (0.05 * rng.standard_normal(m)).astype(np.float32)
+    f = (0.05 * rng.standard_normal(n)).astype(np.float32)
+    say("update_f/update_g with %s=%s, n=%d m=%d d=%d eps=%g" % (hook, value, n, m, d, eps))
+    prob = make_problem(x, y, a, b)
+    old = os.environ.get(hook)
+    os.environ[hook] = value
+    try:
+        f_gpu = host(ctx.fs_update_f(prob, eps, dev(g)))
+        g_gpu = host(ctx.fs_update_g(prob, eps, dev(f)))
+    finally:
+        if old is None:
+            os.environ.pop(hook, None)
+        else:
+            os.environ[hook] = old
+    assert max_err_over_eps(f_gpu, oracle.update_f(x, y, b, eps, g), eps) <= TOL
+    assert max_err_over_eps(g_gpu, oracle.update_g(x, y, a, eps, f), eps) <= TOL
