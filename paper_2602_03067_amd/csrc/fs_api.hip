@@ -626,16 +626,24 @@ fs_status fs_solve_symmetric(fs_ctx *ctx, const fs_problem *prob, float eps_in, 
             }
         }
         P.partial = first_partial;
-        if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits_f)) != FS_OK) return st;   // Eq. 4: from the old g
-        P.partial = second_partial;
-        if ((st = run_lse(c, &P, &P.Y, &P.X, eps, &splits_g)) != FS_OK) return st;   // Eq. 5: from the old f
-        // only now are the potentials (and the biases the next iteration streams) replaced
+        const bool f64_kernels = P.path == Path::F64 || (P.path == Path::LowD && P.X.pts_d && P.Y.pts_d);
+        if (f64_kernels) {
+            // (fp64 matrix-core passes, also on behalf of the low-d path at d > 3: both in one launch)
+            if ((st = f64_lse_pair(c, &P, eps, first_partial, second_partial, &splits_f, &splits_g)) != FS_OK) return st;
+        } else {
+            if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits_f)) != FS_OK) return st;   // Eq. 4: from the old g
+            P.partial = second_partial;
+            if ((st = run_lse(c, &P, &P.Y, &P.X, eps, &splits_g)) != FS_OK) return st;   // Eq. 5: from the old f
+        }
+        // only now are the potentials (and the biases the next iteration streams) replaced: both merges in one launch
         P.partial = first_partial;
-        if ((st = finalize(c, &P, &P.X, splits_f, eps, eps_bias, last ? f : nullptr, nullptr, 0.5)) != FS_OK)
-            return st;
-        P.partial = second_partial;
-        if ((st = finalize(c, &P, &P.Y, splits_g, eps, eps_bias, last ? g : nullptr, nullptr, 0.5)) != FS_OK)
-            return st;
+        {
+            const bool fl = P.path == Path::LowD && !lowd_precise(&P, eps);   // which norms the pass was biased with
+            if ((st = launch_finalize_pair(c, &P, &P.X, fl ? P.X.norm_f : P.X.norm, first_partial, splits_f, last ? f : nullptr,
+                                           &P.Y, fl ? P.Y.norm_f : P.Y.norm, second_partial, splits_g, last ? g : nullptr, eps,
+                                           eps_bias, 0.5)) != FS_OK)
+                return st;
+        }
     }
     return FS_OK;
 }

@@ -73,7 +73,7 @@ struct PassArgs {
 // LAZY: the stabiliser of the epilogue (see there); the LSE pass uses it for the short contractions it
 // runs on behalf of the low-dimension path, whose scores spread little.
 template <bool APPLY, bool HAD = false, int NCT = 4, int JT = 4, int NW = 4, bool LAZY = APPLY>
-__global__ __launch_bounds__(64 * NW, 2) void k_pass_f64(PassArgs a)
+__device__ __forceinline__ void pass_f64_body(const PassArgs &a, const int bx, const int by)
 {
     static_assert(LAZY || !APPLY, "the application has the lazy stabiliser only");
     constexpr int NT = 64 * NW;   // threads
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_pass_f64(PassArgs a)
     const int w = tid >> 6, l = tid & 63, lg = l >> 4, lj = l & 15;
     const int kld = a.kp;         // row stride of the records: a multiple of KC, zero beyond the coordinates
     const int kc = a.kc;          // contraction length: coordinates rounded up to 8
-    const int64_t row0 = (int64_t)blockIdx.x * BR;
+    const int64_t row0 = (int64_t)bx * BR;
     const bool res_cached = kc <= KRES;
     const int n_chunks = (kc + KC - 1) / KC;
 
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_pass_f64(PassArgs a)
             for (int ct = 0; ct < NCT; ++ct) O[jt][ct] = d4{0.0, 0.0, 0.0, 0.0};
     }
 
-    const int t_begin = blockIdx.y * a.tiles_per_split;
+    const int t_begin = by * a.tiles_per_split;
     const int t_end = min(a.n_tiles, t_begin + a.tiles_per_split);
 
     // Staging of one (tile, chunk) stage goes through registers: its global loads are issued
@@ -451,7 +451,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_pass_f64(PassArgs a)
         }
         for (int e = tid; e < BR * PCH; e += NT) {
             int r = e >> 6, cc = e & 63;
-            a.opart[((int64_t)blockIdx.y * a.partial_stride + row0 + r) * PCH + cc] = cc < 16 * NCT ? (float)obuf[e] : 0.0f;
+            a.opart[((int64_t)by * a.partial_stride + row0 + r) * PCH + cc] = cc < 16 * NCT ? (float)obuf[e] : 0.0f;
         }
     }
     __syncthreads();
@@ -462,8 +462,25 @@ __global__ __launch_bounds__(64 * NW, 2) void k_pass_f64(PassArgs a)
         double S = 0.0;
 #pragma unroll
         for (int k = 0; k < 4 * NW; ++k) S += (double)sred[tid][k];
-        a.partial[(int64_t)blockIdx.y * a.partial_stride + row0 + tid] = make_double2((double)M, S);
+        a.partial[(int64_t)by * a.partial_stride + row0 + tid] = make_double2((double)M, S);
     }
+}
+
+template <bool APPLY, bool HAD = false, int NCT = 4, int JT = 4, int NW = 4, bool LAZY = APPLY>
+__global__ __launch_bounds__(64 * NW, 2) void k_pass_f64(PassArgs a)
+{
+    pass_f64_body<APPLY, HAD, NCT, JT, NW, LAZY>(a, blockIdx.x, blockIdx.y);
+}
+
+// Both LSE passes of one iteration of the averaged schedule (Eq. 4-5) in one launch: they read the same
+// old potentials, so the row blocks of the f-pass (a0, the first rb0 of the grid) and of the g-pass (a1)
+// share a grid; grid.y covers the larger of the two split counts.
+template <int JT, int NW, bool LAZY>
+__global__ __launch_bounds__(64 * NW, 2) void k_pass_f64_pair(PassArgs a0, PassArgs a1, int rb0, int splits0, int splits1)
+{
+    const bool second = (int)blockIdx.x >= rb0;   // uniform over the workgroup
+    if ((int)blockIdx.y >= (second ? splits1 : splits0)) return;
+    pass_f64_body<false, false, 4, JT, NW, LAZY>(second ? a1 : a0, (int)blockIdx.x - (second ? rb0 : 0), blockIdx.y);
 }
 
 constexpr int kLseJT = 4, kApplyJT = 2;   // resident blocks per workgroup of the two passes
@@ -507,9 +524,11 @@ PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str, int br, int bc, 
 
 }  // namespace
 
-fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out, int prof_kind)
+// arguments and launch shape of an LSE pass (res resident, str streamed) writing its records to `partial`
+static fs_status lse_pass_args(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, void *partial,
+                               PassArgs *out, PassShape *shape)
 {
-    PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kLseJT, 16 * kLseNW, P->d);
+    const PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kLseJT, 16 * kLseNW, P->d);
     constexpr int BC = 16 * kLseNW;
     PassArgs a{};
     a.res = res->pts_d;
@@ -520,11 +539,22 @@ fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, d
     a.cscale = 2.0 * kLog2e / eps;
     a.n_tiles = (int)ceil_div(str->cnt, BC);
     a.tiles_per_split = (int)(s.cols_per_split / BC);
-    a.partial = (double2 *)P->partial;
+    a.partial = (double2 *)partial;
     a.partial_stride = res->cnt_pad;
     if ((int64_t)s.row_blocks * s.rows_per_block > res->cnt_pad || (int64_t)a.n_tiles * BC > str->cnt_pad ||
         (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp % KC) != 0 || a.kc > a.kp)
         return fail(c, FS_ERR_DEVICE, "internal: fp64 launch shape exceeds the padded buffers");
+    *out = a;
+    *shape = s;
+    return FS_OK;
+}
+
+fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out, int prof_kind)
+{
+    PassArgs a;
+    PassShape s;
+    fs_status st = lse_pass_args(c, P, res, str, eps, P->partial, &a, &s);
+    if (st != FS_OK) return st;
     prof_begin(c, (double)res->cnt * (double)str->cnt, prof_kind);
     const dim3 grid((unsigned)s.row_blocks, (unsigned)s.splits);
     if (P->path == Path::LowD)
@@ -534,6 +564,30 @@ fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, d
     prof_end(c);
     FS_HIP(c, hipGetLastError());
     *splits_out = s.splits;
+    return FS_OK;
+}
+
+// The f-pass (records to partial_x) and the g-pass (records to partial_y) of one iteration of the averaged
+// schedule (Eq. 4-5) in ONE launch.
+fs_status f64_lse_pair(Ctx *c, const Prepared *P, double eps, void *partial_x, void *partial_y, int *splits_x, int *splits_y)
+{
+    PassArgs ax, ay;
+    PassShape sx, sy;
+    fs_status st;
+    if ((st = lse_pass_args(c, P, &P->X, &P->Y, eps, partial_x, &ax, &sx)) != FS_OK) return st;
+    if ((st = lse_pass_args(c, P, &P->Y, &P->X, eps, partial_y, &ay, &sy)) != FS_OK) return st;
+    const dim3 grid((unsigned)(sx.row_blocks + sy.row_blocks), (unsigned)(sx.splits > sy.splits ? sx.splits : sy.splits));
+    prof_begin(c, 2.0 * (double)P->X.cnt * (double)P->Y.cnt, P->path == Path::LowD ? 1 : 0);
+    if (P->path == Path::LowD)
+        hipLaunchKernelGGL((k_pass_f64_pair<kLseJT, kLseNW, true>), grid, dim3(64 * kLseNW), 0, c->stream, ax, ay, sx.row_blocks,
+                           sx.splits, sy.splits);
+    else
+        hipLaunchKernelGGL((k_pass_f64_pair<kLseJT, kLseNW, false>), grid, dim3(64 * kLseNW), 0, c->stream, ax, ay, sx.row_blocks,
+                           sx.splits, sy.splits);
+    prof_end(c);
+    FS_HIP(c, hipGetLastError());
+    *splits_x = sx.splits;
+    *splits_y = sy.splits;
     return FS_OK;
 }
 

@@ -281,6 +281,8 @@ fs_status lowd_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str
 // (prof_kind: how the launch is booked by the profiling hooks, see Ctx::ev_kind)
 fs_status f64_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,
                   int *splits_out, int prof_kind = 0);
+fs_status f64_lse_pair(Ctx *c, const Prepared *P, double eps, void *partial_x, void *partial_y, int *splits_x,
+                       int *splits_y);
 size_t f64_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t d, int64_t p);
 fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,
                     const float *V, int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out,
