@@ -630,6 +630,8 @@ fs_status fs_solve_symmetric(fs_ctx *ctx, const fs_problem *prob, float eps_in, 
         if (f64_kernels) {
             // (fp64 matrix-core passes, also on behalf of the low-d path at d > 3: both in one launch)
             if ((st = f64_lse_pair(c, &P, eps, first_partial, second_partial, &splits_f, &splits_g)) != FS_OK) return st;
+        } else if (P.path == Path::BF16) {
+            if ((st = bf16_lse_pair(c, &P, eps, first_partial, second_partial, &splits_f, &splits_g)) != FS_OK) return st;
         } else {
             if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits_f)) != FS_OK) return st;   // Eq. 4: from the old g
             P.partial = second_partial;

@@ -89,7 +89,7 @@ constexpr int kVRow = 520;                       // bytes per value column in th
 constexpr int kVImgBytes(int pc) { return (pc * kVRow + 1023) / 1024 * 1024; }
 
 template <int WJ, int NS, int JTW, int PC>
-__global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a)
+__device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
 {
     constexpr bool APPLY = PC > 0;
     constexpr int BJ = 32 * JTW * WJ;            // resident rows per workgroup
@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a
     // each XCD gets a contiguous, equally long run of the work list, which is ordered in patches of
     // 8 resident tiles x 8 splits (clipped at the edges), so that the workgroups running on an
     // XCD at any time share their panels through that XCD's L2.
-    const int b = blockIdx.x;
+    const int b = block;
     const int total = a.n_jtiles * a.splits;
     const int per = (total + 7) >> 3;
     const int lb = b >> 3;
@@ -511,6 +511,22 @@ __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a
     }
 }
 
+template <int WJ, int NS, int JTW, int PC>
+__global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a)
+{
+    lse_bf16_body<WJ, NS, JTW, PC>(a, blockIdx.x);
+}
+
+// Both LSE passes of one iteration of the averaged schedule (Eq. 4-5) in one launch: the first `blocks0`
+// workgroups (a multiple of 8, so that the dealing to XCDs is the same as in a launch of its own) run the
+// f-pass, the others the g-pass.
+template <int WJ, int NS, int JTW>
+__global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16_pair(BfArgs a0, BfArgs a1, int blocks0)
+{
+    const bool second = (int)blockIdx.x >= blocks0;   // uniform over the workgroup
+    lse_bf16_body<WJ, NS, JTW, 0>(second ? a1 : a0, (int)blockIdx.x - (second ? blocks0 : 0));
+}
+
 // Value image of every streamed tile for the plan application: bf16 Vt[c][i], c < pc value columns
 // starting at p0, i < 256 points of tile t, rows of kVRow bytes, one image per img_bytes; zero
 // outside the matrix.  (The pad bytes are copied to LDS with the rest and never read.)
@@ -553,7 +569,9 @@ constexpr int kApplyBJ = 128;   // resident rows per workgroup of the applicatio
 
 }  // namespace
 
-fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out)
+// arguments of an LSE pass (res resident, str streamed) writing its records to `partial`; *blocks = its grid
+static fs_status lse_pass_args(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, void *partial, BfArgs *out,
+                               int *blocks)
 {
     // (a 256 x 128 workgroup tile, two workgroups per CU, was measured slower and is not built)
     const int bj = 256, per_cu = 1;
@@ -568,17 +586,56 @@ fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
     a.splits = choose_splits(c, a.n_jtiles, a.n_itiles, max_splits(res->cnt), per_cu);
     a.tiles_per_split = (int)ceil_div(a.n_itiles, a.splits);
     const int total = a.n_jtiles * a.splits;
-    const int per = (total + 7) / 8;
-    a.partial = (double2 *)P->partial;
+    a.partial = (double2 *)partial;
     a.partial_stride = res->cnt_pad;
     if ((int64_t)a.n_jtiles * bj > res->cnt_pad || (int64_t)a.n_itiles * BI > str->cnt_pad ||
         (size_t)a.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp & 31) != 0 || a.kp < 32)
         return fail(c, FS_ERR_DEVICE, "internal: bf16 launch shape exceeds the padded buffers");
+    *out = a;
+    *blocks = (total + 7) / 8 * 8;
+    return FS_OK;
+}
+
+fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits_out)
+{
+    BfArgs a;
+    int blocks = 0;
+    fs_status st = lse_pass_args(c, P, res, str, eps, P->partial, &a, &blocks);
+    if (st != FS_OK) return st;
     prof_begin(c, (double)res->cnt * (double)str->cnt);
-    hipLaunchKernelGGL((k_lse_bf16<2, 4, 4, 0>), dim3((unsigned)(per * 8)), dim3(512), 0, c->stream, a);
+    hipLaunchKernelGGL((k_lse_bf16<2, 4, 4, 0>), dim3((unsigned)blocks), dim3(512), 0, c->stream, a);
     prof_end(c);
     FS_HIP(c, hipGetLastError());
     *splits_out = a.splits;
+    return FS_OK;
+}
+
+// The f-pass (records to partial_x) and the g-pass (records to partial_y) of one iteration of the averaged
+// schedule (Eq. 4-5) in ONE launch.
+fs_status bf16_lse_pair(Ctx *c, const Prepared *P, double eps, void *partial_x, void *partial_y, int *splits_x, int *splits_y)
+{
+    BfArgs ax, ay;
+    int bx = 0, by = 0;
+    fs_status st;
+    if ((st = lse_pass_args(c, P, &P->X, &P->Y, eps, partial_x, &ax, &bx)) != FS_OK) return st;
+    if ((st = lse_pass_args(c, P, &P->Y, &P->X, eps, partial_y, &ay, &by)) != FS_OK) return st;
+    if (bx + by <= 4 * c->num_cu) {
+        prof_begin(c, 2.0 * (double)P->X.cnt * (double)P->Y.cnt);
+        hipLaunchKernelGGL((k_lse_bf16_pair<2, 4, 4>), dim3((unsigned)(bx + by)), dim3(512), 0, c->stream, ax, ay, bx);
+        prof_end(c);
+    } else {
+        // many rounds of workgroups: one launch saves nothing there, and two passes of different shape in one
+        // grid share the L2 of an XCD worse than one after the other (n = 50000, m = 20000, d = 1024: 4 % slower)
+        prof_begin(c, (double)P->X.cnt * (double)P->Y.cnt);
+        hipLaunchKernelGGL((k_lse_bf16<2, 4, 4, 0>), dim3((unsigned)bx), dim3(512), 0, c->stream, ax);
+        prof_end(c);
+        prof_begin(c, (double)P->X.cnt * (double)P->Y.cnt);
+        hipLaunchKernelGGL((k_lse_bf16<2, 4, 4, 0>), dim3((unsigned)by), dim3(512), 0, c->stream, ay);
+        prof_end(c);
+    }
+    FS_HIP(c, hipGetLastError());
+    *splits_x = ax.splits;
+    *splits_y = ay.splits;
     return FS_OK;
 }
 

@@ -291,6 +291,8 @@ fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str,
 // fs_bf16.hip
 fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps,
                    int *splits_out);
+fs_status bf16_lse_pair(Ctx *c, const Prepared *P, double eps, void *partial_x, void *partial_y, int *splits_x,
+                        int *splits_y);
 // plan application in bf16 mode (Alg. 2 / Alg. 4): workspace bytes and the pass itself
 size_t bf16_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str);
 fs_status bf16_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, const float *V, int64_t p,
