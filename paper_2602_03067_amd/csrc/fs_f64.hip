@@ -24,6 +24,7 @@ namespace fs {
 namespace {
 
 typedef double d4 __attribute__((ext_vector_type(4)));
+typedef float f4 __attribute__((ext_vector_type(4)));
 typedef double d2 __attribute__((ext_vector_type(2)));   // staging registers: a plain vector type, so that they stay registers
 
 constexpr int KC = 32;     // contraction chunk staged for the streamed points
@@ -113,7 +114,10 @@ __device__ __forceinline__ void pass_f64_body(const PassArgs &a, const int bx, c
     }
 
     float mrun[JT], srun[JT];
-    d4 O[APPLY ? JT : 1][APPLY ? NCT : 1];
+    // Output accumulators of the second contraction, in fp32: E <= 2^60 and V are floats, a register adds a
+    // few thousand products, and fp32 MFMAs take half the time and half the registers of fp64 ones.
+    // v_mfma_f32_16x16x4_f32: A and B as in the fp64 form, D: lane l, register r holds D[4 (l / 16) + r][l % 16].
+    f4 O[APPLY ? JT : 1][APPLY ? NCT : 1];
 #pragma unroll
     for (int jt = 0; jt < JT; ++jt) {
         mrun[jt] = kNegInit;
@@ -123,7 +127,7 @@ __device__ __forceinline__ void pass_f64_body(const PassArgs &a, const int bx, c
 #pragma unroll
         for (int jt = 0; jt < JT; ++jt)
 #pragma unroll
-            for (int ct = 0; ct < NCT; ++ct) O[jt][ct] = d4{0.0, 0.0, 0.0, 0.0};
+            for (int ct = 0; ct < NCT; ++ct) O[jt][ct] = f4{0.0f, 0.0f, 0.0f, 0.0f};
     }
 
     const int t_begin = by * a.tiles_per_split;
@@ -289,10 +293,10 @@ __device__ __forceinline__ void pass_f64_body(const PassArgs &a, const int bx, c
                 if constexpr (APPLY) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        // accumulator register r holds resident row 4r + lg of this column block
-                        const double scd = (double)__shfl(scale, 4 * r + lg, 64);
+                        // output register r holds resident row 4 lg + r of this column block
+                        const float scr = __shfl(scale, 4 * lg + r, 64);
 #pragma unroll
-                        for (int ct = 0; ct < NCT; ++ct) O[jt][ct][r] *= scd;
+                        for (int ct = 0; ct < NCT; ++ct) O[jt][ct][r] *= scr;
                     }
                 }
                 md = (double)mnew;
@@ -307,12 +311,12 @@ __device__ __forceinline__ void pass_f64_body(const PassArgs &a, const int bx, c
             if constexpr (APPLY) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    double E = (double)e[r];
-                    if constexpr (HAD) E *= accW[jt][r];
+                    float E = e[r];
+                    if constexpr (HAD) E *= (float)accW[jt][r];
 #pragma unroll
                     for (int ct = 0; ct < NCT; ++ct) {
-                        double vv = (double)vt[(sp0 + 4 * r + lg) * PCH + 16 * ct + lj];
-                        O[jt][ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(E, vv, O[jt][ct], 0, 0, 0);
+                        const float vv = vt[(sp0 + 4 * r + lg) * PCH + 16 * ct + lj];
+                        O[jt][ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(E, vv, O[jt][ct], 0, 0, 0);
                     }
                 }
             }
@@ -434,7 +438,7 @@ __device__ __forceinline__ void pass_f64_body(const PassArgs &a, const int bx, c
                 for (int jt = 0; jt < JT; ++jt)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        int row = 16 * jt + 4 * r + lg;
+                        int row = 16 * jt + 4 * lg + r;
                         float M = mw[0][row];
 #pragma unroll
                         for (int w2 = 1; w2 < NW; ++w2) M = fmaxf(M, mw[w2][row]);
@@ -442,7 +446,7 @@ __device__ __forceinline__ void pass_f64_body(const PassArgs &a, const int bx, c
 #pragma unroll
                         for (int ct = 0; ct < NCT; ++ct) {
                             int idx = row * PCH + 16 * ct + lj;
-                            double v = O[jt][ct][r] * sc;
+                            double v = (double)O[jt][ct][r] * sc;
                             obuf[idx] = (ww == 0) ? v : obuf[idx] + v;
                         }
                     }
