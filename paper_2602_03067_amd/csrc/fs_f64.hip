@@ -470,8 +470,9 @@ __device__ __forceinline__ void pass_f64_body(const PassArgs &a, const int bx, c
     }
 }
 
+// (the plain application needs at most 158 registers and 51 KB of LDS: three workgroups per CU)
 template <bool APPLY, bool HAD = false, int NCT = 4, int JT = 4, int NW = 4, bool LAZY = APPLY>
-__global__ __launch_bounds__(64 * NW, 2) void k_pass_f64(PassArgs a)
+__global__ __launch_bounds__(64 * NW, (APPLY && !HAD) ? 3 : 2) void k_pass_f64(PassArgs a)
 {
     pass_f64_body<APPLY, HAD, NCT, JT, NW, LAZY>(a, blockIdx.x, blockIdx.y);
 }
@@ -489,7 +490,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_pass_f64_pair(PassArgs a0, PassA
 
 constexpr int kLseJT = 4, kApplyJT = 2;   // resident blocks per workgroup of the two passes
 constexpr int kLseNW = 8, kApplyNW = 4;   // waves per workgroup
-constexpr int kWgPerCu = 2;               // as in the kernel's launch bounds
+constexpr int kLseWgPerCu = 2, kApplyWgPerCu = 3;   // as in the kernels' launch bounds (the Hadamard variant: 2)
 
 // Launch shape: row blocks x splits of the streamed side.  The split count minimises a makespan
 // model in units of the time a CU needs for one tile: workgroups are dealt to the CUs evenly, a CU
@@ -498,7 +499,7 @@ constexpr int kWgPerCu = 2;               // as in the kernel's launch bounds
 // every split adds a record per row to the merge.  Filling "twice the CUs" regardless of the size, as
 // the first version did, gave e.g. 628 workgroups on 512 slots at n = 10000: a second round at a
 // quarter of the chip.
-PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str, int br, int bc, int64_t kc)
+PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str, int br, int bc, int64_t kc, int wg_per_cu)
 {
     PassShape s;
     s.rows_per_block = br;
@@ -515,7 +516,13 @@ PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str, int br, int bc, 
         const int eff = (int)ceil_div(n_tiles, tps);
         if (eff != sp) continue;   // the same shape as a smaller count
         const int64_t w = ceil_div((int64_t)s.row_blocks * eff, (int64_t)c->num_cu);
-        const double cost = (double)w * ((double)tps + startup) * (w < kWgPerCu ? 1.4 : 1.0) + 0.02 * eff;
+        // workgroups of a CU run wg_per_cu at a time; an incomplete last batch cannot fill the CU: one
+        // workgroup alone is charged 1.4x, two of three 1.08x (measured on the plan application)
+        // (with two per CU the charge applies to a single workgroup only: a third one running alone at the
+        // end measured cheaper than the coarser split that avoids it, n = m = 10000, d = 64: 0.46 against 0.49 ms)
+        const int64_t rem = (w < wg_per_cu || wg_per_cu >= 3) ? w % wg_per_cu : 0;
+        const double units = (double)(w - rem) + (double)rem * (rem == 1 ? 1.4 : 1.08);
+        const double cost = units * ((double)tps + startup) + 0.02 * eff;
         if (sp == 1 || cost < best * 0.995) {
             best = cost;
             best_tps = tps;
@@ -532,7 +539,7 @@ PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str, int br, int bc, 
 static fs_status lse_pass_args(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, void *partial,
                                PassArgs *out, PassShape *shape)
 {
-    const PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kLseJT, 16 * kLseNW, P->d);
+    const PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kLseJT, 16 * kLseNW, P->d, kLseWgPerCu);
     constexpr int BC = 16 * kLseNW;
     PassArgs a{};
     a.res = res->pts_d;
@@ -598,14 +605,16 @@ fs_status f64_lse_pair(Ctx *c, const Prepared *P, double eps, void *partial_x, v
 size_t f64_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t d, int64_t p)
 {
     (void)p;
-    PassShape s = shape_f64(c, n_res, n_str, 16 * kApplyJT, 16 * kApplyNW, d);
-    return (size_t)s.splits * (size_t)round_up(n_res, 1024) * PCH * 4;
+    // the larger of the shapes of the plain and of the Hadamard-weighted application
+    const PassShape s1 = shape_f64(c, n_res, n_str, 16 * kApplyJT, 16 * kApplyNW, d, kApplyWgPerCu);
+    const PassShape s2 = shape_f64(c, n_res, n_str, 16 * kApplyJT, 16 * kApplyNW, d, 2);
+    return (size_t)(s1.splits > s2.splits ? s1.splits : s2.splits) * (size_t)round_up(n_res, 1024) * PCH * 4;
 }
 
 fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, const float *V,
                     int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out, const float *hadA, int64_t lda)
 {
-    PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kApplyJT, 16 * kApplyNW, P->d);
+    PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kApplyJT, 16 * kApplyNW, P->d, hadA ? 2 : kApplyWgPerCu);
     constexpr int BC = 16 * kApplyNW;
     PassArgs a{};
     a.res = res->pts_d;
