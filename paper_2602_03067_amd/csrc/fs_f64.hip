@@ -35,7 +35,7 @@ constexpr int KRES = 64;   // resident coordinates kept in LDS across the pass
 constexpr int LDR = KRES + 2;
 constexpr int LDS_ = KC + 2;
 constexpr int kReadAhead = 16;  // the operand reads run one contraction step ahead of the MFMAs: slack behind the arrays
-constexpr int PCH = 64;    // value columns per application pass
+constexpr int PCH = 64;    // value columns per application pass (128 in the wide form, see the kernel)
 
 __device__ inline float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
 
@@ -83,7 +83,12 @@ __device__ __forceinline__ void pass_f64_body(const PassArgs &a, const int bx, c
     __shared__ __attribute__((aligned(16))) double res_lds[BR * LDR + kReadAhead];   // 33.8 KB (JT = 4); reused for the final merge
     __shared__ __attribute__((aligned(16))) double str_lds[BC * LDS_ + kReadAhead];  // 17.4 KB: 16 points per wave, wave-private
     __shared__ double bias_lds[BC];
-    __shared__ float vt[APPLY ? BC * PCH : 1];    // 16,384 B (application)
+    // value columns of a pass: 64, or 128 in the wide form (NCT > 4: twice the output registers, two workgroups
+    // per CU), which halves the passes -- and the repeated score contractions -- of an application with p > 64
+    constexpr int PCH = NCT > 4 ? 128 : 64;
+    constexpr int NVQ = PCH / 64;                 // value columns per lane and streamed point
+    static_assert(NCT >= 1 && NCT <= 8 && (!HAD || NCT <= 4), "column blocks of a pass");
+    __shared__ __attribute__((aligned(16))) float vt[APPLY ? BC * PCH : 1];    // 16 or 32 KB (application)
     __shared__ __attribute__((aligned(16))) double had_lds[HAD ? BR * LDR + kReadAhead : 1];  // rows of hadA, laid out like res_lds
     // final merge: per-wave running max and per-(wave, lane group) sums, on top of the streamed
     // staging area, which is free by then (this keeps the LSE pass at three workgroups per CU)
@@ -151,7 +156,7 @@ __device__ __forceinline__ void pass_f64_body(const PassArgs &a, const int bx, c
     // value rows of the tile go through registers too, except in the Hadamard variant, which has
     // no registers to spare and loads them at the store instead
     constexpr bool VPRE = APPLY && !HAD;
-    float pre_v[VPRE ? 16 : 1];
+    float pre_v[VPRE ? 16 * NVQ : 1];
     const int sk = (l & 15) * 2;                  // coordinate pair of this thread within a chunk
     const int toff_s = (16 * w + lg) * kld + sk;  // streamed: point 16 w + 4 q + lg of the tile
     const int sp = tid >> 4;
@@ -181,7 +186,11 @@ __device__ __forceinline__ void pass_f64_body(const PassArgs &a, const int bx, c
 #pragma unroll
                 for (int q = 0; q < 16; ++q) {
                     const int64_t j = col0 + 16 * w + q;
-                    pre_v[q] = (j < a.n_str && a.p0 + l < a.p) ? a.V[j * a.ldv + a.p0 + l] : 0.0f;
+#pragma unroll
+                    for (int h = 0; h < NVQ; ++h) {
+                        const int cc = a.p0 + l + 64 * h;
+                        pre_v[q * NVQ + h] = (j < a.n_str && cc < a.p) ? a.V[j * a.ldv + cc] : 0.0f;
+                    }
                 }
             }
         }
@@ -202,7 +211,9 @@ __device__ __forceinline__ void pass_f64_body(const PassArgs &a, const int bx, c
         if constexpr (VPRE) {
             if (ch == 0) {
 #pragma unroll
-                for (int q = 0; q < 16; ++q) vt[(16 * w + q) * PCH + l] = pre_v[q];
+                for (int q = 0; q < 16; ++q)
+#pragma unroll
+                    for (int h = 0; h < NVQ; ++h) vt[(16 * w + q) * PCH + l + 64 * h] = pre_v[q * NVQ + h];
             }
         } else if constexpr (APPLY) {
             if (ch == 0) {
@@ -431,7 +442,10 @@ __device__ __forceinline__ void pass_f64_body(const PassArgs &a, const int bx, c
         sred[r][4 * w + lg] = srun[jt] * fast_exp2(mrun[jt] - M);
     }
     if constexpr (APPLY) {
-        double *obuf = res_lds;   // [BR][PCH] doubles = 32 KB <= sizeof(res_lds)
+        // [BR][PCH] doubles: on top of the resident rows, or (wide form) of the value rows
+        static_assert(NCT > 4 ? sizeof(double) * BR * PCH <= sizeof(float) * BC * PCH : sizeof(double) * BR * PCH <= sizeof(double) * BR * LDR,
+                      "merge buffer of the outputs");
+        double *obuf = NCT > 4 ? reinterpret_cast<double *>(vt) : res_lds;
         for (int ww = 0; ww < NW; ++ww) {
             if (w == ww) {
 #pragma unroll
@@ -454,7 +468,7 @@ __device__ __forceinline__ void pass_f64_body(const PassArgs &a, const int bx, c
             __syncthreads();
         }
         for (int e = tid; e < BR * PCH; e += NT) {
-            int r = e >> 6, cc = e & 63;
+            int r = e / PCH, cc = e % PCH;
             a.opart[((int64_t)by * a.partial_stride + row0 + r) * PCH + cc] = cc < 16 * NCT ? (float)obuf[e] : 0.0f;
         }
     }
@@ -472,7 +486,7 @@ __device__ __forceinline__ void pass_f64_body(const PassArgs &a, const int bx, c
 
 // (the plain application needs at most 158 registers and 51 KB of LDS: three workgroups per CU)
 template <bool APPLY, bool HAD = false, int NCT = 4, int JT = 4, int NW = 4, bool LAZY = APPLY>
-__global__ __launch_bounds__(64 * NW, (APPLY && !HAD) ? 3 : 2) void k_pass_f64(PassArgs a)
+__global__ __launch_bounds__(64 * NW, (APPLY && !HAD && NCT <= 4) ? 3 : 2) void k_pass_f64(PassArgs a)
 {
     pass_f64_body<APPLY, HAD, NCT, JT, NW, LAZY>(a, blockIdx.x, blockIdx.y);
 }
@@ -602,19 +616,20 @@ fs_status f64_lse_pair(Ctx *c, const Prepared *P, double eps, void *partial_x, v
     return FS_OK;
 }
 
+constexpr int kWidePCH = 128;   // value columns of a pass of the wide form
+
 size_t f64_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t d, int64_t p)
 {
     (void)p;
-    // the larger of the shapes of the plain and of the Hadamard-weighted application
+    // the larger of the shapes of the plain and of the Hadamard-weighted / wide application, at the wide row length
     const PassShape s1 = shape_f64(c, n_res, n_str, 16 * kApplyJT, 16 * kApplyNW, d, kApplyWgPerCu);
     const PassShape s2 = shape_f64(c, n_res, n_str, 16 * kApplyJT, 16 * kApplyNW, d, 2);
-    return (size_t)(s1.splits > s2.splits ? s1.splits : s2.splits) * (size_t)round_up(n_res, 1024) * PCH * 4;
+    return (size_t)(s1.splits > s2.splits ? s1.splits : s2.splits) * (size_t)round_up(n_res, 1024) * kWidePCH * 4;
 }
 
 fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, const float *V,
                     int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out, const float *hadA, int64_t lda)
 {
-    PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kApplyJT, 16 * kApplyNW, P->d, hadA ? 2 : kApplyWgPerCu);
     constexpr int BC = 16 * kApplyNW;
     PassArgs a{};
     a.res = res->pts_d;
@@ -624,7 +639,6 @@ fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str,
     a.kc = (int)round_up(P->d, 8);
     a.cscale = 2.0 * kLog2e / eps;
     a.n_tiles = (int)ceil_div(str->cnt, BC);
-    a.tiles_per_split = (int)(s.cols_per_split / BC);
     a.partial = (double2 *)P->partial;
     a.partial_stride = res->cnt_pad;
     a.V = V;
@@ -636,14 +650,20 @@ fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str,
     a.lda = lda;
     a.n_res = res->cnt;
     a.d = (int)P->d;
-    if ((int64_t)s.row_blocks * s.rows_per_block > res->cnt_pad || (int64_t)a.n_tiles * BC > str->cnt_pad ||
-        (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp % KC) != 0 || a.kc > a.kp ||
-        (size_t)s.splits * res->cnt_pad * PCH * 4 > P->extra_bytes)
-        return fail(c, FS_ERR_DEVICE, "internal: fp64 apply launch shape exceeds the padded buffers");
-    for (int p0 = 0; p0 < p; p0 += PCH) {
+    for (int p0 = 0; p0 < p;) {
         a.p0 = p0;
+        // more than 64 columns left: a wide pass (128 columns) -- every pass repeats the score contraction
+        const bool wide = !hadA && p - p0 > PCH;
+        const int width = wide ? kWidePCH : PCH;
+        const int cols = (int)(p - p0 < width ? p - p0 : width);
+        const int nct = (int)ceil_div(cols, 16);
+        const PassShape s = shape_f64(c, res->cnt, str->cnt, 16 * kApplyJT, BC, P->d, (hadA || wide) ? 2 : kApplyWgPerCu);
+        a.tiles_per_split = (int)(s.cols_per_split / BC);
+        if ((int64_t)s.row_blocks * s.rows_per_block > res->cnt_pad || (int64_t)a.n_tiles * BC > str->cnt_pad ||
+            (size_t)s.splits * res->cnt_pad * 16 > P->partial_bytes || (a.kp % KC) != 0 || a.kc > a.kp ||
+            (size_t)s.splits * res->cnt_pad * width * 4 > P->extra_bytes)
+            return fail(c, FS_ERR_DEVICE, "internal: fp64 apply launch shape exceeds the padded buffers");
         const dim3 grid((unsigned)s.row_blocks, (unsigned)s.splits);
-        const int nct = (int)ceil_div((p - p0 < PCH ? p - p0 : (int64_t)PCH), 16);
 #define FS_F64_APPLY(H, N) hipLaunchKernelGGL((k_pass_f64<true, H, N, kApplyJT, kApplyNW>), grid, dim3(64 * kApplyNW), 0, c->stream, a)
         if (hadA) {
             switch (nct) {
@@ -657,13 +677,18 @@ fs_status f64_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str,
             case 1: FS_F64_APPLY(false, 1); break;
             case 2: FS_F64_APPLY(false, 2); break;
             case 3: FS_F64_APPLY(false, 3); break;
-            default: FS_F64_APPLY(false, 4); break;
+            case 4: FS_F64_APPLY(false, 4); break;
+            case 5: FS_F64_APPLY(false, 5); break;
+            case 6: FS_F64_APPLY(false, 6); break;
+            case 7: FS_F64_APPLY(false, 7); break;
+            default: FS_F64_APPLY(false, 8); break;
             }
         }
 #undef FS_F64_APPLY
-        fs_status st = launch_apply_finalize(c, P, res, res->norm, s.splits, eps, a.opart, PCH, p0, (int)p, out, ldo,
+        fs_status st = launch_apply_finalize(c, P, res, res->norm, s.splits, eps, a.opart, width, p0, (int)p, out, ldo,
                                              mass_out);
         if (st != FS_OK) return st;
+        p0 += width;
     }
     FS_HIP(c, hipGetLastError());
     return FS_OK;
