@@ -29,7 +29,7 @@ PEAKS = {"bf16": 2.5e15, "f64": 78.6e12}
 # this script on the default size of each workload, scaled by what the same counters read for a
 # 1 GiB device copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); the summaries are under profiles/.
 MEASURED_TRAFFIC = {"lowdim_anneal": 191.85e6, "mnist_shape": 16258.16e6, "embedding": 4384.08e6,
-                    "transport_grad": 77.15e6}
+                    "transport_grad": 77.17e6}
 
 
 def algorithmic_slots_per_pair(exp_cost: float = 4.0) -> float:
