@@ -35,7 +35,10 @@ def _problem(rng, n, m, d, scale):
                                              # very different split counts of the two passes that share a launch
                                              (2100, 150, 3, 0.2, 6), (77, 6000, 3, 0.3, 6),
                                              (500, 900, 3, 0.01, 8),   # float64-score half-steps
-                                             (200, 333, 40, 2.0, 15), (130, 257, 64, 1.0, 8)])     # fp64 MFMA pass
+                                             (200, 333, 40, 2.0, 15), (130, 257, 64, 1.0, 8),      # fp64 MFMA pass
+                                             # the paired fp64 pass with very different shapes of its two halves,
+                                             # and on behalf of the low-d path (float64 scores at d = 8)
+                                             (2100, 150, 64, 1.0, 5), (90, 5000, 40, 2.0, 5), (700, 400, 8, 0.03, 5)])
 def test_symmetric_fp32_mode(ctx, oracle, n, m, d, eps, iters):
     rng = np.random.default_rng(1000 * n + m + d)
     x, y, a, b = _problem(rng, n, m, d, 1.0 if d <= 16 else 0.5)
@@ -69,9 +72,9 @@ def test_symmetric_equal_clouds_keep_f_equal_g(ctx, oracle):
     assert max_err_over_eps(host(f), fo, eps) <= 1e-4
 
 
-def test_symmetric_bf16_mode(ctx, oracle):
-    rng = np.random.default_rng(77)
-    n, m, d = 300, 520, 96
+@pytest.mark.parametrize("n,m,d", [(300, 520, 96), (3000, 260, 64)])
+def test_symmetric_bf16_mode(ctx, oracle, n, m, d):
+    rng = np.random.default_rng(77 + n)
     x, y, a, b = _problem(rng, n, m, d, 0.3)
     eps = float(np.float32(1.5))
     iters = 10
