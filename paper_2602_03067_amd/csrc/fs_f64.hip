@@ -13,7 +13,10 @@
 // the online LSE of Alg. 1 runs inside the lane, and lanes are merged only once, at the end.
 // For plan application (Alg. 2/4) the exponentiated tile is, register by register, already
 // in A-operand layout for the second contraction  O[j][c] += sum_i E[i][j] V[i][c]  (k = l/16
-// <-> i = 4r + k), so P never leaves the registers.
+// <-> i = 4r + k), so P never leaves the registers.  That second contraction runs on the fp32 matrix
+// cores (v_mfma_f32_16x16x4_f32, operands laid out as above, D: lane l, register r holds
+// D[4 (l/16) + r][l%16]): exponentials and values are floats, and fp32 accumulators take half the
+// time and half the registers.
 //
 // Workgroup: 4 or 8 waves; 64 (LSE) or 32 (application) resident rows in column blocks j of 16 x
 // tiles of 16 streamed points per wave.  The resident block lives in LDS for the whole pass when
