@@ -52,7 +52,8 @@ typedef enum {
     FS_ERR_BAD_WEIGHTS = 4, /* fs_check_weights: a weight <= 0 or not finite, sum != 1 */
     FS_ERR_UNSUPPORTED = 5, /* dtype/compute combination not available                 */
     FS_ERR_ALLOC = 6,       /* device allocation failed                                */
-    FS_ERR_DEVICE = 7       /* a HIP call failed (message in fs_last_error)            */
+    FS_ERR_DEVICE = 7,      /* a HIP call failed (message in fs_last_error)            */
+    FS_ERR_NONFINITE = 8    /* fs_check_finite: an entry is NaN or infinite            */
 } fs_status;
 
 /* storage type of x and y */
@@ -203,6 +204,14 @@ fs_status fs_ot_value(fs_ctx *ctx, const fs_problem *prob, float eps, const floa
  */
 fs_status fs_check_weights(fs_ctx *ctx, const fs_problem *prob, float tol, double *sum_a /* host, nullable */,
                            double *sum_b /* host, nullable */);
+
+/*
+ * Optional check of a result (potentials, a plan application, a gradient): FS_ERR_NONFINITE if one
+ * of the cnt floats at v (device) is NaN or infinite, FS_OK otherwise; bad_count: NULL or a HOST
+ * int64 that receives how many are.  The entry points do not check their outputs themselves (it
+ * costs a pass).  Synchronises the stream.
+ */
+fs_status fs_check_finite(fs_ctx *ctx, const float *v /* device */, int64_t cnt, int64_t *bad_count /* host, nullable */);
 
 /*
  * Debiased Sinkhorn divergence  S = OT(a,b) - OT(a,a)/2 - OT(b,b)/2  (Section 4.2 uses it as the

@@ -21,7 +21,7 @@ FS_COMPUTE_FP32, FS_COMPUTE_BF16_MFMA = 0, 1
 
 EXPORTS = (
     "fs_create", "fs_destroy", "fs_status_str", "fs_last_error", "fs_version", "fs_row_norms",
-    "fs_update_f", "fs_update_g", "fs_solve", "fs_solve_symmetric", "fs_solve_tol", "fs_marginal_err", "fs_ot_value", "fs_check_weights", "fs_divergence", "fs_apply_plan",
+    "fs_update_f", "fs_update_g", "fs_solve", "fs_solve_symmetric", "fs_solve_tol", "fs_marginal_err", "fs_ot_value", "fs_check_weights", "fs_check_finite", "fs_divergence", "fs_apply_plan",
     "fs_apply_plan_T", "fs_grad_x", "fs_grad_y", "fs_hvp", "fs_profile_enable", "fs_profile_read",
 )
 
@@ -74,6 +74,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fs_solve_tol.argtypes = [vp, PP, f32, i32, i32, f32, vp, vp, ctypes.POINTER(i32), ctypes.POINTER(f32)]
     lib.fs_marginal_err.argtypes = [vp, PP, f32, vp, vp, ctypes.POINTER(f32), ctypes.POINTER(f32)]
     lib.fs_ot_value.argtypes = [vp, PP, f32, vp, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.fs_check_finite.argtypes = [vp, vp, i64, ctypes.POINTER(ctypes.c_int64)]
     lib.fs_check_weights.argtypes = [vp, PP, f32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.fs_divergence.argtypes = [vp, PP, f32, i32, vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.fs_apply_plan.argtypes = [vp, PP, f32, vp, vp, vp, i64, i64, vp, i64, vp]
@@ -210,6 +211,13 @@ class Context:
         self._check(self.lib.fs_ot_value(self.h, ctypes.byref(prob.c), eps, _ptr(f), _ptr(g), ctypes.byref(v)),
                     "fs_ot_value")
         return v.value
+
+    def fs_check_finite(self, v: torch.Tensor) -> int:
+        """Raises (status 8) if an entry of the float tensor is NaN or infinite; returns 0 otherwise."""
+        assert v.dtype == torch.float32 and v.is_contiguous()
+        bad = ctypes.c_int64()
+        self._check(self.lib.fs_check_finite(self.h, _ptr(v), v.numel(), ctypes.byref(bad)), "fs_check_finite")
+        return bad.value
 
     def fs_check_weights(self, prob: Problem, tol: float = 1e-5):
         """Raises if a weight is not positive and finite or a sum is off by more than tol; returns the two sums."""

@@ -378,6 +378,7 @@ const char *fs_status_str(fs_status s)
     case FS_ERR_UNSUPPORTED: return "unsupported";
     case FS_ERR_ALLOC: return "device allocation failed";
     case FS_ERR_DEVICE: return "device error";
+    case FS_ERR_NONFINITE: return "non-finite value";
     }
     return "unknown status";
 }
@@ -706,6 +707,28 @@ fs_status fs_ot_value(fs_ctx *ctx, const fs_problem *prob, float eps, const floa
     FS_HIP(c, hipStreamSynchronize(c->stream));
     // App. B: <a,f> + <b,g> - eps (sum_ij P_ij - sum_ij a_i b_j)
     *value = h[1] + h[3] - (double)eps * (h[0] - h[2] * h[4]);
+    return FS_OK;
+}
+
+fs_status fs_check_finite(fs_ctx *ctx, const float *v, int64_t cnt, int64_t *bad_count)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    if (!c) return FS_ERR_INVALID_ARG;
+    c->err.clear();
+    if (!v) return fail(c, FS_ERR_INVALID_ARG, "v is NULL");
+    if (cnt < 1) return fail(c, FS_ERR_BAD_SHAPE, "cnt must be >= 1");
+    if (c->device < 0) return fail(c, FS_ERR_DEVICE, "host-only context: arguments are valid, nothing was launched");
+    FS_HIP(c, hipSetDevice(c->device));
+    const size_t nb = (size_t)ceil_div(cnt, 256);
+    fs_status st = ensure_aux(c, (nb + 1) * sizeof(double));
+    if (st != FS_OK) return st;
+    double *res = reinterpret_cast<double *>(c->aux);
+    if ((st = launch_count_nonfinite(c, v, cnt, res + 1, res)) != FS_OK) return st;
+    double h = 0.0;
+    FS_HIP(c, hipMemcpyAsync(&h, res, sizeof h, hipMemcpyDeviceToHost, c->stream));
+    FS_HIP(c, hipStreamSynchronize(c->stream));
+    if (bad_count) *bad_count = (int64_t)h;
+    if (h > 0.0) return fail(c, FS_ERR_NONFINITE, "%.0f of %lld values are not finite", h, (long long)cnt);
     return FS_OK;
 }
 

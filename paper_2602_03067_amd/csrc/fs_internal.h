@@ -249,6 +249,7 @@ fs_status launch_row_norms(Ctx *c, const void *pts, int dtype, int64_t rows, int
                            float *out);
 fs_status launch_fill_f64(Ctx *c, double *dst, double v, int64_t cnt);
 fs_status launch_weight_stats(Ctx *c, const float *w, int64_t cnt, double *scratch, double *dst);
+fs_status launch_count_nonfinite(Ctx *c, const float *v, int64_t cnt, double *scratch, double *dst);
 // merge the splits of an application pass (partial (max,sum) + opart[split][row][PC]) and apply
 // the epilogue  out_i = w_i exp(pot_shifted_i/eps + m_i) O_i  for columns p0 .. p0+PC-1
 fs_status launch_apply_finalize(Ctx *c, const Prepared *P, const Side *res, const double *res_norm, int splits,

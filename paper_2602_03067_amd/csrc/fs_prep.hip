@@ -540,6 +540,16 @@ __global__ __launch_bounds__(256) void k_value_terms(const double2 *partial, int
     }
 }
 
+// block counts of the entries that are NaN or infinite
+__global__ __launch_bounds__(256) void k_count_nonfinite(const float *v, int64_t cnt, double *part)
+{
+    __shared__ double sh[256];
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const double t = (i < cnt && !(fabsf(v[i]) < INFINITY)) ? 1.0 : 0.0;
+    const double s = block_sum_256(t, sh);
+    if (threadIdx.x == 0) part[blockIdx.x] = s;
+}
+
 // block sums of the weights (part[0][.]) and of the indicator "not positive and finite" (part[1][.])
 __global__ __launch_bounds__(256) void k_weight_stats(const float *w, int64_t cnt, double *part)
 {
@@ -863,6 +873,16 @@ fs_status launch_finalize_pair(Ctx *c, const Prepared *P, Side *X, const double 
     const FinalizeArgs ax = finalize_args(P, partial_x, X, norm_x, splits_x, eps_cur, eps_next_bias, f_out, nullptr, mix, nullptr);
     const FinalizeArgs ay = finalize_args(P, partial_y, Y, norm_y, splits_y, eps_cur, eps_next_bias, g_out, nullptr, mix, nullptr);
     hipLaunchKernelGGL(k_finalize_pair, dim3((unsigned)(ax.blocks + ay.blocks)), dim3(256), 0, c->stream, ax, ay);
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
+// dst[0] <- how many of the cnt floats are NaN or infinite; `scratch` holds one double per 256 values
+fs_status launch_count_nonfinite(Ctx *c, const float *v, int64_t cnt, double *scratch, double *dst)
+{
+    const unsigned nb = (unsigned)ceil_div(cnt, 256);
+    hipLaunchKernelGGL(k_count_nonfinite, dim3(nb), dim3(256), 0, c->stream, v, cnt, scratch);
+    hipLaunchKernelGGL(k_sum_to, dim3(1), dim3(256), 0, c->stream, scratch, (int64_t)nb, dst);
     FS_HIP(c, hipGetLastError());
     return FS_OK;
 }

@@ -53,8 +53,8 @@ P = ctypes.c_void_p
 
 
 def test_status_strings(lib):
-    seen = {lib.fs_status_str(s).decode() for s in range(8)}
-    assert len(seen) == 8 and "ok" in seen
+    seen = {lib.fs_status_str(s).decode() for s in range(9)}
+    assert len(seen) == 9 and "ok" in seen
 
 
 def test_valid_arguments_reach_the_device_stage(lib, hctx):
@@ -192,6 +192,14 @@ def test_check_weights_validation(lib, hctx):
     assert sa.value == 1.0 and sb.value == 1.0
     q = _prob(a=1 << 24)
     assert lib.fs_check_weights(hctx, ctypes.byref(q), F(1e-5), None, None) == 7   # valid: reaches device stage
+
+
+def test_check_finite_validation(lib, hctx):
+    bad = ctypes.c_int64()
+    assert lib.fs_check_finite(None, P(1 << 20), 10, None) == 1
+    assert lib.fs_check_finite(hctx, None, 10, None) == 1
+    assert lib.fs_check_finite(hctx, P(1 << 20), 0, ctypes.byref(bad)) == 2
+    assert lib.fs_check_finite(hctx, P(1 << 20), 10, ctypes.byref(bad)) == 7   # valid: reaches device stage
 
 
 def test_bench_refuses_more_than_one_gpu():

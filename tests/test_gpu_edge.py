@@ -146,3 +146,16 @@ def test_check_weights(oracle):
     with pytest.raises(binding.FlashSinkError):
         ctx.fs_check_weights(binding.Problem(dev(x), dev(y), dev(bad), None), 1e-5)
     ctx.close()
+
+
+def test_check_finite():
+    ctx = binding.Context(0)
+    v = torch.randn(100001, device="cuda:0")
+    say("check_finite on %d values" % v.numel())
+    assert ctx.fs_check_finite(v) == 0
+    v[77] = float("nan")
+    v[99999] = float("-inf")
+    with pytest.raises(binding.FlashSinkError) as e:
+        ctx.fs_check_finite(v)
+    assert e.value.status == 8 and "2 of 100001" in str(e.value)
+    ctx.close()
