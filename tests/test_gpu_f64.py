@@ -104,7 +104,9 @@ def test_transport_grad_trajectory_scaled_down(ctx, oracle):
     assert np.linalg.norm(gy_gpu - gy_ref) <= 2e-4 * np.linalg.norm(gy_ref)
 
 
-@pytest.mark.parametrize("n,m,d,p", [(130, 70, 20, 1), (200, 333, 64, 5), (257, 190, 40, 70), (64, 64, 96, 64)])
+@pytest.mark.parametrize("n,m,d,p", [(130, 70, 20, 1), (200, 333, 64, 5), (257, 190, 40, 70), (64, 64, 96, 64),
+                                     # more than 64 columns: passes of 128, then the rest (wide or plain)
+                                     (150, 333, 100, 200), (90, 260, 33, 129), (1100, 700, 64, 128)])
 def test_apply_shapes(ctx, oracle, n, m, d, p):
     rng = np.random.default_rng(11 * n + m + d + p)
     x, y, a, b = _rand_problem(rng, n, m, d)
