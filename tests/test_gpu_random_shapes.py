@@ -1,6 +1,7 @@
 """GPU parity on a seeded sweep of random shapes: sizes that are not multiples of any tile, every
 dimension from 1 to 100, both schedules and compute modes, plan applications with odd widths --
-against the float64 oracle at the bars of the other GPU tests."""
+against the float64 oracle at the bars of the other GPU tests.  A second batch stays on the fp64 matrix-core
+path with contractions up to d = 260 and plan applications up to 200 columns."""
 import numpy as np
 import pytest
 import torch
@@ -24,6 +25,16 @@ def _cases():
         iters = int(rng.integers(1, 6))
         p = int(rng.choice([1, 2, 3, 4, 5, 9, 63, 64, 65]))
         out.append(pytest.param(k, n, m, d, bf, eps, iters, p, id="case%02d_n%d_m%d_d%d_%s" % (k, n, m, d, "bf16" if bf else "fp32")))
+    # the fp64 matrix-core path once more, with longer contractions and wide plan applications
+    rng = np.random.default_rng(20260204)
+    for k in range(100, 124):
+        n = int(rng.integers(1, 2600))
+        m = int(rng.integers(1, 2600))
+        d = int(rng.choice([17, 20, 33, 40, 64, 65, 72, 100, 130, 200, 260]))
+        eps = float(rng.choice([0.2, 1.0, 3.0]))
+        iters = int(rng.integers(1, 5))
+        p = int(rng.choice([1, 16, 17, 64, 65, 100, 128, 129, 200]))
+        out.append(pytest.param(k, n, m, d, False, eps, iters, p, id="case%03d_n%d_m%d_d%d_p%d_fp32" % (k, n, m, d, p)))
     return out
 
 
