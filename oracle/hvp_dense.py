@@ -11,8 +11,10 @@ the formulas stay consistent for potentials that are not converged; at convergen
   Schur system    (diag(c) - P^T diag(r)^-1 P + tau I) w2 = r2 - P^T (r1 / r)    (step 2)
   back to G       R^T w                                            (step 3)
 tau = 0 takes the Moore-Penrose solution of the full system instead of the Schur complement.
-Pinned in tests/test_oracle_pins.py by central differences of the gradient of Cor. 4 at converged
-potentials (which shares none of these formulas).
+Pinned in tests/test_oracle_pins.py: hvp by central differences of the gradient of Cor. 4 at
+converged potentials (which shares none of these formulas); hadamard_transport by the entry-by-entry
+double loop and by the special direction A_i = e_k, which turns it into an ordinary plan
+application computed by the C oracle.
 """
 from __future__ import annotations
 
@@ -57,9 +59,12 @@ def hvp(x, y, a, b, eps, f, g, A, tau=0.0):
     return Rtw / eps + EA
 
 
-def hadamard_transport(x, y, a, b, eps, f, g, A):
-    """(P o (A Y^T)) Y  (Alg. 5's output), dense."""
+def hadamard_transport(x, y, a, b, eps, f, g, A, V=None):
+    """(P o (A Y^T)) V, n x p: the output of Alg. 5 with B = Y (Thm. 5 uses it with V = Y, the
+    default), dense: every plan entry P_ij is multiplied by the weight <A_i, y_j> before the
+    product with V."""
     x, y, A = (np.asarray(v, dtype=np.float64) for v in (x, y, A))
+    V = y if V is None else np.asarray(V, dtype=np.float64)
     P = _plan(x, y, *(np.asarray(v, dtype=np.float64) for v in (a, b)), eps,
               np.asarray(f, dtype=np.float64), np.asarray(g, dtype=np.float64))
-    return (P * (A @ y.T)) @ y
+    return (P * (A @ y.T)) @ V

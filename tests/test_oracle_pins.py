@@ -570,3 +570,45 @@ def test_hvp_dense_matches_central_differences_of_the_gradient(oracle):
     # the Hessian is symmetric: <B, T A> = <A, T B>
     TB = hvp_dense.hvp(x, y, a, b, eps, f, g, A2)
     assert abs((A2 * G).sum() - (A * TB).sum()) <= 1e-8 * abs((A2 * G).sum())
+
+
+# ---- Hadamard-weighted transport (Alg. 5): the dense oracle against its entry-by-entry definition ----
+def test_hadamard_transport_matches_the_double_loop_and_reduces_to_a_plan_application(oracle):
+    """out_i = sum_j P_ij <A_i, y_j> V_j written as plain loops over a hand-built plan (Section 2.1's
+    P_ij = a_i b_j exp((f_i + g_j - C_ij)/eps)), for potentials that are NOT converged; and with every
+    row of A equal to the unit vector e_k the weights are y_jk, so the result is the ordinary plan
+    application P (diag(y_k) V), which the C oracle computes with none of this code."""
+    import math
+
+    from oracle import hvp_dense
+    rng = np.random.default_rng(29)
+    n, m, d, p = 6, 5, 3, 4
+    x, y, a, b = _problem(rng, n, m, d)
+    f = rng.standard_normal(n) * 0.3
+    g = rng.standard_normal(m) * 0.3
+    A = rng.standard_normal((n, d))
+    V = rng.standard_normal((m, p))
+    eps = 0.6
+    want = np.zeros((n, p))
+    for i in range(n):
+        for j in range(m):
+            c = sum((x[i, k] - y[j, k]) ** 2 for k in range(d))
+            pij = a[i] * b[j] * math.exp((f[i] + g[j] - c) / eps)
+            wij = sum(A[i, k] * y[j, k] for k in range(d))
+            for q in range(p):
+                want[i, q] += pij * wij * V[j, q]
+    got = hvp_dense.hadamard_transport(x, y, a, b, eps, f, g, A, V)
+    assert np.abs(got - want).max() <= 1e-13 * np.abs(want).max()
+    # default value matrix: the clouds' own y (the form Thm. 5 uses)
+    got_y = hvp_dense.hadamard_transport(x, y, a, b, eps, f, g, A)
+    assert np.array_equal(got_y, hvp_dense.hadamard_transport(x, y, a, b, eps, f, g, A, y))
+    # a transposed or swapped operand would fail here: weights <A_i, y_j> with A_i = e_k are y_jk
+    for k in range(d):
+        Ak = np.zeros((n, d))
+        Ak[:, k] = 1.0
+        ref = oracle.apply_plan(x, y, a, b, eps, f, g, y[:, k:k + 1] * V)
+        assert np.abs(hvp_dense.hadamard_transport(x, y, a, b, eps, f, g, Ak, V) - ref).max() <= 1e-13 * np.abs(ref).max()
+    # linear in A, and a row scaling of A scales the matching output row
+    s = rng.random(n) + 0.5
+    assert np.allclose(hvp_dense.hadamard_transport(x, y, a, b, eps, f, g, s[:, None] * A, V), s[:, None] * got,
+                       rtol=1e-13, atol=0)
