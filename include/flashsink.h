@@ -281,6 +281,22 @@ fs_status fs_hvp(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f 
                  int32_t *cg_iters /* host, nullable */);
 
 /*
+ * Hadamard-weighted transport (Alg. 5) with the second factor of the weights taken from the target
+ * cloud, the form Thm. 5 uses:   out = (P o (A y^T)) V,   out_i = sum_j P_ij <A_i, y_j> V_j,
+ * for ANY potentials, in streaming passes (P and the weights are formed tile by tile and never stored).
+ *   A   [n x d] device floats, row stride lda >= d
+ *   V   [m x p] device floats, row stride ldv;   out [n x p] device floats, row stride ldo, written
+ * For d <= 16 the weights are formed against the centred points and the mean's share is added from a
+ * plain application of the same plan (two streaming passes per block of value columns).
+ * Available for float32 points and FS_COMPUTE_FP32 (FS_ERR_UNSUPPORTED otherwise).  out may not
+ * overlap an input.  Does not synchronise.
+ */
+fs_status fs_apply_plan_hadamard(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f /* device */,
+                                 const float *g /* device */, const float *A /* device */, int64_t lda,
+                                 const float *V /* device */, int64_t p, int64_t ldv, float *out /* device */,
+                                 int64_t ldo);
+
+/*
  * Timing hook for benchmarks: average duration in milliseconds of the streaming
  * LSE kernel launches recorded with HIP events on the context's stream since the
  * last call of this function, and their count.  Where a solve mixes two LSE

@@ -22,7 +22,7 @@ FS_COMPUTE_FP32, FS_COMPUTE_BF16_MFMA = 0, 1
 EXPORTS = (
     "fs_create", "fs_destroy", "fs_status_str", "fs_last_error", "fs_version", "fs_row_norms",
     "fs_update_f", "fs_update_g", "fs_solve", "fs_solve_symmetric", "fs_solve_tol", "fs_marginal_err", "fs_ot_value", "fs_check_weights", "fs_check_finite", "fs_divergence", "fs_apply_plan",
-    "fs_apply_plan_T", "fs_grad_x", "fs_grad_y", "fs_hvp", "fs_profile_enable", "fs_profile_read",
+    "fs_apply_plan_T", "fs_apply_plan_hadamard", "fs_grad_x", "fs_grad_y", "fs_hvp", "fs_profile_enable", "fs_profile_read",
 )
 
 
@@ -79,6 +79,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fs_divergence.argtypes = [vp, PP, f32, i32, vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.fs_apply_plan.argtypes = [vp, PP, f32, vp, vp, vp, i64, i64, vp, i64, vp]
     lib.fs_apply_plan_T.argtypes = [vp, PP, f32, vp, vp, vp, i64, i64, vp, i64, vp]
+    lib.fs_apply_plan_hadamard.argtypes = [vp, PP, f32, vp, vp, vp, i64, vp, i64, i64, vp, i64]
     lib.fs_grad_x.argtypes = [vp, PP, f32, vp, vp, i32, vp, i64]
     lib.fs_grad_y.argtypes = [vp, PP, f32, vp, vp, i32, vp, i64]
     lib.fs_hvp.argtypes = [vp, PP, f32, vp, vp, vp, i64, f32, f32, i32, vp, i64, ctypes.POINTER(i32)]
@@ -272,6 +273,20 @@ class Context:
     def fs_apply_plan_T(self, prob: Problem, eps: float, f, g, U, want_mass: bool = False):
         return self._apply(self.lib.fs_apply_plan_T, "fs_apply_plan_T", prob, eps, f, g, U, prob.m,
                            prob.n, want_mass)
+
+    def fs_apply_plan_hadamard(self, prob: Problem, eps: float, f, g, A: torch.Tensor, V: torch.Tensor) -> torch.Tensor:
+        """(P o (A y^T)) V (Alg. 5); A is n x d, V is m x p; returns n x p."""
+        _dev_f32(f, "f", (prob.n,))
+        _dev_f32(g, "g", (prob.m,))
+        _dev_f32(A, "A", (prob.n, prob.d))
+        if V.dim() != 2 or V.shape[0] != prob.m or V.dtype != torch.float32 or V.stride(1) != 1:
+            raise TypeError("V must be float32 (m, p) with unit inner stride")
+        p = V.shape[1]
+        out = torch.empty((prob.n, p), dtype=torch.float32, device=V.device)
+        self._check(self.lib.fs_apply_plan_hadamard(self.h, ctypes.byref(prob.c), eps, _ptr(f), _ptr(g), _ptr(A), A.stride(0),
+                                                    _ptr(V), p, V.stride(0), _ptr(out), out.stride(0)),
+                    "fs_apply_plan_hadamard")
+        return out
 
     def _grad(self, fn, name, prob: Problem, eps: float, f, g, mode: int, rows: int) -> torch.Tensor:
         _dev_f32(f, "f", (prob.n,))

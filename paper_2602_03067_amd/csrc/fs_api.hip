@@ -874,6 +874,39 @@ fs_status fs_hvp(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f,
     return st;
 }
 
+fs_status fs_apply_plan_hadamard(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, const float *g,
+                                 const float *A, int64_t lda, const float *V, int64_t p, int64_t ldv, float *out, int64_t ldo)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    fs_status st = validate_problem(c, prob);
+    if (st != FS_OK) return st;
+    if ((st = validate_eps(c, eps)) != FS_OK) return st;
+    if (!f || !g || !A || !V) return fail(c, FS_ERR_INVALID_ARG, "f, g, A or V is NULL");
+    if (p <= 0 || p > 4096 || ldv < p || ldo < p || lda < prob->d)
+        return fail(c, FS_ERR_BAD_SHAPE, "need 0 < p <= 4096, ldv >= p, ldo >= p and lda >= d");
+    if (prob->dtype != FS_F32 || prob->compute != FS_COMPUTE_FP32)
+        return fail(c, FS_ERR_UNSUPPORTED, "the Hadamard-weighted transport is available for float32 points and FS_COMPUTE_FP32");
+    const size_t out_bytes = (size_t)((prob->n - 1) * ldo + p) * 4;
+    if ((st = check_out(c, prob, out, out_bytes, "out")) != FS_OK) return st;
+    if (overlap(out, out_bytes, A, (size_t)((prob->n - 1) * lda + prob->d) * 4) ||
+        overlap(out, out_bytes, V, (size_t)((prob->m - 1) * ldv + p) * 4) || overlap(out, out_bytes, f, (size_t)prob->n * 4) ||
+        overlap(out, out_bytes, g, (size_t)prob->m * 4))
+        return fail(c, FS_ERR_INVALID_ARG, "out overlaps an input");
+    // The low-d kernels form the weights against the points centred at the common mean; the mean's share,
+    // <A_i, mean> (P V)_i, comes from a plain application into the workspace.  Above d = 16 nothing is centred.
+    const bool lowd = choose_path(prob) == Path::LowD;
+    Prepared P;
+    char *tail = nullptr;
+    if ((st = apply_begin(c, prob, eps, f, g, p, false, lowd ? (size_t)prob->n * p * 4 : 0, &P, &tail)) != FS_OK) return st;
+    if (lowd) {
+        if ((st = lowd_apply(c, &P, &P.X, &P.Y, eps, V, p, ldv, out, ldo, nullptr, A, lda)) != FS_OK) return st;
+        float *PV = reinterpret_cast<float *>(tail);
+        if ((st = lowd_apply(c, &P, &P.X, &P.Y, eps, V, p, ldv, PV, p, nullptr)) != FS_OK) return st;
+        return launch_add_mean_share(c, A, lda, P.mean, PV, prob->n, (int)prob->d, (int)p, out, ldo);
+    }
+    return f64_apply(c, &P, &P.X, &P.Y, eps, V, p, ldv, out, ldo, nullptr, A, lda);
+}
+
 fs_status fs_profile_enable(fs_ctx *ctx, int32_t on)
 {
     Ctx *c = reinterpret_cast<Ctx *>(ctx);

@@ -151,9 +151,31 @@ __global__ void k_assemble(const float *X, int64_t ldx, const float *A, int64_t 
     out[i * ldo + t] = (float)(rtw * inv_eps + ea);
 }
 
+// out_i += <A_i, mean> PV_i: the share of the common mean in the Hadamard weights <A_i, y_j> when the
+// application kernel forms them against the centred streamed points
+__global__ void k_add_mean_share(const float *A, int64_t lda, const double *mean, const float *PV, int64_t n, int d, int p,
+                                 float *out, int64_t ldo)
+{
+    int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n * p) return;
+    const int64_t i = e / p;
+    const int q = (int)(e - i * p);
+    double s = 0.0;
+    for (int k = 0; k < d; ++k) s += (double)A[i * lda + k] * mean[k];
+    out[i * ldo + q] = (float)((double)out[i * ldo + q] + s * (double)PV[e]);
+}
+
 inline dim3 g256(int64_t cnt) { return dim3((unsigned)ceil_div(cnt, 256)); }
 
 }  // namespace
+
+fs_status launch_add_mean_share(Ctx *c, const float *A, int64_t lda, const double *mean, const float *PV, int64_t n, int d,
+                                int p, float *out, int64_t ldo)
+{
+    hipLaunchKernelGGL(k_add_mean_share, g256(n * p), dim3(256), 0, c->stream, A, lda, mean, PV, n, d, p, out, ldo);
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
 
 size_t hvp_scratch_bytes(int64_t n, int64_t m, int64_t d)
 {

@@ -68,12 +68,12 @@ __device__ inline void dma4s(const void *g_uniform, unsigned lane_off, unsigned 
 
 inline int split_ksteps(int64_t d) { return (int)(8 * d + 6 + 15) / 16; }   // 1..9 for d = 1..16
 // Position (in 16-byte units) of piece `piece` inside the record of point `point`: 64-byte records
-// (ks = 2) are rotated so that the eight lanes the LDS serves per cycle read eight different bank
-// groups when 32 consecutive records are read at one piece; HBM holds the records already rotated,
+// (ks = 2) are rotated so that sixteen consecutive lanes read sixteen different 16-byte bank groups
+// of a 256-byte line when 32 consecutive records are read at one piece; HBM holds the records already rotated,
 // so tiles are copied to LDS linearly.
 __host__ __device__ inline int split_piece_pos(int ks, int64_t point, int piece)
 {
-    return ks == 2 ? (piece ^ (int)((point >> 1) & 3)) : piece;
+    return ks == 2 ? (piece ^ (int)((point >> 2) & 3)) : piece;
 }
 __device__ inline void split3(float v, __bf16 (&p)[3])
 {
@@ -261,6 +261,10 @@ size_t hvp_scratch_bytes(int64_t n, int64_t m, int64_t d);
 fs_status hvp_run(Ctx *c, Prepared *P, const float *x, int64_t ldx, const float *y, int64_t ldy, double eps,
                   const float *A, int64_t lda, double tau, double eta, int max_cg, float *out, int64_t ldo,
                   char *scratch, int *cg_iters);
+
+// out (n x p, ldo) += <A_i, mean> PV_i (PV: n x p, dense): the mean's share of the Hadamard weights
+fs_status launch_add_mean_share(Ctx *c, const float *A, int64_t lda, const double *mean, const float *PV, int64_t n, int d,
+                                int p, float *out, int64_t ldo);
 
 // fs_lowd.hip
 PassShape lowd_shape(const Ctx *c, int64_t n_res, int64_t n_str);

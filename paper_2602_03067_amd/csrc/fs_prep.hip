@@ -266,7 +266,7 @@ __global__ void k_prep_f64(const void *pts, int dtype, int64_t cnt, int64_t cnt_
 // ---- bfloat16 derived copy (bf16 matrix-core path); norms of the ROUNDED points ----------
 // Layout: the copy is stored in 1 KB tiles of 16 rows x 32 coordinates, tile (rb, ch) at
 // ((rb * n_chunks + ch) * 1024) bytes; inside a tile row r occupies 64 bytes and its 16-byte
-// piece p (coordinates 8p..8p+7 of the chunk) sits at position p ^ ((r >> 1) & 3).  This is
+// piece p (coordinates 8p..8p+7 of the chunk) sits at position p ^ ((r >> 2) & 3).  This is
 // exactly the image a pipeline stage needs in LDS, so the streaming kernel fills LDS with
 // linear 1 KB direct loads and reads MFMA fragments without bank conflicts.
 __global__ void k_prep_bf16(const void *pts, int dtype, int64_t cnt, int64_t cnt_pad, int64_t d, int64_t ld, int kp,
@@ -293,7 +293,7 @@ __global__ void k_prep_bf16(const void *pts, int dtype, int64_t cnt, int64_t cnt
             }
         }
         const int ch = pi >> 2, piece = pi & 3;
-        const int pos = piece ^ ((rl >> 1) & 3);
+        const int pos = piece ^ ((rl >> 2) & 3);
         uint4 v;
         v.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
         v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);

@@ -137,6 +137,26 @@ def test_apply_validation(lib, hctx):
     assert lib.fs_apply_plan(*args(4, 4, 4)) == 7                  # valid: reaches device stage
 
 
+def test_hadamard_validation(lib, hctx):
+    p = _prob()
+    args = lambda pp=4, lda=3, ldv=4, ldo=4, out=1 << 22, A=1 << 24, V=1 << 23, prob=p: (
+        hctx, ctypes.byref(prob), F(0.1), P(1 << 21), P(1 << 20), P(A) if A else None, lda, P(V) if V else None, pp, ldv,
+        P(out) if out else None, ldo)
+    assert lib.fs_apply_plan_hadamard(*args(A=None)) == 1
+    assert lib.fs_apply_plan_hadamard(*args(V=None)) == 1
+    assert lib.fs_apply_plan_hadamard(*args(out=None)) == 1
+    assert lib.fs_apply_plan_hadamard(*args(pp=0)) == 2
+    assert lib.fs_apply_plan_hadamard(*args(lda=2)) == 2             # lda < d
+    assert lib.fs_apply_plan_hadamard(*args(ldv=3)) == 2
+    assert lib.fs_apply_plan_hadamard(*args(ldo=3)) == 2
+    assert lib.fs_apply_plan_hadamard(*args(out=1 << 24)) == 1       # out on top of A
+    assert lib.fs_apply_plan_hadamard(*args(out=1 << 23)) == 1       # out on top of V
+    assert lib.fs_apply_plan_hadamard(*args(out=4096)) == 1          # out on top of x
+    q = _prob(compute=1, d=32, ldx=32, ldy=32)
+    assert lib.fs_apply_plan_hadamard(*args(lda=32, prob=q)) == 5    # bf16 mode is not covered
+    assert lib.fs_apply_plan_hadamard(*args()) == 7                  # valid: reaches device stage
+
+
 def test_grad_validation(lib, hctx):
     p = _prob()
     args = lambda mode, ldg, out=1 << 22, f=1 << 21: (hctx, ctypes.byref(p), F(0.1), P(f), P(1 << 20), mode, P(out), ldg)

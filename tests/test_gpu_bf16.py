@@ -131,13 +131,35 @@ def test_full_size_sampled(ctx, oracle, name, iters):
     eg = max_err_over_eps(host(g_next)[cols], oracle.update_g(w.x, w.y, w.a, eps, fnh, cols=cols), eps)
     say("%s full: sampled max|df|/eps=%.3e max|dg|/eps=%.3e" % (name, ef, eg))
     assert ef <= TOL_A and eg <= TOL_A
+    # marginals of the plan the solve ended on: the column marginal is exact after a g-update (holds at any size), and
+    # on the sampled rows / columns the marginals Prop. 3 gives from the GPU's half-steps equal the oracle's plan sums
     er, ec = ctx.fs_marginal_err(prob, eps, f, g)
     say("%s full: err_row=%.4e err_col=%.4e" % (name, er, ec))
-    assert ec <= 1e-3 and 0.0 <= er < 2.0
+    assert ec <= 1e-4 and 0.0 <= er < 2.0
+    xb, yb = workloads.to_bf16_round(w.x), workloads.to_bf16_round(w.y)
+    fh = host(f)
+    r_or = oracle.apply_plan(xb, yb, w.a, w.b, eps, fh, gh, np.ones((w.m, 1)), rows=rows)[:, 0]
+    c_or = oracle.apply_plan_T(xb, yb, w.a, w.b, eps, fh, gh, np.ones((w.n, 1)), cols=cols)[:, 0]
+    r_gpu = w.a[rows].astype(np.float64) * np.exp((fh[rows] - fnh[rows]) / eps)
+    c_gpu = w.b[cols].astype(np.float64) * np.exp((gh[cols] - host(ctx.fs_update_g(prob, eps, f))[cols]) / eps)
+    dr = np.abs(r_gpu / r_or - 1).max()
+    dc = np.abs(c_gpu / c_or - 1).max()
+    say("%s full: sampled marginals against the oracle on the rounded points: rows %.3e cols %.3e (relative)" % (name, dr, dc))
+    # one half-step agrees with the oracle on the rounded points to TOL_B in units of eps; r = a exp(df/eps)
+    assert dr <= 2 * TOL_B and dc <= 2 * TOL_B
+    # the sampled part of the L1 errors, term by term
+    assert abs(np.abs(r_gpu - w.a[rows]).sum() - np.abs(r_or - w.a[rows]).sum()) <= 1e-5
+    assert abs(np.abs(c_gpu - w.b[cols]).sum() - np.abs(c_or - w.b[cols]).sum()) <= 1e-5
 
 
 TOL_APPLY_A = 2e-2    # relative Frobenius error against the oracle on the inputs as given
 TOL_APPLY_B = 6e-3    # ... on the bf16-rounded points (what is left: bf16 plan entries and values)
+# Element by element: an entry of P V is a sum of terms P_ij V_jc of either sign, and every term carries the bf16
+# roundings of its plan entry and of its value (2^-9 relative each, 2^-8 = 3.9e-3 together), so the error of an entry
+# is bounded relative to (P |V|)_ic, which the oracle gives as a second application; against the inputs as given the
+# rounding of the points moves every exponent by up to the 2e-2 the contract allows.
+TOL_APPLY_EL_A = 2e-2
+TOL_APPLY_EL_B = 5e-3
 
 
 @pytest.mark.parametrize("n,m,d,p", [(1, 1, 16, 1), (130, 70, 20, 1), (200, 333, 64, 5), (257, 600, 40, 70),
@@ -159,14 +181,19 @@ def test_apply_shapes_bf16_mode(ctx, oracle, n, m, d, p):
     out, mass = ctx.fs_apply_plan(prob, eps, dev(f32), dev(g32), dev(V), want_mass=True)
     outT, massT = ctx.fs_apply_plan_T(prob, eps, dev(f32), dev(g32), dev(U), want_mass=True)
     torch.cuda.synchronize()
-    for tag, xs, ys, tol in (("given", x, y, TOL_APPLY_A), ("bf16-rounded", xb, yb, TOL_APPLY_B)):
+    for tag, xs, ys, tol, tol_el in (("given", x, y, TOL_APPLY_A, TOL_APPLY_EL_A),
+                                     ("bf16-rounded", xb, yb, TOL_APPLY_B, TOL_APPLY_EL_B)):
         want, r = oracle.apply_plan(xs, ys, a, b, eps, f32, g32, V, return_mass=True)
         wantT, c = oracle.apply_plan_T(xs, ys, a, b, eps, f32, g32, U, return_mass=True)
         e1 = np.linalg.norm(host(out) - want) / np.linalg.norm(want)
         e2 = np.linalg.norm(host(outT) - wantT) / np.linalg.norm(wantT)
         em = max(np.abs(host(mass) / r - 1).max(), np.abs(host(massT) / c - 1).max())
-        say("  vs oracle on %s inputs: PV %.3e  PtU %.3e  mass %.3e" % (tag, e1, e2, em))
+        scale = oracle.apply_plan(xs, ys, a, b, eps, f32, g32, np.abs(V))
+        scaleT = oracle.apply_plan_T(xs, ys, a, b, eps, f32, g32, np.abs(U))
+        el = max((np.abs(host(out) - want) / scale).max(), (np.abs(host(outT) - wantT) / scaleT).max())
+        say("  vs oracle on %s inputs: PV %.3e  PtU %.3e  mass %.3e  element-wise / (P|V|) %.3e" % (tag, e1, e2, em, el))
         assert e1 <= tol and e2 <= tol and em <= tol
+        assert el <= tol_el
 
 
 def test_apply_bf16_mode_large_score_spread(ctx, oracle):
@@ -188,5 +215,7 @@ def test_apply_bf16_mode_large_score_spread(ctx, oracle):
     want, r_o = oracle.apply_plan(xb, yb, a, b, eps, f32, g32, y, return_mass=True)
     e1 = np.linalg.norm(host(PY) - want) / np.linalg.norm(want)
     em = np.abs(host(r) / r_o - 1).max()
-    say("  PY %.3e  mass %.3e" % (e1, em))
+    el = (np.abs(host(PY) - want) / oracle.apply_plan(xb, yb, a, b, eps, f32, g32, np.abs(y))).max()
+    say("  PY %.3e  mass %.3e  element-wise / (P|y|) %.3e" % (e1, em, el))
     assert e1 <= TOL_APPLY_B and em <= TOL_APPLY_B
+    assert el <= TOL_APPLY_EL_B

@@ -2,7 +2,8 @@
 oracle (oracle/hvp_dense.py, pinned by central differences of the gradient).
 
 The GPU works with float32 vectors inside conjugate gradients; the bar is a relative Frobenius
-error of 1e-4 against the oracle at the SAME damping tau (measured: 2e-6 .. 5e-6).  Against the
+error of 1e-4 against the oracle at the SAME damping tau (measured: 2e-6 .. 5e-6), and entry by entry
+1e-3 of the largest entry.  Against the
 undamped pseudo-inverse the damping itself shows: the paper's parity protocol (n = m = 512, d = 4,
 tau = 1e-5, eta = 1e-6) reports 4.6e-3 there, this implementation 3.0e-3 on its own random data."""
 import numpy as np
@@ -48,10 +49,13 @@ def test_hvp_matches_dense_oracle(ctx, oracle, n, m, d, eps, iters):
     G, k = ctx.fs_hvp(make_problem(x, y, a, b), eps, dev(f32), dev(g32), dev(A), tau, eta, 400)
     want = hvp_dense.hvp(x, y, a, b, eps, f32.astype(np.float64), g32.astype(np.float64), A, tau=tau)
     rel = np.linalg.norm(host(G) - want) / np.linalg.norm(want)
+    mx = np.abs(host(G) - want).max() / np.abs(want).max()
     undamped = hvp_dense.hvp(x, y, a, b, eps, f32.astype(np.float64), g32.astype(np.float64), A)
     rel0 = np.linalg.norm(host(G) - undamped) / np.linalg.norm(undamped)
-    say("  CG iterations %d, rel. error vs oracle at the same tau %.3e, vs the pseudo-inverse %.3e" % (k, rel, rel0))
+    say("  CG iterations %d, rel. error vs oracle at the same tau %.3e (largest entry error / largest entry %.3e), "
+        "vs the pseudo-inverse %.3e" % (k, rel, mx, rel0))
     assert rel <= 1e-4
+    assert mx <= 1e-3      # entry by entry, against the largest entry (entries of T A change sign)
     assert rel0 <= 2e-2
 
 
