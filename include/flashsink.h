@@ -297,6 +297,18 @@ fs_status fs_apply_plan_hadamard(fs_ctx *ctx, const fs_problem *prob, float eps,
                                  int64_t ldo);
 
 /*
+ * Test and experiment switches of ONE context (there is no process-wide state; a new context has
+ * every switch at 0 = the library decides).  Not needed for normal use.
+ *   "lowd_splits"        1..1024: split count of the streamed side of the d <= 16 passes
+ *   "lowd_score"         32 / 64: fp32-accurate / float64-grade scores in every d <= 16 half-step and
+ *                        application (fs_marginal_err and fs_ot_value always take float64-grade scores)
+ *   "lowd_precise_valu"  1: float64-grade scores at d <= 3 on the vector ALU instead of the matrix cores
+ *   "bf16_variant"       schedule variant of the bf16 matrix-core kernels
+ * Unknown keys and values out of range: FS_ERR_INVALID_ARG.  key: HOST string.
+ */
+fs_status fs_debug_set(fs_ctx *ctx, const char *key /* host */, int64_t value);
+
+/*
  * Timing hook for benchmarks: average duration in milliseconds of the streaming
  * LSE kernel launches recorded with HIP events on the context's stream since the
  * last call of this function, and their count.  Where a solve mixes two LSE

@@ -50,6 +50,23 @@ void prof_end(Ctx *c)
 
 namespace {
 
+// Makes the context's device current for the duration of an entry call and restores the caller's.
+struct DeviceGuard {
+    int prev = -1;
+    bool active = false;
+    explicit DeviceGuard(const Ctx *c)
+    {
+        if (c && c->device >= 0 && hipGetDevice(&prev) == hipSuccess && prev != c->device)
+            active = hipSetDevice(c->device) == hipSuccess;
+    }
+    ~DeviceGuard()
+    {
+        if (active) (void)hipSetDevice(prev);
+    }
+    DeviceGuard(const DeviceGuard &) = delete;
+    DeviceGuard &operator=(const DeviceGuard &) = delete;
+};
+
 Path choose_path(const fs_problem *p)
 {
     if (p->compute == FS_COMPUTE_BF16_MFMA) return Path::BF16;
@@ -177,7 +194,7 @@ size_t layout(const Ctx *c, const fs_problem *p, Prepared *P, char *base, size_t
     side(P->Y, p->m, p->b);
     int64_t big = P->X.cnt_pad > P->Y.cnt_pad ? P->X.cnt_pad : P->Y.cnt_pad;
     // [splits][rows] records of the pass over either side
-    const size_t pbx = (size_t)max_splits(p->n) * P->X.cnt_pad * 16, pby = (size_t)max_splits(p->m) * P->Y.cnt_pad * 16;
+    const size_t pbx = (size_t)max_splits(c->partial_budget, p->n) * P->X.cnt_pad * 16, pby = (size_t)max_splits(c->partial_budget, p->m) * P->Y.cnt_pad * 16;
     P->partial_bytes = pbx > pby ? pbx : pby;
     size_t o = A.take(P->partial_bytes);
     P->partial = base ? (void *)(base + o) : nullptr;
@@ -195,6 +212,7 @@ size_t layout(const Ctx *c, const fs_problem *p, Prepared *P, char *base, size_t
 fs_status ensure_ws(Ctx *c, size_t need)
 {
     if (need <= c->ws_bytes) return FS_OK;
+    if (c->ws_static) return fail(c, FS_ERR_BAD_SHAPE, "the problem needs %zu bytes of workspace, the static scratch holds %zu", need, c->ws_bytes);
     FS_HIP(c, hipStreamSynchronize(c->stream));
     if (c->ws) {
         FS_HIP(c, hipFree(c->ws));
@@ -215,11 +233,12 @@ fs_status ensure_ws(Ctx *c, size_t need)
 fs_status prepare(Ctx *c, const fs_problem *p, Prepared *P, size_t extra, char **extra_ptr)
 {
     if (c->device < 0) return fail(c, FS_ERR_DEVICE, "host-only context: arguments are valid, nothing was launched");
-    FS_HIP(c, hipSetDevice(c->device));
     size_t need = layout(c, p, P, nullptr, extra);
     fs_status st = ensure_ws(c, need);
     if (st != FS_OK) return st;
     layout(c, p, P, c->ws, extra);
+    P->dbg_score = c->dbg_lowd_score;
+    P->dbg_precise_valu = c->dbg_lowd_precise_valu != 0;
     if (extra_ptr) *extra_ptr = c->ws + (need - ((extra + 255) & ~size_t(255)));
     return launch_prepare(c, p, P);
 }
@@ -282,6 +301,7 @@ fs_status apply_common(Ctx *c, const fs_problem *prob, float eps, const float *f
                        const float *V, int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass,
                        bool transposed)
 {
+    DeviceGuard device_guard(c);
     fs_status st = validate_problem(c, prob);
     if (st != FS_OK) return st;
     if ((st = validate_eps(c, eps)) != FS_OK) return st;
@@ -305,6 +325,7 @@ fs_status apply_common(Ctx *c, const fs_problem *prob, float eps, const float *f
 fs_status grad_common(Ctx *c, const fs_problem *prob, float eps, const float *f, const float *g, int32_t mode,
                       float *grad, int64_t ldg, bool wrt_y)
 {
+    DeviceGuard device_guard(c);
     fs_status st = validate_problem(c, prob);
     if (st != FS_OK) return st;
     if ((st = validate_eps(c, eps)) != FS_OK) return st;
@@ -401,14 +422,20 @@ fs_status fs_create(fs_ctx **ctx, int device, void *hip_stream)
     }
     int count = 0;
     if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return FS_ERR_DEVICE;
-    if (hipSetDevice(device) != hipSuccess) return FS_ERR_DEVICE;
     Ctx *c = new (std::nothrow) Ctx;
     if (!c) return FS_ERR_ALLOC;
     c->device = device;
     c->stream = (hipStream_t)hip_stream;
+    int prev = -1;
+    const bool had_prev = hipGetDevice(&prev) == hipSuccess;
+    if (hipSetDevice(device) != hipSuccess) {
+        delete c;
+        return FS_ERR_DEVICE;
+    }
     int cu = 0;
     if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cu > 0)
         c->num_cu = cu;
+    if (had_prev && prev != device) (void)hipSetDevice(prev);
     *ctx = reinterpret_cast<fs_ctx *>(c);
     return FS_OK;
 }
@@ -417,8 +444,9 @@ fs_status fs_destroy(fs_ctx *ctx)
 {
     if (!ctx) return FS_OK;
     Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
     if (c->device >= 0) {
-        (void)hipSetDevice(c->device);
+        DeviceGuard device_guard(c);
         (void)hipStreamSynchronize(c->stream);
         for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
         if (c->ws) (void)hipFree(c->ws);
@@ -432,6 +460,7 @@ fs_status fs_row_norms(fs_ctx *ctx, const void *pts, int32_t dtype, int64_t rows
                        float *out)
 {
     Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
     if (!c) return FS_ERR_INVALID_ARG;
     c->err.clear();
     if (!pts || !out) return fail(c, FS_ERR_INVALID_ARG, "pts or out is NULL");
@@ -441,13 +470,13 @@ fs_status fs_row_norms(fs_ctx *ctx, const void *pts, int32_t dtype, int64_t rows
     if (overlap(out, (size_t)rows * 4, pts, (size_t)((rows - 1) * ld + d) * es))
         return fail(c, FS_ERR_INVALID_ARG, "out overlaps pts");
     if (c->device < 0) return fail(c, FS_ERR_DEVICE, "host-only context: arguments are valid, nothing was launched");
-    FS_HIP(c, hipSetDevice(c->device));
     return launch_row_norms(c, pts, dtype, rows, d, ld, out);
 }
 
 fs_status fs_update_f(fs_ctx *ctx, const fs_problem *prob, float eps, const float *g, float *f_out)
 {
     Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
     fs_status st = validate_problem(c, prob);
     if (st != FS_OK) return st;
     if ((st = validate_eps(c, eps)) != FS_OK) return st;
@@ -466,6 +495,7 @@ fs_status fs_update_f(fs_ctx *ctx, const fs_problem *prob, float eps, const floa
 fs_status fs_update_g(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, float *g_out)
 {
     Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
     fs_status st = validate_problem(c, prob);
     if (st != FS_OK) return st;
     if ((st = validate_eps(c, eps)) != FS_OK) return st;
@@ -481,10 +511,10 @@ fs_status fs_update_g(fs_ctx *ctx, const fs_problem *prob, float eps, const floa
     return finalize(c, &P, &P.Y, splits, eps, 0.0, g_out, nullptr);
 }
 
-fs_status fs_solve(fs_ctx *ctx, const fs_problem *prob, float eps_start, float eps_end, int32_t n_stages,
-                   int32_t iters_per_stage, float *f, float *g)
+static fs_status solve_impl(Ctx *c, const fs_problem *prob, float eps_start, float eps_end, int32_t n_stages,
+                            int32_t iters_per_stage, float *f, float *g)
 {
-    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
     fs_status st = validate_problem(c, prob);
     if (st != FS_OK) return st;
     if ((st = validate_eps(c, eps_end)) != FS_OK) return st;
@@ -523,10 +553,17 @@ fs_status fs_solve(fs_ctx *ctx, const fs_problem *prob, float eps_start, float e
     return FS_OK;
 }
 
+fs_status fs_solve(fs_ctx *ctx, const fs_problem *prob, float eps_start, float eps_end, int32_t n_stages,
+                   int32_t iters_per_stage, float *f, float *g)
+{
+    return solve_impl(reinterpret_cast<Ctx *>(ctx), prob, eps_start, eps_end, n_stages, iters_per_stage, f, g);
+}
+
 fs_status fs_solve_tol(fs_ctx *ctx, const fs_problem *prob, float eps_in, int32_t max_iters, int32_t check_every,
                        float tol, float *f, float *g, int32_t *iters_done, float *err_row_l1)
 {
     Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
     fs_status st = validate_problem(c, prob);
     if (st != FS_OK) return st;
     if ((st = validate_eps(c, eps_in)) != FS_OK) return st;
@@ -583,6 +620,7 @@ fs_status fs_solve_tol(fs_ctx *ctx, const fs_problem *prob, float eps_in, int32_
 fs_status fs_solve_symmetric(fs_ctx *ctx, const fs_problem *prob, float eps_in, int32_t iters, float *f, float *g)
 {
     Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
     fs_status st = validate_problem(c, prob);
     if (st != FS_OK) return st;
     if ((st = validate_eps(c, eps_in)) != FS_OK) return st;
@@ -655,6 +693,7 @@ fs_status fs_marginal_err(fs_ctx *ctx, const fs_problem *prob, float eps, const 
                           float *err_row_l1, float *err_col_l1)
 {
     Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
     fs_status st = validate_problem(c, prob);
     if (st != FS_OK) return st;
     if ((st = validate_eps(c, eps)) != FS_OK) return st;
@@ -685,6 +724,7 @@ fs_status fs_marginal_err(fs_ctx *ctx, const fs_problem *prob, float eps, const 
 fs_status fs_ot_value(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, const float *g, double *value)
 {
     Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
     fs_status st = validate_problem(c, prob);
     if (st != FS_OK) return st;
     if ((st = validate_eps(c, eps)) != FS_OK) return st;
@@ -713,12 +753,12 @@ fs_status fs_ot_value(fs_ctx *ctx, const fs_problem *prob, float eps, const floa
 fs_status fs_check_finite(fs_ctx *ctx, const float *v, int64_t cnt, int64_t *bad_count)
 {
     Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
     if (!c) return FS_ERR_INVALID_ARG;
     c->err.clear();
     if (!v) return fail(c, FS_ERR_INVALID_ARG, "v is NULL");
     if (cnt < 1) return fail(c, FS_ERR_BAD_SHAPE, "cnt must be >= 1");
     if (c->device < 0) return fail(c, FS_ERR_DEVICE, "host-only context: arguments are valid, nothing was launched");
-    FS_HIP(c, hipSetDevice(c->device));
     const size_t nb = (size_t)ceil_div(cnt, 256);
     fs_status st = ensure_aux(c, (nb + 1) * sizeof(double));
     if (st != FS_OK) return st;
@@ -735,6 +775,7 @@ fs_status fs_check_finite(fs_ctx *ctx, const float *v, int64_t cnt, int64_t *bad
 fs_status fs_check_weights(fs_ctx *ctx, const fs_problem *prob, float tol, double *sum_a, double *sum_b)
 {
     Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
     fs_status st = validate_problem(c, prob);
     if (st != FS_OK) return st;
     if (!(tol >= 0.0f) || !(tol < INFINITY)) return fail(c, FS_ERR_INVALID_ARG, "tol must be finite and >= 0");
@@ -742,7 +783,6 @@ fs_status fs_check_weights(fs_ctx *ctx, const fs_problem *prob, float tol, doubl
     if (sum_b) *sum_b = 1.0;
     if (!prob->a && !prob->b) return FS_OK;   // uniform weights on both sides
     if (c->device < 0) return fail(c, FS_ERR_DEVICE, "host-only context: arguments are valid, nothing was launched");
-    FS_HIP(c, hipSetDevice(c->device));
     const size_t ba = (size_t)ceil_div(prob->n, 256), bb = (size_t)ceil_div(prob->m, 256);
     if ((st = ensure_aux(c, (2 * (ba + bb) + 4) * sizeof(double))) != FS_OK) return st;
     double *res = reinterpret_cast<double *>(c->aux), *scratch = res + 4;
@@ -765,6 +805,7 @@ fs_status fs_divergence(fs_ctx *ctx, const fs_problem *prob, float eps, int32_t 
                         double *terms)
 {
     Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
     fs_status st = validate_problem(c, prob);
     if (st != FS_OK) return st;
     if ((st = validate_eps(c, eps)) != FS_OK) return st;
@@ -774,7 +815,6 @@ fs_status fs_divergence(fs_ctx *ctx, const fs_problem *prob, float eps, int32_t 
     if ((st = check_out(c, prob, g, (size_t)prob->m * 4, "g")) != FS_OK) return st;
     if (overlap(f, (size_t)prob->n * 4, g, (size_t)prob->m * 4)) return fail(c, FS_ERR_INVALID_ARG, "f overlaps g");
     if (c->device < 0) return fail(c, FS_ERR_DEVICE, "host-only context: arguments are valid, nothing was launched");
-    FS_HIP(c, hipSetDevice(c->device));
     // potentials of the two self-terms: the entry points called below lay the workspace out anew, so
     // these live in a buffer of their own
     const int64_t big = prob->n > prob->m ? prob->n : prob->m;
@@ -842,6 +882,7 @@ fs_status fs_hvp(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f,
                  int64_t lda, float tau, float eta, int32_t max_cg, float *out, int64_t ldo, int32_t *cg_iters)
 {
     Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
     fs_status st = validate_problem(c, prob);
     if (st != FS_OK) return st;
     if ((st = validate_eps(c, eps)) != FS_OK) return st;
@@ -878,6 +919,7 @@ fs_status fs_apply_plan_hadamard(fs_ctx *ctx, const fs_problem *prob, float eps,
                                  const float *A, int64_t lda, const float *V, int64_t p, int64_t ldv, float *out, int64_t ldo)
 {
     Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
     fs_status st = validate_problem(c, prob);
     if (st != FS_OK) return st;
     if ((st = validate_eps(c, eps)) != FS_OK) return st;
@@ -907,9 +949,31 @@ fs_status fs_apply_plan_hadamard(fs_ctx *ctx, const fs_problem *prob, float eps,
     return f64_apply(c, &P, &P.X, &P.Y, eps, V, p, ldv, out, ldo, nullptr, A, lda);
 }
 
+fs_status fs_debug_set(fs_ctx *ctx, const char *key, int64_t value)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
+    if (!c) return FS_ERR_INVALID_ARG;
+    c->err.clear();
+    if (!key) return fail(c, FS_ERR_INVALID_ARG, "key is NULL");
+    const std::string k(key);
+    if (k == "lowd_splits" && value >= 0 && value <= 1024)
+        c->dbg_lowd_splits = (int)value;
+    else if (k == "lowd_score" && (value == 0 || value == 32 || value == 64))
+        c->dbg_lowd_score = (int)value;
+    else if (k == "lowd_precise_valu" && (value == 0 || value == 1))
+        c->dbg_lowd_precise_valu = (int)value;
+    else if (k == "bf16_variant" && value >= 0 && value <= 15)
+        c->dbg_bf16_variant = (int)value;
+    else
+        return fail(c, FS_ERR_INVALID_ARG, "unknown switch or value out of range: %s = %lld", key, (long long)value);
+    return FS_OK;
+}
+
 fs_status fs_profile_enable(fs_ctx *ctx, int32_t on)
 {
     Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
     if (!c) return FS_ERR_INVALID_ARG;
     c->prof_on = on != 0;
     return FS_OK;
@@ -918,6 +982,7 @@ fs_status fs_profile_enable(fs_ctx *ctx, int32_t on)
 fs_status fs_profile_read(fs_ctx *ctx, double *avg_ms, int64_t *launches, double *pairs_per_launch)
 {
     Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
     if (!c) return FS_ERR_INVALID_ARG;
     if (c->device < 0) return fail(c, FS_ERR_DEVICE, "host-only context");
     FS_HIP(c, hipStreamSynchronize(c->stream));

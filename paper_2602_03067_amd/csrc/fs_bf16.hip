@@ -89,7 +89,7 @@ struct BfArgs {
 constexpr int kVRow = 520;                       // bytes per value column in the LDS image (256 points + pad)
 constexpr int kVImgBytes(int pc) { return (pc * kVRow + 1023) / 1024 * 1024; }
 
-template <int WJ, int NS, int JTW, int PC>
+template <int WJ, int NS, int JTW, int PC, int SCHED = 0>
 __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
 {
     constexpr bool APPLY = PC > 0;
@@ -262,6 +262,44 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
     __builtin_amdgcn_sched_barrier(0);       \
     if (Q < NPW && issue) issue_piece(Q);    \
     __builtin_amdgcn_sched_barrier(0)
+            if constexpr (JTW == 4 && SCHED == 1) {
+                // Barrier in the middle of the stage: F1(g) is requested at the start of the stage and F0(g+1)
+                // right after the barrier, so each fragment read has eight MFMAs (of both waves of the SIMD)
+                // to return behind.
+                read_frags(a1, b1, g, pk1);
+                __builtin_amdgcn_sched_barrier(0);
+                FS_MFMA(0, 0, a0, b0);
+                FS_PIECE(0);
+                FS_MFMA(0, 1, a0, b0);
+                FS_PIECE(1);
+                FS_MFMA(0, 2, a0, b0);
+                FS_PIECE(2);
+                FS_MFMA(0, 3, a0, b0);
+                FS_PIECE(3);
+                FS_MFMA(1, 0, a0, b0);
+                FS_PIECE(4);
+                FS_MFMA(1, 1, a0, b0);
+                FS_PIECE(5);
+                FS_MFMA(1, 2, a0, b0);
+                FS_PIECE(6);
+                FS_MFMA(1, 3, a0, b0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (g + 1 < G) {
+                    wait_landed(g + 1, pg - 1);
+                    lds_done_barrier();
+                    read_frags(a0, b0, g + 1, pk0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                FS_MFMA(0, 0, a1, b1);
+                FS_MFMA(0, 1, a1, b1);
+                FS_MFMA(0, 2, a1, b1);
+                FS_MFMA(0, 3, a1, b1);
+                FS_MFMA(1, 0, a1, b1);
+                FS_MFMA(1, 1, a1, b1);
+                FS_MFMA(1, 2, a1, b1);
+                FS_MFMA(1, 3, a1, b1);
+                continue;
+            }
             if constexpr (JTW == 4) {
                 // (only F0(g) is pending here, so the wait the compiler puts before the first MFMA is
                 // exactly "F0 has arrived"; F1 is requested behind the first MFMA group)
@@ -512,10 +550,10 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
     }
 }
 
-template <int WJ, int NS, int JTW, int PC>
+template <int WJ, int NS, int JTW, int PC, int SCHED = 0>
 __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a)
 {
-    lse_bf16_body<WJ, NS, JTW, PC>(a, blockIdx.x);
+    lse_bf16_body<WJ, NS, JTW, PC, SCHED>(a, blockIdx.x);
 }
 
 // Both LSE passes of one iteration of the averaged schedule (Eq. 4-5) in one launch: the first `blocks0`
@@ -584,7 +622,7 @@ static fs_status lse_pass_args(Ctx *c, const Prepared *P, const Side *res, const
     a.cscale = (float)(2.0 * kLog2e / eps);
     a.n_jtiles = (int)ceil_div(res->cnt, bj);
     a.n_itiles = (int)ceil_div(str->cnt, BI);
-    a.splits = choose_splits(c, a.n_jtiles, a.n_itiles, max_splits(res->cnt), per_cu);
+    a.splits = choose_splits(c, a.n_jtiles, a.n_itiles, max_splits(c->partial_budget, res->cnt), per_cu);
     a.tiles_per_split = (int)ceil_div(a.n_itiles, a.splits);
     const int total = a.n_jtiles * a.splits;
     a.partial = (double2 *)partial;
@@ -604,7 +642,10 @@ fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
     fs_status st = lse_pass_args(c, P, res, str, eps, P->partial, &a, &blocks);
     if (st != FS_OK) return st;
     prof_begin(c, (double)res->cnt * (double)str->cnt);
-    hipLaunchKernelGGL((k_lse_bf16<2, 4, 4, 0>), dim3((unsigned)blocks), dim3(512), 0, c->stream, a);
+    if (c->dbg_bf16_variant == 1)
+        hipLaunchKernelGGL((k_lse_bf16<2, 4, 4, 0, 1>), dim3((unsigned)blocks), dim3(512), 0, c->stream, a);
+    else
+        hipLaunchKernelGGL((k_lse_bf16<2, 4, 4, 0>), dim3((unsigned)blocks), dim3(512), 0, c->stream, a);
     prof_end(c);
     FS_HIP(c, hipGetLastError());
     *splits_out = a.splits;
@@ -644,7 +685,7 @@ fs_status bf16_lse_pair(Ctx *c, const Prepared *P, double eps, void *partial_x, 
 size_t bf16_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str)
 {
     const int n_jtiles = (int)ceil_div(n_res, kApplyBJ), n_itiles = (int)ceil_div(n_str, BI);
-    const int splits = choose_splits(c, n_jtiles, n_itiles, max_splits(n_res), 1);
+    const int splits = choose_splits(c, n_jtiles, n_itiles, max_splits(c->partial_budget, n_res), 1);
     const size_t opart = (size_t)splits * (size_t)round_up(n_res, 1024) * kApplyPC * 4;
     return ((opart + 1023) & ~size_t(1023)) + (size_t)n_itiles * kVImgBytes(kApplyPC);
 }
@@ -660,7 +701,7 @@ fs_status bf16_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str
     a.cscale = (float)(2.0 * kLog2e / eps);
     a.n_jtiles = (int)ceil_div(res->cnt, kApplyBJ);
     a.n_itiles = (int)ceil_div(str->cnt, BI);
-    a.splits = choose_splits(c, a.n_jtiles, a.n_itiles, max_splits(res->cnt), 1);
+    a.splits = choose_splits(c, a.n_jtiles, a.n_itiles, max_splits(c->partial_budget, res->cnt), 1);
     a.tiles_per_split = (int)ceil_div(a.n_itiles, a.splits);
     a.partial = (double2 *)P->partial;
     a.partial_stride = res->cnt_pad;

@@ -522,7 +522,7 @@ PassShape shape_f64(const Ctx *c, int64_t n_res, int64_t n_str, int br, int bc, 
     s.rows_per_block = br;
     s.row_blocks = (int)ceil_div(n_res, br);
     const int n_tiles = (int)ceil_div(n_str, bc);
-    int cap = max_splits(n_res);
+    int cap = max_splits(c->partial_budget, n_res);
     if (cap > n_tiles) cap = n_tiles;
     if (cap < 1) cap = 1;
     const double startup = 64.0 / (double)(kc < 8 ? 8 : kc);   // ~5 us of start-up and wind-down in tile times

@@ -21,10 +21,11 @@ constexpr float kNegInit = -3.0e38f;               // finite "-inf" seed of the 
 constexpr int kLowdMaxD = 16;                      // d <= 16: fp32 vector-ALU path
 // Most column splits of one streaming pass over `n_res` resident rows: as many as fill the chip
 // even for a handful of rows (n << m), as long as the [splits][rows] partial records stay at 64 MB.
-inline int max_splits(int64_t n_res)
+// (`budget`: bytes the records may take; the context's Ctx::partial_budget)
+inline int max_splits(size_t budget, int64_t n_res)
 {
     const int64_t pad = (n_res + 1023) / 1024 * 1024;
-    const int64_t s = (int64_t(64) << 20) / (pad * 16);
+    const int64_t s = (int64_t)budget / (pad * 16);
     return s < 1 ? 1 : (s > 1024 ? 1024 : (int)s);
 }
 
@@ -119,10 +120,18 @@ struct Ctx {
     // grow-only device workspace
     char *ws = nullptr;
     size_t ws_bytes = 0;
+    bool ws_static = false;          // ws is the library's static scratch array for the duration of a call: never freed or grown
+    char *static_ws = nullptr;       // this device's address of the static scratch array (resolved in fs_create)
+    size_t partial_budget = size_t(64) << 20;   // bytes the [splits][rows] partial records of a pass may take
     // grow-only second buffer for entry points that call other entry points (which lay the workspace out anew)
     char *aux = nullptr;
     size_t aux_bytes = 0;
     std::string err;
+    // test and experiment switches of this context (fs_debug_set); 0 = the library decides
+    int dbg_lowd_splits = 0;         // forced split count of the streamed side of a low-d pass
+    int dbg_lowd_score = 0;          // 32: fp32 scores, 64: float64 scores in every low-d half-step
+    int dbg_lowd_precise_valu = 0;   // 1: float64 scores at d <= 3 on the vector ALU instead of the precise records
+    int dbg_bf16_variant = 0;        // schedule variant of the bf16 kernels
     // profiling of the streaming LSE launches
     bool prof_on = false;
     std::vector<hipEvent_t> ev_pool;   // pairs (start, stop)
@@ -198,6 +207,8 @@ struct Prepared {
     double pot_mag_eps = 0.0, logw_mag = 0.0;
     int halfsteps_per_eps = 2;    // LowD: half-steps the caller runs at one eps (error budget)
     bool force_precise = false;   // LowD: float64 scores regardless (marginal error evaluation)
+    int dbg_score = 0;            // LowD: the context's score switch (see Ctx::dbg_lowd_score)
+    bool dbg_precise_valu = false;   // LowD: the context's kernel switch (see Ctx::dbg_lowd_precise_valu)
     int kp = 0;   // F64 / BF16: padded contraction length
     Side X, Y;
     // partial reductions of a streaming pass: [splits][max(n,m)_pad] records

@@ -709,14 +709,15 @@ void launch_apply_d(dim3 grid, hipStream_t st, const S *res, const S *str, const
 // Among the split counts within 2 % of the cheapest the one closest to 32 workgroups per CU from
 // below is taken (finer load balance at large sizes; measured at n = m = 262144), else the smallest.
 // One tile per workgroup, which filling the chip 32 times over used to give at n ~ 10^4, made the
-// pass four times slower than this choice.  FS_LOWD_SPLITS=<s> overrides (experiments only).
+// pass four times slower than this choice.  The context's "lowd_splits" switch overrides (tests and experiments).
 PassShape shape_for(const Ctx *c, int64_t n_res, int64_t n_str, int rows_per_block, int tj = kTJ, int startup_tiles = 7)
 {
     PassShape s;
     s.rows_per_block = rows_per_block;
     s.row_blocks = (int)ceil_div(n_res, s.rows_per_block);
     const int n_tiles = (int)ceil_div(n_str, tj);
-    int smax = n_tiles < max_splits(n_res) ? n_tiles : max_splits(n_res);
+    const int cap_splits = max_splits(c->partial_budget, n_res);
+    int smax = n_tiles < cap_splits ? n_tiles : cap_splits;
     if (smax < 1) smax = 1;
     int legacy = (int)ceil_div(32 * c->num_cu, s.row_blocks);
     if (legacy > smax) legacy = smax;
@@ -732,10 +733,7 @@ PassShape shape_for(const Ctx *c, int64_t n_res, int64_t n_str, int rows_per_blo
         if (cost(sp) <= 1.02 * best) splits = sp;
     for (int sp = legacy + 1; sp <= smax && !splits; ++sp)
         if (cost(sp) <= 1.02 * best) splits = sp;
-    if (const char *e = getenv("FS_LOWD_SPLITS")) {
-        const int v = atoi(e);
-        if (v >= 1) splits = v < smax ? v : smax;
-    }
+    if (c->dbg_lowd_splits >= 1) splits = c->dbg_lowd_splits < smax ? c->dbg_lowd_splits : smax;
     const int tps = (int)ceil_div(n_tiles, splits);
     s.splits = (int)ceil_div(n_tiles, tps);
     s.cols_per_split = (int64_t)tps * tj;
@@ -751,13 +749,13 @@ PassShape shape_for(const Ctx *c, int64_t n_res, int64_t n_str, int rows_per_blo
 // measured against the float64 reference, a run of T half-steps at one eps accumulates about
 // 0.05..0.07 * T * 2^-24 * Mag.  fp32 scores are used while both stay below ~3e-5 and 2e-5, i.e.
 // Mag <= 480 and Mag * T <= 5000; otherwise the scores are formed in float64.
-// FS_LOWD_SCORE=f32|f64 overrides the choice (experiments and tests only).
+// The context's "lowd_score" switch overrides the choice (tests and experiments), except for the
+// measurements that always take float64 scores.
 bool lowd_precise(const Prepared *P, double eps)
 {
-    const char *force = getenv("FS_LOWD_SCORE");
-    if (force && force[0] == 'f' && force[1] == '3') return false;
-    if (force && force[0] == 'f' && force[1] == '6') return true;
     if (P->force_precise) return true;
+    if (P->dbg_score == 32) return false;
+    if (P->dbg_score == 64) return true;
     const double k = kLog2e / eps;
     const double mag = fmax(2.0 * k * P->rho_max, P->pot_mag_eps / eps + P->logw_mag);
     return mag > 480.0 || mag * (double)(P->halfsteps_per_eps > 0 ? P->halfsteps_per_eps : 1) > 5000.0;
@@ -788,8 +786,7 @@ void launch_lse_split(dim3 grid, hipStream_t st, const SplitArgs &a)
 // caller's potentials give, or four times the cost scale for potentials the iteration produces).
 static bool precise_on_matrix_cores(const Prepared *P, const Side *res, const Side *str, double eps, double *gx_out)
 {
-    const char *force = getenv("FS_LOWD_PRECISE");   // "valu": experiments and tests only
-    if (force && force[0] == 'v') return false;
+    if (P->dbg_precise_valu) return false;   // the context's "lowd_precise_valu" switch
     if (P->d > 3 || !str->split_p || !res->packed_d) return false;
     double gx, gy;
     split_grids(P->rho_max, eps, &gx, &gy);

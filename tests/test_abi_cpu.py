@@ -183,6 +183,22 @@ def test_divergence_validation(lib, hctx):
     assert lib.fs_divergence(*args(5)) == 7                        # valid: reaches device stage
 
 
+def test_debug_switches_are_per_context(lib, hctx):
+    assert lib.fs_debug_set(hctx, b"lowd_score", 64) == 0
+    assert lib.fs_debug_set(hctx, b"lowd_score", 0) == 0
+    assert lib.fs_debug_set(hctx, b"lowd_splits", 7) == 0
+    assert lib.fs_debug_set(hctx, b"lowd_precise_valu", 1) == 0
+    assert lib.fs_debug_set(hctx, b"lowd_score", 16) == 1            # value out of range
+    assert lib.fs_debug_set(hctx, b"lowd_splits", -1) == 1
+    assert lib.fs_debug_set(hctx, b"no_such_switch", 1) == 1 and b"no_such_switch" in lib.fs_last_error(hctx)
+    assert lib.fs_debug_set(hctx, None, 1) == 1
+    assert lib.fs_debug_set(None, b"lowd_score", 0) == 1
+    # the library reads no environment variable: its sources do not call getenv
+    import glob
+    for src in glob.glob(os.path.join(ROOT, "paper_2602_03067_amd", "csrc", "*")):
+        assert "getenv" not in open(src).read(), src
+
+
 def test_row_norms_validation(lib, hctx):
     assert lib.fs_row_norms(hctx, None, 0, 4, 3, 3, P(1 << 20)) == 1
     assert lib.fs_row_norms(hctx, P(4096), 0, 0, 3, 3, P(1 << 20)) == 2

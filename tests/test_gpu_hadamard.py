@@ -75,8 +75,9 @@ def test_hadamard_transport_with_the_clouds_own_points_and_row_strides(ctx, orac
     lib = ctx.lib
     out = torch.full((n, d + 3), 7.0, dtype=torch.float32, device="cuda:0")
     import ctypes
-    st = lib.fs_apply_plan_hadamard(ctx.h, ctypes.byref(prob.c), eps, ctypes.c_void_p(dev(f32).data_ptr()),
-                                    ctypes.c_void_p(dev(g32).data_ptr()), ctypes.c_void_p(A_dev.data_ptr()), d + 2,
+    f_dev, g_dev = dev(f32), dev(g32)
+    st = lib.fs_apply_plan_hadamard(ctx.h, ctypes.byref(prob.c), eps, ctypes.c_void_p(f_dev.data_ptr()),
+                                    ctypes.c_void_p(g_dev.data_ptr()), ctypes.c_void_p(A_dev.data_ptr()), d + 2,
                                     ctypes.c_void_p(prob.y.data_ptr()), d, prob.y.stride(0),
                                     ctypes.c_void_p(out.data_ptr()), d + 3)
     assert st == 0

@@ -3,8 +3,6 @@
 Tolerances: |f_gpu - f_oracle| / eps <= 1e-4 and marginal errors equal to 1e-5 (the
 fp32-path bar); plan applications 2e-4 relative (Frobenius) and 1e-3 of the largest entry.
 """
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -91,16 +89,11 @@ def test_running_max_is_lifted_many_times(ctx, oracle, direction, score):
     say("update_f with a potential ramp of 400 (%s), scores %s, n=%d m=%d"
         % ("rising" if direction > 0 else "falling", score, n, m))
     prob = make_problem(x, y, a, b)
-    old = os.environ.get("FS_LOWD_SCORE")
     try:
-        if score != "auto":
-            os.environ["FS_LOWD_SCORE"] = score
+        ctx.fs_debug_set("lowd_score", {"auto": 0, "f32": 32, "f64": 64}[score])
         f_gpu = host(ctx.fs_update_f(prob, eps, dev(g)))
     finally:
-        if old is None:
-            os.environ.pop("FS_LOWD_SCORE", None)
-        else:
-            os.environ["FS_LOWD_SCORE"] = old
+        ctx.fs_debug_set("lowd_score", 0)
     err = max_err_over_eps(f_gpu, oracle.update_f(x, y, b, eps, g), eps)
     say("  max|df|/eps = %.3e" % err)
     assert err <= (TOL if score == "auto" else 1e-3)
@@ -315,8 +308,7 @@ def test_float64_scores_above_three_dimensions(ctx, oracle, n, m, d, p):
     A = rng.standard_normal((n, d)).astype(np.float32)
     say("float64 scores forced, n=%d m=%d d=%d p=%d" % (n, m, d, p))
     prob = make_problem(x, y, a, b)
-    old = os.environ.get("FS_LOWD_SCORE")
-    os.environ["FS_LOWD_SCORE"] = "f64"
+    ctx.fs_debug_set("lowd_score", 64)
     try:
         f_gpu = host(ctx.fs_update_f(prob, eps, dev(g32)))
         g_gpu = host(ctx.fs_update_g(prob, eps, dev(f32)))
@@ -326,10 +318,7 @@ def test_float64_scores_above_three_dimensions(ctx, oracle, n, m, d, p):
         ctx.fs_solve_symmetric(prob, eps, 6, fs, gs)
         G, k = ctx.fs_hvp(prob, eps, dev(fo.astype(np.float32)), dev(g32), dev(A), 1e-5, 1e-6, 400)
     finally:
-        if old is None:
-            os.environ.pop("FS_LOWD_SCORE", None)
-        else:
-            os.environ["FS_LOWD_SCORE"] = old
+        ctx.fs_debug_set("lowd_score", 0)
     assert max_err_over_eps(f_gpu, oracle.update_f(x, y, b, eps, g32), eps) <= TOL
     assert max_err_over_eps(g_gpu, oracle.update_g(x, y, a, eps, f32), eps) <= TOL
     want, r = oracle.apply_plan(x, y, a, b, eps, f32, g32, V, return_mass=True)
@@ -366,25 +355,21 @@ def test_float64_scores_above_three_dimensions_many_blocks(ctx, oracle):
     cols = np.sort(rng.choice(m, 200, replace=False))
     say("float64 scores forced at n=%d m=%d d=%d, sampled rows" % (n, m, d))
     prob = make_problem(x, y, a, b)
-    old = os.environ.get("FS_LOWD_SCORE")
-    os.environ["FS_LOWD_SCORE"] = "f64"
+    ctx.fs_debug_set("lowd_score", 64)
     try:
         f_gpu = host(ctx.fs_update_f(prob, eps, dev(g)))
         g_gpu = host(ctx.fs_update_g(prob, eps, dev(f)))
         V = rng.standard_normal((m, 3)).astype(np.float32)
         out = host(ctx.fs_apply_plan(prob, eps, dev(f_gpu), dev(g), dev(V)))
     finally:
-        if old is None:
-            os.environ.pop("FS_LOWD_SCORE", None)
-        else:
-            os.environ["FS_LOWD_SCORE"] = old
+        ctx.fs_debug_set("lowd_score", 0)
     assert max_err_over_eps(f_gpu[rows], oracle.update_f(x, y, b, eps, g, rows=rows), eps) <= TOL
     assert max_err_over_eps(g_gpu[cols], oracle.update_g(x, y, a, eps, f, cols=cols), eps) <= TOL
     want = oracle.apply_plan(x, y, a, b, eps, f_gpu, g, V, rows=rows)
     assert np.linalg.norm(out[rows] - want) <= 2e-4 * np.linalg.norm(want)
 
 
-@pytest.mark.parametrize("hook,value", [("FS_LOWD_SPLITS", "1"), ("FS_LOWD_SPLITS", "7"), ("FS_LOWD_PRECISE", "valu")])
+@pytest.mark.parametrize("hook,value", [("lowd_splits", 1), ("lowd_splits", 7), ("lowd_precise_valu", 1)])
 def test_alternative_launch_shapes_and_kernels_agree(ctx, oracle, hook, value):
     """The library's experiment switches (a forced split count of the streamed side; float64 scores on the
     vector ALU instead of the precise split records) must give the same potentials: a cross-check of the
@@ -395,17 +380,13 @@ def test_alternative_launch_shapes_and_kernels_agree(ctx, oracle, hook, value):
     eps = float(np.float32(0.01))   # small enough for float64 scores
     g = (0.05 * rng.standard_normal(m)).astype(np.float32)
     f = (0.05 * rng.standard_normal(n)).astype(np.float32)
-    say("update_f/update_g with %s=%s, n=%d m=%d d=%d eps=%g" % (hook, value, n, m, d, eps))
+    say("update_f/update_g with the context switch %s=%s, n=%d m=%d d=%d eps=%g" % (hook, value, n, m, d, eps))
     prob = make_problem(x, y, a, b)
-    old = os.environ.get(hook)
-    os.environ[hook] = value
+    ctx.fs_debug_set(hook, value)
     try:
         f_gpu = host(ctx.fs_update_f(prob, eps, dev(g)))
         g_gpu = host(ctx.fs_update_g(prob, eps, dev(f)))
     finally:
-        if old is None:
-            os.environ.pop(hook, None)
-        else:
-            os.environ[hook] = old
+        ctx.fs_debug_set(hook, 0)
     assert max_err_over_eps(f_gpu, oracle.update_f(x, y, b, eps, g), eps) <= TOL
     assert max_err_over_eps(g_gpu, oracle.update_g(x, y, a, eps, f), eps) <= TOL
