@@ -145,6 +145,23 @@ fs_status fs_solve(fs_ctx *ctx, const fs_problem *prob, float eps_start, float e
                    int32_t n_stages, int32_t iters_per_stage, float *f, float *g);
 
 /*
+ * fs_solve for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same arguments, arithmetic and results as fs_solve, but
+ * the workspace (derived copies of x and y, norms, biases, potentials, partial reductions) lives in a
+ * static device array of 32 MiB inside the library, of which the partial reductions of a pass take at
+ * most 8 MiB (so a pass may be cut into fewer column splits than fs_solve would choose).  The call
+ * performs no hipMalloc / hipFree and leaves the context's own workspace untouched.  Problems whose
+ * workspace does not fit are refused with FS_ERR_BAD_SHAPE before anything is launched (n = m up to
+ * 54272 at d = 3, 15360 at d = 16, 22528 at d = 64, 5120 at d = 1024 in bfloat16 mode).
+ * Every GPU holds ONE such array for the whole process: calls of this entry point that overlap in time
+ * on one GPU -- from any context or stream -- race on it.  Nothing is assumed about its contents on
+ * entry (it keeps what the previous call left).  Synchronises like fs_solve.
+ */
+fs_status fs_solve_noalloc(fs_ctx *ctx, const fs_problem *prob, float eps_start, float eps_end,
+                           int32_t n_stages, int32_t iters_per_stage, float *f /* device, in/out */,
+                           float *g /* device, in/out */);
+
+/*
  * Symmetric (Jacobi, averaged) schedule with a fixed iteration count (Eq. 4-5):
  * in every iteration both updates read the OLD potentials,
  *     f <- f/2 + (1/2) (-eps LSE_j[(g_j - C_ij)/eps + log b_j]),

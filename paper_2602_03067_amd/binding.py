@@ -21,7 +21,7 @@ FS_COMPUTE_FP32, FS_COMPUTE_BF16_MFMA = 0, 1
 
 EXPORTS = (
     "fs_create", "fs_destroy", "fs_status_str", "fs_last_error", "fs_version", "fs_row_norms",
-    "fs_update_f", "fs_update_g", "fs_solve", "fs_solve_symmetric", "fs_solve_tol", "fs_marginal_err", "fs_ot_value", "fs_check_weights", "fs_check_finite", "fs_divergence", "fs_apply_plan",
+    "fs_update_f", "fs_update_g", "fs_solve", "fs_solve_noalloc", "fs_solve_symmetric", "fs_solve_tol", "fs_marginal_err", "fs_ot_value", "fs_check_weights", "fs_check_finite", "fs_divergence", "fs_apply_plan",
     "fs_apply_plan_T", "fs_apply_plan_hadamard", "fs_grad_x", "fs_grad_y", "fs_hvp", "fs_debug_set", "fs_profile_enable", "fs_profile_read",
 )
 
@@ -70,6 +70,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fs_update_f.argtypes = [vp, PP, f32, vp, vp]
     lib.fs_update_g.argtypes = [vp, PP, f32, vp, vp]
     lib.fs_solve.argtypes = [vp, PP, f32, f32, i32, i32, vp, vp]
+    lib.fs_solve_noalloc.argtypes = [vp, PP, f32, f32, i32, i32, vp, vp]
     lib.fs_solve_symmetric.argtypes = [vp, PP, f32, i32, vp, vp]
     lib.fs_solve_tol.argtypes = [vp, PP, f32, i32, i32, f32, vp, vp, ctypes.POINTER(i32), ctypes.POINTER(f32)]
     lib.fs_marginal_err.argtypes = [vp, PP, f32, vp, vp, ctypes.POINTER(f32), ctypes.POINTER(f32)]
@@ -194,6 +195,15 @@ class Context:
         self._check(self.lib.fs_solve(self.h, ctypes.byref(prob.c), eps_start, eps_end,
                                       int(n_stages), int(iters_per_stage), _ptr(f), _ptr(g)),
                     "fs_solve")
+
+    def fs_solve_noalloc(self, prob: Problem, eps_start: float, eps_end: float, n_stages: int,
+                         iters_per_stage: int, f: torch.Tensor, g: torch.Tensor) -> None:
+        """fs_solve in the library's static scratch array (no device allocation); in place like fs_solve."""
+        _dev_f32(f, "f", (prob.n,))
+        _dev_f32(g, "g", (prob.m,))
+        self._check(self.lib.fs_solve_noalloc(self.h, ctypes.byref(prob.c), eps_start, eps_end,
+                                              int(n_stages), int(iters_per_stage), _ptr(f), _ptr(g)),
+                    "fs_solve_noalloc")
 
     def fs_solve_tol(self, prob: Problem, eps: float, max_iters: int, check_every: int, tol: float,
                      f: torch.Tensor, g: torch.Tensor) -> Tuple[int, float]:

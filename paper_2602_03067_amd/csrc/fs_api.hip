@@ -50,6 +50,14 @@ void prof_end(Ctx *c)
 
 namespace {
 
+// Workspace of the entry point that allocates nothing (fs_solve_noalloc): every GPU the library runs on holds
+// its own copy of this array, at its own address, until the process ends.  In host code the name is only a
+// handle for hipGetSymbolAddress (fs_create resolves it, with the context's device current); kernels and
+// copies get the resolved address.
+constexpr size_t kStaticScratchBytes = size_t(32) << 20;
+constexpr size_t kStaticPartialBudget = size_t(8) << 20;   // of which the partial records of a pass may take
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 // Makes the context's device current for the duration of an entry call and restores the caller's.
 struct DeviceGuard {
     int prev = -1;
@@ -435,7 +443,15 @@ fs_status fs_create(fs_ctx **ctx, int device, void *hip_stream)
     int cu = 0;
     if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cu > 0)
         c->num_cu = cu;
+    // this device's copy of the static scratch array (the device is current here)
+    void *sp = nullptr;
+    const hipError_t se = hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch));
     if (had_prev && prev != device) (void)hipSetDevice(prev);
+    if (se != hipSuccess || !sp) {
+        delete c;
+        return FS_ERR_DEVICE;
+    }
+    c->static_ws = static_cast<char *>(sp);
     *ctx = reinterpret_cast<fs_ctx *>(c);
     return FS_OK;
 }
@@ -511,8 +527,9 @@ fs_status fs_update_g(fs_ctx *ctx, const fs_problem *prob, float eps, const floa
     return finalize(c, &P, &P.Y, splits, eps, 0.0, g_out, nullptr);
 }
 
+// fs_solve and fs_solve_noalloc: `static_only` runs in the library's static scratch array and fails instead of allocating
 static fs_status solve_impl(Ctx *c, const fs_problem *prob, float eps_start, float eps_end, int32_t n_stages,
-                            int32_t iters_per_stage, float *f, float *g)
+                            int32_t iters_per_stage, float *f, float *g, bool static_only)
 {
     DeviceGuard device_guard(c);
     fs_status st = validate_problem(c, prob);
@@ -525,6 +542,44 @@ static fs_status solve_impl(Ctx *c, const fs_problem *prob, float eps_start, flo
     if ((st = check_out(c, prob, g, (size_t)prob->m * 4, "g")) != FS_OK) return st;
     if (overlap(f, (size_t)prob->n * 4, g, (size_t)prob->m * 4))
         return fail(c, FS_ERR_INVALID_ARG, "f overlaps g");
+    // The workspace of a call that may not allocate is the static scratch array: sizes beyond it are refused here,
+    // on the host, before anything is launched (also on a host-only context).
+    struct StaticWs {   // swaps the static array in as the context's workspace for this call
+        Ctx *c;
+        char *ws;
+        size_t bytes, budget;
+        explicit StaticWs(Ctx *c_) : c(c_), ws(c_->ws), bytes(c_->ws_bytes), budget(c_->partial_budget)
+        {
+            c->ws = c->static_ws;
+            c->ws_bytes = kStaticScratchBytes;
+            c->ws_static = true;
+            c->partial_budget = kStaticPartialBudget;
+        }
+        ~StaticWs()
+        {
+            c->ws = ws;
+            c->ws_bytes = bytes;
+            c->ws_static = false;
+            c->partial_budget = budget;
+        }
+    };
+    struct Maybe {   // (no heap: the guard lives in this frame)
+        alignas(StaticWs) unsigned char buf[sizeof(StaticWs)];
+        StaticWs *p = nullptr;
+        ~Maybe()
+        {
+            if (p) p->~StaticWs();
+        }
+    } sw;
+    if (static_only) {
+        sw.p = new (sw.buf) StaticWs(c);
+        Prepared sizing;
+        const size_t need = layout(c, prob, &sizing, nullptr, 0);
+        if (need > kStaticScratchBytes)
+            return fail(c, FS_ERR_BAD_SHAPE,
+                        "this problem needs %zu bytes of workspace; fs_solve_noalloc holds %zu (use fs_solve)", need,
+                        kStaticScratchBytes);
+    }
     if (iters_per_stage == 0) return c->device < 0 ? fail(c, FS_ERR_DEVICE, "host-only context") : FS_OK;
 
     Prepared P;
@@ -556,7 +611,13 @@ static fs_status solve_impl(Ctx *c, const fs_problem *prob, float eps_start, flo
 fs_status fs_solve(fs_ctx *ctx, const fs_problem *prob, float eps_start, float eps_end, int32_t n_stages,
                    int32_t iters_per_stage, float *f, float *g)
 {
-    return solve_impl(reinterpret_cast<Ctx *>(ctx), prob, eps_start, eps_end, n_stages, iters_per_stage, f, g);
+    return solve_impl(reinterpret_cast<Ctx *>(ctx), prob, eps_start, eps_end, n_stages, iters_per_stage, f, g, false);
+}
+
+fs_status fs_solve_noalloc(fs_ctx *ctx, const fs_problem *prob, float eps_start, float eps_end, int32_t n_stages,
+                           int32_t iters_per_stage, float *f, float *g)
+{
+    return solve_impl(reinterpret_cast<Ctx *>(ctx), prob, eps_start, eps_end, n_stages, iters_per_stage, f, g, true);
 }
 
 fs_status fs_solve_tol(fs_ctx *ctx, const fs_problem *prob, float eps_in, int32_t max_iters, int32_t check_every,

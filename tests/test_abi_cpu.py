@@ -114,6 +114,22 @@ def test_solve_count_validation(lib, hctx):
     assert lib.fs_ot_value(hctx, ctypes.byref(p), F(-1.0), P(1 << 21), P(1 << 20), ctypes.byref(v)) == 3
 
 
+def test_noalloc_solve_checks_sizes_on_the_host(lib, hctx):
+    """fs_solve_noalloc validates like fs_solve and refuses, before any launch, a problem whose workspace is beyond
+    the static scratch array."""
+    args = lambda p, **kw: (hctx, ctypes.byref(p), F(kw.get("e0", 0.1)), F(kw.get("e1", 0.1)), kw.get("stages", 1),
+                            kw.get("iters", 1), P(1 << 32), P(1 << 33))
+    small = _prob(n=50000, m=50000)
+    assert lib.fs_solve_noalloc(*args(small)) == 7                     # valid: reaches device stage
+    big = _prob(n=60000, m=60000)
+    assert lib.fs_solve_noalloc(*args(big)) == 2 and b"fs_solve_noalloc" in lib.fs_last_error(hctx)
+    assert lib.fs_solve(*args(big)) == 7                               # the allocating entry point takes it
+    assert lib.fs_solve_noalloc(*args(big, iters=0)) == 2              # also with nothing to do
+    assert lib.fs_solve_noalloc(*args(small, e1=-1.0)) == 3
+    assert lib.fs_solve_noalloc(*args(small, stages=0)) == 3
+    assert lib.fs_solve_noalloc(*args(_prob(d=0))) == 2
+
+
 def test_null_and_aliasing(lib, hctx):
     p = _prob()
     assert lib.fs_update_f(hctx, ctypes.byref(p), F(0.1), None, P(1 << 21)) == 1
