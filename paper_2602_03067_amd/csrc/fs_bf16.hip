@@ -16,8 +16,9 @@
 //   D: lane l, register r holds D[i = 8*(r/4) + 4*(l/32) + r%4][j = l%32],
 // i.e. the 16 accumulator registers of a lane are 16 streamed points of ONE resident row, so
 // the row-wise LSE runs inside the lane; lanes/waves are merged once per workgroup.
-#include "fs_internal.h"
+#include <type_traits>
 
+#include "fs_internal.h"
 
 namespace fs {
 namespace {
@@ -35,6 +36,46 @@ __device__ inline float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
 // all LDS reads of this wave have returned, then the workgroup barrier
 __device__ inline void lds_done_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 template <int N> __device__ inline void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+// N consecutive 1 KB pieces (N <= 4) by direct global -> LDS loads behind ONE write of the LDS base to m0, the
+// pieces addressed by immediate offsets (they advance the memory and the LDS address alike).  A write to m0 waits
+// until the wave's earlier direct loads have left for the address unit, so a load with its own m0 write between the
+// MFMAs of the contraction loop stalls the wave behind the queue of all eight waves' loads: issuing a stage's loads
+// as one run took the pass at n = m = 70000, d = 784 from 7.7 to 6.6 ms.
+template <int N>
+__device__ inline void dma16_run(const void *g_uniform, unsigned lane_off, unsigned lds_off)
+{
+    static_assert(N >= 1 && N <= 4, "immediate offsets reach 3 KB");
+    if constexpr (N == 1)
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(g_uniform), "s"(lds_off)
+                     : "memory", "m0");
+    else if constexpr (N == 2)
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n\tglobal_load_lds_dwordx4 %0, %1 offset:1024" ::"v"(
+                         lane_off),
+                     "s"(g_uniform), "s"(lds_off)
+                     : "memory", "m0");
+    else if constexpr (N == 3)
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n\tglobal_load_lds_dwordx4 %0, %1 offset:1024\n\t"
+                     "global_load_lds_dwordx4 %0, %1 offset:2048" ::"v"(lane_off),
+                     "s"(g_uniform), "s"(lds_off)
+                     : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n\tglobal_load_lds_dwordx4 %0, %1 offset:1024\n\t"
+                     "global_load_lds_dwordx4 %0, %1 offset:2048\n\tglobal_load_lds_dwordx4 %0, %1 offset:3072" ::"v"(lane_off),
+                     "s"(g_uniform), "s"(lds_off)
+                     : "memory", "m0");
+}
+// (n is uniform over the wave)
+__device__ inline void dma16_run_n(int n, const void *g_uniform, unsigned lane_off, unsigned lds_off)
+{
+    switch (n) {
+    case 1: dma16_run<1>(g_uniform, lane_off, lds_off); break;
+    case 2: dma16_run<2>(g_uniform, lane_off, lds_off); break;
+    case 3: dma16_run<3>(g_uniform, lane_off, lds_off); break;
+    case 4: dma16_run<4>(g_uniform, lane_off, lds_off); break;
+    default: break;
+    }
+}
 
 struct BfArgs {
     const uint16_t *res;     // resident side, tiled bf16 copy (see k_prep_bf16)
@@ -89,7 +130,7 @@ struct BfArgs {
 constexpr int kVRow = 520;                       // bytes per value column in the LDS image (256 points + pad)
 constexpr int kVImgBytes(int pc) { return (pc * kVRow + 1023) / 1024 * 1024; }
 
-template <int WJ, int NS, int JTW, int PC, int SCHED = 0>
+template <int WJ, int NS, int JTW, int PC>
 __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
 {
     constexpr bool APPLY = PC > 0;
@@ -98,12 +139,11 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
     constexpr int STAGE_BYTES = ROWS * KC * 2;   // 32 KB / 24 KB
     constexpr int NW = 4 * WJ;                   // waves
     constexpr int PPW = (ROWS / 16) / NW;        // 1 KB pieces of a stage per wave
-    constexpr int NPW = PPW + 1;                 // ... plus its share of the bias tile
     constexpr int D = NS - 1;                    // stages in flight
     constexpr int NCB = APPLY ? PC / 32 : 1;     // 32-column blocks of the value matrix
     constexpr int VIMG = APPLY ? kVImgBytes(PC) : 16;
     constexpr int NVP = VIMG / 1024;             // 1 KB pieces of a value image
-    static_assert((ROWS / 16) % NW == 0 && NPW <= 12 && D >= 2 && D <= 3, "pipeline shape");
+    static_assert((ROWS / 16) % NW == 0 && PPW <= 4 && D >= 2 && D <= 3, "pipeline shape");
     static_assert(JTW == 4 || JTW == 2, "MFMA schedules below");
     static_assert(!APPLY || (PC % 32 == 0 && BJ * PC * 4 + BJ * 64 <= NS * STAGE_BYTES), "merge buffers fit the ring");
     __shared__ __attribute__((aligned(1024))) unsigned char ring[NS * STAGE_BYTES];
@@ -156,30 +196,33 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
     const unsigned bias_off = (unsigned)(size_t)&bias_ring[0][0];
     const unsigned vimg_off = (unsigned)(size_t)vimg;
 
-    // The bf16 copies are stored as 1 KB tiles (16 rows x 32 coordinates, already swizzled), tile
-    // (row block rb, chunk ch) at byte ((rb * n_chunks + ch) << 10): a stage is ROWS/16 linear
-    // 1 KB copies, PPW per wave (pieces q NW + w; 0..15 streamed rows, then the resident rows).
-    const unsigned char *res_tiles =
-        reinterpret_cast<const unsigned char *>(a.res) + (((int64_t)jtile * (BJ / 16) * n_chunks) << 10);
+    // The bf16 copies are stored as 1 KB tiles (16 rows x 32 coordinates, already swizzled); the sixteen
+    // tiles of a group of 256 rows at one chunk are contiguous (16 KB) and the chunks of a group follow
+    // each other: a stage is ROWS/16 linear 1 KB copies, PPW consecutive ones per wave (pieces w PPW + q;
+    // 0..15 streamed rows, then the resident rows), so a wave's loads of a stage, and of the next, walk
+    // through memory linearly.
+    const unsigned char *res_tiles = reinterpret_cast<const unsigned char *>(a.res) +
+                                     (((int64_t)(row0 >> 8) * n_chunks * 16 + ((row0 >> 4) & 15)) << 10);
     const unsigned char *str_tiles = reinterpret_cast<const unsigned char *>(a.str);
     const unsigned l16 = l * 16, l4 = l * 4;
 
     int pg = 0, pch = 0, pt = t_begin;   // next stage this wave issues: number, chunk, tile
-    auto issue_piece = [&](int q) {      // q < PPW: 1 KB of points, q == PPW: bias, then advance to the next stage
-        if (q < PPW) {
-            const int sidx = q * NW + w;
-            const unsigned char *src = sidx < 16 ? str_tiles + ((((int64_t)pt * 16 + sidx) * n_chunks + pch) << 10)
-                                                 : res_tiles + ((((int64_t)(sidx - 16)) * n_chunks + pch) << 10);
-            dma16s(src, l16, ring_off + (pg % NS) * STAGE_BYTES + sidx * 1024);
-        } else {
-            // (with two waves per streamed quarter both write the same 256 bytes: harmless, and every
-            // wave has the same number of loads in flight)
-            dma4s(a.bias + (int64_t)pt * BI + wi * 64, l4, bias_off + (pg & (NBIAS - 1)) * (BI * 4) + wi * 256);
-            ++pg;
-            if (++pch == n_chunks) {
-                pch = 0;
-                ++pt;
-            }
+    // This wave's share of the next stage: PPW consecutive pieces starting at piece w PPW, i.e. one run of the
+    // streamed group and / or one of the resident group; with the first stage of a tile also the wave's quarter of the
+    // tile's biases (with two waves per streamed quarter both write the same 256 bytes: harmless).
+    auto issue_stage = [&]() {
+        if (pch == 0) dma4s(a.bias + (int64_t)pt * BI + wi * 64, l4, bias_off + ((pt - t_begin) & (NBIAS - 1)) * (BI * 4) + wi * 256);
+        const int s0 = w * PPW;
+        const int n_str = s0 >= 16 ? 0 : (16 - s0 < PPW ? 16 - s0 : PPW);
+        const unsigned lds = ring_off + (pg % NS) * STAGE_BYTES;
+        if (n_str > 0)
+            dma16_run_n(n_str, str_tiles + ((((int64_t)pt * n_chunks + pch) * 16 + s0) << 10), l16, lds + s0 * 1024);
+        if (n_str < PPW)
+            dma16_run_n(PPW - n_str, res_tiles + (((int64_t)pch * 16 + (s0 + n_str - 16)) << 10), l16, lds + (s0 + n_str) * 1024);
+        ++pg;
+        if (++pch == n_chunks) {
+            pch = 0;
+            ++pt;
         }
     };
 
@@ -215,10 +258,12 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
     // (loads of a value image issued in between only make these waits stricter)
     auto wait_landed = [&](int upto, int issued) {
         const int newer = issued - upto;   // whole stages issued after `upto`
+        // (a stage has PPW loads of this wave, the first stage of a tile one more: counting PPW per newer stage
+        // can only wait for more than necessary)
         if (newer >= 2)
-            wait_vm<2 * NPW>();
+            wait_vm<2 * PPW>();
         else if (newer == 1)
-            wait_vm<NPW>();
+            wait_vm<PPW>();
         else
             wait_vm<0>();
     };
@@ -226,19 +271,21 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
     auto issue_vimg = [&](int t) {
         if constexpr (APPLY) {
             const unsigned char *src = reinterpret_cast<const unsigned char *>(a.vimg) + (int64_t)t * VIMG;
+            // consecutive pieces per wave, in runs of up to four behind one LDS base each
+            constexpr int VPW = (NVP + NW - 1) / NW;
+            const int p0 = w * VPW;
+            const int cnt = p0 >= NVP ? 0 : (NVP - p0 < VPW ? NVP - p0 : VPW);
 #pragma unroll
-            for (int q = 0; q * NW < NVP; ++q) {
-                const int pidx = q * NW + w;
-                if (pidx < NVP) dma16s(src + pidx * 1024, l16, vimg_off + pidx * 1024);
+            for (int r0 = 0; r0 < VPW; r0 += 4) {
+                const int n = cnt - r0 < 4 ? cnt - r0 : 4;
+                if (n > 0) dma16_run_n(n, src + (p0 + r0) * 1024, l16, vimg_off + (p0 + r0) * 1024);
             }
             vstamp = pg;
         }
     };
 
     // ---- prologue: D stages in flight, stage 0 landed, its first fragments on the way ----
-    while (pg < D && pg < G)
-#pragma unroll
-        for (int q = 0; q < NPW; ++q) issue_piece(q);
+    while (pg < D && pg < G) issue_stage();
     wait_landed(0, pg - 1);
     lds_done_barrier();
     read_frags(a0, b0, 0, pk0);
@@ -246,79 +293,81 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
     int g = 0;
     for (int t = t_begin; t < t_end; ++t) {
         f16v acc[2][JTW];
+        if constexpr (APPLY) {
 #pragma unroll
-        for (int it = 0; it < 2; ++it)
+            for (int it = 0; it < 2; ++it)
 #pragma unroll
-            for (int jt = 0; jt < JTW; ++jt)
+                for (int jt = 0; jt < JTW; ++jt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[it][jt][r] = 0.0f;
+                    for (int r = 0; r < 16; ++r) acc[it][jt][r] = 0.0f;
+        }
 
-        for (int ch = 0; ch < n_chunks; ++ch, ++g) {
+        if constexpr (!APPLY) {
+            // One stage of the LSE pass.  The first chunk of a tile has a code copy of its own, in which the first
+            // eight MFMAs start from a zero accumulator operand: no registers to clear per tile.
+            //     4 MFMA on F0(g) | read F1(g), issue stage g+3 | 4 MFMA on F0(g) | 4 MFMA on F1(g) |
+            //     wait "stage g+1 landed" + barrier | read F0(g+1) | 4 MFMA on F1(g)
             // Stage g + D goes to the ring slot of stage g - 1, which nobody reads any more: every
             // wave had its reads of that stage back before it passed the barrier of stage g - 1.
+            auto stage = [&](auto first_c) {
+                constexpr bool FIRST = decltype(first_c)::value;
+                const f16v zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+#define FS_MFMA0(IT, JT) acc[IT][JT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[IT], b0[JT], FIRST ? zero : acc[IT][JT], 0, 0, 0)
+#define FS_MFMA1(IT, JT) acc[IT][JT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[IT], b1[JT], acc[IT][JT], 0, 0, 0)
+                // (only F0(g) is pending here, so the wait the compiler puts before the first MFMA is
+                // exactly "F0 has arrived"; F1 is requested behind the first MFMA group)
+                FS_MFMA0(0, 0);
+                FS_MFMA0(0, 1);
+                FS_MFMA0(0, 2);
+                FS_MFMA0(0, 3);
+                __builtin_amdgcn_sched_barrier(0);
+                read_frags(a1, b1, g, pk1);
+                if (g + D < G) issue_stage();
+                __builtin_amdgcn_sched_barrier(0);
+                FS_MFMA0(1, 0);
+                FS_MFMA0(1, 1);
+                FS_MFMA0(1, 2);
+                FS_MFMA0(1, 3);
+                FS_MFMA1(0, 0);
+                FS_MFMA1(0, 1);
+                FS_MFMA1(0, 2);
+                FS_MFMA1(0, 3);
+                __builtin_amdgcn_sched_barrier(0);
+                if (g + 1 < G) {
+                    wait_landed(g + 1, pg - 1);   // this wave's pieces of stage g+1 have landed ...
+                    lds_done_barrier();           // ... and after the barrier everybody's; F0 may be refilled
+                    read_frags(a0, b0, g + 1, pk0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                FS_MFMA1(1, 0);
+                FS_MFMA1(1, 1);
+                FS_MFMA1(1, 2);
+                FS_MFMA1(1, 3);
+#undef FS_MFMA0
+#undef FS_MFMA1
+                ++g;
+            };
+            stage(std::integral_constant<bool, true>{});
+            for (int ch = 1; ch < n_chunks; ++ch) stage(std::integral_constant<bool, false>{});
+        }
+        for (int ch = 0; APPLY && ch < n_chunks; ++ch, ++g) {
             const bool issue = g + D < G;
 #define FS_MFMA(IT, JT, AF, BF) acc[IT][JT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(AF[IT], BF[JT], acc[IT][JT], 0, 0, 0)
 #define FS_PIECE(Q)                          \
     __builtin_amdgcn_sched_barrier(0);       \
-    if (Q < NPW && issue) issue_piece(Q);    \
+    if (Q == 0 && issue) issue_stage();      \
     __builtin_amdgcn_sched_barrier(0)
-            if constexpr (JTW == 4 && SCHED == 1) {
-                // Barrier in the middle of the stage: F1(g) is requested at the start of the stage and F0(g+1)
-                // right after the barrier, so each fragment read has eight MFMAs (of both waves of the SIMD)
-                // to return behind.
-                read_frags(a1, b1, g, pk1);
-                __builtin_amdgcn_sched_barrier(0);
-                FS_MFMA(0, 0, a0, b0);
-                FS_PIECE(0);
-                FS_MFMA(0, 1, a0, b0);
-                FS_PIECE(1);
-                FS_MFMA(0, 2, a0, b0);
-                FS_PIECE(2);
-                FS_MFMA(0, 3, a0, b0);
-                FS_PIECE(3);
-                FS_MFMA(1, 0, a0, b0);
-                FS_PIECE(4);
-                FS_MFMA(1, 1, a0, b0);
-                FS_PIECE(5);
-                FS_MFMA(1, 2, a0, b0);
-                FS_PIECE(6);
-                FS_MFMA(1, 3, a0, b0);
-                __builtin_amdgcn_sched_barrier(0);
-                if (g + 1 < G) {
-                    wait_landed(g + 1, pg - 1);
-                    lds_done_barrier();
-                    read_frags(a0, b0, g + 1, pk0);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                FS_MFMA(0, 0, a1, b1);
-                FS_MFMA(0, 1, a1, b1);
-                FS_MFMA(0, 2, a1, b1);
-                FS_MFMA(0, 3, a1, b1);
-                FS_MFMA(1, 0, a1, b1);
-                FS_MFMA(1, 1, a1, b1);
-                FS_MFMA(1, 2, a1, b1);
-                FS_MFMA(1, 3, a1, b1);
-                continue;
-            }
             if constexpr (JTW == 4) {
-                // (only F0(g) is pending here, so the wait the compiler puts before the first MFMA is
-                // exactly "F0 has arrived"; F1 is requested behind the first MFMA group)
                 FS_MFMA(0, 0, a0, b0);
                 FS_PIECE(0);
                 FS_MFMA(0, 1, a0, b0);
-                FS_PIECE(1);
                 FS_MFMA(0, 2, a0, b0);
-                FS_PIECE(2);
                 FS_MFMA(0, 3, a0, b0);
                 __builtin_amdgcn_sched_barrier(0);
                 read_frags(a1, b1, g, pk1);
-                FS_PIECE(3);
                 FS_MFMA(1, 0, a0, b0);
-                FS_PIECE(4);
                 FS_MFMA(1, 1, a0, b0);
-                FS_PIECE(5);
                 FS_MFMA(1, 2, a0, b0);
-                FS_PIECE(6);
                 FS_MFMA(1, 3, a0, b0);
                 FS_MFMA(0, 0, a1, b1);
                 FS_MFMA(0, 1, a1, b1);
@@ -330,13 +379,9 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
                 FS_MFMA(0, 1, a0, b0);
                 __builtin_amdgcn_sched_barrier(0);
                 read_frags(a1, b1, g, pk1);
-                FS_PIECE(1);
                 FS_MFMA(1, 0, a0, b0);
-                FS_PIECE(2);
                 FS_MFMA(1, 1, a0, b0);
-                FS_PIECE(3);
                 FS_MFMA(0, 0, a1, b1);
-                FS_PIECE(4);
                 FS_MFMA(0, 1, a1, b1);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -371,7 +416,7 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
         // ---- epilogue: fold 2 x 16 streamed points per resident row into (max, sum) ----------
         // lazy stabiliser: exponents against the current integer running max; the slow branch
         // (lift the max, rescale by an exact power of two) runs only when a sum leaves [0, 2^60)
-        const int bslot = (g - 1) & (NBIAS - 1);   // the last stage of this tile carried its bias
+        const int bslot = (t - t_begin) & (NBIAS - 1);   // the first stage of this tile carried its biases
         float bias[2][16];
 #pragma unroll
         for (int it = 0; it < 2; ++it)
@@ -460,9 +505,9 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
             {
                 const int newer = pg - vstamp;
                 if (newer >= 2)
-                    wait_vm<2 * NPW>();
+                    wait_vm<2 * PPW>();
                 else if (newer == 1)
-                    wait_vm<NPW>();
+                    wait_vm<PPW>();
                 else
                     wait_vm<0>();
             }
@@ -550,10 +595,10 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
     }
 }
 
-template <int WJ, int NS, int JTW, int PC, int SCHED = 0>
+template <int WJ, int NS, int JTW, int PC>
 __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a)
 {
-    lse_bf16_body<WJ, NS, JTW, PC, SCHED>(a, blockIdx.x);
+    lse_bf16_body<WJ, NS, JTW, PC>(a, blockIdx.x);
 }
 
 // Both LSE passes of one iteration of the averaged schedule (Eq. 4-5) in one launch: the first `blocks0`
@@ -642,10 +687,7 @@ fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
     fs_status st = lse_pass_args(c, P, res, str, eps, P->partial, &a, &blocks);
     if (st != FS_OK) return st;
     prof_begin(c, (double)res->cnt * (double)str->cnt);
-    if (c->dbg_bf16_variant == 1)
-        hipLaunchKernelGGL((k_lse_bf16<2, 4, 4, 0, 1>), dim3((unsigned)blocks), dim3(512), 0, c->stream, a);
-    else
-        hipLaunchKernelGGL((k_lse_bf16<2, 4, 4, 0>), dim3((unsigned)blocks), dim3(512), 0, c->stream, a);
+    hipLaunchKernelGGL((k_lse_bf16<2, 4, 4, 0>), dim3((unsigned)blocks), dim3(512), 0, c->stream, a);
     prof_end(c);
     FS_HIP(c, hipGetLastError());
     *splits_out = a.splits;

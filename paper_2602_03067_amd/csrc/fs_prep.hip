@@ -264,11 +264,14 @@ __global__ void k_prep_f64(const void *pts, int dtype, int64_t cnt, int64_t cnt_
 }
 
 // ---- bfloat16 derived copy (bf16 matrix-core path); norms of the ROUNDED points ----------
-// Layout: the copy is stored in 1 KB tiles of 16 rows x 32 coordinates, tile (rb, ch) at
-// ((rb * n_chunks + ch) * 1024) bytes; inside a tile row r occupies 64 bytes and its 16-byte
-// piece p (coordinates 8p..8p+7 of the chunk) sits at position p ^ ((r >> 2) & 3).  This is
-// exactly the image a pipeline stage needs in LDS, so the streaming kernel fills LDS with
-// linear 1 KB direct loads and reads MFMA fragments without bank conflicts.
+// Layout: the copy is stored in 1 KB tiles of 16 rows x 32 coordinates; the sixteen tiles of a group
+// of 256 rows at one chunk of 32 coordinates are contiguous (16 KB), and the groups of one row group
+// follow each other chunk by chunk: tile (rb, ch) sits at (((rb / 16) * n_chunks + ch) * 16 + rb % 16) KB.
+// Inside a tile row r occupies 64 bytes and its 16-byte piece p (coordinates 8p..8p+7 of the chunk)
+// sits at position p ^ ((r >> 2) & 3).  A 16 KB group is exactly the image that half a pipeline stage
+// needs in LDS, so the streaming kernel fills LDS with linear direct loads, each wave a contiguous run
+// of it, and reads MFMA fragments without bank conflicts; the contraction loop of a tile walks through
+// memory linearly.
 __global__ void k_prep_bf16(const void *pts, int dtype, int64_t cnt, int64_t cnt_pad, int64_t d, int64_t ld, int kp,
                             uint16_t *out, float *bias, double *norm)
 {
@@ -299,8 +302,8 @@ __global__ void k_prep_bf16(const void *pts, int dtype, int64_t cnt, int64_t cnt
         v.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
         v.z = (uint32_t)h[4] | ((uint32_t)h[5] << 16);
         v.w = (uint32_t)h[6] | ((uint32_t)h[7] << 16);
-        *reinterpret_cast<uint4 *>(reinterpret_cast<unsigned char *>(out) + ((rb * n_chunks + ch) << 10) + rl * 64 +
-                                   pos * 16) = v;
+        *reinterpret_cast<uint4 *>(reinterpret_cast<unsigned char *>(out) +
+                                   ((((rb >> 4) * n_chunks + ch) * 16 + (rb & 15)) << 10) + rl * 64 + pos * 16) = v;
     }
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_xor(nrm, off, 64);
     if (lane == 0) {
