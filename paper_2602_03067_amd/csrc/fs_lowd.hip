@@ -287,9 +287,19 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
     const unsigned tile_off = (unsigned)(size_t)&tile[0][0];
     const unsigned vtile_off = (unsigned)(size_t)&vtile[0][0];
     auto fetch = [&](int t, int bufi) {
+        // each wave brings UPT consecutive KB of the tile, in runs of up to four loads behind one write of the LDS
+        // base to m0 (immediate offsets advance the memory and the LDS address alike; a write to m0 waits for the
+        // wave's earlier direct loads to leave for the address unit)
+        const Unit *src = gsrc + (int64_t)t * (TJ * NP) + (w * UPT) * 64 + l;
+        const unsigned dst = tile_off + (bufi * (TJ * NP) + (w * UPT) * 64) * 16;
 #pragma unroll
-        for (int q = 0; q < UPT; ++q)
-            dma16(gsrc + (int64_t)t * (TJ * NP) + q * kBlock + tid, tile_off + (bufi * (TJ * NP) + q * kBlock + w * 64) * 16);
+        for (int q = 0; q < UPT; ++q) {
+            if (q % 4 == 0) {
+                const unsigned m = __builtin_amdgcn_readfirstlane(dst + q * 1024);
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" ::"s"(m) : "memory", "m0");
+            }
+            asm volatile("global_load_lds_dwordx4 %0, off offset:%1" ::"v"(src + (q / 4) * 256), "n"((q % 4) * 1024) : "memory");
+        }
         if constexpr (APPLY) {
             // value rows of the tile, one dword per lane; entries outside the matrix are read from a
             // valid address instead (their exponentials are zero / their columns are not stored)
