@@ -162,6 +162,26 @@ fs_status fs_solve_noalloc(fs_ctx *ctx, const fs_problem *prob, float eps_start,
                            float *g /* device, in/out */);
 
 /*
+ * Alternating Sinkhorn for the label-augmented cost of the dataset-distance application (Section 3.1's remark on
+ * generalised costs; Section 4 and its appendix):
+ *     C_ij = lambda1 |x_i - y_j|^2 + lambda2 W[lx_i, ly_j],
+ * `iters` iterations at eps, "f from g, then g from the new f", from the given potentials (of THIS cost), which are
+ * overwritten with the result.  lx [n], ly [m]: device int32 class labels in [0, V); W: device floats, V x V row-major
+ * (row = class of the source point).  lambda1 > 0.
+ * The n x m cost is never stored and no kernel does a table lookup: W[lx, ly] = <onehot(lx), W[:, ly]> is a
+ * contraction, so the library appends V coordinates to device copies of both clouds and runs the squared-Euclidean
+ * kernels on them at eps / lambda1; the per-point constants this adds to the cost are absorbed exactly by the
+ * potentials, which are mapped on the device on entry and exit.  In FS_COMPUTE_BF16_MFMA mode the table entries are
+ * rounded to bfloat16 like the coordinates.  The augmented copies (float, (n + m)(d + V) values) live in the context's
+ * second buffer.  Labels outside [0, V): FS_ERR_INVALID_ARG after the run (the potentials are then undefined).
+ * Synchronises the stream.
+ */
+fs_status fs_solve_labeled(fs_ctx *ctx, const fs_problem *prob, const int32_t *lx /* device */,
+                           const int32_t *ly /* device */, const float *W /* device */, int32_t V, float lambda1,
+                           float lambda2, float eps, int32_t iters, float *f /* device, in/out */,
+                           float *g /* device, in/out */);
+
+/*
  * Symmetric (Jacobi, averaged) schedule with a fixed iteration count (Eq. 4-5):
  * in every iteration both updates read the OLD potentials,
  *     f <- f/2 + (1/2) (-eps LSE_j[(g_j - C_ij)/eps + log b_j]),

@@ -21,7 +21,7 @@ FS_COMPUTE_FP32, FS_COMPUTE_BF16_MFMA = 0, 1
 
 EXPORTS = (
     "fs_create", "fs_destroy", "fs_status_str", "fs_last_error", "fs_version", "fs_row_norms",
-    "fs_update_f", "fs_update_g", "fs_solve", "fs_solve_noalloc", "fs_solve_symmetric", "fs_solve_tol", "fs_marginal_err", "fs_ot_value", "fs_check_weights", "fs_check_finite", "fs_divergence", "fs_apply_plan",
+    "fs_update_f", "fs_update_g", "fs_solve", "fs_solve_noalloc", "fs_solve_labeled", "fs_solve_symmetric", "fs_solve_tol", "fs_marginal_err", "fs_ot_value", "fs_check_weights", "fs_check_finite", "fs_divergence", "fs_apply_plan",
     "fs_apply_plan_T", "fs_apply_plan_hadamard", "fs_grad_x", "fs_grad_y", "fs_hvp", "fs_debug_set", "fs_profile_enable", "fs_profile_read",
 )
 
@@ -71,6 +71,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fs_update_g.argtypes = [vp, PP, f32, vp, vp]
     lib.fs_solve.argtypes = [vp, PP, f32, f32, i32, i32, vp, vp]
     lib.fs_solve_noalloc.argtypes = [vp, PP, f32, f32, i32, i32, vp, vp]
+    lib.fs_solve_labeled.argtypes = [vp, PP, vp, vp, vp, i32, f32, f32, f32, i32, vp, vp]
     lib.fs_solve_symmetric.argtypes = [vp, PP, f32, i32, vp, vp]
     lib.fs_solve_tol.argtypes = [vp, PP, f32, i32, i32, f32, vp, vp, ctypes.POINTER(i32), ctypes.POINTER(f32)]
     lib.fs_marginal_err.argtypes = [vp, PP, f32, vp, vp, ctypes.POINTER(f32), ctypes.POINTER(f32)]
@@ -204,6 +205,21 @@ class Context:
         self._check(self.lib.fs_solve_noalloc(self.h, ctypes.byref(prob.c), eps_start, eps_end,
                                               int(n_stages), int(iters_per_stage), _ptr(f), _ptr(g)),
                     "fs_solve_noalloc")
+
+    def fs_solve_labeled(self, prob: Problem, lx: torch.Tensor, ly: torch.Tensor, W: torch.Tensor, lambda1: float,
+                         lambda2: float, eps: float, iters: int, f: torch.Tensor, g: torch.Tensor) -> None:
+        """Alternating Sinkhorn for lambda1 |x - y|^2 + lambda2 W[lx, ly]; in place like fs_solve."""
+        _dev_f32(f, "f", (prob.n,))
+        _dev_f32(g, "g", (prob.m,))
+        _dev_f32(W, "W")
+        if W.dim() != 2 or W.shape[0] != W.shape[1]:
+            raise ValueError("W must be square")
+        for t, nm, cnt in ((lx, "lx", prob.n), (ly, "ly", prob.m)):
+            if not t.is_cuda or t.dtype != torch.int32 or not t.is_contiguous() or tuple(t.shape) != (cnt,):
+                raise TypeError("%s must be a contiguous int32 GPU tensor of %d labels" % (nm, cnt))
+        self._check(self.lib.fs_solve_labeled(self.h, ctypes.byref(prob.c), _ptr(lx), _ptr(ly), _ptr(W), W.shape[0],
+                                              float(lambda1), float(lambda2), float(eps), int(iters), _ptr(f), _ptr(g)),
+                    "fs_solve_labeled")
 
     def fs_solve_tol(self, prob: Problem, eps: float, max_iters: int, check_every: int, tol: float,
                      f: torch.Tensor, g: torch.Tensor) -> Tuple[int, float]:

@@ -208,7 +208,11 @@ size_t layout(const Ctx *c, const fs_problem *p, Prepared *P, char *base, size_t
     P->partial = base ? (void *)(base + o) : nullptr;
     o = A.take((size_t)ceil_div(big, 256) * 8);
     P->dev_part = base ? (double *)(base + o) : nullptr;
-    o = A.take(8 * 8);
+    o = A.take((size_t)ceil_div(big, 256) * 16);
+    P->gauge_part = base ? (double *)(base + o) : nullptr;
+    o = A.take((size_t)ceil_div(big, 256) * 16);
+    P->gauge_part_x = base ? (double *)(base + o) : nullptr;
+    o = A.take(16 * 8);
     P->scalars = base ? (double *)(base + o) : nullptr;
     o = A.take((size_t)(256 + 1) * 16 * 8);
     P->mean = base ? (double *)(base + o) : nullptr;
@@ -253,10 +257,12 @@ fs_status prepare(Ctx *c, const fs_problem *p, Prepared *P, size_t extra, char *
 
 // merge the splits of the pass that just ran over `res` (see launch_finalize)
 fs_status finalize(Ctx *c, const Prepared *P, Side *res, int splits, double eps, double eps_next_bias, float *user_out,
-                   double *abs_dev_sum, double mix = 1.0, double *save_old = nullptr)
+                   double *abs_dev_sum, double mix = 1.0, double *save_old = nullptr, GaugeMode gauge = GaugeMode::None,
+                   int64_t gauge_prev_cnt = 0, double gauge_prev_eps = 0.0)
 {
     const double *nrm = (P->path == Path::LowD && !lowd_precise(P, eps)) ? res->norm_f : res->norm;
-    return launch_finalize(c, P, res, nrm, splits, eps, eps_next_bias, user_out, abs_dev_sum, mix, save_old);
+    return launch_finalize(c, P, res, nrm, splits, eps, eps_next_bias, user_out, abs_dev_sum, mix, save_old, gauge,
+                           gauge_prev_cnt, gauge_prev_eps);
 }
 
 fs_status run_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, int *splits)
@@ -587,8 +593,13 @@ static fs_status solve_impl(Ctx *c, const fs_problem *prob, float eps_start, flo
     if ((st = prepare(c, prob, &P, 0, nullptr)) != FS_OK) return st;
     double eps0 = stage_eps(eps_start, eps_end, n_stages, 0);
     if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps0)) != FS_OK) return st;
+    // the drift along (f + t, g - t) that the g-updates measure (see GaugeMode) is summed up on the device and taken
+    // out when the potentials are handed to the caller
+    if ((st = launch_fill_f64(c, P.scalars + 8, 0.0, 2)) != FS_OK) return st;
+    double eps_prev = 0.0;
+    double eps = eps0;
     for (int s = 0; s < n_stages; ++s) {
-        double eps = stage_eps(eps_start, eps_end, n_stages, s);
+        eps = stage_eps(eps_start, eps_end, n_stages, s);
         for (int t = 0; t < iters_per_stage; ++t) {
             bool last = (s == n_stages - 1) && (t == iters_per_stage - 1);
             double eps_next = eps;
@@ -596,16 +607,18 @@ static fs_status solve_impl(Ctx *c, const fs_problem *prob, float eps_start, flo
             int splits = 1;
             // Alg. 1: f from g
             if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits)) != FS_OK) return st;
-            if ((st = finalize(c, &P, &P.X, splits, eps, eps, last ? f : nullptr, nullptr)) != FS_OK)
+            if ((st = finalize(c, &P, &P.X, splits, eps, eps, nullptr, nullptr, 1.0, nullptr,
+                               eps_prev > 0.0 ? GaugeMode::Collect : GaugeMode::None, prob->m, eps_prev)) != FS_OK)
                 return st;
             // Alg. 3: g from the new f
             if ((st = run_lse(c, &P, &P.Y, &P.X, eps, &splits)) != FS_OK) return st;
-            if ((st = finalize(c, &P, &P.Y, splits, eps, last ? 0.0 : eps_next, last ? g : nullptr,
-                                      nullptr)) != FS_OK)
+            if ((st = finalize(c, &P, &P.Y, splits, eps, last ? 0.0 : eps_next, nullptr, nullptr, 1.0, nullptr,
+                               GaugeMode::Measure)) != FS_OK)
                 return st;
+            eps_prev = eps;
         }
     }
-    return FS_OK;
+    return launch_gauge_export(c, &P, true, eps, P.X.pot, f, g);
 }
 
 fs_status fs_solve(fs_ctx *ctx, const fs_problem *prob, float eps_start, float eps_end, int32_t n_stages,
@@ -618,6 +631,68 @@ fs_status fs_solve_noalloc(fs_ctx *ctx, const fs_problem *prob, float eps_start,
                            int32_t iters_per_stage, float *f, float *g)
 {
     return solve_impl(reinterpret_cast<Ctx *>(ctx), prob, eps_start, eps_end, n_stages, iters_per_stage, f, g, true);
+}
+
+fs_status fs_solve_labeled(fs_ctx *ctx, const fs_problem *prob, const int32_t *lx, const int32_t *ly, const float *W,
+                           int32_t V, float lambda1, float lambda2, float eps, int32_t iters, float *f, float *g)
+{
+    Ctx *c = reinterpret_cast<Ctx *>(ctx);
+    DeviceGuard device_guard(c);
+    fs_status st = validate_problem(c, prob);
+    if (st != FS_OK) return st;
+    if ((st = validate_eps(c, eps)) != FS_OK) return st;
+    if (iters < 0) return fail(c, FS_ERR_BAD_EPS, "need iters >= 0");
+    if (!lx || !ly || !W) return fail(c, FS_ERR_INVALID_ARG, "lx, ly or W is NULL");
+    if (V < 1 || prob->d + V > 8192) return fail(c, FS_ERR_BAD_SHAPE, "need V >= 1 and d + V <= 8192");
+    if (!(lambda1 > 0.0f) || !isfinite(lambda1) || !isfinite(lambda2))
+        return fail(c, FS_ERR_INVALID_ARG, "need lambda1 > 0 and both weights finite");
+    if ((st = check_out(c, prob, f, (size_t)prob->n * 4, "f")) != FS_OK) return st;
+    if ((st = check_out(c, prob, g, (size_t)prob->m * 4, "g")) != FS_OK) return st;
+    if (overlap(f, (size_t)prob->n * 4, g, (size_t)prob->m * 4)) return fail(c, FS_ERR_INVALID_ARG, "f overlaps g");
+    if (c->device < 0) return fail(c, FS_ERR_DEVICE, "host-only context: arguments are valid, nothing was launched");
+    if (iters == 0) return FS_OK;
+
+    // augmented clouds, the per-point constants and the augmented potentials live in the context's second buffer (the
+    // solve below lays the workspace out anew)
+    const int64_t n = prob->n, m = prob->m, da = prob->d + V;
+    auto al = [](size_t b) { return (b + 255) & ~size_t(255); };
+    const size_t bx = al((size_t)n * da * 4), by = al((size_t)m * da * 4), bv = al((size_t)m * 4), bf = al((size_t)n * 4),
+                 bg = al((size_t)m * 4);
+    if ((st = ensure_aux(c, bx + by + bv + bf + bg + 256)) != FS_OK) return st;
+    char *p = c->aux;
+    float *xa = reinterpret_cast<float *>(p);
+    float *ya = reinterpret_cast<float *>(p + bx);
+    float *vc = reinterpret_cast<float *>(p + bx + by);
+    float *fa = reinterpret_cast<float *>(p + bx + by + bv);
+    float *ga = reinterpret_cast<float *>(p + bx + by + bv + bf);
+    unsigned *bad = reinterpret_cast<unsigned *>(p + bx + by + bv + bf + bg);
+    const double l1 = (double)lambda1, l2 = (double)lambda2;
+    const bool bf16 = prob->compute == FS_COMPUTE_BF16_MFMA;
+    if ((st = launch_fill_f64(c, reinterpret_cast<double *>(bad), 0.0, 1)) != FS_OK) return st;
+    if ((st = launch_label_augment(c, prob->x, prob->dtype, n, prob->d, prob->ldx, lx, W, V, false, l1, l2, bf16, xa, nullptr,
+                                   bad)) != FS_OK)
+        return st;
+    if ((st = launch_label_augment(c, prob->y, prob->dtype, m, prob->d, prob->ldy, ly, W, V, true, l1, l2, bf16, ya, vc, bad)) !=
+        FS_OK)
+        return st;
+    // |xa - ya|^2 = (C + l1 + v_j) / l1: the augmented problem at eps / l1 with potentials ((f + l1) / l1, (g + v) / l1)
+    if ((st = launch_label_potential(c, f, nullptr, l1, l1, true, n, fa)) != FS_OK) return st;
+    if ((st = launch_label_potential(c, g, vc, 0.0, l1, true, m, ga)) != FS_OK) return st;
+    fs_problem aug = *prob;
+    aug.x = xa;
+    aug.y = ya;
+    aug.dtype = FS_F32;
+    aug.d = da;
+    aug.ldx = aug.ldy = da;
+    const float eps_a = (float)((double)eps / l1);
+    if ((st = solve_impl(c, &aug, eps_a, eps_a, 1, iters, fa, ga, false)) != FS_OK) return st;
+    if ((st = launch_label_potential(c, fa, nullptr, l1, l1, false, n, f)) != FS_OK) return st;
+    if ((st = launch_label_potential(c, ga, vc, 0.0, l1, false, m, g)) != FS_OK) return st;
+    unsigned nbad = 0;
+    FS_HIP(c, hipMemcpyAsync(&nbad, bad, sizeof nbad, hipMemcpyDeviceToHost, c->stream));
+    FS_HIP(c, hipStreamSynchronize(c->stream));
+    if (nbad) return fail(c, FS_ERR_INVALID_ARG, "%u labels are outside [0, V)", nbad);
+    return FS_OK;
 }
 
 fs_status fs_solve_tol(fs_ctx *ctx, const fs_problem *prob, float eps_in, int32_t max_iters, int32_t check_every,
@@ -644,6 +719,8 @@ fs_status fs_solve_tol(fs_ctx *ctx, const fs_problem *prob, float eps_in, int32_
     double *f_before = reinterpret_cast<double *>(extra);   // f of the last completed iteration at a check
     if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps)) != FS_OK) return st;
     if ((st = launch_fill_f64(c, P.scalars, 0.0, 1)) != FS_OK) return st;
+    if ((st = launch_fill_f64(c, P.scalars + 8, 0.0, 2)) != FS_OK) return st;   // drift along (f + t, g - t), see GaugeMode
+    bool gauge_pending = false;   // a g-update's measurement waits for the next f-update to collect it
     // The row marginal error of (f_t, g_t) is a by-product of the f-update that starts iteration
     // t + 1 (Prop. 3: r = a exp((f_t - f_{t+1})/eps)), so a check costs no extra pass unless it stops
     // the iteration.  `pending`: that f-update has already been done.
@@ -654,24 +731,31 @@ fs_status fs_solve_tol(fs_ctx *ctx, const fs_problem *prob, float eps_in, int32_
         int splits = 1;
         if (!pending) {   // Alg. 1: f from g
             if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits)) != FS_OK) return st;
-            if ((st = finalize(c, &P, &P.X, splits, eps, eps, nullptr, nullptr)) != FS_OK) return st;
+            if ((st = finalize(c, &P, &P.X, splits, eps, eps, nullptr, nullptr, 1.0, nullptr,
+                               gauge_pending ? GaugeMode::Collect : GaugeMode::None, prob->m, eps)) != FS_OK)
+                return st;
+            gauge_pending = false;
         }
         pending = false;
         // Alg. 3: g from the new f
         if ((st = run_lse(c, &P, &P.Y, &P.X, eps, &splits)) != FS_OK) return st;
-        if ((st = finalize(c, &P, &P.Y, splits, eps, eps, nullptr, nullptr)) != FS_OK) return st;
+        if ((st = finalize(c, &P, &P.Y, splits, eps, eps, nullptr, nullptr, 1.0, nullptr, GaugeMode::Measure)) != FS_OK) return st;
+        gauge_pending = true;
         ++t;
         if (t % check_every != 0 && t != max_iters) continue;
         // the next f-update, measuring the error of (f_t, g_t) on the way
         if ((st = run_lse(c, &P, &P.X, &P.Y, eps, &splits)) != FS_OK) return st;
-        if ((st = finalize(c, &P, &P.X, splits, eps, eps, nullptr, P.scalars, 1.0, f_before)) != FS_OK) return st;
+        if ((st = finalize(c, &P, &P.X, splits, eps, eps, nullptr, P.scalars, 1.0, f_before, GaugeMode::Collect, prob->m, eps)) !=
+            FS_OK)
+            return st;
+        gauge_pending = false;
         FS_HIP(c, hipMemcpyAsync(&err, P.scalars, sizeof(double), hipMemcpyDeviceToHost, c->stream));
         FS_HIP(c, hipStreamSynchronize(c->stream));
         if (err <= (double)tol || t == max_iters) break;
         pending = true;
     }
-    if ((st = launch_export_f32(c, f_before, prob->n, f)) != FS_OK) return st;
-    if ((st = launch_export_f32(c, P.Y.pot, prob->m, g)) != FS_OK) return st;
+    // f_t sat before the last g-update's term entered the sum, g_t behind it
+    if ((st = launch_gauge_export(c, &P, false, eps, f_before, f, g)) != FS_OK) return st;
     FS_HIP(c, hipStreamSynchronize(c->stream));
     *iters_done = t;
     *err_row_l1 = (float)err;
@@ -705,6 +789,7 @@ fs_status fs_solve_symmetric(fs_ctx *ctx, const fs_problem *prob, float eps_in, 
     if ((st = launch_bias_from_user(c, &P, &P.X, f, eps, true, false)) != FS_OK) return st;
     if ((st = launch_bias_from_user(c, &P, &P.Y, g, eps, false, true)) != FS_OK) return st;
     void *const first_partial = P.partial;
+    if ((st = launch_fill_f64(c, P.scalars + 8, 0.0, 2)) != FS_OK) return st;
     for (int t = 0; t < iters; ++t) {
         const bool last = t == iters - 1;
         int splits_f = 1, splits_g = 1;
@@ -718,9 +803,9 @@ fs_status fs_solve_symmetric(fs_ctx *ctx, const fs_problem *prob, float eps_in, 
                 return st;
             if (done) {
                 const bool pr = lowd_precise(&P, eps);
-                if ((st = launch_finalize_pair(c, &P, &P.X, pr ? P.X.norm : P.X.norm_f, first_partial, splits_f,
-                                               last ? f : nullptr, &P.Y, pr ? P.Y.norm : P.Y.norm_f, second_partial,
-                                               splits_g, last ? g : nullptr, eps, eps_bias, 0.5)) != FS_OK)
+                if ((st = launch_finalize_pair(c, &P, &P.X, pr ? P.X.norm : P.X.norm_f, first_partial, splits_f, nullptr, &P.Y,
+                                               pr ? P.Y.norm : P.Y.norm_f, second_partial, splits_g, nullptr, eps, eps_bias, 0.5, t,
+                                               t > 0)) != FS_OK)
                     return st;
                 continue;
             }
@@ -741,13 +826,15 @@ fs_status fs_solve_symmetric(fs_ctx *ctx, const fs_problem *prob, float eps_in, 
         P.partial = first_partial;
         {
             const bool fl = P.path == Path::LowD && !lowd_precise(&P, eps);   // which norms the pass was biased with
-            if ((st = launch_finalize_pair(c, &P, &P.X, fl ? P.X.norm_f : P.X.norm, first_partial, splits_f, last ? f : nullptr,
-                                           &P.Y, fl ? P.Y.norm_f : P.Y.norm, second_partial, splits_g, last ? g : nullptr, eps,
-                                           eps_bias, 0.5)) != FS_OK)
+            if ((st = launch_finalize_pair(c, &P, &P.X, fl ? P.X.norm_f : P.X.norm, first_partial, splits_f, nullptr, &P.Y,
+                                           fl ? P.Y.norm_f : P.Y.norm, second_partial, splits_g, nullptr, eps, eps_bias, 0.5, t,
+                                           t > 0)) != FS_OK)
                 return st;
         }
     }
-    return FS_OK;
+    // the drift along (f + t, g - t) that the iterations measured (see launch_finalize_pair), taken out on the way out
+    if ((st = launch_gauge_collect_pair(c, &P, eps, iters - 1)) != FS_OK) return st;
+    return launch_gauge_export(c, &P, false, eps, P.X.pot, f, g);
 }
 
 fs_status fs_marginal_err(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f, const float *g,

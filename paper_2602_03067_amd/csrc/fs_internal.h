@@ -215,7 +215,9 @@ struct Prepared {
     void *partial = nullptr;
     size_t partial_bytes = 0;
     double *dev_part = nullptr;  // [ceil(max(n,m)/256)] per-block sums of the marginal deviation
-    double *scalars = nullptr;   // [8] device doubles (marginal errors, centring sums...)
+    double *gauge_part = nullptr;   // [2][ceil(max(n,m)/256)] per-block sums of the plan's mass seen by a g-update
+    double *gauge_part_x = nullptr; // the same for an f-update (averaged schedule: both passes measure, halves by parity)
+    double *scalars = nullptr;   // [16] device doubles (marginal errors, centring sums...; [8], [9]: gauge drift, see GaugeMode)
     double *mean = nullptr;      // [kLowdMaxD] common mean (LowD)
     char *extra = nullptr;       // entry-point specific scratch (plan application partials)
     size_t extra_bytes = 0;
@@ -244,13 +246,46 @@ fs_status launch_bias_from_user(Ctx *c, Prepared *P, Side *side, const float *po
 // `mix`: the new potential is (1 - mix) * old + mix * update (1: plain update, 1/2: averaged schedule).
 // `abs_dev_sum` != nullptr measures the marginal deviation instead of storing the update; with
 // `save_old` it does both and leaves the replaced potential in save_old[0..cnt).
+// Drift of the alternating iteration along its neutral direction (f + t, g - t), and how it is taken out.
+// The exact iterates keep the plan's total mass at 1: after "f from g" the row marginals are exact.  A g-update
+// measures that mass on its way (Prop. 3: c_j = b_j exp((g_j - g_j^+)/eps) are the column sums of the plan that
+// (f, g) induce).  When the f-pass and the g-pass carry different systematic rounding biases u_f, u_g (the matrix
+// cores truncate when they align the products of a score), the computed mass is exp((u_f - u_g)/eps), and the
+// difference is exactly what one iteration adds to t: a random error would be damped, this one accumulates linearly
+// (measured on the annealed low-dimension workload: 8e-5 eps at n = 16384, 2.5e-4 eps at n = 32768 after 200
+// iterations, with a scatter around that constant of 8e-6).  So a solve adds up eps ln(mass) over its g-updates
+// (scalars[8]; scalars[9] keeps the sum without the last term) and hands f - scalars[9], g + scalars[8] to the caller.
+//   Measure: this merge is a g-update of an alternating solve: leave the block sums of c_j in gauge_part
+//   Collect: this merge is the f-update after one: its first workgroup adds eps_prev ln(sum gauge_part) to scalars[8]
+enum class GaugeMode { None, Measure, Collect };
 fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, const double *res_norm, int splits,
                           double eps_cur, double eps_next_bias, float *user_out, double *abs_dev_sum,
-                          double mix = 1.0, double *save_old = nullptr);
+                          double mix = 1.0, double *save_old = nullptr, GaugeMode gauge = GaugeMode::None,
+                          int64_t gauge_prev_cnt = 0, double gauge_prev_eps = 0.0);
+// the last g-update's term, then f_user = (float)(X.pot - scalars[9]) and g_user = (float)(Y.pot + scalars[8])
+// (x_pot: the f to hand out, X.pot or a saved copy of it)
+fs_status launch_gauge_export(Ctx *c, const Prepared *P, bool collect_last, double eps_last, const double *x_pot,
+                              float *f_user, float *g_user);
+// `gauge`: the averaged schedule's form of the drift removal (see GaugeMode): both passes of an iteration read the
+// same old potentials, so the plan's mass as the f-pass sees it (row sums) and as the g-pass sees it (column sums)
+// differ by exp((u_f - u_g)/eps) exactly, and an averaged iteration moves t by a quarter of u_f - u_g.  With
+// gauge_parity >= 0 (the iteration number) both merges leave their block sums in half `gauge_parity & 1` of
+// gauge_part_x / gauge_part, and, `collect_prev`, the first workgroup adds the previous iteration's term
+// eps (ln mass_g - ln mass_f) / 4 to scalars[8] and [9] from the other half; the caller hands out f - scalars[9],
+// g + scalars[8] (launch_gauge_collect_pair for the last iteration, then launch_gauge_export with collect_last = false).
 fs_status launch_finalize_pair(Ctx *c, const Prepared *P, Side *X, const double *norm_x, const void *partial_x, int splits_x,
                                float *f_out, Side *Y, const double *norm_y, const void *partial_y, int splits_y,
-                               float *g_out, double eps_cur, double eps_next_bias, double mix);
+                               float *g_out, double eps_cur, double eps_next_bias, double mix, int gauge_parity = -1,
+                               bool collect_prev = false);
+fs_status launch_gauge_collect_pair(Ctx *c, const Prepared *P, double eps, int gauge_parity);
 fs_status launch_export_f32(Ctx *c, const double *src, int64_t cnt, float *dst);
+// label-augmented cost: augmented copy [rows][d + V] of one cloud (see k_label_augment) and the map between the
+// potentials of the labelled and of the augmented problem
+fs_status launch_label_augment(Ctx *c, const void *pts, int dtype, int64_t rows, int64_t d, int64_t ld,
+                               const int32_t *labels, const float *W, int V, bool target_side, double l1, double l2,
+                               bool round_bf16, float *out, float *vconst, unsigned *bad);
+fs_status launch_label_potential(Ctx *c, const float *src, const float *vconst, double cshift, double l1, bool to_augmented,
+                                 int64_t cnt, float *dst);
 fs_status launch_pts_to_f32(Ctx *c, const void *pts, int dtype, int64_t rows, int64_t d, int64_t ld, float *dst);
 fs_status launch_grad_assemble(Ctx *c, float *g, int64_t ldg, const void *pts, int dtype, int64_t ld, int64_t rows,
                                int64_t d, const float *w, const float *mass, int mode);

@@ -757,8 +757,12 @@ PassShape shape_for(const Ctx *c, int64_t n_res, int64_t n_str, int rows_per_blo
 // rho_max = largest squared norm after centring.  A single half-step can be off by about
 // 1.5 * 2^-24 * Mag * ln2 in units of eps when few terms dominate a row (no averaging), and,
 // measured against the float64 reference, a run of T half-steps at one eps accumulates about
-// 0.05..0.07 * T * 2^-24 * Mag.  fp32 scores are used while both stay below ~3e-5 and 2e-5, i.e.
+// 0.05..0.07 * T * 2^-24 * Mag in single rows (small clouds with outlying points, where the iteration
+// damps little).  fp32 scores are used while both stay below ~3e-5 and 2e-5, i.e.
 // Mag <= 480 and Mag * T <= 5000; otherwise the scores are formed in float64.
+// (The part of these errors that is common to all rows and differs between the two passes is a
+// different matter: it adds up along the iteration's neutral direction and grows with the size of the
+// clouds; the solvers measure and remove it, see GaugeMode.)
 // The context's "lowd_score" switch overrides the choice (tests and experiments), except for the
 // measurements that always take float64 scores.
 bool lowd_precise(const Prepared *P, double eps)

@@ -422,15 +422,64 @@ struct FinalizeArgs {
     double mix;
     double *save_old;
     int blocks;   // workgroups of this side
+    // gauge drift (see GaugeMode): where a g-update leaves the block sums of the plan's column marginals, and what
+    // the first workgroup of the following f-update collects
+    double *gauge_out;
+    const double *gauge_prev;
+    int64_t gauge_prev_cnt;
+    double gauge_prev_eps;
+    double *gauge_scalars;   // [0]: the sum so far, [1]: the sum without its last term
+    const double *gauge_prev_x;   // averaged schedule: the f-pass's block sums of the previous iteration
+    int64_t gauge_prev_x_cnt;
 };
+
+// one workgroup: scalars[1] <- scalars[0], scalars[0] += eps ln(sum of part[0..cnt)), in a fixed order
+__device__ inline void gauge_collect(const double *part, int64_t cnt, double eps, double *scalars, double *sh)
+{
+    double acc = 0.0;
+    for (int64_t i = threadIdx.x; i < cnt; i += 256) acc += part[i];
+    const double t = block_sum_256(acc, sh);
+    if (threadIdx.x == 0) {
+        const double prev = scalars[0];
+        scalars[1] = prev;
+        scalars[0] = prev + ((t > 0.0 && t < INFINITY) ? eps * log(t) : 0.0);
+    }
+    __syncthreads();
+}
+
+// averaged schedule, one workgroup: scalars[0] = scalars[1] += eps (ln sum(part_y) - ln sum(part_x)) / 4
+__device__ inline void gauge_collect_pair(const double *part_x, int64_t cnt_x, const double *part_y, int64_t cnt_y, double eps,
+                                          double *scalars, double *sh)
+{
+    double ax = 0.0, ay = 0.0;
+    for (int64_t i = threadIdx.x; i < cnt_x; i += 256) ax += part_x[i];
+    for (int64_t i = threadIdx.x; i < cnt_y; i += 256) ay += part_y[i];
+    const double sx = block_sum_256(ax, sh);
+    __syncthreads();
+    const double sy = block_sum_256(ay, sh);
+    if (threadIdx.x == 0) {
+        const bool ok = sx > 0.0 && sx < INFINITY && sy > 0.0 && sy < INFINITY;
+        const double v = scalars[0] + (ok ? 0.25 * eps * (log(sy) - log(sx)) : 0.0);
+        scalars[0] = v;
+        scalars[1] = v;
+    }
+    __syncthreads();
+}
 
 __device__ __forceinline__ void finalize_body(const FinalizeArgs &a, const int bx)
 {
     // dev_part == nullptr: store the update.  dev_part != nullptr: measure the marginal deviation
     // only, unless save_old is given: then measure AND store, keeping the old potential in save_old.
     __shared__ double sh[256];
+    if (a.gauge_prev && bx == 0) {
+        if (a.gauge_prev_x)
+            gauge_collect_pair(a.gauge_prev_x, a.gauge_prev_x_cnt, a.gauge_prev, a.gauge_prev_cnt, a.gauge_prev_eps,
+                               a.gauge_scalars, sh);
+        else
+            gauge_collect(a.gauge_prev, a.gauge_prev_cnt, a.gauge_prev_eps, a.gauge_scalars, sh);
+    }
     const int64_t i = (int64_t)bx * 256 + threadIdx.x;
-    double dev = 0.0;
+    double dev = 0.0, mass = 0.0;
     if (i < a.cnt) {
         double M = -INFINITY;
 #pragma unroll 8
@@ -446,10 +495,16 @@ __device__ __forceinline__ void finalize_body(const FinalizeArgs &a, const int b
         }
         // fhat = -eps * LSE (Alg. 1), f = fhat + alpha (Prop. 1)
         double pot_new = -a.eps * kLn2 * (M + log2(S)) + a.res_norm[i];
+        const double pot_upd = pot_new;
         if (a.mix != 1.0) pot_new = (1.0 - a.mix) * a.pot[i] + a.mix * pot_new;   // averaged schedule (Eq. 4-5)
         if (a.dev_part) {
             double wi = a.w ? (double)a.w[i] : exp(a.log_uniform);
             dev = fabs(wi * exp((a.pot[i] - pot_new) / a.eps) - wi);   // Prop. 3: r = a exp((fhat - fhat+)/eps)
+        }
+        if (a.gauge_out) {
+            // Prop. 3: the plan's column (row) sum, from the UPDATE itself also where the stored potential is an average
+            const double wi = a.w ? (double)a.w[i] : exp(a.log_uniform);
+            mass = wi > 0.0 ? wi * exp((a.pot[i] - pot_upd) / a.eps) : 0.0;
         }
         if (!a.dev_part || a.save_old) {
             if (a.save_old) a.save_old[i] = a.pot[i];
@@ -463,6 +518,35 @@ __device__ __forceinline__ void finalize_body(const FinalizeArgs &a, const int b
         double t = block_sum_256(dev, sh);
         if (threadIdx.x == 0) a.dev_part[bx] = t;
     }
+    if (a.gauge_out) {
+        __syncthreads();
+        double t = block_sum_256(mass, sh);
+        if (threadIdx.x == 0) a.gauge_out[bx] = t;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_gauge_collect(const double *part, int64_t cnt, double eps, double *scalars)
+{
+    __shared__ double sh[256];
+    gauge_collect(part, cnt, eps, scalars, sh);
+}
+
+__global__ __launch_bounds__(256) void k_gauge_collect_pair(const double *part_x, int64_t cnt_x, const double *part_y,
+                                                            int64_t cnt_y, double eps, double *scalars)
+{
+    __shared__ double sh[256];
+    gauge_collect_pair(part_x, cnt_x, part_y, cnt_y, eps, scalars, sh);
+}
+
+// f_user = (float)(x_pot - scalars[1]) for i < n, g_user = (float)(y_pot + scalars[0]) for the next m indices
+__global__ void k_gauge_export(const double *x_pot, int64_t n, const double *y_pot, int64_t m, const double *scalars,
+                               float *f_user, float *g_user)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n)
+        f_user[i] = (float)(x_pot[i] - scalars[1]);
+    else if (i < n + m)
+        g_user[i - n] = (float)(y_pot[i - n] + scalars[0]);
 }
 
 __global__ __launch_bounds__(256) void k_finalize(FinalizeArgs a) { finalize_body(a, blockIdx.x); }
@@ -720,6 +804,71 @@ __global__ void k_grad_assemble(float *g, int64_t ldg, const void *pts, int dtyp
     g[i * ldg + k] = (float)r;
 }
 
+// ---- label-augmented cost  l1 |x_i - y_j|^2 + l2 W[lx_i, ly_j]  (Section 3.1's remark on generalised costs; the
+// appendix on the dataset-distance application).  The table lookup is itself a contraction,
+// W[lx, ly] = <onehot(lx), W[:, ly]>, so V more coordinates carry it through the score contraction of every kernel:
+//     xa_i = [x_i, onehot(lx_i)],   ya_j = [y_j, u_j],  u_j = -(l2 / 2 l1) W[:, ly_j]
+//     l1 |xa_i - ya_j|^2 = l1 |x_i - y_j|^2 + l2 W[lx_i, ly_j] + l1 + v_j,   v_j = l1 |u_j|^2,
+// a cost that differs from the wanted one by per-point constants only, which the potentials absorb exactly.
+// In bf16 mode u is rounded to bfloat16 here, so that v_j is taken from the values the matrix cores will see.
+// Labels outside [0, V) are counted in *bad (and read as class 0).
+__global__ void k_label_augment(const void *pts, int dtype, int64_t rows, int64_t d, int64_t ld, const int32_t *labels,
+                                const float *W, int V, int target_side, double half_ratio, double l1, int round_bf16,
+                                float *out, float *vconst, unsigned *bad)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= rows) return;
+    int lab = labels[i];
+    if (lab < 0 || lab >= V) {
+        atomicAdd(bad, 1u);
+        lab = 0;
+    }
+    float *o = out + i * (d + V);
+    for (int64_t k = 0; k < d; ++k) o[k] = load_pt(pts, dtype, i * ld + k);
+    double v = 0.0;
+    for (int k = 0; k < V; ++k) {
+        float u;
+        if (target_side) {
+            u = (float)(-half_ratio * (double)W[(int64_t)k * V + lab]);
+            if (round_bf16) u = bf16_to_float(float_to_bf16(u));
+            v += (double)u * (double)u;
+        } else {
+            u = k == lab ? 1.0f : 0.0f;
+        }
+        o[d + k] = u;
+    }
+    if (vconst) vconst[i] = (float)(l1 * v);
+}
+
+// potentials of the labelled problem <-> potentials of the augmented one:  p' = (p + shift) / l1  and back
+__global__ void k_label_potential(const float *src, const float *vconst, double cshift, double l1, int to_augmented,
+                                  int64_t cnt, float *dst)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= cnt) return;
+    const double sh = cshift + (vconst ? (double)vconst[i] : 0.0);
+    dst[i] = to_augmented ? (float)(((double)src[i] + sh) / l1) : (float)((double)src[i] * l1 - sh);
+}
+
+fs_status launch_label_augment(Ctx *c, const void *pts, int dtype, int64_t rows, int64_t d, int64_t ld,
+                               const int32_t *labels, const float *W, int V, bool target_side, double l1, double l2,
+                               bool round_bf16, float *out, float *vconst, unsigned *bad)
+{
+    hipLaunchKernelGGL(k_label_augment, dim3((unsigned)ceil_div(rows, 128)), dim3(128), 0, c->stream, pts, dtype, rows, d, ld,
+                       labels, W, V, target_side ? 1 : 0, l2 / (2.0 * l1), l1, round_bf16 ? 1 : 0, out, vconst, bad);
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
+fs_status launch_label_potential(Ctx *c, const float *src, const float *vconst, double cshift, double l1, bool to_augmented,
+                                 int64_t cnt, float *dst)
+{
+    hipLaunchKernelGGL(k_label_potential, dim3((unsigned)ceil_div(cnt, 256)), dim3(256), 0, c->stream, src, vconst, cshift, l1,
+                       to_augmented ? 1 : 0, cnt, dst);
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
 fs_status launch_pts_to_f32(Ctx *c, const void *pts, int dtype, int64_t rows, int64_t d, int64_t ld, float *dst)
 {
     hipLaunchKernelGGL(k_pts_to_f32, dim3((unsigned)ceil_div(rows * d, 256)), dim3(256), 0, c->stream, pts, dtype, rows, d,
@@ -855,12 +1004,32 @@ static FinalizeArgs finalize_args(const Prepared *P, const void *partial, Side *
     return a;
 }
 
+fs_status launch_gauge_export(Ctx *c, const Prepared *P, bool collect_last, double eps_last, const double *x_pot,
+                              float *f_user, float *g_user)
+{
+    if (collect_last)
+        hipLaunchKernelGGL(k_gauge_collect, dim3(1), dim3(256), 0, c->stream, P->gauge_part, (int64_t)ceil_div(P->Y.cnt, 256),
+                           eps_last, P->scalars + 8);
+    hipLaunchKernelGGL(k_gauge_export, dim3((unsigned)ceil_div(P->X.cnt + P->Y.cnt, 256)), dim3(256), 0, c->stream, x_pot,
+                       P->X.cnt, P->Y.pot, P->Y.cnt, P->scalars + 8, f_user, g_user);
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
 fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, const double *res_norm, int splits, double eps_cur,
-                          double eps_next_bias, float *user_out, double *abs_dev_sum, double mix, double *save_old)
+                          double eps_next_bias, float *user_out, double *abs_dev_sum, double mix, double *save_old,
+                          GaugeMode gauge, int64_t gauge_prev_cnt, double gauge_prev_eps)
 {
     double *dev_part = abs_dev_sum ? P->dev_part : nullptr;   // per-block sums of the marginal deviation
-    const FinalizeArgs a = finalize_args(P, P->partial, res, res_norm, splits, eps_cur, eps_next_bias, user_out, dev_part,
-                                         mix, save_old);
+    FinalizeArgs a = finalize_args(P, P->partial, res, res_norm, splits, eps_cur, eps_next_bias, user_out, dev_part,
+                                   mix, save_old);
+    if (gauge == GaugeMode::Measure) a.gauge_out = P->gauge_part;
+    if (gauge == GaugeMode::Collect && gauge_prev_cnt > 0) {
+        a.gauge_prev = P->gauge_part;
+        a.gauge_prev_cnt = (int64_t)ceil_div(gauge_prev_cnt, 256);
+        a.gauge_prev_eps = gauge_prev_eps;
+        a.gauge_scalars = P->scalars + 8;
+    }
     hipLaunchKernelGGL(k_finalize, dim3((unsigned)a.blocks), dim3(256), 0, c->stream, a);
     if (abs_dev_sum)
         hipLaunchKernelGGL(k_sum_to, dim3(1), dim3(256), 0, c->stream, dev_part, (int64_t)a.blocks, abs_dev_sum);
@@ -871,11 +1040,38 @@ fs_status launch_finalize(Ctx *c, const Prepared *P, Side *res, const double *re
 // merges of the f-pass (records in partial_x) and of the g-pass (partial_y) in one launch
 fs_status launch_finalize_pair(Ctx *c, const Prepared *P, Side *X, const double *norm_x, const void *partial_x, int splits_x,
                                float *f_out, Side *Y, const double *norm_y, const void *partial_y, int splits_y,
-                               float *g_out, double eps_cur, double eps_next_bias, double mix)
+                               float *g_out, double eps_cur, double eps_next_bias, double mix, int gauge_parity, bool collect_prev)
 {
-    const FinalizeArgs ax = finalize_args(P, partial_x, X, norm_x, splits_x, eps_cur, eps_next_bias, f_out, nullptr, mix, nullptr);
-    const FinalizeArgs ay = finalize_args(P, partial_y, Y, norm_y, splits_y, eps_cur, eps_next_bias, g_out, nullptr, mix, nullptr);
+    FinalizeArgs ax = finalize_args(P, partial_x, X, norm_x, splits_x, eps_cur, eps_next_bias, f_out, nullptr, mix, nullptr);
+    FinalizeArgs ay = finalize_args(P, partial_y, Y, norm_y, splits_y, eps_cur, eps_next_bias, g_out, nullptr, mix, nullptr);
+    if (gauge_parity >= 0) {
+        // the sums of this iteration go to one half of the two arrays while the first workgroup of the f side
+        // collects the previous iteration's from the other half
+        const int64_t nbx = ceil_div(X->cnt, 256), nby = ceil_div(Y->cnt, 256);
+        const int64_t half = nbx > nby ? nbx : nby;
+        ax.gauge_out = P->gauge_part_x + (gauge_parity & 1) * half;
+        ay.gauge_out = P->gauge_part + (gauge_parity & 1) * half;
+        if (collect_prev) {
+            ax.gauge_prev = P->gauge_part + ((gauge_parity & 1) ^ 1) * half;
+            ax.gauge_prev_cnt = nby;
+            ax.gauge_prev_x = P->gauge_part_x + ((gauge_parity & 1) ^ 1) * half;
+            ax.gauge_prev_x_cnt = nbx;
+            ax.gauge_prev_eps = eps_cur;
+            ax.gauge_scalars = P->scalars + 8;
+        }
+    }
     hipLaunchKernelGGL(k_finalize_pair, dim3((unsigned)(ax.blocks + ay.blocks)), dim3(256), 0, c->stream, ax, ay);
+    FS_HIP(c, hipGetLastError());
+    return FS_OK;
+}
+
+// the term of the last averaged iteration (its sums sit in half `gauge_parity` of the two arrays)
+fs_status launch_gauge_collect_pair(Ctx *c, const Prepared *P, double eps, int gauge_parity)
+{
+    const int64_t nbx = ceil_div(P->X.cnt, 256), nby = ceil_div(P->Y.cnt, 256);
+    const int64_t half = nbx > nby ? nbx : nby;
+    hipLaunchKernelGGL(k_gauge_collect_pair, dim3(1), dim3(256), 0, c->stream, P->gauge_part_x + (gauge_parity & 1) * half, nbx,
+                       P->gauge_part + (gauge_parity & 1) * half, nby, eps, P->scalars + 8);
     FS_HIP(c, hipGetLastError());
     return FS_OK;
 }

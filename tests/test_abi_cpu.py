@@ -130,6 +130,24 @@ def test_noalloc_solve_checks_sizes_on_the_host(lib, hctx):
     assert lib.fs_solve_noalloc(*args(_prob(d=0))) == 2
 
 
+def test_labeled_solve_validation(lib, hctx):
+    p = _prob()
+    args = lambda V=4, l1=0.5, l2=0.5, eps=0.1, iters=3, lx=1 << 24, ly=1 << 25, W=1 << 26, f=1 << 21, g=1 << 22, prob=p: (
+        hctx, ctypes.byref(prob), P(lx) if lx else None, P(ly) if ly else None, P(W) if W else None, V, F(l1), F(l2), F(eps),
+        iters, P(f) if f else None, P(g) if g else None)
+    assert lib.fs_solve_labeled(*args(lx=None)) == 1
+    assert lib.fs_solve_labeled(*args(W=None)) == 1
+    assert lib.fs_solve_labeled(*args(f=None)) == 1
+    assert lib.fs_solve_labeled(*args(V=0)) == 2
+    assert lib.fs_solve_labeled(*args(V=8190)) == 2                   # d + V beyond the supported dimension
+    assert lib.fs_solve_labeled(*args(l1=0.0)) == 1
+    assert lib.fs_solve_labeled(*args(l2=float("inf"))) == 1
+    assert lib.fs_solve_labeled(*args(eps=0.0)) == 3
+    assert lib.fs_solve_labeled(*args(iters=-1)) == 3
+    assert lib.fs_solve_labeled(*args(g=(1 << 21) + 8)) == 1          # g on top of f
+    assert lib.fs_solve_labeled(*args()) == 7                         # valid: reaches device stage
+
+
 def test_null_and_aliasing(lib, hctx):
     p = _prob()
     assert lib.fs_update_f(hctx, ctypes.byref(p), F(0.1), None, P(1 << 21)) == 1

@@ -55,6 +55,24 @@ def test_symmetric_fp32_mode(ctx, oracle, n, m, d, eps, iters):
     assert ef <= 1e-4 and eg <= 1e-4
 
 
+def test_symmetric_long_run_at_a_larger_size(ctx, oracle):
+    """80 averaged iterations at a small eps on two clouds of different shape (uniform cube against a clustered
+    mixture, n = m = 12288): the run where a systematic difference between the roundings of the f-pass and of the
+    g-pass would add up along the iteration's neutral direction (f + t, g - t) if it were not measured and removed."""
+    from paper_2602_03067_amd import workloads
+    w = workloads.make("lowdim_anneal", n=12288, m=12288)
+    eps = float(np.float32(0.02))
+    iters = 80
+    say("solve_symmetric on the annealed workload's clouds, n=m=%d eps=%g iters=%d" % (w.n, eps, iters))
+    fo, go = oracle.solve_symmetric(w.x, w.y, w.a, w.b, eps, iters)
+    prob = make_problem(w.x, w.y, w.a, w.b)
+    f, g = dev(np.zeros(w.n, dtype=np.float32)), dev(np.zeros(w.m, dtype=np.float32))
+    ctx.fs_solve_symmetric(prob, eps, iters, f, g)
+    df, dg = (host(f) - fo) / eps, (host(g) - go) / eps
+    say("  max|df|/eps=%.3e max|dg|/eps=%.3e (mean shifts %.3e, %.3e)" % (np.abs(df).max(), np.abs(dg).max(), df.mean(), dg.mean()))
+    assert np.abs(df).max() <= 1e-4 and np.abs(dg).max() <= 1e-4
+
+
 def test_symmetric_equal_clouds_keep_f_equal_g(ctx, oracle):
     """x = y and a = b: under the symmetric schedule f = g at every iteration (the oracle is pinned
     to this); on the GPU the two passes are the same arithmetic on swapped roles."""
