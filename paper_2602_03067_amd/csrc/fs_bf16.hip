@@ -130,7 +130,7 @@ struct BfArgs {
 constexpr int kVRow = 520;                       // bytes per value column in the LDS image (256 points + pad)
 constexpr int kVImgBytes(int pc) { return (pc * kVRow + 1023) / 1024 * 1024; }
 
-template <int WJ, int NS, int JTW, int PC>
+template <int WJ, int NS, int JTW, int PC, bool HALF = false>
 __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
 {
     constexpr bool APPLY = PC > 0;
@@ -309,8 +309,9 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
             //     wait "stage g+1 landed" + barrier | read F0(g+1) | 4 MFMA on F1(g)
             // Stage g + D goes to the ring slot of stage g - 1, which nobody reads any more: every
             // wave had its reads of that stage back before it passed the barrier of stage g - 1.
-            auto stage = [&](auto first_c) {
+            auto stage = [&](auto first_c, auto half_c) {
                 constexpr bool FIRST = decltype(first_c)::value;
+                constexpr bool skip_second = decltype(half_c)::value;
                 const f16v zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
 #define FS_MFMA0(IT, JT) acc[IT][JT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[IT], b0[JT], FIRST ? zero : acc[IT][JT], 0, 0, 0)
 #define FS_MFMA1(IT, JT) acc[IT][JT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[IT], b1[JT], acc[IT][JT], 0, 0, 0)
@@ -321,17 +322,21 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
                 FS_MFMA0(0, 2);
                 FS_MFMA0(0, 3);
                 __builtin_amdgcn_sched_barrier(0);
-                read_frags(a1, b1, g, pk1);
+                if constexpr (!skip_second) read_frags(a1, b1, g, pk1);
                 if (g + D < G) issue_stage();
                 __builtin_amdgcn_sched_barrier(0);
                 FS_MFMA0(1, 0);
                 FS_MFMA0(1, 1);
                 FS_MFMA0(1, 2);
                 FS_MFMA0(1, 3);
-                FS_MFMA1(0, 0);
-                FS_MFMA1(0, 1);
-                FS_MFMA1(0, 2);
-                FS_MFMA1(0, 3);
+                // (the second 16 coordinates of a tile's last chunk are zero padding when d ends in its first half:
+                // 784 = 49 x 16 saves 2 % of the MFMAs this way)
+                if constexpr (!skip_second) {
+                    FS_MFMA1(0, 0);
+                    FS_MFMA1(0, 1);
+                    FS_MFMA1(0, 2);
+                    FS_MFMA1(0, 3);
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 if (g + 1 < G) {
                     wait_landed(g + 1, pg - 1);   // this wave's pieces of stage g+1 have landed ...
@@ -339,16 +344,27 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
                     read_frags(a0, b0, g + 1, pk0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                FS_MFMA1(1, 0);
-                FS_MFMA1(1, 1);
-                FS_MFMA1(1, 2);
-                FS_MFMA1(1, 3);
+                if constexpr (!skip_second) {
+                    FS_MFMA1(1, 0);
+                    FS_MFMA1(1, 1);
+                    FS_MFMA1(1, 2);
+                    FS_MFMA1(1, 3);
+                }
 #undef FS_MFMA0
 #undef FS_MFMA1
                 ++g;
             };
-            stage(std::integral_constant<bool, true>{});
-            for (int ch = 1; ch < n_chunks; ++ch) stage(std::integral_constant<bool, false>{});
+            using yes = std::integral_constant<bool, true>;
+            using no = std::integral_constant<bool, false>;
+            // (HALF: the launcher has checked that d ends in the first 16 coordinates of the last chunk and that a
+            // tile has at least two chunks; the three code copies follow each other without a branch between them)
+            stage(yes{}, no{});
+            if constexpr (HALF) {
+                for (int ch = 1; ch + 1 < n_chunks; ++ch) stage(no{}, no{});
+                stage(no{}, yes{});
+            } else {
+                for (int ch = 1; ch < n_chunks; ++ch) stage(no{}, no{});
+            }
         }
         for (int ch = 0; APPLY && ch < n_chunks; ++ch, ++g) {
             const bool issue = g + D < G;
@@ -595,10 +611,10 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
     }
 }
 
-template <int WJ, int NS, int JTW, int PC>
+template <int WJ, int NS, int JTW, int PC, bool HALF = false>
 __global__ __launch_bounds__(256 * WJ, WJ == 2 ? 1 : 2) void k_lse_bf16(BfArgs a)
 {
-    lse_bf16_body<WJ, NS, JTW, PC>(a, blockIdx.x);
+    lse_bf16_body<WJ, NS, JTW, PC, HALF>(a, blockIdx.x);
 }
 
 // Both LSE passes of one iteration of the averaged schedule (Eq. 4-5) in one launch: the first `blocks0`
@@ -686,8 +702,14 @@ fs_status bf16_lse(Ctx *c, const Prepared *P, const Side *res, const Side *str, 
     int blocks = 0;
     fs_status st = lse_pass_args(c, P, res, str, eps, P->partial, &a, &blocks);
     if (st != FS_OK) return st;
+    // the coordinates end in the first 16 of a tile's last chunk (d = 784 = 49 x 16): the kernel copy that leaves
+    // out that chunk's second, all-zero k-step (2 % of the MFMAs at d = 784)
+    const bool half = (P->d % 32) >= 1 && (P->d % 32) <= 16 && a.kp >= 64;
     prof_begin(c, (double)res->cnt * (double)str->cnt);
-    hipLaunchKernelGGL((k_lse_bf16<2, 4, 4, 0>), dim3((unsigned)blocks), dim3(512), 0, c->stream, a);
+    if (half)
+        hipLaunchKernelGGL((k_lse_bf16<2, 4, 4, 0, true>), dim3((unsigned)blocks), dim3(512), 0, c->stream, a);
+    else
+        hipLaunchKernelGGL((k_lse_bf16<2, 4, 4, 0>), dim3((unsigned)blocks), dim3(512), 0, c->stream, a);
     prof_end(c);
     FS_HIP(c, hipGetLastError());
     *splits_out = a.splits;
