@@ -373,33 +373,19 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
     __builtin_amdgcn_sched_barrier(0);       \
     if (Q == 0 && issue) issue_stage();      \
     __builtin_amdgcn_sched_barrier(0)
-            if constexpr (JTW == 4) {
-                FS_MFMA(0, 0, a0, b0);
-                FS_PIECE(0);
-                FS_MFMA(0, 1, a0, b0);
-                FS_MFMA(0, 2, a0, b0);
-                FS_MFMA(0, 3, a0, b0);
-                __builtin_amdgcn_sched_barrier(0);
-                read_frags(a1, b1, g, pk1);
-                FS_MFMA(1, 0, a0, b0);
-                FS_MFMA(1, 1, a0, b0);
-                FS_MFMA(1, 2, a0, b0);
-                FS_MFMA(1, 3, a0, b0);
-                FS_MFMA(0, 0, a1, b1);
-                FS_MFMA(0, 1, a1, b1);
-                FS_MFMA(0, 2, a1, b1);
-                FS_MFMA(0, 3, a1, b1);
-            } else {
-                FS_MFMA(0, 0, a0, b0);
-                FS_PIECE(0);
-                FS_MFMA(0, 1, a0, b0);
-                __builtin_amdgcn_sched_barrier(0);
-                read_frags(a1, b1, g, pk1);
-                FS_MFMA(1, 0, a0, b0);
-                FS_MFMA(1, 1, a0, b0);
-                FS_MFMA(0, 0, a1, b1);
-                FS_MFMA(0, 1, a1, b1);
-            }
+            // (plan application: 64 x 64 scores per wave)
+            //     2 MFMA on F0(g) | read F1(g), issue stage g+3 | 2 MFMA on F0(g) | 2 MFMA on F1(g) |
+            //     wait "stage g+1 landed" + barrier | read F0(g+1) | 2 MFMA on F1(g)
+            static_assert(!APPLY || JTW == 2, "schedule of the application");
+            FS_MFMA(0, 0, a0, b0);
+            FS_MFMA(0, 1, a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            read_frags(a1, b1, g, pk1);
+            FS_PIECE(0);
+            FS_MFMA(1, 0, a0, b0);
+            FS_MFMA(1, 1, a0, b0);
+            FS_MFMA(0, 0, a1, b1);
+            FS_MFMA(0, 1, a1, b1);
             __builtin_amdgcn_sched_barrier(0);
             if (g + 1 < G) {
                 // this wave's pieces of stage g+1 have landed ...
@@ -416,15 +402,8 @@ __device__ __forceinline__ void lse_bf16_body(const BfArgs &a, const int block)
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (JTW == 4) {
-                FS_MFMA(1, 0, a1, b1);
-                FS_MFMA(1, 1, a1, b1);
-                FS_MFMA(1, 2, a1, b1);
-                FS_MFMA(1, 3, a1, b1);
-            } else {
-                FS_MFMA(1, 0, a1, b1);
-                FS_MFMA(1, 1, a1, b1);
-            }
+            FS_MFMA(1, 0, a1, b1);
+            FS_MFMA(1, 1, a1, b1);
 #undef FS_MFMA
 #undef FS_PIECE
         }
