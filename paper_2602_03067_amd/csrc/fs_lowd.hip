@@ -195,6 +195,7 @@ __global__ __launch_bounds__(kBlock) void k_lse_lowd(const S *__restrict__ res, 
 // chunk sum leaves [0, 2^60), the wave zeroes those slots, recomputes the chunk's raw scores,
 // lifts the integer max, writes it back into B and takes the chunk's sums again.
 typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 
 //
@@ -225,20 +226,35 @@ struct SplitArgs {
     int64_t ldv, n_str;
     int p0, p;
     float *opart;
+    const unsigned char *vimg;   // PC == 8: value images of the streamed tiles (see k_vimg_lowd)
 };
 
 // one workgroup of the pass: row block bx, column split by.
-// PC > 0 makes it the plan application (Alg. 2 / Alg. 4) for PC value columns: every exponential
-// also multiplies the value row of its streamed point, which all lanes of a half-wave share (a
-// lane's registers are streamed points, its lane index the resident row), so the value row comes
-// as one broadcast LDS read per exponential and the products stay on the vector ALU in fp32.
+// PC > 0 makes it the plan application (Alg. 2 / Alg. 4) for PC value columns, in one of two forms.
+// PC == 4: every exponential also multiplies the value row of its streamed point, which all lanes of a
+// half-wave share (a lane's registers are streamed points, its lane index the resident row), so the
+// value row comes as one broadcast LDS read per exponential and the products stay on the vector ALU
+// in fp32: 4 FMAs and an LDS read per exponential.
+// PC == 8: the products go to the matrix cores as well.  The sixteen exponentials of a lane ARE the B
+// operand of an MFMA whose contraction runs over the streamed points (k-step 0 = registers 0..7,
+// k-step 1 = registers 8..15), once split into a bf16 head (E rounded) and a bf16 tail (E - head, exact
+// in fp32, then rounded: E is kept to 2^-17, the size of the error that fp32 scores of a few hundred
+// base-2 units leave in E anyway).  The A operand is an image of the tile's
+// value rows in the matching order, 32 rows = 8 columns x (three bf16 pieces of the value, exact to
+// 24 bits, + a spare row, the first of which holds ones and so yields the row sum):
+//     O[c'][j] += sum_i A2[c'][i] (Eh[i][j] + El[i][j]),   c' = 8 (col / 2) + 4 (col % 2) + piece,
+// so in the accumulator layout lane half h of resident row j ends up with columns h, 2 + h, 4 + h, 6 + h
+// in its registers 4 q + piece, and half 0 with the row sum in register 3.  Per 32 x 32 pairs that
+// is 48 simple vector instructions and 4 MFMAs instead of 64 FMAs and 16 LDS reads, for twice the columns.
 template <int KS, int R, int TJ, int CH, bool PRECISE, int PC = 0, int PCU = PC>
 __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx, const int by)
 {
     // PCU <= PC: value columns actually wanted (the others are not multiplied; zeros are stored for them)
     constexpr bool APPLY = PC > 0;
-    static_assert(PC == 0 || PC == 4, "one float4 of values per streamed point");
-    __shared__ __attribute__((aligned(16))) float vtile[APPLY ? 2 : 1][APPLY ? TJ * PC : 4];
+    constexpr bool MM = PC == 8;   // products on the matrix cores
+    static_assert(PC == 0 || PC == 4 || PC == 8, "one float4 of values per streamed point, or an image of eight columns");
+    constexpr int VBYTES = MM ? (TJ / 32) * 2048 : (APPLY ? TJ * PC * 4 : 16);   // values of a tile in LDS
+    __shared__ __attribute__((aligned(1024))) unsigned char vbuf[APPLY ? 2 : 1][VBYTES];
     constexpr int NP = 2 * KS;               // 16-byte pieces per record
     constexpr int UPT = TJ * NP / kBlock;    // pieces each thread moves per tile
     constexpr int NG = TJ / 32;              // groups of 32 streamed points per tile
@@ -263,12 +279,19 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
 
     bf8 b[R][KS];
     float mrun[R], srun[R], stile[R];
-    float orun[APPLY ? R : 1][APPLY ? PC : 1], otile[APPLY ? R : 1][APPLY ? PC : 1];
-    if constexpr (APPLY) {
+    float orun[APPLY && !MM ? R : 1][APPLY && !MM ? PC : 1], otile[APPLY && !MM ? R : 1][APPLY && !MM ? PC : 1];
+    f16v omm[MM ? R : 1];   // PC == 8: running outputs in the accumulator layout
+    if constexpr (APPLY && !MM) {
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int c = 0; c < PC; ++c) orun[r][c] = otile[r][c] = 0.0f;
+    }
+    if constexpr (MM) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) omm[r][e] = 0.0f;
     }
     auto set_max = [&](int r, float neg_m) {   // slots 3..5 of that piece <- pieces of -max
         __bf16 q[3];
@@ -285,7 +308,7 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
 
     // a tile is a linear 16 KS TJ / 8 byte copy, moved by direct global -> LDS loads (no registers)
     const unsigned tile_off = (unsigned)(size_t)&tile[0][0];
-    const unsigned vtile_off = (unsigned)(size_t)&vtile[0][0];
+    const unsigned vtile_off = (unsigned)(size_t)&vbuf[0][0];
     auto fetch = [&](int t, int bufi) {
         // each wave brings UPT consecutive KB of the tile, in runs of up to four loads behind one write of the LDS
         // base to m0 (immediate offsets advance the memory and the LDS address alike; a write to m0 waits for the
@@ -300,7 +323,16 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
             }
             asm volatile("global_load_lds_dwordx4 %0, off offset:%1" ::"v"(src + (q / 4) * 256), "n"((q % 4) * 1024) : "memory");
         }
-        if constexpr (APPLY) {
+        if constexpr (MM) {
+            // the tile's value image: VBYTES / 1024 consecutive KB, this wave's share as one run
+            constexpr int VPW = VBYTES / 1024 / 4;
+            static_assert(VBYTES % 4096 == 0 && VPW <= 4, "a run of at most four loads per wave");
+            const unsigned char *vsrc = a.vimg + (int64_t)t * VBYTES + (w * VPW) * 1024 + l * 16;
+            const unsigned m = __builtin_amdgcn_readfirstlane(vtile_off + bufi * VBYTES + (w * VPW) * 1024);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" ::"s"(m) : "memory", "m0");
+#pragma unroll
+            for (int q = 0; q < VPW; ++q) asm volatile("global_load_lds_dwordx4 %0, off offset:%1" ::"v"(vsrc), "n"(q * 1024) : "memory");
+        } else if constexpr (APPLY) {
             // value rows of the tile, one dword per lane; entries outside the matrix are read from a
             // valid address instead (their exponentials are zero / their columns are not stored)
 #pragma unroll
@@ -437,17 +469,106 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
         }
     };
 
+    // PC == 8: the same pipeline with the products on the matrix cores.  dch[r] receives, for the chunk alone,
+    // sum_i A2[c'][i] E[i][j]; the four product MFMAs of a step (two k-steps x head/tail) are issued between
+    // the exponentials of the NEXT step, like the score MFMAs, so that the two pipes alternate.
+    auto load_va = [&](const unsigned char *vi, int grp, bf8(&va)[2]) {
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) va[k2] = *reinterpret_cast<const bf8 *>(vi + ((((grp * 2 + k2) * 2 + lh) * 32 + lj) << 4));
+    };
+    const uint32_t kmask = 0xffff0000u;
+    auto chunk_mm = [&](const Unit *tl, const unsigned char *vi, int c0, f16v(&dch)[MM ? R : 1]) {
+        constexpr int NS = CH * R;
+        bf8 av[2][KS], va[2][2];
+        bf8 eh[2], el[2];   // heads and tails of the previous step's exponentials, per k-step
+        f16v dd[2];
+        f16v z;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) z[e] = 0.0f;
+        load_a(tl, c0, av[0]);
+        if (CH > 1 && R == 1) load_a(tl, c0 + 1, av[1]);
+        load_va(vi, c0, va[0]);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            dd[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[0][ks], b[0][ks], ks == 0 ? z : dd[0], 0, 0, 0);
+#pragma unroll
+        for (int st = 0; st <= NS; ++st) {
+            const int g = st / R, r = st % R;
+            const int sn = st + 1, gn = sn / R, rn = sn % R;
+            const int pst = st > 0 ? st - 1 : 0;
+            const int pg = pst / R, pr = pst % R;   // the step whose products are pending
+            if (st < NS) {
+                if (R == 1) {
+                    if (g + 2 < CH) load_a(tl, c0 + g + 2, av[g & 1]);
+                } else if (r == 0 && g + 1 < CH) {
+                    load_a(tl, c0 + g + 1, av[(g + 1) & 1]);
+                }
+            }
+            // four quarters, each: one pending product MFMA, its share of the next step's score MFMAs, four
+            // exponentials (consecutive MFMAs into one accumulator are a dependent chain: the exponentials between
+            // them cover its latency)
+            float ev[16];
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                if (st > 0)
+                    dch[pr] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[pg & 1][qd >> 1], (qd & 1) ? el[qd >> 1] : eh[qd >> 1],
+                                                                      (pg == 0 && qd == 0) ? z : dch[pr], 0, 0, 0);
+                if (sn < NS) {
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+                        if (ks * 4 / KS == qd)
+                            dd[sn & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[gn & 1][ks], b[rn][ks], ks == 0 ? z : dd[sn & 1], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (st < NS) {
+#pragma unroll
+                    for (int e = 4 * qd; e < 4 * qd + 4; ++e) ev[e] = fast_exp2(dd[st & 1][e]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (st < NS) {
+                // the value image of the next group, once the pending products of the group before it are issued
+                if (r == 0 && g + 1 < CH) load_va(vi, c0 + g + 1, va[(g + 1) & 1]);
+#pragma unroll
+                for (int k2 = 0; k2 < 2; ++k2) {
+                    uint32_t hp[4];
+#pragma unroll
+                    for (int q = 0; q < 8; q += 2) {
+                        // heads: the two exponentials rounded to bf16, packed; tails: what the heads leave, rounded
+                        const float x0 = ev[8 * k2 + q], x1 = ev[8 * k2 + q + 1];
+                        const bf2 hd = {(__bf16)x0, (__bf16)x1};
+                        const uint32_t pk = __builtin_bit_cast(uint32_t, hd);
+                        hp[q >> 1] = pk;
+                        el[k2][q] = (__bf16)(x0 - __builtin_bit_cast(float, pk << 16));
+                        el[k2][q + 1] = (__bf16)(x1 - __builtin_bit_cast(float, pk & kmask));
+                    }
+                    const uint4 u = make_uint4(hp[0], hp[1], hp[2], hp[3]);
+                    eh[k2] = __builtin_bit_cast(bf8, u);
+                }
+            }
+        }
+    };
+
     int buf = 0;
     for (int t = t_begin; t < t_end; ++t) {
         if (t + 1 < t_end) fetch(t + 1, buf ^ 1);   // that buffer was last read before the previous barrier
         const Unit *tl = tile[buf];
-        const float *vt = vtile[APPLY ? buf : 0];
+        const float *vt = reinterpret_cast<const float *>(vbuf[APPLY ? buf : 0]);
+        const unsigned char *vi = vbuf[APPLY ? buf : 0];
 #pragma unroll 1
         for (int c0 = 0; c0 < NG; c0 += CH) {
             float csum[R];
-            float co[APPLY ? R : 1][APPLY ? PC : 1];
-            chunk_sums(tl, vt, c0, csum, co);
-            if constexpr (APPLY) {
+            float co[APPLY && !MM ? R : 1][APPLY && !MM ? PC : 1];
+            f16v dch[MM ? R : 1];
+            if constexpr (MM) {
+                chunk_mm(tl, vi, c0, dch);
+                // (the row sum of the chunk sits in register 3 of lane half 0; the other half has a zero row there)
+#pragma unroll
+                for (int r = 0; r < R; ++r) csum[r] = dch[r][3];
+            } else {
+                chunk_sums(tl, vt, c0, csum, co);
+            }
+            if constexpr (APPLY && !MM) {
                 // pin the products to this point: left alone, the compiler sinks all of them behind the
                 // branch below (they are only needed when the chunk is accepted) and keeps 64
                 // exponentials and 64 value rows alive for that, in scratch memory
@@ -485,22 +606,35 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
                     const float scale = fast_exp2(mrun[r] - mnew);
                     srun[r] *= scale;
                     stile[r] *= scale;
-                    if constexpr (APPLY) {
+                    if constexpr (APPLY && !MM) {
 #pragma unroll
                         for (int c = 0; c < PC; ++c) {
                             orun[r][c] *= scale;
                             otile[r][c] *= scale;
                         }
                     }
+                    if constexpr (MM) {
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) omm[r][e] *= scale;
+                    }
                     mrun[r] = mnew;
                     set_max(r, -mnew);
                 }
-                chunk_sums(tl, vt, c0, csum, co);   // all exponents are <= 0 now: no second check
+                // all exponents are <= 0 now: no second check
+                if constexpr (MM)
+                    chunk_mm(tl, vi, c0, dch);
+                else
+                    chunk_sums(tl, vt, c0, csum, co);
             }
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                stile[r] += csum[r];
-                if constexpr (APPLY) {
+                if constexpr (MM) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) omm[r][e] += dch[r][e];
+                } else {
+                    stile[r] += csum[r];
+                }
+                if constexpr (APPLY && !MM) {
 #pragma unroll
                     for (int c = 0; c < PC; ++c) otile[r][c] += co[r][c];
                 }
@@ -510,7 +644,7 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
         for (int r = 0; r < R; ++r) {
             srun[r] += stile[r];
             stile[r] = 0.0f;
-            if constexpr (APPLY) {
+            if constexpr (APPLY && !MM) {
 #pragma unroll
                 for (int c = 0; c < PC; ++c) {
                     orun[r][c] += otile[r][c];
@@ -523,6 +657,19 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
         buf ^= 1;
     }
 
+    if constexpr (MM) {
+        // the second contraction has already summed over both lane halves' streamed points; the max of a row is
+        // common to its two lanes
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int64_t row = row0 + 32 * r + lj;
+            if (lh == 0) partial[(int64_t)by * partial_stride + row] = make_double2((double)mrun[r], (double)omm[r][3]);
+            float *o = a.opart + ((int64_t)by * partial_stride + row) * PC + lh;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) o[2 * q] = (omm[r][4 * q] + omm[r][4 * q + 1]) + omm[r][4 * q + 2];
+        }
+        return;
+    }
     // merge the two lane halves (streamed points 8q+4h .. of every 32) of each resident row
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -531,7 +678,7 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
         const float M = fmaxf(m, mo);
         const float S = sv * fast_exp2(m - M) + so * fast_exp2(mo - M);
         if (lh == 0) partial[(int64_t)by * partial_stride + row0 + 32 * r + lj] = make_double2((double)M, (double)S);
-        if constexpr (APPLY) {
+        if constexpr (APPLY && !MM) {
             float4 o;
             o.x = orun[r][0] * fast_exp2(m - M) + __shfl_xor(orun[r][0], 32) * fast_exp2(mo - M);
             o.y = orun[r][1] * fast_exp2(m - M) + __shfl_xor(orun[r][1], 32) * fast_exp2(mo - M);
@@ -815,13 +962,14 @@ static bool precise_on_matrix_cores(const Prepared *P, const Side *res, const Si
 // false when this half-step does not run on the split-record kernels (float64 scores off the
 // matrix cores) or its shape does not fit the padded copies (*st says which).
 static bool split_pass_args(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, void *partial,
-                            SplitArgs *a, bool *precise_out, fs_status *st)
+                            SplitArgs *a, bool *precise_out, fs_status *st, int rblocks = kSplitR)
 {
     *st = FS_OK;
     const bool precise = lowd_precise(P, eps);
     double gx = 0.0;
     if (precise && !precise_on_matrix_cores(P, res, str, eps, &gx)) return false;
-    const PassShape s = shape_for(c, res->cnt, str->cnt, 128 * kSplitR, kSplitTJ);
+    // (rblocks: blocks of 32 resident rows per wave of the kernel that will run)
+    const PassShape s = shape_for(c, res->cnt, str->cnt, 128 * rblocks, kSplitTJ);
     const int n_tiles = (int)ceil_div(str->cnt, kSplitTJ);
     // host-side shape checks: every access of the kernel stays inside the padded copies
     if ((int64_t)s.row_blocks * s.rows_per_block > res->cnt_pad || (int64_t)n_tiles * kSplitTJ > str->cnt_pad ||
@@ -944,22 +1092,78 @@ fs_status lowd_lse_pair(Ctx *c, const Prepared *P, double eps, void *partial_x, 
     return FS_OK;
 }
 
+// Value image for the matrix-core application (PC == 8): per tile of kSplitTJ streamed points and group of 32
+// of them, [k-step 0/1][lane half h][row c' 0..31][8 bf16]; slot e of (k-step ks, half h) is streamed point
+// 8 (2 ks + e / 4) + 4 h + e % 4 of the group, i.e. the order in which a lane of the score MFMA holds its sixteen
+// exponentials.  Row c' = 8 (col / 2) + 4 (col % 2) + piece holds bf16 piece `piece` (0..2) of value column
+// p0 + col; row 3 holds ones (the row sum), the other spare rows zeros.  One thread per 16-byte unit.
+constexpr int kApplyMM = 8;   // value columns per pass of the matrix-core application
+__global__ __launch_bounds__(256) void k_vimg_lowd(const float *__restrict__ V, int64_t ldv, int64_t n_str, int p0, int p,
+                                                   int64_t units, unsigned char *__restrict__ img)
+{
+    const int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (u >= units) return;
+    const int cr = (int)(u & 31), h = (int)(u >> 5) & 1, ks = (int)(u >> 6) & 1;
+    const int64_t grp = u >> 7;   // group of 32 streamed points
+    const int piece = cr & 3, col = 2 * (cr >> 3) + ((cr >> 2) & 1);
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+        __bf16 v[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int64_t i = grp * 32 + 8 * (2 * ks + ((e + k) >> 2)) + 4 * h + ((e + k) & 3);
+            float x = 0.0f;
+            if (i < n_str) {
+                if (piece == 3) {
+                    x = cr == 3 ? 1.0f : 0.0f;
+                } else if (p0 + col < p) {
+                    __bf16 q[3];
+                    split3(V[i * ldv + p0 + col], q);
+                    x = (float)q[piece];
+                }
+            }
+            v[k] = (__bf16)x;
+        }
+        w[e >> 1] = bf16_pair(v[0], v[1]);
+    }
+    *reinterpret_cast<uint4 *>(img + u * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// workspace of an application: [splits][rows][columns per pass] float accumulators, then the value images
+static size_t lowd_opart_bytes(int splits, int64_t res_pad) { return ((size_t)splits * (size_t)res_pad * kApplyMM * 4 + 1023) & ~size_t(1023); }
+static size_t lowd_vimg_bytes(int64_t n_str) { return (size_t)ceil_div(n_str, kSplitTJ) * (kSplitTJ / 32) * 2048; }
+
 size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t d, int64_t p)
 {
-    // the largest of the launch shapes an application can take (split records / vector ALU / fp64 matrix cores)
+    // the largest of the launch shapes an application can take (split records with one or two row blocks per
+    // wave / vector ALU / fp64 matrix cores)
     const PassShape s1 = shape_for(c, n_res, n_str, kBlock);
     const PassShape s2 = shape_for(c, n_res, n_str, 128 * kSplitR, kSplitTJ);
-    const int splits = s1.splits > s2.splits ? s1.splits : s2.splits;
-    const size_t own = (size_t)splits * (size_t)round_up(n_res, 1024) * kApplyPC * 4;
+    const PassShape s3 = shape_for(c, n_res, n_str, 128, kSplitTJ);
+    int splits = s1.splits > s2.splits ? s1.splits : s2.splits;
+    splits = splits > s3.splits ? splits : s3.splits;
+    const size_t own = lowd_opart_bytes(splits, round_up(n_res, 1024)) + lowd_vimg_bytes(n_str);
     const size_t f64 = d > 3 ? f64_apply_ws(c, n_res, n_str, d, p) : 0;
     return own > f64 ? own : f64;
 }
 
-// `cols`: value columns of this launch that exist (1..kApplyPC).  A single column (transport-vector
-// products) has a kernel of its own for the short records: 8.9 against 13.9 ms at n = m = 262144; a
-// three-column variant measured slower than the four-column one (15.9 ms) and is not built.
+// Matrix-core application on the split records: eight value columns per pass.  Two blocks of 32 resident rows per
+// wave while the records are short; one block for KS > 4, where two would not leave registers for the operands.
 template <int KS>
-void launch_apply_split(dim3 grid, hipStream_t st, const SplitArgs &a, int cols)
+void launch_apply_split(dim3 grid, hipStream_t st, const SplitArgs &a)
+{
+    hipLaunchKernelGGL((k_apply_lowd_split<KS, (KS <= 4 ? kSplitR : 1), kSplitTJ, kSplitCH, false, kApplyMM, kApplyMM>), grid,
+                       dim3(kBlock), 0, st, a);
+}
+// The form with the products on the vector ALU (four columns per pass) is kept where it measured faster
+// (n = m = 65536): a single column on short records, where a kernel copy multiplies one column only
+// (d = 3: 0.71 against 0.89 ms), and up to four columns at d = 16, where the matrix-core form runs one
+// workgroup per CU (1.8 against 2.2 ms).  Everywhere else the matrix-core form wins: 0.92 against 1.06 ms
+// for three columns at d = 3, 0.97 against 2.02 ms for eight.
+static bool apply_on_valu(int ks, bool precise, int64_t p) { return (p == 1 && (precise || ks <= 3)) || (!precise && ks == 9 && p <= 4); }
+template <int KS>
+void launch_apply_split_valu(dim3 grid, hipStream_t st, const SplitArgs &a, int cols)
 {
     if constexpr (KS <= 3) {
         if (cols == 1) {
@@ -974,37 +1178,54 @@ fs_status lowd_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str
                      int64_t p, int64_t ldv, float *out, int64_t ldo, float *mass_out, const float *had_A, int64_t lda)
 {
     float *opart = (float *)P->extra;
-    // Plain applications run on the split records (scores on the matrix cores, as in the LSE pass);
+    // Plain applications run on the split records (scores and products on the matrix cores);
     // the Hadamard-weighted form and float64 scores outside the matrix cores' reach stay on the
     // vector-ALU kernel below.
     if (!had_A) {
         SplitArgs a;
         bool precise = false;
         fs_status st;
-        if (split_pass_args(c, P, res, str, eps, P->partial, &a, &precise, &st)) {
-            if ((size_t)a.splits * res->cnt_pad * kApplyPC * 4 > P->extra_bytes || !opart)
-                return fail(c, FS_ERR_DEVICE, "internal: low-d apply workspace");
+        const bool valu = apply_on_valu(P->ks, lowd_precise(P, eps), p);
+        const int rblocks = (valu || lowd_precise(P, eps) || P->ks <= 4) ? kSplitR : 1;
+        if (split_pass_args(c, P, res, str, eps, P->partial, &a, &precise, &st, rblocks)) {
+            const size_t ob = lowd_opart_bytes(a.splits, res->cnt_pad);
+            const int64_t units = (int64_t)a.n_tiles * (kSplitTJ / 32) * 128;
+            if (!opart || ob + (size_t)units * 16 > P->extra_bytes) return fail(c, FS_ERR_DEVICE, "internal: low-d apply workspace");
+            unsigned char *vimg = reinterpret_cast<unsigned char *>(opart) + ob;
             a.V = V;
             a.ldv = ldv;
             a.n_str = str->cnt;
             a.p = (int)p;
             a.opart = opart;
+            a.vimg = vimg;
             const dim3 grid((unsigned)a.row_blocks, (unsigned)a.splits);
-            for (int p0 = 0; p0 < p; p0 += kApplyPC) {
+            for (int p0 = 0; valu && p0 < p; p0 += kApplyPC) {
                 a.p0 = p0;
                 const int cols = (int)(p - p0 < kApplyPC ? p - p0 : kApplyPC);
                 if (precise) {
-                    if (cols == 1)
-                        hipLaunchKernelGGL((k_apply_lowd_split<3, kSplitR, kSplitTJ, kSplitCH, true, kApplyPC, 1>), grid,
-                                           dim3(kBlock), 0, c->stream, a);
-                    else
-                        hipLaunchKernelGGL((k_apply_lowd_split<3, kSplitR, kSplitTJ, kSplitCH, true, kApplyPC, kApplyPC>), grid,
-                                           dim3(kBlock), 0, c->stream, a);
+                    hipLaunchKernelGGL((k_apply_lowd_split<3, kSplitR, kSplitTJ, kSplitCH, true, kApplyPC, 1>), grid, dim3(kBlock), 0,
+                                       c->stream, a);
                 } else {
-                    FS_SPLIT_KS_DISPATCH(P->ks, (launch_apply_split<KS_>(grid, c->stream, a, cols)));
+                    FS_SPLIT_KS_DISPATCH(P->ks, (launch_apply_split_valu<KS_>(grid, c->stream, a, cols)));
                 }
                 FS_HIP(c, hipGetLastError());
                 st = launch_apply_finalize(c, P, res, precise ? res->norm : res->norm_f, a.splits, eps, opart, kApplyPC, p0,
+                                           (int)p, out, ldo, mass_out);
+                if (st != FS_OK) return st;
+            }
+            if (valu) return FS_OK;
+            for (int p0 = 0; p0 < p; p0 += kApplyMM) {
+                a.p0 = p0;
+                hipLaunchKernelGGL(k_vimg_lowd, dim3((unsigned)ceil_div(units, 256)), dim3(256), 0, c->stream, V, ldv, str->cnt, p0,
+                                   (int)p, units, vimg);
+                if (precise) {
+                    hipLaunchKernelGGL((k_apply_lowd_split<3, kSplitR, kSplitTJ, kSplitCH, true, kApplyMM, kApplyMM>), grid,
+                                       dim3(kBlock), 0, c->stream, a);
+                } else {
+                    FS_SPLIT_KS_DISPATCH(P->ks, (launch_apply_split<KS_>(grid, c->stream, a)));
+                }
+                FS_HIP(c, hipGetLastError());
+                st = launch_apply_finalize(c, P, res, precise ? res->norm : res->norm_f, a.splits, eps, opart, kApplyMM, p0,
                                            (int)p, out, ldo, mass_out);
                 if (st != FS_OK) return st;
             }

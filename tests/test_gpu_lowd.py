@@ -277,7 +277,11 @@ def test_full_size_lowdim_every_stage_sampled(ctx, oracle):
         % (worst, 2 * w.total_iters, sum_abs / eps_end))
 
 
-@pytest.mark.parametrize("n,m,d,p", [(300, 200, 3, 3), (1000, 1300, 3, 1), (513, 255, 2, 7), (260, 300, 8, 5)])
+# (p = 1 runs the kernel with the products on the vector ALU, as does p <= 4 at d = 16; everything else has them on the
+# matrix cores, eight columns per pass: p = 8, 9 and 17 are one full pass, a second one with a single column, three)
+@pytest.mark.parametrize("n,m,d,p", [(300, 200, 3, 3), (1000, 1300, 3, 1), (513, 255, 2, 7), (260, 300, 8, 5), (700, 900, 3, 8),
+                                     (450, 520, 1, 9), (390, 1100, 5, 17), (640, 300, 16, 16), (300, 640, 16, 3),
+                                     (1200, 900, 12, 12)])
 def test_apply_plan_and_transpose(ctx, oracle, n, m, d, p):
     rng = np.random.default_rng(n + m + d + p)
     x, y, a, b = _rand_problem(rng, n, m, d)
@@ -298,6 +302,34 @@ def test_apply_plan_and_transpose(ctx, oracle, n, m, d, p):
         assert np.abs(got - ref).max() <= 1e-3 * np.abs(ref).max()
     np.testing.assert_allclose(host(mass), r, rtol=2e-4)
     np.testing.assert_allclose(host(massT), c, rtol=2e-4)
+
+
+@pytest.mark.parametrize("direction", [1, -1])
+@pytest.mark.parametrize("p", [1, 3])
+@pytest.mark.parametrize("span", [18.0, 150.0])
+def test_apply_with_a_running_max_that_is_lifted(ctx, oracle, direction, p, span):
+    """Plan application with potentials that rise (fall) steeply along the streamed index: the lazy stabiliser of the
+    application lifts the max along the way and rescales the output accumulators with it (vector-ALU products for
+    p = 1, matrix-core products for p = 3).  A ramp of 18 spans 87 base-2 units at eps = 0.3: beyond the 2^60 window,
+    still fp32 scores; a ramp of 150 spans 720, a dozen lifts, and the library takes its float64-grade records."""
+    rng = np.random.default_rng(23 + p)
+    n, m, d = 600, 2300, 3
+    x, y, a, b = _rand_problem(rng, n, m, d)
+    eps = float(np.float32(0.3))
+    ramp = np.linspace(0.0, span, m)[::direction]
+    g32 = (ramp + 0.1 * rng.standard_normal(m)).astype(np.float32)
+    f32 = oracle.update_f(x, y, b, eps, g32).astype(np.float32)
+    V = (rng.standard_normal((m, p)) + 2.0).astype(np.float32)
+    say("apply_plan under a potential ramp of %g (%s), n=%d m=%d p=%d" % (span, "rising" if direction > 0 else "falling", n, m, p))
+    prob = make_problem(x, y, a, b)
+    out, mass = ctx.fs_apply_plan(prob, eps, dev(f32), dev(g32), dev(V), want_mass=True)
+    want, r = oracle.apply_plan(x, y, a, b, eps, f32, g32, V, return_mass=True)
+    got = host(out)
+    say("  rel. Frobenius %.2e, max-abs / max %.2e" % (np.linalg.norm(got - want) / np.linalg.norm(want),
+                                                      np.abs(got - want).max() / np.abs(want).max()))
+    assert np.linalg.norm(got - want) <= 2e-4 * np.linalg.norm(want)
+    assert np.abs(got - want).max() <= 1e-3 * np.abs(want).max()
+    np.testing.assert_allclose(host(mass), r, rtol=2e-4)
 
 
 def test_zero_weight_points_drop_out(ctx, oracle):
