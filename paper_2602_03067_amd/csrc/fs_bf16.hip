@@ -109,14 +109,15 @@ struct BfArgs {
 // 64-byte row segments, and a 256 x 256 tile needs 32 B/clk/CU at full MFMA rate.
 //
 // Schedule of one stage g in every wave (F0/F1 = fragment registers of the two 16-wide k-steps):
-//     4 MFMA on F0(g) | read F1(g) | 4 MFMA on F0(g) | 4 MFMA on F1(g) |
+//     4 MFMA on F0(g) | read F1(g), issue the loads of stage g + NS - 1 | 4 MFMA on F0(g) | 4 MFMA on F1(g) |
 //     wait "stage g+1 landed" + barrier | read F0(g+1) | 4 MFMA on F1(g)
-// with the direct loads of stage g + NS - 1 (this wave's 1 KB pieces and its quarter of the bias
-// tile) issued one by one between the first MFMAs.  The barrier and the LDS latency of the next
-// fragments hide behind the last MFMAs.
+// A wave's loads of a stage (its 1 KB pieces, consecutive in memory and in LDS) go out as ONE run behind a
+// single write of m0; the biases of a streamed tile come with the tile's first stage.  The barrier and the
+// LDS latency of the next fragments hide behind the last MFMAs.
 // Ceiling: with random operands the matrix cores sustain ~1.83 PFLOP/s here (a loop of nothing but
 // this MFMA: 2.42 PFLOP/s on constant operands, 1.83 on uniform random ones), i.e. the chip is
-// power-limited well below the 2.5 PFLOP/s peak that the roofline fraction is quoted against.
+// power-limited well below the 2.5 PFLOP/s peak that the roofline fraction is quoted against; the
+// shipped pass runs at 1.84 GHz with the matrix pipe 67 % busy.
 //
 // PC > 0 is the plan application (Alg. 2 / Alg. 4) in this mode: a fused matmul - softmax - matmul.
 // A wave then owns JTW = 2 blocks of 32 resident rows (64 x 64 scores per tile, 256 x 128 per
