@@ -109,6 +109,19 @@ def run_workload(name, steps, warmup, schedule="alternating", n_override=None, c
     p_avg, p_launches, _ = ctx.fs_profile_read()
     ctx.fs_profile_enable(False)
     prologue_ms = pe0.elapsed_time(pe1) - p_avg * p_launches
+    # A plan application with 64 value columns (outside the timed region too): at d <= 16 the step's own applications
+    # have only d columns, and an application takes eight columns per streaming pass there.
+    wide_ms = None
+    if w.d <= 16:
+        U64 = torch.from_numpy(np.random.Generator(np.random.PCG64(w.seed + 8)).standard_normal((w.n, 64)).astype(np.float32)).to("cuda:0")
+        ctx.fs_apply_plan_T(prob, w.eps_end, f, g, U64)
+        we0, we1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        we0.record()
+        ctx.fs_apply_plan_T(prob, w.eps_end, f, g, U64)
+        we1.record()
+        torch.cuda.synchronize()
+        wide_ms = we0.elapsed_time(we1)
+        del U64
     if calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")   # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
@@ -180,7 +193,8 @@ def run_workload(name, steps, warmup, schedule="alternating", n_override=None, c
                    "step": "row_norms + solve + marginal_err + grad_x (plan applied to y + assembly) + apply_plan_T"},
         "marginal_err": {"row": er, "col": ec},
         "apply_ms": {"grad_x": apply_avg["grad_x"], "grad_x_value_columns": w.d,
-                     "apply_plan_T": apply_avg["apply_plan_T"], "apply_plan_T_value_columns": int(U.shape[1])},
+                     "apply_plan_T": apply_avg["apply_plan_T"], "apply_plan_T_value_columns": int(U.shape[1]),
+                     "apply_plan_T_64_columns": wide_ms},
         "solve_overhead_ms": prologue_ms,
         "roofline": roof,
         "rates": rates,
