@@ -382,6 +382,26 @@ def test_full_size_lowdim_sampled_rows(ctx, oracle):
     f_plus = host(ctx.fs_update_f(prob, eps, g))[rows]
     r_gpu = w.a[rows].astype(np.float64) * np.exp((host(f)[rows] - f_plus) / eps)
     np.testing.assert_allclose(r_gpu, r_or, rtol=5e-4)
+    # the two plan applications of the bench step on sampled rows / columns: the gradient x - (P y)/a (three value
+    # columns) and P^T U with the workload's U, and one with eleven columns (two passes, the second with three)
+    fh0 = host(f)
+    say("full size: plan applications on sampled rows")
+    grad = host(ctx.fs_grad_x(prob, eps, f, g, 2))[rows]
+    T = oracle.apply_plan(w.x, w.y, w.a, w.b, eps, fh0, gh, w.y, rows=rows)
+    want_grad = w.x[rows].astype(np.float64) - T / w.a[rows].astype(np.float64)[:, None]
+    scale = np.abs(w.x).max()
+    eg = np.abs(grad - want_grad).max() / scale
+    say("full size: gradient max abs error / max|x| = %.3e" % eg)
+    assert eg <= 1e-4
+    U = np.random.default_rng(77).standard_normal((w.n, 11)).astype(np.float32)
+    outT, cm = ctx.fs_apply_plan_T(prob, eps, f, g, dev(U), want_mass=True)
+    wantT, c_or = oracle.apply_plan_T(w.x, w.y, w.a, w.b, eps, fh0, gh, U, cols=rows, return_mass=True)
+    gotT = host(outT)[rows]
+    eT = np.linalg.norm(gotT - wantT) / np.linalg.norm(wantT)
+    say("full size: P^T U on sampled columns, rel. Frobenius %.3e, max-abs / max %.3e"
+        % (eT, np.abs(gotT - wantT).max() / np.abs(wantT).max()))
+    assert eT <= 2e-4 and np.abs(gotT - wantT).max() <= 1e-3 * np.abs(wantT).max()
+    np.testing.assert_allclose(host(cm)[rows], c_or, rtol=2e-4)
 
 
 @pytest.mark.parametrize("n,m,d", [(1500000, 1048576 + 77, 2), (3000000, 130, 5)])
