@@ -80,6 +80,9 @@ def run_workload(name, steps, warmup, schedule="alternating", n_override=None, c
     def step():
         f.zero_()
         g.zero_()
+        # one batch: the clouds stay as they are for the five entry calls of the step, so the library prepares their
+        # derived copies in the first one (the solve) and reuses them; the declaration ends with the step
+        ctx.fs_points_keep(prob)
         ctx.fs_row_norms(prob.x)
         ctx.fs_row_norms(prob.y)
         if schedule == "symmetric":
@@ -91,6 +94,7 @@ def run_workload(name, steps, warmup, schedule="alternating", n_override=None, c
         # applied to y (d value columns) and the assembly, inside the library
         grad = timed("grad_x", lambda: ctx.fs_grad_x(prob, w.eps_end, f, g, 2))
         timed("apply_plan_T", lambda: ctx.fs_apply_plan_T(prob, w.eps_end, f, g, U))
+        ctx.fs_points_release()
         return er, ec, grad
 
     for _ in range(warmup):
@@ -98,7 +102,7 @@ def run_workload(name, steps, warmup, schedule="alternating", n_override=None, c
     torch.cuda.synchronize()
     # What a solve costs beyond its streaming passes (derived copies of both clouds, norms, first biases, and
     # the merges of one iteration): a one-iteration solve at the final eps, minus its two pass launches.
-    # Outside the timed region; every timed step contains the one-time part again (the rate is a "cold" one).
+    # Outside the timed region; every timed step prepares the derived copies once (in its solve; the rate is a "cold" one).
     ctx.fs_profile_enable(True)
     ctx.fs_profile_read()
     pe0, pe1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -339,6 +339,22 @@ fs_status fs_apply_plan_hadamard(fs_ctx *ctx, const fs_problem *prob, float eps,
                                  int64_t ldo);
 
 /*
+ * Keeping the derived copies of the clouds across entry calls (the norms alpha, beta of Prop. 1 and the
+ * tiled / split / centred copies the kernels stream).  Every entry call above prepares them from x and y
+ * anew, because the library cannot see whether the caller has changed the points in between.
+ * fs_points_keep declares that the clouds of `prob` (the addresses x and y, n, m, d, ldx, ldy, storage and
+ * compute mode; the weights may change freely) will not be written until fs_points_release: the next entry
+ * call on these clouds prepares the copies as usual, and later calls on the same clouds reuse them and skip
+ * that part of their prologue (coordinate sums, mean, derived copies, norms; biases and potentials are
+ * always written anew).  The copies live in the context's workspace: a call on other clouds, or one that
+ * needs a larger workspace, overwrites them, and the next call on the kept clouds prepares them again, so
+ * results never depend on the declaration as long as it is true.  Host-only state; nothing is launched.
+ * Changing the points while the declaration stands gives results for the OLD points.
+ */
+fs_status fs_points_keep(fs_ctx *ctx, const fs_problem *prob);
+fs_status fs_points_release(fs_ctx *ctx);
+
+/*
  * Test and experiment switches of ONE context (there is no process-wide state; a new context has
  * every switch at 0 = the library decides).  Not needed for normal use.
  *   "lowd_splits"        1..1024: split count of the streamed side of the d <= 16 passes

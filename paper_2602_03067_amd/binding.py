@@ -22,7 +22,7 @@ FS_COMPUTE_FP32, FS_COMPUTE_BF16_MFMA = 0, 1
 EXPORTS = (
     "fs_create", "fs_destroy", "fs_status_str", "fs_last_error", "fs_version", "fs_row_norms",
     "fs_update_f", "fs_update_g", "fs_solve", "fs_solve_noalloc", "fs_solve_labeled", "fs_solve_symmetric", "fs_solve_tol", "fs_marginal_err", "fs_ot_value", "fs_check_weights", "fs_check_finite", "fs_divergence", "fs_apply_plan",
-    "fs_apply_plan_T", "fs_apply_plan_hadamard", "fs_grad_x", "fs_grad_y", "fs_hvp", "fs_debug_set", "fs_profile_enable", "fs_profile_read",
+    "fs_apply_plan_T", "fs_apply_plan_hadamard", "fs_grad_x", "fs_grad_y", "fs_hvp", "fs_points_keep", "fs_points_release", "fs_debug_set", "fs_profile_enable", "fs_profile_read",
 )
 
 
@@ -86,6 +86,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fs_grad_y.argtypes = [vp, PP, f32, vp, vp, i32, vp, i64]
     lib.fs_hvp.argtypes = [vp, PP, f32, vp, vp, vp, i64, f32, f32, i32, vp, i64, ctypes.POINTER(i32)]
     lib.fs_debug_set.argtypes = [vp, ctypes.c_char_p, i64]
+    lib.fs_points_keep.argtypes = [vp, PP]
+    lib.fs_points_release.argtypes = [vp]
     lib.fs_profile_enable.argtypes = [vp, i32]
     lib.fs_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64),
                                     ctypes.POINTER(ctypes.c_double)]
@@ -341,6 +343,13 @@ class Context:
                                     float(tau), float(eta), int(max_cg), _ptr(out), prob.d, ctypes.byref(it)),
                     "fs_hvp")
         return out, it.value
+
+    def fs_points_keep(self, prob: Problem) -> None:
+        """Declare the clouds of `prob` unchanged until fs_points_release: later calls reuse their derived copies."""
+        self._check(self.lib.fs_points_keep(self.h, ctypes.byref(prob.c)), "fs_points_keep")
+
+    def fs_points_release(self) -> None:
+        self._check(self.lib.fs_points_release(self.h), "fs_points_release")
 
     def fs_debug_set(self, key: str, value: int) -> None:
         """Test and experiment switches of this context (0 = the library decides)."""

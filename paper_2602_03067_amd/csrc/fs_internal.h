@@ -127,6 +127,26 @@ struct Ctx {
     char *aux = nullptr;
     size_t aux_bytes = 0;
     std::string err;
+    // Derived copies kept across entry calls (fs_points_keep): what identifies the clouds the caller has declared
+    // unchanged, whether the workspace currently holds their derived copies, and the host-side value that belongs
+    // to them (largest squared norm after centring, low-d path)
+    struct PointsKey {
+        const void *x = nullptr, *y = nullptr;
+        int dtype = 0, compute = 0;
+        int64_t n = 0, m = 0, d = 0, ldx = 0, ldy = 0;
+        const char *ws = nullptr;      // the workspace the copies live in
+        size_t partial_budget = 0;     // (the offsets of the device scalars depend on it)
+        bool same(const PointsKey &o) const
+        {
+            return x == o.x && y == o.y && dtype == o.dtype && compute == o.compute && n == o.n && m == o.m && d == o.d &&
+                   ldx == o.ldx && ldy == o.ldy && ws == o.ws && partial_budget == o.partial_budget;
+        }
+    };
+    bool keep_on = false;
+    PointsKey keep_key;                // declared by the caller (ws and partial_budget unset)
+    bool kept_valid = false;
+    PointsKey kept_key;
+    double kept_rho_max = -1.0;
     // test and experiment switches of this context (fs_debug_set); 0 = the library decides
     int dbg_lowd_splits = 0;         // forced split count of the streamed side of a low-d pass
     int dbg_lowd_score = 0;          // 32: fp32 scores, 64: float64 scores in every low-d half-step

@@ -976,6 +976,7 @@ fs_status launch_bias_from_user(Ctx *c, Prepared *P, Side *side, const float *po
         if (h[0] > P->logw_mag) P->logw_mag = h[0];
         if (h[1] * eps > P->pot_mag_eps) P->pot_mag_eps = h[1] * eps;
         P->rho_max = h[2];
+        if (c->kept_valid) c->kept_rho_max = h[2];   // belongs to the kept derived copies (no-op when they are another problem's)
     }
     return FS_OK;
 }

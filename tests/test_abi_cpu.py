@@ -233,6 +233,23 @@ def test_debug_switches_are_per_context(lib, hctx):
         assert "getenv" not in open(src).read(), src
 
 
+def test_points_keep_validation(lib, hctx):
+    """Host-only state: the declaration is validated like any problem and can be withdrawn; nothing is launched."""
+    p = _prob()
+    assert lib.fs_points_keep(hctx, ctypes.byref(p)) == 0
+    assert lib.fs_points_release(hctx) == 0
+    assert lib.fs_points_release(hctx) == 0                        # releasing twice is harmless
+    assert lib.fs_points_keep(hctx, ctypes.byref(_prob(n=0))) == 2
+    assert lib.fs_points_keep(hctx, ctypes.byref(_prob(x=None))) == 1
+    assert lib.fs_points_keep(hctx, None) == 1
+    assert lib.fs_points_keep(None, ctypes.byref(p)) == 1
+    assert lib.fs_points_release(None) == 1
+    # an entry call after the declaration still validates and reaches the device stage of a host-only context
+    assert lib.fs_points_keep(hctx, ctypes.byref(p)) == 0
+    assert lib.fs_update_f(hctx, ctypes.byref(p), F(0.1), P(1 << 20), P(1 << 21)) == 7
+    assert lib.fs_points_release(hctx) == 0
+
+
 def test_row_norms_validation(lib, hctx):
     assert lib.fs_row_norms(hctx, None, 0, 4, 3, 3, P(1 << 20)) == 1
     assert lib.fs_row_norms(hctx, P(4096), 0, 0, 3, 3, P(1 << 20)) == 2

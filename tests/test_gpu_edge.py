@@ -1,6 +1,6 @@
 """GPU edge cases of the C ABI against the float64 oracle: row strides larger than the row,
 a context on a stream of its own, one context reused over problems of different sizes and paths
-(workspace regrowth), very small eps in low dimension."""
+(workspace regrowth), very small eps in low dimension, derived copies kept across calls."""
 import numpy as np
 import pytest
 import torch
@@ -159,3 +159,59 @@ def test_check_finite():
         ctx.fs_check_finite(v)
     assert e.value.status == 8 and "2 of 100001" in str(e.value)
     ctx.close()
+
+
+@pytest.mark.parametrize("d,compute", [(3, "fp32"), (2, "fp32"), (9, "fp32"), (40, "fp32"), (48, "bf16")])
+def test_kept_derived_copies_change_nothing(oracle, d, compute):
+    """fs_points_keep: a sequence of entry calls on one pair of clouds gives bit-identical results with and without the
+    declaration (the copies are the same bytes either way); a call on other clouds in between overwrites the kept copies
+    and the next call prepares them again; after fs_points_release new coordinates at the same addresses are seen."""
+    rng = np.random.default_rng(500 + d)
+    n, m = 700, 900
+    x, y, a, b = _cloud(rng, n, m, d, 0.4)
+    if compute == "bf16":   # coordinates the matrix cores see exactly (and so are their doubles further down)
+        x = torch.from_numpy(x).bfloat16().float().numpy()
+        y = torch.from_numpy(y).bfloat16().float().numpy()
+    eps = float(np.float32(0.25))
+    cm = BF if compute == "bf16" else binding.FS_COMPUTE_FP32
+    xd, yd = dev(x), dev(y)
+    prob = binding.Problem(xd, yd, dev(a), dev(b), cm)
+    other = binding.Problem(dev(x[:300] * 2.0), dev(y[:500] * 0.5), None, None, cm)
+    V = dev(rng.standard_normal((m, 5)).astype(np.float32))
+    say("kept derived copies d=%d %s" % (d, compute))
+
+    def sequence(ctx, interleave):
+        f = torch.zeros(n, device="cuda:0")
+        g = torch.zeros(m, device="cuda:0")
+        ctx.fs_solve(prob, 2 * eps, eps, 3, 4, f, g)
+        if interleave:   # another problem through the same workspace
+            fo = torch.zeros(300, device="cuda:0")
+            go = torch.zeros(500, device="cuda:0")
+            ctx.fs_solve(other, eps, eps, 1, 2, fo, go)
+        er, ec = ctx.fs_marginal_err(prob, eps, f, g)
+        grad = ctx.fs_grad_x(prob, eps, f, g, 0)
+        out = ctx.fs_apply_plan(prob, eps, f, g, V)
+        f2 = ctx.fs_update_f(prob, eps, g)
+        return [host(f), host(g), np.array([er, ec]), host(grad), host(out), host(f2)]
+
+    ctx = binding.Context(0)
+    plain = sequence(ctx, False)
+    ctx.fs_points_keep(prob)
+    kept = sequence(ctx, False)
+    kept_again = sequence(ctx, True)
+    for u, v, w in zip(plain, kept, kept_again):
+        assert np.array_equal(u, v) and np.array_equal(u, w)
+    # parity of the kept run against the oracle
+    fo, go = oracle.solve(x, y, a, b, 2 * eps, eps, 3, 4)
+    assert max_err_over_eps(kept[0], fo, eps) <= (2e-2 if compute == "bf16" else 1e-4)
+    # the points change at the same addresses: with the declaration standing the OLD copies answer; after the
+    # release the new coordinates do
+    g_fix = dev(kept[1])
+    xd.mul_(2.0)
+    stale = host(ctx.fs_update_f(prob, eps, g_fix))
+    assert np.array_equal(stale, plain[5])
+    ctx.fs_points_release()
+    fresh = host(ctx.fs_update_f(prob, eps, g_fix))
+    want = oracle.update_f(host(xd), y, b, eps, kept[1])
+    assert max_err_over_eps(fresh, want, eps) <= (2e-2 if compute == "bf16" else 1e-4)
+    assert not np.array_equal(fresh, stale)
