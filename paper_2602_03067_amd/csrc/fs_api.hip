@@ -268,7 +268,8 @@ fs_status prepare(Ctx *c, const fs_problem *p, Prepared *P, size_t extra, char *
     }
     c->kept_valid = false;   // whatever was kept is overwritten now
     fs_status st2 = launch_prepare(c, p, P);
-    if (st2 == FS_OK && c->keep_on && declared.same(c->keep_key)) {
+    // (not in the static scratch array: other contexts on this GPU write there too)
+    if (st2 == FS_OK && c->keep_on && !c->ws_static && declared.same(c->keep_key)) {
         c->kept_key = key;
         c->kept_rho_max = -1.0;   // (low-d path: set when the host reads it back, see launch_bias_from_user)
         c->kept_valid = true;
