@@ -348,7 +348,8 @@ fs_status fs_apply_plan_hadamard(fs_ctx *ctx, const fs_problem *prob, float eps,
  * that part of their prologue (coordinate sums, mean, derived copies, norms; biases and potentials are
  * always written anew).  The copies live in the context's workspace: a call on other clouds, or one that
  * needs a larger workspace, overwrites them, and the next call on the kept clouds prepares them again, so
- * results never depend on the declaration as long as it is true.  Host-only state; nothing is launched.
+ * results never depend on the declaration as long as it is true.  fs_solve_noalloc prepares its copies
+ * on every call (its scratch array is shared by all contexts of a GPU).  Host-only state; nothing is launched.
  * Changing the points while the declaration stands gives results for the OLD points.
  */
 fs_status fs_points_keep(fs_ctx *ctx, const fs_problem *prob);
