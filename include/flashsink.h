@@ -362,6 +362,7 @@ fs_status fs_points_release(fs_ctx *ctx);
  *   "lowd_score"         32 / 64: fp32-accurate / float64-grade scores in every d <= 16 half-step and
  *                        application (fs_marginal_err and fs_ot_value always take float64-grade scores)
  *   "lowd_precise_valu"  1: float64-grade scores at d <= 3 on the vector ALU instead of the matrix cores
+ *   "lowd_precise_any_bias"  1: those matrix-core records also for biases beyond their digit range
  *   "bf16_variant"       schedule variant of the bf16 matrix-core kernels
  * Unknown keys and values out of range: FS_ERR_INVALID_ARG.  key: HOST string.
  */

@@ -251,6 +251,7 @@ fs_status prepare(Ctx *c, const fs_problem *p, Prepared *P, size_t extra, char *
     layout(c, p, P, c->ws, extra);
     P->dbg_score = c->dbg_lowd_score;
     P->dbg_precise_valu = c->dbg_lowd_precise_valu != 0;
+    P->dbg_any_bias = c->dbg_lowd_any_bias != 0;
     if (extra_ptr) *extra_ptr = c->ws + (need - ((extra + 255) & ~size_t(255)));
     // The prepared part of the layout comes first and depends on the problem alone, so the derived copies of the clouds
     // sit at the same place in every entry call on the same problem.  When the caller has declared the clouds unchanged
@@ -1159,6 +1160,8 @@ fs_status fs_debug_set(fs_ctx *ctx, const char *key, int64_t value)
         c->dbg_lowd_score = (int)value;
     else if (k == "lowd_precise_valu" && (value == 0 || value == 1))
         c->dbg_lowd_precise_valu = (int)value;
+    else if (k == "lowd_precise_any_bias" && (value == 0 || value == 1))
+        c->dbg_lowd_any_bias = (int)value;
     else if (k == "bf16_variant" && value >= 0 && value <= 15)
         c->dbg_bf16_variant = (int)value;
     else

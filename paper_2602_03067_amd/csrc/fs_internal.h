@@ -151,6 +151,7 @@ struct Ctx {
     int dbg_lowd_splits = 0;         // forced split count of the streamed side of a low-d pass
     int dbg_lowd_score = 0;          // 32: fp32 scores, 64: float64 scores in every low-d half-step
     int dbg_lowd_precise_valu = 0;   // 1: float64 scores at d <= 3 on the vector ALU instead of the precise records
+    int dbg_lowd_any_bias = 0;       // 1: the precise records also for biases beyond their digit range (tests of that case)
     int dbg_bf16_variant = 0;        // schedule variant of the bf16 kernels
     // profiling of the streaming LSE launches
     bool prof_on = false;
@@ -229,6 +230,7 @@ struct Prepared {
     bool force_precise = false;   // LowD: float64 scores regardless (marginal error evaluation)
     int dbg_score = 0;            // LowD: the context's score switch (see Ctx::dbg_lowd_score)
     bool dbg_precise_valu = false;   // LowD: the context's kernel switch (see Ctx::dbg_lowd_precise_valu)
+    bool dbg_any_bias = false;       // LowD: see Ctx::dbg_lowd_any_bias
     int kp = 0;   // F64 / BF16: padded contraction length
     Side X, Y;
     // partial reductions of a streaming pass: [splits][max(n,m)_pad] records

@@ -190,26 +190,32 @@ __global__ __launch_bounds__(256) void k_prep_lowd(PrepLowdSide s0, PrepLowdSide
 //   1: Ba Bb Bc 1 1 1 0 0                bias digits on the grid gx gy, ones    x  1 1 1 m1 m2 m3
 //   2+k: ry1 ry2 ry3 Y1 Y1 Y1 ry1 ry2    residual pieces of coordinate k        x  X1 X1 X1 rx1 rx2 rx3 rx1 rx1
 //   5: rb1 rb2 rb3 0 0 ry1_0 ry1_1 ry1_2 bias residual, second-order terms      x  1 1 1 0 0 rx2_0 rx2_1 rx2_2
-__device__ inline uint4 split_precise_bias_digits(double bias, double q)
+// The three 8-bit digits of a bias on the grid q and what they leave.  Inside the digit range (|bias| < 2^21 q: the
+// launcher checks the biases it can foresee) every digit is exact in bf16 and the residual is bias - rint(bias/q) q.
+// Each digit is taken from what the ROUNDED digits before it leave, and the residual from all three as stored, so a
+// bias beyond the range (potentials that grew during a solve) still has pieces that sum to it to double precision:
+// the exact window of the first k-step is lost there and the score falls back to fp32-grade accuracy instead of
+// carrying a silently rounded digit.
+__device__ inline void split_precise_bias(double bias, double q, uint4 *digits, uint2 *residual)
 {
-    const __bf16 one = (__bf16)1.0f;
+    const __bf16 one = (__bf16)1.0f, z = (__bf16)0.0f;
     if (!(fabs(bias) < INFINITY)) {   // padding and zero-weight points: -inf
-        const __bf16 z = (__bf16)0.0f;
-        return make_uint4(bf16_pair((__bf16)(float)bias, z), bf16_pair(z, one), bf16_pair(one, one), 0u);
+        *digits = make_uint4(bf16_pair((__bf16)(float)bias, z), bf16_pair(z, one), bf16_pair(one, one), 0u);
+        if (residual) *residual = make_uint2(0u, 0u);
+        return;
     }
     const double B = rint(bias / q);
-    const double ba = rint(B * (1.0 / 65536.0)) * 65536.0;
-    const double bb = rint((B - ba) * (1.0 / 256.0)) * 256.0;
-    const double bc = B - ba - bb;
-    return make_uint4(bf16_pair((__bf16)(float)(ba * q), (__bf16)(float)(bb * q)),
-                      bf16_pair((__bf16)(float)(bc * q), one), bf16_pair(one, one), 0u);
-}
-__device__ inline uint2 split_precise_bias_residual(double bias, double q)
-{
-    if (!(fabs(bias) < INFINITY)) return make_uint2(0u, 0u);
-    __bf16 rb[3];
-    split3d(bias - rint(bias / q) * q, rb);
-    return make_uint2(bf16_pair(rb[0], rb[1]), bf16_pair(rb[2], (__bf16)0.0f));
+    const __bf16 da = (__bf16)(float)(rint(B * (1.0 / 65536.0)) * 65536.0 * q);
+    const double ra = B * q - (double)(float)da;
+    const __bf16 db = (__bf16)(float)(rint(ra / (256.0 * q)) * 256.0 * q);
+    const double rb = ra - (double)(float)db;
+    const __bf16 dc = (__bf16)(float)rb;
+    *digits = make_uint4(bf16_pair(da, db), bf16_pair(dc, one), bf16_pair(one, one), 0u);
+    if (residual) {
+        __bf16 r[3];
+        split3d(bias - ((double)(float)da + (double)(float)db + (double)(float)dc), r);
+        *residual = make_uint2(bf16_pair(r[0], r[1]), bf16_pair(r[2], z));
+    }
 }
 
 // `rho_max`: device scalar (largest squared norm after centring): the grid comes from it
@@ -234,7 +240,7 @@ __global__ void k_prep_split_precise(const double *packed_d0, int64_t cnt_pad0, 
     const __bf16 z = (__bf16)0.0f;
     uint4 *rec = reinterpret_cast<uint4 *>(out) + i * 6;
     rec[0] = make_uint4(bf16_pair(Y1[0], Y1[1]), bf16_pair(Y1[2], z), 0u, 0u);
-    rec[1] = split_precise_bias_digits(-INFINITY, 1.0);
+    split_precise_bias(-INFINITY, 1.0, rec + 1, nullptr);
     for (int k = 0; k < 3; ++k)
         rec[2 + k] = make_uint4(bf16_pair(ry[k][0], ry[k][1]), bf16_pair(ry[k][2], Y1[k]), bf16_pair(Y1[k], Y1[k]),
                                 bf16_pair(ry[k][0], ry[k][1]));
@@ -349,8 +355,7 @@ __device__ inline void store_bias(const BiasSink &s, int64_t i, double pot, doub
             q = gx * gy;
         }
         uint4 *rec = reinterpret_cast<uint4 *>(s.split_p) + i * 6;
-        rec[1] = split_precise_bias_digits(b, q);
-        *reinterpret_cast<uint2 *>(rec + 5) = split_precise_bias_residual(b, q);
+        split_precise_bias(b, q, rec + 1, reinterpret_cast<uint2 *>(rec + 5));
     }
     if (s.bias_f) s.bias_f[i] = (float)b;
     if (s.bias_d) s.bias_d[i] = b;

@@ -222,6 +222,8 @@ def test_debug_switches_are_per_context(lib, hctx):
     assert lib.fs_debug_set(hctx, b"lowd_score", 0) == 0
     assert lib.fs_debug_set(hctx, b"lowd_splits", 7) == 0
     assert lib.fs_debug_set(hctx, b"lowd_precise_valu", 1) == 0
+    assert lib.fs_debug_set(hctx, b"lowd_precise_any_bias", 1) == 0
+    assert lib.fs_debug_set(hctx, b"lowd_precise_any_bias", 2) == 1
     assert lib.fs_debug_set(hctx, b"lowd_score", 16) == 1            # value out of range
     assert lib.fs_debug_set(hctx, b"lowd_splits", -1) == 1
     assert lib.fs_debug_set(hctx, b"no_such_switch", 1) == 1 and b"no_such_switch" in lib.fs_last_error(hctx)

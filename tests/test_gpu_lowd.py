@@ -101,6 +101,43 @@ def test_running_max_is_lifted_many_times(ctx, oracle, direction, score):
     assert err <= (TOL if score == "auto" else 1e-3)
 
 
+def test_biases_beyond_the_digit_range_of_the_float64_grade_records(ctx, oracle):
+    """d <= 3, float64-grade scores on the matrix cores: the bias of a streamed point is carried as three 8-bit digits on
+    a fixed grid q plus a residual.  The library takes those records only for biases it can foresee inside the digit
+    range; potentials that outgrow the bound during a solve would still meet them.  Forced here with a potential of 300
+    on a cloud of radius ~0.17 at eps = 0.05: the bias is 8656 base-2 units = 2^25 q, so its leading digit needs nine
+    bits and cannot be stored exactly.  The pieces must still sum to the bias, i.e. the half-step stays at fp32-grade
+    accuracy of the score (2^-24 x 8656 x ln 2 = 3.6e-4 of eps) instead of carrying a rounded digit (off by up to
+    2^-9 x 8656 = 17 units).  Both runs are also held by the float format of the output: |f| ~ 300 has an ulp of
+    3e-5, i.e. 3e-4 of eps, which is why the bar here is not 1e-4."""
+    rng = np.random.default_rng(77)
+    n, m, d = 500, 1400, 3
+    x = (0.05 * rng.standard_normal((n, d))).astype(np.float32)
+    y = (0.05 * rng.standard_normal((m, d)) + 0.02).astype(np.float32)
+    a = np.full(n, 1.0 / n, np.float32)
+    b = np.full(m, 1.0 / m, np.float32)
+    eps = float(np.float32(0.05))
+    g = (300.0 + 0.01 * rng.standard_normal(m)).astype(np.float32)
+    want = oracle.update_f(x, y, b, eps, g)
+    out_rounding = 0.5 * float(np.spacing(np.float32(300.0))) / eps
+    prob = make_problem(x, y, a, b)
+    say("update_f with biases of ~8656 base-2 units on a cloud of radius ~0.17 (digits of the records reach ~2048)")
+    f_own = host(ctx.fs_update_f(prob, eps, dev(g)))
+    e_own = max_err_over_eps(f_own, want, eps)
+    try:
+        ctx.fs_debug_set("lowd_score", 64)
+        ctx.fs_debug_set("lowd_precise_any_bias", 1)
+        f_forced = host(ctx.fs_update_f(prob, eps, dev(g)))
+    finally:
+        ctx.fs_debug_set("lowd_score", 0)
+        ctx.fs_debug_set("lowd_precise_any_bias", 0)
+    e_forced = max_err_over_eps(f_forced, want, eps)
+    say("  library's own choice: %.3e; records forced beyond their range: %.3e (output rounding alone: %.1e)"
+        % (e_own, e_forced, out_rounding))
+    assert e_own <= out_rounding * 1.05 + TOL
+    assert e_forced <= out_rounding + 1e-3
+
+
 def test_uniform_weights_by_null_pointer(ctx, oracle):
     rng = np.random.default_rng(5)
     n, m = 600, 500
