@@ -363,7 +363,6 @@ fs_status fs_points_release(fs_ctx *ctx);
  *                        application (fs_marginal_err and fs_ot_value always take float64-grade scores)
  *   "lowd_precise_valu"  1: float64-grade scores at d <= 3 on the vector ALU instead of the matrix cores
  *   "lowd_precise_any_bias"  1: those matrix-core records also for biases beyond their digit range
- *   "bf16_variant"       schedule variant of the bf16 matrix-core kernels
  * Unknown keys and values out of range: FS_ERR_INVALID_ARG.  key: HOST string.
  */
 fs_status fs_debug_set(fs_ctx *ctx, const char *key /* host */, int64_t value);

@@ -1162,8 +1162,6 @@ fs_status fs_debug_set(fs_ctx *ctx, const char *key, int64_t value)
         c->dbg_lowd_precise_valu = (int)value;
     else if (k == "lowd_precise_any_bias" && (value == 0 || value == 1))
         c->dbg_lowd_any_bias = (int)value;
-    else if (k == "bf16_variant" && value >= 0 && value <= 15)
-        c->dbg_bf16_variant = (int)value;
     else
         return fail(c, FS_ERR_INVALID_ARG, "unknown switch or value out of range: %s = %lld", key, (long long)value);
     return FS_OK;

@@ -152,7 +152,6 @@ struct Ctx {
     int dbg_lowd_score = 0;          // 32: fp32 scores, 64: float64 scores in every low-d half-step
     int dbg_lowd_precise_valu = 0;   // 1: float64 scores at d <= 3 on the vector ALU instead of the precise records
     int dbg_lowd_any_bias = 0;       // 1: the precise records also for biases beyond their digit range (tests of that case)
-    int dbg_bf16_variant = 0;        // schedule variant of the bf16 kernels
     // profiling of the streaming LSE launches
     bool prof_on = false;
     std::vector<hipEvent_t> ev_pool;   // pairs (start, stop)
