@@ -113,6 +113,22 @@ def run_workload(name, steps, warmup, schedule="alternating", n_override=None, c
     p_avg, p_launches, _ = ctx.fs_profile_read()
     ctx.fs_profile_enable(False)
     prologue_ms = pe0.elapsed_time(pe1) - p_avg * p_launches
+    # The solve alone with the derived copies of the clouds already in place (the "warm" rate beside the step's cold
+    # one): a second solve in a row under fs_points_keep, outside the timed region.
+    ctx.fs_points_keep(prob)
+    ctx.fs_solve(prob, w.eps_end, w.eps_end, 1, 1, f, g)
+    f.zero_()
+    g.zero_()
+    se0, se1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    se0.record()
+    if schedule == "symmetric":
+        ctx.fs_solve_symmetric(prob, w.eps_end, w.total_iters, f, g)
+    else:
+        ctx.fs_solve(prob, w.eps_start, w.eps_end, w.n_stages, w.iters, f, g)
+    se1.record()
+    torch.cuda.synchronize()
+    ctx.fs_points_release()
+    solve_ms = se0.elapsed_time(se1)
     # A plan application with 64 value columns (outside the timed region too): at d <= 16 the step's own applications
     # have only d columns, and an application takes eight columns per streaming pass there.
     wide_ms = None
@@ -200,6 +216,7 @@ def run_workload(name, steps, warmup, schedule="alternating", n_override=None, c
                      "apply_plan_T": apply_avg["apply_plan_T"], "apply_plan_T_value_columns": int(U.shape[1]),
                      "apply_plan_T_64_columns": wide_ms},
         "solve_overhead_ms": prologue_ms,
+        "solve_only_warm": {"ms": solve_ms, "iterations_per_s": w.total_iters / (solve_ms * 1e-3)},
         "roofline": roof,
         "rates": rates,
     }
