@@ -645,6 +645,7 @@ int choose_splits(const Ctx *c, int n_jtiles, int n_itiles, int cap, int per_cu)
 }
 
 constexpr int kApplyPC = 64;    // value columns per application pass
+constexpr int kApplyPCWide = 96;   // ... when there are more than 64 (every pass repeats the score contraction)
 constexpr int kApplyBJ = 128;   // resident rows per workgroup of the application kernel
 
 }  // namespace
@@ -730,8 +731,8 @@ size_t bf16_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str)
 {
     const int n_jtiles = (int)ceil_div(n_res, kApplyBJ), n_itiles = (int)ceil_div(n_str, BI);
     const int splits = choose_splits(c, n_jtiles, n_itiles, max_splits(c->partial_budget, n_res), 1);
-    const size_t opart = (size_t)splits * (size_t)round_up(n_res, 1024) * kApplyPC * 4;
-    return ((opart + 1023) & ~size_t(1023)) + (size_t)n_itiles * kVImgBytes(kApplyPC);
+    const size_t opart = (size_t)splits * (size_t)round_up(n_res, 1024) * kApplyPCWide * 4;
+    return ((opart + 1023) & ~size_t(1023)) + (size_t)n_itiles * kVImgBytes(kApplyPCWide);
 }
 
 fs_status bf16_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str, double eps, const float *V, int64_t p,
@@ -749,8 +750,10 @@ fs_status bf16_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str
     a.tiles_per_split = (int)ceil_div(a.n_itiles, a.splits);
     a.partial = (double2 *)P->partial;
     a.partial_stride = res->cnt_pad;
-    const size_t opart_bytes = ((size_t)a.splits * res->cnt_pad * kApplyPC * 4 + 1023) & ~size_t(1023);
-    const size_t vimg_bytes = (size_t)a.n_itiles * kVImgBytes(kApplyPC);
+    // 96 columns per pass when there are more than 64 (the registers allow three 32-column accumulator blocks), 64 else
+    const int pc = p > kApplyPC ? kApplyPCWide : kApplyPC;
+    const size_t opart_bytes = ((size_t)a.splits * res->cnt_pad * pc * 4 + 1023) & ~size_t(1023);
+    const size_t vimg_bytes = (size_t)a.n_itiles * kVImgBytes(pc);
     a.opart = reinterpret_cast<float *>(P->extra);
     unsigned char *vimg = reinterpret_cast<unsigned char *>(P->extra) + opart_bytes;
     a.vimg = vimg;
@@ -761,13 +764,15 @@ fs_status bf16_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str
         return fail(c, FS_ERR_DEVICE, "internal: bf16 apply launch shape exceeds the padded buffers");
     const int total = a.n_jtiles * a.splits;
     const int per = (total + 7) / 8;
-    for (int p0 = 0; p0 < p; p0 += kApplyPC) {
-        hipLaunchKernelGGL(k_vimg_bf16, dim3((unsigned)a.n_itiles), dim3(BI), 0, c->stream, V, ldv, str->cnt, p0, (int)p,
-                           kApplyPC, kVImgBytes(kApplyPC), vimg);
-        hipLaunchKernelGGL((k_lse_bf16<2, 4, 2, kApplyPC>), dim3((unsigned)(per * 8)), dim3(512), 0, c->stream, a);
+    for (int p0 = 0; p0 < p; p0 += pc) {
+        hipLaunchKernelGGL(k_vimg_bf16, dim3((unsigned)a.n_itiles), dim3(BI), 0, c->stream, V, ldv, str->cnt, p0, (int)p, pc,
+                           kVImgBytes(pc), vimg);
+        if (pc == kApplyPCWide)
+            hipLaunchKernelGGL((k_lse_bf16<2, 4, 2, kApplyPCWide>), dim3((unsigned)(per * 8)), dim3(512), 0, c->stream, a);
+        else
+            hipLaunchKernelGGL((k_lse_bf16<2, 4, 2, kApplyPC>), dim3((unsigned)(per * 8)), dim3(512), 0, c->stream, a);
         FS_HIP(c, hipGetLastError());
-        fs_status st = launch_apply_finalize(c, P, res, res->norm, a.splits, eps, a.opart, kApplyPC, p0, (int)p, out, ldo,
-                                             mass_out);
+        fs_status st = launch_apply_finalize(c, P, res, res->norm, a.splits, eps, a.opart, pc, p0, (int)p, out, ldo, mass_out);
         if (st != FS_OK) return st;
     }
     return FS_OK;

@@ -684,7 +684,7 @@ __global__ __launch_bounds__(256) void k_weighted_sums(int64_t cnt, const float 
 //   out_i = a_i * exp(fhat_i/eps + m_i) * O_i   with everything in base 2;  mass_i = same with s.
 // A block of 256 threads covers 256 / PC rows; thread (row, c) produces one output entry, so the
 // reads of the [splits][rows][PC] accumulators are contiguous; the row's max and factor are
-// computed once (by its thread c = 0) and shared.  PC divides 256.
+// computed once (by its thread c = 0) and shared.  (When PC does not divide 256 the last 256 % PC threads idle.)
 __global__ __launch_bounds__(256) void k_apply_finalize(const double2 *partial, int64_t stride, const float *opart,
                                                         int64_t opart_stride, int PC, int splits, int64_t cnt,
                                                         double inv_eps, const float *w, double log_uniform,
@@ -694,7 +694,7 @@ __global__ __launch_bounds__(256) void k_apply_finalize(const double2 *partial, 
     __shared__ double shM[256], shFac[256];
     const int rows_per_block = 256 / PC;
     const int rl = threadIdx.x / PC, c = threadIdx.x - rl * PC;
-    const int64_t i = (int64_t)blockIdx.x * rows_per_block + rl;
+    const int64_t i = rl < rows_per_block ? (int64_t)blockIdx.x * rows_per_block + rl : cnt;   // (idle threads: no row)
     if (c == 0 && i < cnt) {
         double M = -INFINITY;
 #pragma unroll 8
@@ -769,7 +769,7 @@ fs_status launch_apply_finalize(Ctx *c, const Prepared *P, const Side *res, cons
                                 double eps, const float *opart, int PC, int p0, int p, float *out, int64_t ldo,
                                 float *mass_out)
 {
-    if (PC < 1 || PC > 256 || 256 % PC != 0) return fail(c, FS_ERR_DEVICE, "internal: accumulator width of the application merge");
+    if (PC < 1 || PC > 256) return fail(c, FS_ERR_DEVICE, "internal: accumulator width of the application merge");
     hipLaunchKernelGGL(k_apply_finalize, dim3((unsigned)ceil_div(res->cnt, 256 / PC)), dim3(256), 0, c->stream,
                        (const double2 *)P->partial, res->cnt_pad, opart, res->cnt_pad, PC, splits, res->cnt, 1.0 / eps,
                        res->w, res->log_uniform, res->pot, res_norm, p0, p, out, ldo, mass_out);
