@@ -269,11 +269,11 @@ fs_status fs_divergence(fs_ctx *ctx, const fs_problem *prob, float eps, int32_t 
  * V: m x p (ldv), out: n x p (ldo), r_out: NULL or n floats receiving P 1_m.
  * The gradient of Cor. 4 is 2*(diag(a) x - P y) (or with r_out in place of a, App. G).
  * Cost: a pass recomputes all n m scores and takes a block of value columns, so a call is
- * ceil(p / 8) passes at d <= 16 (ceil(p / 4) for a single column or at d = 16 with p <= 4),
+ * one pass for p <= 8 and ceil(p / 15) passes beyond at d <= 16,
  * ceil(p / 64) passes at d > 16 (when p > 64: ceil(p / 128) with FS_COMPUTE_FP32, ceil(p / 96) with
  * FS_COMPUTE_BF16_MFMA).
  * Accuracy at d <= 16, FS_COMPUTE_FP32: every plan entry enters the products to 2^-17 relative
- * (1e-6 to 3e-6 of the result's norm in practice), values to 24 bits.
+ * (1e-6 to 3e-6 of the result's norm in practice), values to 24 bits (p <= 8) or 2^-17 (p > 8).
  */
 fs_status fs_apply_plan(fs_ctx *ctx, const fs_problem *prob, float eps, const float *f,
                         const float *g, const float *V, int64_t p, int64_t ldv, float *out,

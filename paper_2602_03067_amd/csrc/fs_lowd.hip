@@ -251,8 +251,11 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
 {
     // PCU <= PC: value columns actually wanted (the others are not multiplied; zeros are stored for them)
     constexpr bool APPLY = PC > 0;
-    constexpr bool MM = PC == 8;   // products on the matrix cores
-    static_assert(PC == 0 || PC == 4 || PC == 8, "one float4 of values per streamed point, or an image of eight columns");
+    constexpr bool MM = PC == 8 || PC == 16;   // products on the matrix cores
+    // PC == 16: fifteen columns with TWO bf16 pieces per value (values to 2^-17, like the exponentials): rows
+    // 2 col + piece, row 30 the ones, so the row sum lands in register 14 of lane half 1
+    constexpr bool V2 = PC == 16;
+    static_assert(PC == 0 || PC == 4 || PC == 8 || PC == 16, "one float4 of values per streamed point, or an image of 8 / 15 columns");
     constexpr int VBYTES = MM ? (TJ / 32) * 2048 : (APPLY ? TJ * PC * 4 : 16);   // values of a tile in LDS
     __shared__ __attribute__((aligned(1024))) unsigned char vbuf[APPLY ? 2 : 1][VBYTES];
     constexpr int NP = 2 * KS;               // 16-byte pieces per record
@@ -570,9 +573,10 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
             f16v dch[MM ? R : 1];
             if constexpr (MM) {
                 chunk_mm(tl, vi, c0, dch);
-                // (the row sum of the chunk sits in register 3 of lane half 0; the other half has a zero row there)
+                // (the row sum of the chunk sits in register 3 of lane half 0; the other half has a zero row there.
+                // With two pieces per value: register 14 of lane half 1, and a product row in the other half)
 #pragma unroll
-                for (int r = 0; r < R; ++r) csum[r] = dch[r][3];
+                for (int r = 0; r < R; ++r) csum[r] = V2 ? (lh == 1 ? dch[r][14] : 0.0f) : dch[r][3];
             } else {
                 chunk_sums(tl, vt, c0, csum, co);
             }
@@ -671,10 +675,21 @@ __device__ __forceinline__ void lse_split_body(const SplitArgs &a, const int bx,
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int64_t row = row0 + 32 * r + lj;
-            if (lh == 0) partial[(int64_t)by * partial_stride + row] = make_double2((double)mrun[r], (double)omm[r][3]);
-            float *o = a.opart + ((int64_t)by * partial_stride + row) * PC + lh;
+            if constexpr (V2) {
+                if (lh == 1) partial[(int64_t)by * partial_stride + row] = make_double2((double)mrun[r], (double)omm[r][14]);
+                // rows 8 q + 4 h + s of this lane half: columns 4 q + 2 h and 4 q + 2 h + 1 (column 15 does not exist)
+                float *o = a.opart + ((int64_t)by * partial_stride + row) * PC + 2 * lh;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) o[2 * q] = (omm[r][4 * q] + omm[r][4 * q + 1]) + omm[r][4 * q + 2];
+                for (int q = 0; q < 4; ++q) {
+                    o[4 * q] = omm[r][4 * q] + omm[r][4 * q + 1];
+                    o[4 * q + 1] = (q == 3 && lh == 1) ? 0.0f : omm[r][4 * q + 2] + omm[r][4 * q + 3];
+                }
+            } else {
+                if (lh == 0) partial[(int64_t)by * partial_stride + row] = make_double2((double)mrun[r], (double)omm[r][3]);
+                float *o = a.opart + ((int64_t)by * partial_stride + row) * PC + lh;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) o[2 * q] = (omm[r][4 * q] + omm[r][4 * q + 1]) + omm[r][4 * q + 2];
+            }
         }
         return;
     }
@@ -1108,15 +1123,20 @@ fs_status lowd_lse_pair(Ctx *c, const Prepared *P, double eps, void *partial_x, 
 // 8 (2 ks + e / 4) + 4 h + e % 4 of the group, i.e. the order in which a lane of the score MFMA holds its sixteen
 // exponentials.  Row c' = 8 (col / 2) + 4 (col % 2) + piece holds bf16 piece `piece` (0..2) of value column
 // p0 + col; row 3 holds ones (the row sum), the other spare rows zeros.  One thread per 16-byte unit.
-constexpr int kApplyMM = 8;   // value columns per pass of the matrix-core application
+constexpr int kApplyMM = 8;   // value columns per pass of the matrix-core application (values in three bf16 pieces)
+constexpr int kApplyMM2 = 15;  // ... with values in two pieces (kept to 2^-17 like the exponentials): for more than 8 columns
+// `pieces` == 2: fifteen columns, row 2 col + piece, row 30 the ones, row 31 zeros.
 __global__ __launch_bounds__(256) void k_vimg_lowd(const float *__restrict__ V, int64_t ldv, int64_t n_str, int p0, int p,
-                                                   int64_t units, unsigned char *__restrict__ img)
+                                                   int64_t units, unsigned char *__restrict__ img, int pieces)
 {
     const int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (u >= units) return;
     const int cr = (int)(u & 31), h = (int)(u >> 5) & 1, ks = (int)(u >> 6) & 1;
     const int64_t grp = u >> 7;   // group of 32 streamed points
-    const int piece = cr & 3, col = 2 * (cr >> 3) + ((cr >> 2) & 1);
+    // piece 3 = a spare row (ones in row `ones_row`, zeros elsewhere)
+    const int piece = pieces == 2 ? (cr >= 30 ? 3 : (cr & 1)) : (cr & 3);
+    const int col = pieces == 2 ? (cr >> 1) : 2 * (cr >> 3) + ((cr >> 2) & 1);
+    const int ones_row = pieces == 2 ? 30 : 3;
     uint32_t w[4];
 #pragma unroll
     for (int e = 0; e < 8; e += 2) {
@@ -1127,7 +1147,7 @@ __global__ __launch_bounds__(256) void k_vimg_lowd(const float *__restrict__ V, 
             float x = 0.0f;
             if (i < n_str) {
                 if (piece == 3) {
-                    x = cr == 3 ? 1.0f : 0.0f;
+                    x = cr == ones_row ? 1.0f : 0.0f;
                 } else if (p0 + col < p) {
                     __bf16 q[3];
                     split3(V[i * ldv + p0 + col], q);
@@ -1142,7 +1162,7 @@ __global__ __launch_bounds__(256) void k_vimg_lowd(const float *__restrict__ V, 
 }
 
 // workspace of an application: [splits][rows][columns per pass] float accumulators, then the value images
-static size_t lowd_opart_bytes(int splits, int64_t res_pad) { return ((size_t)splits * (size_t)res_pad * kApplyMM * 4 + 1023) & ~size_t(1023); }
+static size_t lowd_opart_bytes(int splits, int64_t res_pad) { return ((size_t)splits * (size_t)res_pad * 16 * 4 + 1023) & ~size_t(1023); }
 static size_t lowd_vimg_bytes(int64_t n_str) { return (size_t)ceil_div(n_str, kSplitTJ) * (kSplitTJ / 32) * 2048; }
 
 size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t d, int64_t p)
@@ -1164,10 +1184,14 @@ size_t lowd_apply_ws(const Ctx *c, int64_t n_res, int64_t n_str, int64_t d, int6
 // (One block per wave and three workgroups per CU instead of two, which the registers allow for KS <= 4, measured
 // 4-6 % slower at d = 2..4 and 15 % slower at d = 6.)
 template <int KS>
-void launch_apply_split(dim3 grid, hipStream_t st, const SplitArgs &a)
+void launch_apply_split(dim3 grid, hipStream_t st, const SplitArgs &a, bool two_pieces)
 {
-    hipLaunchKernelGGL((k_apply_lowd_split<KS, (KS <= 4 ? kSplitR : 1), kSplitTJ, kSplitCH, false, kApplyMM, kApplyMM>), grid,
-                       dim3(kBlock), 0, st, a);
+    if (two_pieces)
+        hipLaunchKernelGGL((k_apply_lowd_split<KS, (KS <= 4 ? kSplitR : 1), kSplitTJ, kSplitCH, false, 16, 16>), grid, dim3(kBlock), 0,
+                           st, a);
+    else
+        hipLaunchKernelGGL((k_apply_lowd_split<KS, (KS <= 4 ? kSplitR : 1), kSplitTJ, kSplitCH, false, kApplyMM, kApplyMM>), grid,
+                           dim3(kBlock), 0, st, a);
 }
 // The form with the products on the vector ALU (four columns per pass) is kept where it measured faster
 // (n = m = 65536): a single column on short records, where a kernel copy multiplies one column only
@@ -1227,19 +1251,27 @@ fs_status lowd_apply(Ctx *c, const Prepared *P, const Side *res, const Side *str
                 if (st != FS_OK) return st;
             }
             if (valu) return FS_OK;
-            for (int p0 = 0; p0 < p; p0 += kApplyMM) {
+            // up to eight columns: values in three bf16 pieces (exact); more: passes of fifteen columns with two pieces
+            const bool two = p > kApplyMM;
+            const int step = two ? kApplyMM2 : kApplyMM, width = two ? 16 : kApplyMM;
+            for (int p0 = 0; p0 < p; p0 += step) {
                 a.p0 = p0;
+                const int p_end = (int)(p0 + step < p ? p0 + step : p);   // columns of this pass: p0 .. p_end - 1
                 hipLaunchKernelGGL(k_vimg_lowd, dim3((unsigned)ceil_div(units, 256)), dim3(256), 0, c->stream, V, ldv, str->cnt, p0,
-                                   (int)p, units, vimg);
+                                   p_end, units, vimg, two ? 2 : 3);
                 if (precise) {
-                    hipLaunchKernelGGL((k_apply_lowd_split<3, kSplitR, kSplitTJ, kSplitCH, true, kApplyMM, kApplyMM>), grid,
-                                       dim3(kBlock), 0, c->stream, a);
+                    if (two)
+                        hipLaunchKernelGGL((k_apply_lowd_split<3, kSplitR, kSplitTJ, kSplitCH, true, 16, 16>), grid, dim3(kBlock), 0,
+                                           c->stream, a);
+                    else
+                        hipLaunchKernelGGL((k_apply_lowd_split<3, kSplitR, kSplitTJ, kSplitCH, true, kApplyMM, kApplyMM>), grid,
+                                           dim3(kBlock), 0, c->stream, a);
                 } else {
-                    FS_SPLIT_KS_DISPATCH(P->ks, (launch_apply_split<KS_>(grid, c->stream, a)));
+                    FS_SPLIT_KS_DISPATCH(P->ks, (launch_apply_split<KS_>(grid, c->stream, a, two)));
                 }
                 FS_HIP(c, hipGetLastError());
-                st = launch_apply_finalize(c, P, res, precise ? res->norm : res->norm_f, a.splits, eps, opart, kApplyMM, p0,
-                                           (int)p, out, ldo, mass_out);
+                st = launch_apply_finalize(c, P, res, precise ? res->norm : res->norm_f, a.splits, eps, opart, width, p0, p_end, out,
+                                           ldo, mass_out);
                 if (st != FS_OK) return st;
             }
             return FS_OK;
