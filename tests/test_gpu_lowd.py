@@ -315,10 +315,11 @@ def test_full_size_lowdim_every_stage_sampled(ctx, oracle):
 
 
 # (p = 1 runs the kernel with the products on the vector ALU, as does p <= 4 at d = 16; everything else has them on the
-# matrix cores, eight columns per pass: p = 8, 9 and 17 are one full pass, a second one with a single column, three)
+# matrix cores: up to eight columns in one pass with the values in three bf16 pieces, more in passes of fifteen with two
+# pieces: p = 9 and 12 are one pass, 16 and 17 two (the second with one and two columns), 31 three)
 @pytest.mark.parametrize("n,m,d,p", [(300, 200, 3, 3), (1000, 1300, 3, 1), (513, 255, 2, 7), (260, 300, 8, 5), (700, 900, 3, 8),
                                      (450, 520, 1, 9), (390, 1100, 5, 17), (640, 300, 16, 16), (300, 640, 16, 3),
-                                     (1200, 900, 12, 12)])
+                                     (1200, 900, 12, 12), (333, 444, 4, 31), (250, 380, 3, 15)])
 def test_apply_plan_and_transpose(ctx, oracle, n, m, d, p):
     rng = np.random.default_rng(n + m + d + p)
     x, y, a, b = _rand_problem(rng, n, m, d)
