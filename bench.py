@@ -32,9 +32,9 @@ PEAKS = {"bf16": 2.5e15, "f64": 78.6e12}
 # These are NOT measured by this run (they need the profiler); each entry names the summary under profiles/ it was
 # copied from, and the figures go stale when a kernel changes without its profile being taken again.
 MEASURED_TRAFFIC = {
-    "lowdim_anneal": (191.96e6, "profiles/lse_lowd_split__lowdim_anneal.txt"),
-    "mnist_shape": (16496.62e6, "profiles/lse_bf16__mnist_shape.txt"),
-    "embedding": (4391.00e6, "profiles/lse_bf16__embedding.txt"),
+    "lowdim_anneal": (191.79e6, "profiles/lse_lowd_split__lowdim_anneal.txt"),
+    "mnist_shape": (16499.31e6, "profiles/lse_bf16__mnist_shape.txt"),
+    "embedding": (4391.51e6, "profiles/lse_bf16__embedding.txt"),
     "transport_grad": (77.17e6, "profiles/pass_f64__transport_grad.txt"),
 }
 PER_CONFIG = ("tiny", "mnist_shape", "embedding", "transport_grad")
